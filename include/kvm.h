@@ -1,0 +1,175 @@
+/*
+ * kvm.h -- C ABI of the Key-Value Means (KVM) attention layer hot path for AMD MI355X (gfx950).
+ *
+ * One KVM layer, as stated in the paper's Method section ("KVM Formulation"): every query runs
+ * a single softmax over [compressed state rows || exact causal block sliding window]; after each
+ * chunk the block that leaves the window is folded into the state (append the least redundant
+ * tokens while the budget allows, merge the rest winner-take-all into running sums), and the
+ * state is re-normalised just in time before it is read (LayerNorm on keys, stored radius on
+ * values).
+ *
+ * Conventions
+ *  - All pointers named q/k/v/gate/out/lse and every state buffer are DEVICE pointers owned by
+ *    the caller; the library owns only the small host handle `kvm_state`.  Pointers inside
+ *    `kvm_config` named ln_*, tau_* are DEVICE pointers too; `budget_table` is a HOST pointer
+ *    that is copied at init.
+ *  - Every call enqueues its kernels on the caller's stream (`void *stream` is a hipStream_t,
+ *    NULL = the default stream) and returns without synchronising the host.  Calls on one
+ *    state must be issued in order on one stream (or be ordered by the caller).
+ *  - Return value: KVM_OK (0) or a negative kvm_status.  Argument and capacity errors are
+ *    detected before anything is enqueued, so a failed call leaves the state untouched.
+ *  - q and k arrive already prepared (normalised, partially RoPE-rotated on the first
+ *    `rope_dims` channels) as the paper states at the end of "KVM weight preparation"; the
+ *    library needs `rope_dims` only to zero the rotary sub-space of memory keys.
+ *  - Shapes: B batch, H_q query heads, H_kv key/value heads (H_q % H_kv == 0; a group of
+ *    H_q/H_kv query heads shares one KV head's state, window, gate and LN_s), d = head_dim
+ *    (64 or 128), C = chunk_len, L = n_bswa_chunks * C.  A "unit" is one (batch, KV head).
+ *  - I/O dtype: KVM_F32 or KVM_BF16 for q, k, v, out, the memory keys and the normalised
+ *    readout rows.  State key sums are fp64, value sums fp32 (see DESIGN notes shipped with
+ *    the library sources).
+ */
+#ifndef KVM_H
+#define KVM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum kvm_status {
+  KVM_OK = 0,
+  KVM_ERR_ARG = -1,         /* bad argument / unsupported shape                          */
+  KVM_ERR_CAPACITY = -2,    /* the bound buffer cannot hold the rows the budget asks for */
+  KVM_ERR_STATE = -3,       /* call not valid in the state's current position            */
+  KVM_ERR_HIP = -4,         /* a HIP runtime call failed (see kvm_last_hip_error)        */
+  KVM_ERR_UNSUPPORTED = -5  /* shape/dtype combination has no kernel                     */
+} kvm_status;
+
+enum { KVM_F32 = 0, KVM_BF16 = 1 };
+enum { KVM_BUDGET_NONE = 0, KVM_BUDGET_FIXED = 1, KVM_BUDGET_SQRT = 2, KVM_BUDGET_TABLE = 3 };
+
+/* Layer constants.  Budget B(e) ("We choose n_append as follows", Method section):
+ *   NONE : no compressed state, the layer is pure block-sliding-window attention;
+ *   FIXED: B(e) = budget_fixed;
+ *   SQRT : B(e) = floor(budget_scale * ceil(sqrt(e)));
+ *   TABLE: B(e) = budget_table[min(e / C - 1, len - 1)].
+ * e is the end of the chunk that has just been attended. */
+typedef struct kvm_config {
+  int32_t batch, n_q_heads, n_kv_heads, head_dim;
+  int32_t rope_dims;       /* r: first r channels are rotary, zeroed in memory keys (eq. "memory key") */
+  int32_t chunk_len;       /* C */
+  int32_t n_bswa_chunks;   /* L = n_bswa_chunks * C ("Chunks and attention regions") */
+  int32_t n_sink;          /* S: first S state rows are never merge targets ("Merge"); default 1 */
+  int32_t io_dtype;        /* KVM_F32 | KVM_BF16 */
+  int32_t budget_kind;
+  int64_t budget_fixed;
+  double budget_scale;
+  const int64_t *budget_table; /* host */
+  int64_t budget_table_len;
+  float ln_eps;            /* LN_s epsilon; 0 selects 1e-5 */
+  float norm_eps;          /* eps_norm of the value readout; 0 selects 1e-12 */
+  const float *ln_gamma;   /* device [H_kv, d] or NULL => 1 */
+  const float *ln_beta;    /* device [H_kv, d] or NULL => 0 */
+  const float *tau_state;  /* device [H_q] or NULL => 1 ("Readout": per-head inverse temperatures) */
+  const float *tau_bswa;   /* device [H_q] or NULL => 1 */
+} kvm_config;
+
+/* Element strides of the prefill operands; the head_dim axis is always contiguous.
+ * NULL in kvm_prefill_chunked means dense [B, T, H, d] (and [B, T, H] for gate and lse). */
+typedef struct kvm_strides {
+  int64_t q_b, q_t, q_h;
+  int64_t k_b, k_t, k_h;
+  int64_t v_b, v_t, v_h;
+  int64_t o_b, o_t, o_h;
+  int64_t g_b, g_t, g_h;
+  int64_t lse_b, lse_t, lse_h;
+} kvm_strides;
+
+typedef struct kvm_state kvm_state;
+
+const char *kvm_strerror(int status);
+/* Text of the last HIP error seen by this thread's library calls ("" if none). */
+const char *kvm_last_hip_error(void);
+
+/* Rows the state reaches after `max_tokens` tokens under the config's budget (integer replay of
+ * M*(e) = max(m, min(B(e), m + C)); creation gives C).  Negative on bad config. */
+int64_t kvm_state_rows_for(const kvm_config *cfg, int64_t max_tokens);
+
+/* Bytes of device memory kvm_state_init needs to run up to `max_tokens` tokens: state sums,
+ * radii, normalised readout rows, window ring and fold/decode scratch.  0 on bad config. */
+size_t kvm_state_bytes(const kvm_config *cfg, int64_t max_tokens);
+
+/* Bind an empty state (m = 0, no tokens seen) to caller memory `dev_buf` (256-byte aligned,
+ * at least kvm_state_bytes(cfg, max_tokens) bytes).  Enqueues nothing.  The buffer must stay
+ * alive until kvm_state_destroy; its contents need not be initialised. */
+int kvm_state_init(kvm_state **out, const kvm_config *cfg, void *dev_buf, size_t bytes,
+                   int64_t max_tokens);
+int kvm_state_destroy(kvm_state *st);
+
+/* Chunk-wise prefill of T more tokens (pseudocode appendix; "Chunks and attention regions").
+ * The running token count must be a multiple of C on entry; T may end inside a chunk (that
+ * chunk is completed by kvm_decode_step).  For each chunk: attention of its queries over the
+ * current state and the window, then, if the chunk is complete and e >= L, the fold of block
+ * [e - L, e - L + C).  Leaves the last L tokens in the state's window ring.
+ *   q, out: [B, T, H_q, d]; k, v: [B, T, H_kv, d]; gate: [B, T, H_kv] fp32 merge gate g_t > 0
+ *   or NULL (g = 1); lse: [B, T, H_q] fp32 natural-log sum of exponentials, or NULL.
+ * KVM_ERR_CAPACITY if the budget over this call exceeds the bound buffer (nothing enqueued). */
+int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void *v,
+                        const float *gate, void *out, float *lse, int64_t T,
+                        const kvm_strides *strides, void *stream);
+
+/* One new token per sequence: append (k, v, g) to the window, attend the query over state and
+ * window, and fold when this token completes a chunk with e >= L.
+ *   q, out: [B, H_q, d]; k, v: [B, H_kv, d]; gate: [B, H_kv] or NULL. */
+int kvm_decode_step(kvm_state *st, const void *q, const void *k, const void *v,
+                    const float *gate, void *out, void *stream);
+
+/* Fold one overflow block into the state ("Append" and "Merge"): memory keys, similarity to
+ * the normalised state, append of the n_append least similar tokens, winner-take-all merge of
+ * the rest into rows >= S of the updated state, refresh of the normalised readout rows.
+ *   k_blk, v_blk: [B, n_tokens, H_kv, d]; gate_blk: [B, n_tokens, H_kv] or NULL;
+ *   n_tokens must equal C; e = end of the chunk just attended (argument of the budget);
+ *   assign_out: nullable int32 [B, H_kv, n_tokens], the row each token went to (an appended
+ *   token gets its new row);  score_out: nullable fp32 [B, H_kv, n_tokens, 2] =
+ *   (append score s_j, winning merge score), NaN where not computed.
+ * Used by the two calls above; exported for callers that keep their own window. */
+int kvm_state_fold(kvm_state *st, const void *k_blk, const void *v_blk, const float *gate_blk,
+                   int32_t n_tokens, int64_t e, int32_t *assign_out, float *score_out,
+                   void *stream);
+
+/* Introspection (host values, no device work). */
+int kvm_state_rows(const kvm_state *st, int64_t *m_out);          /* current m, same for all units */
+int kvm_state_tokens(const kvm_state *st, int64_t *tokens_seen);
+int kvm_state_capacity(const kvm_state *st, int64_t *rows_out);   /* rows the bound buffer holds */
+int kvm_state_folds(const kvm_state *st, int64_t *folds_out);     /* folds done so far */
+
+/* Record every later fold's assignments and scores: fold number f (0 = the creation fold of
+ * this state, counted over its whole life) writes assign[f] as int32 [B, H_kv, C] and
+ * score[f] as fp32 [B, H_kv, C, 2].  Folds beyond `max_folds` are not recorded.  NULLs stop it. */
+int kvm_state_trace(kvm_state *st, int32_t *assign, float *score, int64_t max_folds);
+
+/* Move the state into a larger buffer sized for `new_max_tokens` (growth scheduler: called
+ * after KVM_ERR_CAPACITY).  Copies on `stream`; the old buffer may be freed once the stream has
+ * passed this point. */
+int kvm_state_grow(kvm_state *st, void *new_buf, size_t new_bytes, int64_t new_max_tokens,
+                   void *stream);
+
+/* Copy the state out / in (checkpoint).  Every pointer is nullable (skipped).  Rows are dense:
+ *   sK fp64 [B, H_kv, m, d], sV fp32 [B, H_kv, m, d], rho fp32 [B, H_kv, m],
+ *   w fp32 [B, H_kv, m] (1 + merged gates), n int32 [B, H_kv, m] (tokens in the row),
+ *   khat, vhat I/O dtype [B, H_kv, m, d] (normalised readout; export only),
+ *   win_k, win_v I/O dtype [B, H_kv, L, d], win_g fp32 [B, H_kv, L]: ring, token p at p % L. */
+int kvm_state_export(const kvm_state *st, double *sK, float *sV, float *rho, float *w,
+                     int32_t *n, void *khat, void *vhat, void *win_k, void *win_v,
+                     float *win_g, void *stream);
+int kvm_state_import(kvm_state *st, const double *sK, const float *sV, const float *rho,
+                     const float *w, const int32_t *n, const void *win_k, const void *win_v,
+                     const float *win_g, int64_t m, int64_t tokens_seen, int64_t folds,
+                     void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVM_H */

@@ -204,14 +204,18 @@ def _argmax_lowest(row: np.ndarray) -> int:
 def fold(state: UnitState, k_blk: np.ndarray, v_blk: np.ndarray, g_blk: Optional[np.ndarray],
          e: int, cfg: KVMConfig, gamma: np.ndarray, beta: np.ndarray,
          positions: Optional[Sequence[int]] = None,
-         overrides: Optional[Dict[int, int]] = None) -> dict:
+         overrides: Optional[Dict[int, int]] = None,
+         append_override: Optional[Sequence[int]] = None) -> dict:
     """Fold one overflow block Omega_e into the state ("Append" then "Merge").
 
     k_blk, v_blk: [n, d] I/O-dtype values (as fp64); g_blk: [n] gates or None (g = 1).
     e: end of the chunk just attended (argument of the budget).
     overrides: {token index in block: slot}.  Only honoured when that slot's score is
-    within TIE_MARGIN of the token's best eligible score, otherwise ValueError.  It lets
-    a test keep following a run after a counted tie; it never changes what is correct.
+    within TIE_MARGIN of the token's best eligible score, otherwise ValueError.
+    append_override: the set of tokens to append instead of the oracle's own choice.  Only
+    honoured when it has n_append tokens and swaps tokens whose s_j lie within TIE_MARGIN of
+    the selection boundary, otherwise ValueError.  Both let a test keep following a run
+    after a counted tie; they never change what is correct.
 
     Returns a log: assign[n] (slot per token; appended tokens get their new row id),
     s_max[n] (append score, or NaN at creation), best[n] and margin[n] (merge score and
@@ -250,6 +254,15 @@ def fold(state: UnitState, k_blk: np.ndarray, v_blk: np.ndarray, g_blk: Optional
     # the n_app smallest scores; equal scores -> lower position first
     order = sorted(range(n_tok), key=lambda j: (s_max[j], j))
     chosen = sorted(order[:n_app])
+    if append_override is not None and sorted(append_override) != chosen:
+        alt = sorted(int(j) for j in append_override)
+        if len(alt) != n_app or len(set(alt)) != n_app or n_app == 0 or n_app == n_tok:
+            raise ValueError("append override has the wrong size")
+        boundary = s_max[order[n_app - 1]]
+        swapped = set(alt) ^ set(chosen)
+        if any(abs(s_max[j] - boundary) > TIE_MARGIN for j in swapped):
+            raise ValueError("append override is not within the tie margin")
+        chosen = alt
     if n_app > 0:
         state.append_rows(kbar[chosen], v_blk[chosen], [positions[j] for j in chosen])
         for a, j in enumerate(chosen):
@@ -346,6 +359,7 @@ class KVMUnit:
         self.g_hist = np.zeros((0,))
         self.fold_logs: List[dict] = []
         self.overrides: Dict[Tuple[int, int], int] = {}   # (fold index, token in block) -> slot
+        self.append_overrides: Dict[int, Sequence[int]] = {}  # fold index -> appended tokens
 
     # -- helpers
     def _push(self, k, v, g):
@@ -379,7 +393,8 @@ class KVMUnit:
         ov = {j: s for (f, j), s in self.overrides.items() if f == idx} or None
         log = fold(self.state, self.k_hist[lo:lo + C], self.v_hist[lo:lo + C],
                    self.g_hist[lo:lo + C], e, self.cfg, self.gamma, self.beta,
-                   positions=list(range(lo, lo + C)), overrides=ov)
+                   positions=list(range(lo, lo + C)), overrides=ov,
+                   append_override=self.append_overrides.get(idx))
         self.fold_logs.append(log)
 
     # -- public

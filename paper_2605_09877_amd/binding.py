@@ -1,0 +1,323 @@
+"""Thin ctypes binding of libkvm.so: same entry points as include/kvm.h, torch tensors in.
+
+Argument marshalling only -- every step of the layer runs in the library's HIP kernels.
+torch is used for device memory and the current stream.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libkvm.so")
+
+KVM_F32, KVM_BF16 = 0, 1
+KVM_BUDGET_NONE, KVM_BUDGET_FIXED, KVM_BUDGET_SQRT, KVM_BUDGET_TABLE = 0, 1, 2, 3
+KVM_OK, KVM_ERR_ARG, KVM_ERR_CAPACITY, KVM_ERR_STATE, KVM_ERR_HIP, KVM_ERR_UNSUPPORTED = 0, -1, -2, -3, -4, -5
+
+EXPORTS = [
+    "kvm_strerror", "kvm_last_hip_error", "kvm_state_rows_for", "kvm_state_bytes", "kvm_state_init",
+    "kvm_state_destroy", "kvm_prefill_chunked", "kvm_decode_step", "kvm_state_fold", "kvm_state_rows",
+    "kvm_state_tokens", "kvm_state_capacity", "kvm_state_folds", "kvm_state_trace", "kvm_state_grow",
+    "kvm_state_export", "kvm_state_import",
+]
+
+
+class kvm_config(C.Structure):
+    _fields_ = [
+        ("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+        ("rope_dims", C.c_int32), ("chunk_len", C.c_int32), ("n_bswa_chunks", C.c_int32),
+        ("n_sink", C.c_int32), ("io_dtype", C.c_int32), ("budget_kind", C.c_int32),
+        ("budget_fixed", C.c_int64), ("budget_scale", C.c_double),
+        ("budget_table", C.POINTER(C.c_int64)), ("budget_table_len", C.c_int64),
+        ("ln_eps", C.c_float), ("norm_eps", C.c_float),
+        ("ln_gamma", C.c_void_p), ("ln_beta", C.c_void_p), ("tau_state", C.c_void_p), ("tau_bswa", C.c_void_p),
+    ]
+
+
+class kvm_strides(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in (
+        "q_b", "q_t", "q_h", "k_b", "k_t", "k_h", "v_b", "v_t", "v_h",
+        "o_b", "o_t", "o_h", "g_b", "g_t", "g_h", "lse_b", "lse_t", "lse_h")]
+
+
+class KVMError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(what)
+
+
+_lib = None
+
+
+def load_library() -> C.CDLL:
+    """Load libkvm.so built in-tree.  There is no fallback: without it nothing here works."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2605_09877_amd.build` (needs hipcc)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i64, i32 = C.c_void_p, C.c_int64, C.c_int32
+    lib.kvm_strerror.restype = C.c_char_p
+    lib.kvm_strerror.argtypes = [C.c_int]
+    lib.kvm_last_hip_error.restype = C.c_char_p
+    lib.kvm_state_rows_for.restype = i64
+    lib.kvm_state_rows_for.argtypes = [C.POINTER(kvm_config), i64]
+    lib.kvm_state_bytes.restype = C.c_size_t
+    lib.kvm_state_bytes.argtypes = [C.POINTER(kvm_config), i64]
+    lib.kvm_state_init.argtypes = [C.POINTER(vp), C.POINTER(kvm_config), vp, C.c_size_t, i64]
+    lib.kvm_state_destroy.argtypes = [vp]
+    lib.kvm_prefill_chunked.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, C.POINTER(kvm_strides), vp]
+    lib.kvm_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+    lib.kvm_state_fold.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp, vp]
+    for name in ("kvm_state_rows", "kvm_state_tokens", "kvm_state_capacity", "kvm_state_folds"):
+        getattr(lib, name).argtypes = [vp, C.POINTER(i64)]
+    lib.kvm_state_trace.argtypes = [vp, vp, vp, i64]
+    lib.kvm_state_grow.argtypes = [vp, vp, C.c_size_t, i64, vp]
+    lib.kvm_state_export.argtypes = [vp] * 12
+    lib.kvm_state_import.argtypes = [vp] * 9 + [i64, i64, i64, vp]
+    _lib = lib
+    return lib
+
+
+def _check(status: int, what: str) -> None:
+    if status != KVM_OK:
+        lib = load_library()
+        msg = lib.kvm_strerror(status).decode()
+        if status == KVM_ERR_HIP:
+            msg += " (" + lib.kvm_last_hip_error().decode() + ")"
+        raise KVMError(status, f"{what}: {msg}")
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _io_dtype(io: int) -> torch.dtype:
+    return torch.bfloat16 if io == KVM_BF16 else torch.float32
+
+
+class KVMState:
+    """A bound state: owns the device buffer and the parameter tensors the handle points to."""
+
+    def __init__(self, *, batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int, rope_dims: int,
+                 chunk_len: int, n_bswa_chunks: int = 2, n_sink: int = 1, io_dtype: int = KVM_BF16,
+                 budget_kind: int = KVM_BUDGET_FIXED, budget_fixed: int = 0, budget_scale: float = 0.0,
+                 budget_table: Optional[Sequence[int]] = None, ln_eps: float = 1e-5, norm_eps: float = 1e-12,
+                 ln_gamma: Optional[torch.Tensor] = None, ln_beta: Optional[torch.Tensor] = None,
+                 tau_state: Optional[torch.Tensor] = None, tau_bswa: Optional[torch.Tensor] = None,
+                 max_tokens: int, device: str = "cuda:0"):
+        self.lib = load_library()
+        self.device = torch.device(device)
+        self._keep = []
+
+        def dev_f32(t, shape):
+            if t is None:
+                return None
+            t = t.to(device=self.device, dtype=torch.float32).contiguous()
+            assert tuple(t.shape) == shape, (tuple(t.shape), shape)
+            self._keep.append(t)
+            return t
+
+        self.ln_gamma = dev_f32(ln_gamma, (n_kv_heads, head_dim))
+        self.ln_beta = dev_f32(ln_beta, (n_kv_heads, head_dim))
+        self.tau_state = dev_f32(tau_state, (n_q_heads,))
+        self.tau_bswa = dev_f32(tau_bswa, (n_q_heads,))
+        table = None
+        if budget_table is not None:
+            table = (C.c_int64 * len(budget_table))(*[int(x) for x in budget_table])
+            self._keep.append(table)
+        self.cfg = kvm_config(
+            batch, n_q_heads, n_kv_heads, head_dim, rope_dims, chunk_len, n_bswa_chunks, n_sink, io_dtype,
+            budget_kind, int(budget_fixed), float(budget_scale),
+            C.cast(table, C.POINTER(C.c_int64)) if table is not None else None,
+            0 if table is None else len(budget_table), ln_eps, norm_eps,
+            _ptr(self.ln_gamma), _ptr(self.ln_beta), _ptr(self.tau_state), _ptr(self.tau_bswa))
+        self.io = io_dtype
+        self.dtype = _io_dtype(io_dtype)
+        self.handle = C.c_void_p()
+        self.buf = None
+        self._bind(max_tokens, first=True)
+        self._trace = None
+
+    # ---- binding / growth
+    def _alloc(self, max_tokens: int) -> torch.Tensor:
+        nbytes = self.lib.kvm_state_bytes(C.byref(self.cfg), max_tokens)
+        if nbytes == 0:
+            raise KVMError(KVM_ERR_ARG, "kvm_state_bytes: bad config")
+        return torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+
+    def _bind(self, max_tokens: int, first: bool) -> None:
+        buf = self._alloc(max_tokens)
+        _check(self.lib.kvm_state_init(C.byref(self.handle), C.byref(self.cfg), buf.data_ptr(), buf.numel(),
+                                       max_tokens), "kvm_state_init")
+        self.buf = buf
+        self.max_tokens = max_tokens
+
+    def grow(self, new_max_tokens: int) -> None:
+        """kvm_state_grow into a freshly allocated, larger buffer."""
+        buf = self._alloc(new_max_tokens)
+        with torch.cuda.device(self.device):
+            _check(self.lib.kvm_state_grow(self.handle, buf.data_ptr(), buf.numel(), new_max_tokens, _stream()),
+                   "kvm_state_grow")
+        old = self.buf
+        self.buf = buf
+        self.max_tokens = new_max_tokens
+        old.record_stream(torch.cuda.current_stream(self.device))
+
+    def close(self) -> None:
+        if self.handle:
+            self.lib.kvm_state_destroy(self.handle)
+            self.handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- introspection
+    def _i64(self, fn) -> int:
+        v = C.c_int64()
+        _check(fn(self.handle, C.byref(v)), fn.__name__)
+        return v.value
+
+    @property
+    def rows(self) -> int:
+        return self._i64(self.lib.kvm_state_rows)
+
+    @property
+    def tokens(self) -> int:
+        return self._i64(self.lib.kvm_state_tokens)
+
+    @property
+    def capacity(self) -> int:
+        return self._i64(self.lib.kvm_state_capacity)
+
+    @property
+    def folds(self) -> int:
+        return self._i64(self.lib.kvm_state_folds)
+
+    def rows_for(self, max_tokens: int) -> int:
+        return self.lib.kvm_state_rows_for(C.byref(self.cfg), max_tokens)
+
+    # ---- the hot path
+    def _chk(self, t: torch.Tensor, shape, dtype, name: str) -> torch.Tensor:
+        if t.device != self.device or t.dtype != dtype or tuple(t.shape) != tuple(shape) or not t.is_contiguous():
+            raise ValueError(f"{name}: want contiguous {dtype} {tuple(shape)} on {self.device}, "
+                             f"got {t.dtype} {tuple(t.shape)} on {t.device}")
+        return t
+
+    def prefill(self, q, k, v, gate=None, out=None, lse=None, want_lse=False):
+        """kvm_prefill_chunked.  q [B,T,Hq,d], k/v [B,T,Hkv,d], gate [B,T,Hkv] fp32 or None."""
+        c = self.cfg
+        T = q.shape[1]
+        self._chk(q, (c.batch, T, c.n_q_heads, c.head_dim), self.dtype, "q")
+        self._chk(k, (c.batch, T, c.n_kv_heads, c.head_dim), self.dtype, "k")
+        self._chk(v, (c.batch, T, c.n_kv_heads, c.head_dim), self.dtype, "v")
+        if gate is not None:
+            self._chk(gate, (c.batch, T, c.n_kv_heads), torch.float32, "gate")
+        if out is None:
+            out = torch.empty_like(q)
+        self._chk(out, q.shape, self.dtype, "out")
+        if lse is None and want_lse:
+            lse = torch.empty((c.batch, T, c.n_q_heads), dtype=torch.float32, device=self.device)
+        if lse is not None:
+            self._chk(lse, (c.batch, T, c.n_q_heads), torch.float32, "lse")
+        with torch.cuda.device(self.device):
+            _check(self.lib.kvm_prefill_chunked(self.handle, q.data_ptr(), k.data_ptr(), v.data_ptr(), _ptr(gate),
+                                                out.data_ptr(), _ptr(lse), T, None, _stream()),
+                   "kvm_prefill_chunked")
+        return (out, lse) if (want_lse or lse is not None) else out
+
+    def decode(self, q, k, v, gate=None, out=None):
+        """kvm_decode_step.  q [B,Hq,d], k/v [B,Hkv,d], gate [B,Hkv] fp32 or None."""
+        c = self.cfg
+        self._chk(q, (c.batch, c.n_q_heads, c.head_dim), self.dtype, "q")
+        self._chk(k, (c.batch, c.n_kv_heads, c.head_dim), self.dtype, "k")
+        self._chk(v, (c.batch, c.n_kv_heads, c.head_dim), self.dtype, "v")
+        if gate is not None:
+            self._chk(gate, (c.batch, c.n_kv_heads), torch.float32, "gate")
+        if out is None:
+            out = torch.empty_like(q)
+        self._chk(out, q.shape, self.dtype, "out")
+        with torch.cuda.device(self.device):
+            _check(self.lib.kvm_decode_step(self.handle, q.data_ptr(), k.data_ptr(), v.data_ptr(), _ptr(gate),
+                                            out.data_ptr(), _stream()), "kvm_decode_step")
+        return out
+
+    def fold(self, k_blk, v_blk, gate_blk=None, *, e: int):
+        """kvm_state_fold.  k_blk/v_blk [B,C,Hkv,d]; returns (assign [B,Hkv,C] int32, score [B,Hkv,C,2])."""
+        c = self.cfg
+        n = k_blk.shape[1]
+        self._chk(k_blk, (c.batch, n, c.n_kv_heads, c.head_dim), self.dtype, "k_blk")
+        self._chk(v_blk, (c.batch, n, c.n_kv_heads, c.head_dim), self.dtype, "v_blk")
+        if gate_blk is not None:
+            self._chk(gate_blk, (c.batch, n, c.n_kv_heads), torch.float32, "gate_blk")
+        assign = torch.empty((c.batch, c.n_kv_heads, n), dtype=torch.int32, device=self.device)
+        score = torch.empty((c.batch, c.n_kv_heads, n, 2), dtype=torch.float32, device=self.device)
+        with torch.cuda.device(self.device):
+            _check(self.lib.kvm_state_fold(self.handle, k_blk.data_ptr(), v_blk.data_ptr(), _ptr(gate_blk), n, e,
+                                           assign.data_ptr(), score.data_ptr(), _stream()), "kvm_state_fold")
+        return assign, score
+
+    # ---- tracing, checkpoint
+    def trace(self, max_folds: int):
+        """kvm_state_trace: returns (assign [F,B,Hkv,C] int32, score [F,B,Hkv,C,2] fp32) filled by later folds."""
+        c = self.cfg
+        assign = torch.full((max_folds, c.batch, c.n_kv_heads, c.chunk_len), -1, dtype=torch.int32, device=self.device)
+        score = torch.zeros((max_folds, c.batch, c.n_kv_heads, c.chunk_len, 2), dtype=torch.float32,
+                            device=self.device)
+        _check(self.lib.kvm_state_trace(self.handle, assign.data_ptr(), score.data_ptr(), max_folds),
+               "kvm_state_trace")
+        self._trace = (assign, score)
+        return assign, score
+
+    def export(self) -> dict:
+        """kvm_state_export into fresh tensors."""
+        c = self.cfg
+        B, H, d, m, L = c.batch, c.n_kv_heads, c.head_dim, self.rows, c.chunk_len * c.n_bswa_chunks
+        dev = self.device
+        o = dict(
+            sK=torch.empty((B, H, m, d), dtype=torch.float64, device=dev),
+            sV=torch.empty((B, H, m, d), dtype=torch.float32, device=dev),
+            rho=torch.empty((B, H, m), dtype=torch.float32, device=dev),
+            w=torch.empty((B, H, m), dtype=torch.float32, device=dev),
+            n=torch.empty((B, H, m), dtype=torch.int32, device=dev),
+            khat=torch.empty((B, H, m, d), dtype=self.dtype, device=dev),
+            vhat=torch.empty((B, H, m, d), dtype=self.dtype, device=dev),
+            win_k=torch.empty((B, H, L, d), dtype=self.dtype, device=dev),
+            win_v=torch.empty((B, H, L, d), dtype=self.dtype, device=dev),
+            win_g=torch.empty((B, H, L), dtype=torch.float32, device=dev),
+        )
+        with torch.cuda.device(dev):
+            _check(self.lib.kvm_state_export(self.handle, *[o[k].data_ptr() for k in (
+                "sK", "sV", "rho", "w", "n", "khat", "vhat", "win_k", "win_v", "win_g")], _stream()),
+                "kvm_state_export")
+        o.update(m=m, tokens=self.tokens, folds=self.folds)
+        return o
+
+    def import_(self, o: dict) -> None:
+        """kvm_state_import from the dict export() returns (khat/vhat are recomputed)."""
+        c = self.cfg
+        B, H, d, L = c.batch, c.n_kv_heads, c.head_dim, c.chunk_len * c.n_bswa_chunks
+        m = int(o["m"])
+        ptrs = []
+        for key, dt, shape in (("sK", torch.float64, (B, H, m, d)), ("sV", torch.float32, (B, H, m, d)),
+                               ("rho", torch.float32, (B, H, m)), ("w", torch.float32, (B, H, m)),
+                               ("n", torch.int32, (B, H, m)), ("win_k", self.dtype, (B, H, L, d)),
+                               ("win_v", self.dtype, (B, H, L, d)), ("win_g", torch.float32, (B, H, L))):
+            t = o.get(key)
+            ptrs.append(None if t is None else self._chk(t, shape, dt, key).data_ptr())
+        with torch.cuda.device(self.device):
+            _check(self.lib.kvm_state_import(self.handle, *ptrs, m, int(o["tokens"]), int(o.get("folds", 0)),
+                                             _stream()), "kvm_state_import")

@@ -1,0 +1,202 @@
+// Row attention: one workgroup per (query, query head, sequence) runs the single softmax of the
+// paper's "Readout" equations over [normalised state rows || visible window tokens], streaming
+// keys and values once from HBM.  This is the decode kernel (one query per sequence, memory
+// bound) and also serves fp32 prefill, where every query of a chunk gets its own workgroup.
+//
+// A key row of D elements is read by D/VEC adjacent lanes with one 16-byte load each, so a wave
+// covers 64/(D/VEC) keys per step; each such lane group keeps its own online-softmax state
+// (running max, sum, output fragment) and the groups are merged at the end.
+#include "kvm_device.h"
+#include "kvm_internal.h"
+
+namespace kvm {
+
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+template <typename T>
+struct Frag;
+template <>
+struct Frag<float> {
+  static constexpr int kVec = 4;
+  __device__ static __forceinline__ void load(const float *p, float (&f)[4]) {
+    const float4 x = *reinterpret_cast<const float4 *>(p);
+    f[0] = x.x; f[1] = x.y; f[2] = x.z; f[3] = x.w;
+  }
+  __device__ static __forceinline__ void store(float *p, const float (&f)[4]) {
+    *reinterpret_cast<float4 *>(p) = make_float4(f[0], f[1], f[2], f[3]);
+  }
+};
+template <>
+struct Frag<bf16_t> {
+  static constexpr int kVec = 8;
+  __device__ static __forceinline__ void load(const bf16_t *p, float (&f)[8]) {
+    const uint4 x = *reinterpret_cast<const uint4 *>(p);
+    const uint32_t wds[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      f[2 * i] = __uint_as_float(wds[i] << 16);
+      f[2 * i + 1] = __uint_as_float(wds[i] & 0xffff0000u);
+    }
+  }
+  __device__ static __forceinline__ void store(bf16_t *p, const float (&f)[8]) {
+    uint32_t wds[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      wds[i] = (uint32_t)float_to_bf16_bits(f[2 * i]) | ((uint32_t)float_to_bf16_bits(f[2 * i + 1]) << 16);
+    *reinterpret_cast<uint4 *>(p) = make_uint4(wds[0], wds[1], wds[2], wds[3]);
+  }
+};
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void attn_rows_kernel(Dev dv, AttnArgs a) {
+  constexpr int VEC = Frag<T>::kVec;
+  constexpr int LPR = D / VEC;   // lanes per key row
+  constexpr int RPW = 64 / LPR;  // key rows per wave step
+  constexpr int KB = 4;          // rows in flight per lane group
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane / LPR, cl = lane % LPR;
+  const int qi = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
+  const int hkv = hq / (dv.Hq / dv.Hkv);
+  const int u = b * dv.Hkv + hkv;
+  const int64_t pos = a.s + qi;
+
+  float qf[VEC];
+  Frag<T>::load((const T *)a.q + b * a.q_b + (int64_t)qi * a.q_t + hq * a.q_h + cl * VEC, qf);
+  const float rs = kLog2e * rsqrtf((float)D);
+  const float c_state = (dv.tau_state ? dv.tau_state[hq] : 1.f) * rs;
+  const float c_bswa = (dv.tau_bswa ? dv.tau_bswa[hq] : 1.f) * rs;
+
+  const int m = a.m;
+  const int total = m + (int)(pos - a.b + 1);
+  const T *khat = (const T *)dv.khat + (int64_t)u * dv.Mcap * D;
+  const T *vhat = (const T *)dv.vhat + (int64_t)u * dv.Mcap * D;
+  const T *ring_k = (const T *)dv.winK + (int64_t)u * dv.L * D;
+  const T *ring_v = (const T *)dv.winV + (int64_t)u * dv.L * D;
+  const T *in_k = (const T *)a.in.k + b * a.in.k_b + hkv * a.in.k_h;
+  const T *in_v = (const T *)a.in.v + b * a.in.v_b + hkv * a.in.v_h;
+
+  float m_run = -INFINITY, l_run = 0.f;
+  float acc[VEC];
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
+
+  for (int n0 = 0; n0 < total; n0 += 4 * RPW * KB) {
+    float kf[KB][VEC], vf[KB][VEC], t[KB];
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb) {
+      const int n = n0 + (kb * 4 + wave) * RPW + sub;
+      const int nc = n < total ? n : total - 1;
+      const T *kp, *vp;
+      if (nc < m) {
+        kp = khat + (int64_t)nc * D;
+        vp = vhat + (int64_t)nc * D;
+      } else {
+        const int64_t p = a.b + (nc - m);
+        if (p >= a.t0) {
+          kp = in_k + (p - a.t0) * a.in.k_t;
+          vp = in_v + (p - a.t0) * a.in.v_t;
+        } else {
+          const int slot = (int)(p % dv.L);
+          kp = ring_k + (int64_t)slot * D;
+          vp = ring_v + (int64_t)slot * D;
+        }
+      }
+      Frag<T>::load(kp + cl * VEC, kf[kb]);
+      Frag<T>::load(vp + cl * VEC, vf[kb]);
+      t[kb] = (n < total) ? (nc < m ? c_state : c_bswa) : 0.f;  // holds the scale for now
+    }
+    float m_new = m_run;
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb) {
+      float dot = 0.f;
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) dot = fmaf(qf[i], kf[kb][i], dot);
+#pragma unroll
+      for (int o = 1; o < LPR; o <<= 1) dot += __shfl_xor(dot, o, kWave);
+      const int n = n0 + (kb * 4 + wave) * RPW + sub;
+      t[kb] = (n < total) ? dot * t[kb] : -INFINITY;
+      m_new = fmaxf(m_new, t[kb]);
+    }
+    if (m_new != -INFINITY) {
+      const float alpha = exp2f(m_run - m_new);
+      l_run *= alpha;
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) acc[i] *= alpha;
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb) {
+        const float p = exp2f(t[kb] - m_new);
+        l_run += p;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[i] = fmaf(p, vf[kb][i], acc[i]);
+      }
+      m_run = m_new;
+    }
+  }
+
+  // merge the lane groups of this wave
+#pragma unroll
+  for (int o = LPR; o < 64; o <<= 1) {
+    const float m_o = __shfl_xor(m_run, o, kWave);
+    const float l_o = __shfl_xor(l_run, o, kWave);
+    const float m_n = fmaxf(m_run, m_o);
+    const float sa = m_n == -INFINITY ? 0.f : exp2f(m_run - m_n);
+    const float sb = m_n == -INFINITY ? 0.f : exp2f(m_o - m_n);
+    l_run = l_run * sa + l_o * sb;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) acc[i] = acc[i] * sa + __shfl_xor(acc[i], o, kWave) * sb;
+    m_run = m_n;
+  }
+  // merge the four waves
+  __shared__ float sh_m[4], sh_l[4], sh_acc[4][D];
+  if (sub == 0) {
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) sh_acc[wave][cl * VEC + i] = acc[i];
+    if (cl == 0) {
+      sh_m[wave] = m_run;
+      sh_l[wave] = l_run;
+    }
+  }
+  __syncthreads();
+  if (wave == 0 && sub == 0) {
+    float mm = fmaxf(fmaxf(sh_m[0], sh_m[1]), fmaxf(sh_m[2], sh_m[3]));
+    float l = 0.f, o[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) o[i] = 0.f;
+#pragma unroll
+    for (int wv = 0; wv < 4; ++wv) {
+      const float sc = exp2f(sh_m[wv] - mm);  // a wave that saw no key has max -inf -> 0
+      l += sh_l[wv] * sc;
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) o[i] += sh_acc[wv][cl * VEC + i] * sc;
+    }
+    const float inv = 1.f / l;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) o[i] *= inv;
+    Frag<T>::store((T *)a.out + b * a.o_b + (int64_t)qi * a.o_t + hq * a.o_h + cl * VEC, o);
+    if (a.lse && cl == 0)
+      a.lse[b * a.lse_b + (int64_t)qi * a.lse_t + hq * a.lse_h] = (mm + log2f(l)) * kLn2;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_attn_rows(const Dev &dv, const AttnArgs &a, hipStream_t st) {
+  if (a.nq <= 0) return hipSuccess;
+  dim3 grid(a.nq, dv.Hq, dv.B);
+  if (dv.io == 0 && dv.d == 64)
+    hipLaunchKernelGGL((attn_rows_kernel<float, 64>), grid, dim3(256), 0, st, dv, a);
+  else if (dv.io == 0 && dv.d == 128)
+    hipLaunchKernelGGL((attn_rows_kernel<float, 128>), grid, dim3(256), 0, st, dv, a);
+  else if (dv.io == 1 && dv.d == 64)
+    hipLaunchKernelGGL((attn_rows_kernel<bf16_t, 64>), grid, dim3(256), 0, st, dv, a);
+  else if (dv.io == 1 && dv.d == 128)
+    hipLaunchKernelGGL((attn_rows_kernel<bf16_t, 128>), grid, dim3(256), 0, st, dv, a);
+  else
+    return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+}  // namespace kvm

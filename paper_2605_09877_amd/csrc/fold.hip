@@ -1,0 +1,367 @@
+// Fold of one overflow block into the compressed state (sections "KVM weight preparation",
+// "Append", "Merge" and the readout equations of the paper's Method section), as wavefront
+// kernels: one 64-lane wave owns one token or one state row and reduces over head_dim.
+//
+//   memkey : k-bar_j = LN_s(k_j with the rotary channels zeroed), materialised in the I/O dtype
+//   score  : s_j = max_i k-bar_j . s-hat^K_i and pi(j) = argmax_{i >= S}   (generic, fp64 dot)
+//   select : the n_append smallest s_j become new rows, in position order
+//   accum  : new rows are created, merged tokens are added to their row in position order,
+//            touched rows get their normalised readout (LN_s on keys, stored radius on values)
+//
+// Everything that decides an integer (LN_s of keys, the key sums) is computed in fp64 so that
+// the decision can be reproduced on a CPU; values and radii are fp32.
+#include "kvm_device.h"
+#include "kvm_internal.h"
+
+namespace kvm {
+
+namespace {
+
+template <typename T, int D>
+__device__ __forceinline__ void write_readout(const Dev &dv, int u, int h, int row,
+                                              const double (&sk)[D / 64], const float (&sv)[D / 64],
+                                              float rho, int lane) {
+  constexpr int CPL = D / 64;
+  double s = 0.0;
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) s += sk[c];
+  const double mean = wave_sum(s) / (double)D;
+  double q = 0.0;
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) {
+    const double dl = sk[c] - mean;
+    q += dl * dl;
+  }
+  const double den = sqrt(wave_sum(q) / (double)D + (double)dv.ln_eps);
+  float nn = 0.f;
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) nn += sv[c] * sv[c];
+  const float nrm = sqrtf(wave_sum(nn));
+  const float vs = rho / fmaxf(nrm, dv.norm_eps);
+  T *kh = (T *)dv.khat + ((int64_t)u * dv.Mcap + row) * D;
+  T *vh = (T *)dv.vhat + ((int64_t)u * dv.Mcap + row) * D;
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) {
+    const int ch = lane * CPL + c;
+    const double ga = dv.gamma ? (double)dv.gamma[h * D + ch] : 1.0;
+    const double be = dv.beta ? (double)dv.beta[h * D + ch] : 0.0;
+    const double y = (sk[c] - mean) / den * ga + be;
+    Io<T>::store(kh + ch, Io<T>::round_from(y));
+    Io<T>::store(vh + ch, sv[c] * vs);
+  }
+}
+
+// ------------------------------------------------------------------ memory keys
+template <typename T, int D>
+__global__ __launch_bounds__(256) void memkey_kernel(Dev dv, Src src) {
+  constexpr int CPL = D / 64;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int u = blockIdx.y, b = u / dv.Hkv, h = u % dv.Hkv;
+  const int j = blockIdx.x * 4 + wave;
+  if (j >= dv.C) return;
+  const T *krow = (const T *)src.k + b * src.k_b + h * src.k_h + (int64_t)j * src.k_t;
+  double x[CPL];
+  double s = 0.0;
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) {
+    const int ch = lane * CPL + c;
+    x[c] = ch < dv.r ? 0.0 : (double)Io<T>::load(krow + ch);
+    s += x[c];
+  }
+  const double mean = wave_sum(s) / (double)D;
+  double q = 0.0;
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) {
+    const double dl = x[c] - mean;
+    q += dl * dl;
+  }
+  const double den = sqrt(wave_sum(q) / (double)D + (double)dv.ln_eps);
+  T *out = (T *)dv.kbar + ((int64_t)u * dv.C + j) * D;
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) {
+    const int ch = lane * CPL + c;
+    const double ga = dv.gamma ? (double)dv.gamma[h * D + ch] : 1.0;
+    const double be = dv.beta ? (double)dv.beta[h * D + ch] : 0.0;
+    Io<T>::store(out + ch, Io<T>::round_from((x[c] - mean) / den * ga + be));
+  }
+}
+
+// ------------------------------------------------------------------ similarity + winners (generic)
+// One wave per token; lanes stride over state rows [row0, row1); each dot product is an fp64 sum
+// of the I/O-dtype operands.  first_pass: rows are the pre-append state, writes s_j (all rows)
+// and the best eligible row.  Otherwise rows are the ones appended in this fold and only tokens
+// that were not appended themselves may move to them (strictly larger score only).
+template <typename T, int D>
+__global__ __launch_bounds__(256) void score_kernel(Dev dv, int row0, int row1, int first_pass) {
+  __shared__ double kb[4][D];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int u = blockIdx.y;
+  const int j = blockIdx.x * 4 + wave;
+  const int64_t tj = (int64_t)u * dv.C + j;
+  const bool active = j < dv.C && (first_pass || dv.app[tj] < 0);
+  if (active) {
+    const T *kbar = (const T *)dv.kbar + tj * D;
+    for (int c = lane; c < D; c += 64) kb[wave][c] = (double)Io<T>::load(kbar + c);
+  }
+  __syncthreads();
+  if (!active) return;
+  double best_all = -INFINITY, best = -INFINITY;
+  int best_i = 0x7fffffff;
+  const T *kh = (const T *)dv.khat + (int64_t)u * dv.Mcap * D;
+  for (int i = row0 + lane; i < row1; i += 64) {
+    const T *row = kh + (int64_t)i * D;
+    double acc = 0.0;
+    for (int c = 0; c < D; ++c) acc += kb[wave][c] * (double)Io<T>::load(row + c);
+    best_all = acc > best_all ? acc : best_all;
+    if (i >= dv.S && acc > best) {
+      best = acc;
+      best_i = i;
+    }
+  }
+  best_all = wave_max(best_all);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const double ob = __shfl_xor(best, o, kWave);
+    const int oi = __shfl_xor(best_i, o, kWave);
+    if (ob > best || (ob == best && oi < best_i)) {
+      best = ob;
+      best_i = oi;
+    }
+  }
+  if (lane == 0) {
+    if (first_pass) {
+      dv.score[tj] = make_float2((float)best_all, (float)best);
+      dv.pi[tj] = best_i;
+      dv.app[tj] = -1;
+    } else if (best_i != 0x7fffffff && (float)best > dv.score[tj].y) {
+      // compare in the stored (fp32) precision so both passes rank alike
+      dv.score[tj].y = (float)best;
+      dv.pi[tj] = best_i;
+    }
+  }
+}
+
+// ------------------------------------------------------------------ append selection
+// One workgroup per unit.  take_all: every token becomes a row, in order (state creation, or a
+// budget with room for the whole block).
+__global__ __launch_bounds__(256) void select_kernel(Dev dv, int m, int n_app, int take_all) {
+  extern __shared__ float sh[];  // C scores, then C flags
+  float *sc = sh;
+  int *flag = (int *)(sh + dv.C);
+  const int u = blockIdx.x, C = dv.C;
+  const int64_t base = (int64_t)u * C;
+  if (take_all) {
+    const float qnan = __uint_as_float(0x7fc00000u);
+    for (int j = threadIdx.x; j < C; j += blockDim.x) {
+      dv.app[base + j] = j;
+      dv.pi[base + j] = m + j;
+      dv.creator[base + j] = j;
+      dv.score[base + j] = make_float2(qnan, qnan);
+    }
+    return;
+  }
+  for (int j = threadIdx.x; j < C; j += blockDim.x) sc[j] = dv.score[base + j].x;
+  __syncthreads();
+  for (int j = threadIdx.x; j < C; j += blockDim.x) {
+    const float sj = sc[j];
+    int rank = 0;
+    for (int t = 0; t < C; ++t) {
+      const float st = sc[t];
+      rank += (st < sj || (st == sj && t < j)) ? 1 : 0;
+    }
+    flag[j] = rank < n_app ? 1 : 0;
+  }
+  __syncthreads();
+  for (int j = threadIdx.x; j < C; j += blockDim.x) {
+    if (flag[j]) {
+      int a = 0;
+      for (int t = 0; t < j; ++t) a += flag[t];
+      dv.app[base + j] = a;
+      dv.pi[base + j] = m + a;
+      dv.creator[base + a] = j;
+      dv.score[base + j].y = __uint_as_float(0x7fc00000u);
+    } else {
+      dv.app[base + j] = -1;
+    }
+  }
+}
+
+// ------------------------------------------------------------------ create + merge + readout refresh
+// One wave per state row of the updated state.  Tokens are added in ascending position.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void accum_kernel(Dev dv, Src src, int m_before, int m_after) {
+  constexpr int CPL = D / 64;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int u = blockIdx.y, b = u / dv.Hkv, h = u % dv.Hkv;
+  const int row = blockIdx.x * 4 + wave;
+  if (row >= m_after) return;
+  const int C = dv.C;
+  const int64_t base = (int64_t)u * C;
+  const int64_t ro = (int64_t)u * dv.Mcap + row;
+  const T *vsrc = (const T *)src.v + b * src.v_b + h * src.v_h;
+  const float *gsrc = src.g ? src.g + b * src.g_b + h * src.g_h : nullptr;
+  const T *kbar = (const T *)dv.kbar + base * D;
+
+  double sk[CPL];
+  float sv[CPL];
+  float rho = 0.f, w = 0.f;
+  int n = 0;
+  bool loaded = false;
+  const bool is_new = row >= m_before;
+  if (is_new) {
+    const int j0 = dv.creator[base + (row - m_before)];
+    float nn = 0.f;
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) {
+      const int ch = lane * CPL + c;
+      sk[c] = (double)Io<T>::load(kbar + (int64_t)j0 * D + ch);
+      sv[c] = Io<T>::load(vsrc + (int64_t)j0 * src.v_t + ch);
+      nn += sv[c] * sv[c];
+    }
+    rho = sqrtf(wave_sum(nn));
+    w = 1.f;
+    n = 1;
+    loaded = true;
+  }
+  if (row >= dv.S) {
+    for (int j0 = 0; j0 < C; j0 += 64) {
+      const int j = j0 + lane;
+      const bool mine = j < C && dv.pi[base + j] == row && dv.app[base + j] < 0;
+      uint64_t mask = __ballot(mine);
+      if (mask && !loaded) {
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) {
+          sk[c] = dv.sK[ro * D + lane * CPL + c];
+          sv[c] = dv.sV[ro * D + lane * CPL + c];
+        }
+        rho = dv.rho[ro];
+        w = dv.w[ro];
+        n = dv.n[ro];
+        loaded = true;
+      }
+      while (mask) {
+        const int t = j0 + __builtin_ctzll(mask);
+        mask &= mask - 1;
+        const float g = gsrc ? gsrc[(int64_t)t * src.g_t] : 1.f;
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) {
+          const int ch = lane * CPL + c;
+          sk[c] = fma((double)g, (double)Io<T>::load(kbar + (int64_t)t * D + ch), sk[c]);
+          sv[c] = fmaf(g, Io<T>::load(vsrc + (int64_t)t * src.v_t + ch), sv[c]);
+        }
+        w += g;
+        n += 1;
+      }
+    }
+  }
+  if (!loaded) return;  // untouched row: sums and readout stay as they are
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) {
+    dv.sK[ro * D + lane * CPL + c] = sk[c];
+    dv.sV[ro * D + lane * CPL + c] = sv[c];
+  }
+  if (lane == 0) {
+    dv.rho[ro] = rho;
+    dv.w[ro] = w;
+    dv.n[ro] = n;
+  }
+  write_readout<T, D>(dv, u, h, row, sk, sv, rho, lane);
+}
+
+// Recompute the normalised readout of rows [0, m) from the stored sums (after an import).
+template <typename T, int D>
+__global__ __launch_bounds__(256) void refresh_kernel(Dev dv, int m) {
+  constexpr int CPL = D / 64;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int u = blockIdx.y, h = u % dv.Hkv;
+  const int row = blockIdx.x * 4 + wave;
+  if (row >= m) return;
+  const int64_t ro = (int64_t)u * dv.Mcap + row;
+  double sk[CPL];
+  float sv[CPL];
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) {
+    sk[c] = dv.sK[ro * D + lane * CPL + c];
+    sv[c] = dv.sV[ro * D + lane * CPL + c];
+  }
+  write_readout<T, D>(dv, u, h, row, sk, sv, dv.rho[ro], lane);
+}
+
+// Copy positions [p0, p1) of a token source (its token 0 is position src_t0) into the ring.
+template <typename T>
+__global__ __launch_bounds__(64) void ring_copy_kernel(Dev dv, Src src, int64_t src_t0, int64_t p0) {
+  const int u = blockIdx.y, b = u / dv.Hkv, h = u % dv.Hkv;
+  const int64_t p = p0 + blockIdx.x;
+  const int64_t t = p - src_t0;
+  const int slot = (int)(p % dv.L);
+  const T *ks = (const T *)src.k + b * src.k_b + h * src.k_h + t * src.k_t;
+  const T *vs = (const T *)src.v + b * src.v_b + h * src.v_h + t * src.v_t;
+  T *kd = (T *)dv.winK + ((int64_t)u * dv.L + slot) * dv.d;
+  T *vd = (T *)dv.winV + ((int64_t)u * dv.L + slot) * dv.d;
+  for (int c = threadIdx.x; c < dv.d; c += 64) {
+    kd[c] = ks[c];
+    vd[c] = vs[c];
+  }
+  if (threadIdx.x == 0)
+    dv.winG[(int64_t)u * dv.L + slot] = src.g ? src.g[b * src.g_b + h * src.g_h + t * src.g_t] : 1.f;
+}
+
+#define KVM_DISPATCH(dv, KERNEL, grid, block, shmem, st, ...)                                   \
+  do {                                                                                          \
+    if ((dv).io == 0 && (dv).d == 64)                                                           \
+      hipLaunchKernelGGL((KERNEL<float, 64>), grid, block, shmem, st, __VA_ARGS__);             \
+    else if ((dv).io == 0 && (dv).d == 128)                                                     \
+      hipLaunchKernelGGL((KERNEL<float, 128>), grid, block, shmem, st, __VA_ARGS__);            \
+    else if ((dv).io == 1 && (dv).d == 64)                                                      \
+      hipLaunchKernelGGL((KERNEL<bf16_t, 64>), grid, block, shmem, st, __VA_ARGS__);            \
+    else if ((dv).io == 1 && (dv).d == 128)                                                     \
+      hipLaunchKernelGGL((KERNEL<bf16_t, 128>), grid, block, shmem, st, __VA_ARGS__);           \
+    else                                                                                        \
+      return hipErrorInvalidValue;                                                              \
+  } while (0)
+
+}  // namespace
+
+hipError_t launch_memkey(const Dev &dv, const Src &src, hipStream_t st) {
+  dim3 grid((dv.C + 3) / 4, dv.U);
+  KVM_DISPATCH(dv, memkey_kernel, grid, dim3(256), 0, st, dv, src);
+  return hipGetLastError();
+}
+
+hipError_t launch_score(const Dev &dv, int row0, int row1, bool first_pass, hipStream_t st) {
+  dim3 grid((dv.C + 3) / 4, dv.U);
+  KVM_DISPATCH(dv, score_kernel, grid, dim3(256), 0, st, dv, row0, row1, first_pass ? 1 : 0);
+  return hipGetLastError();
+}
+
+hipError_t launch_select(const Dev &dv, int m, int n_app, bool take_all, hipStream_t st) {
+  hipLaunchKernelGGL(select_kernel, dim3(dv.U), dim3(256), (size_t)dv.C * 8, st, dv, m, n_app,
+                     take_all ? 1 : 0);
+  return hipGetLastError();
+}
+
+hipError_t launch_accum(const Dev &dv, const Src &src, int m_before, int m_after, hipStream_t st) {
+  dim3 grid((m_after + 3) / 4, dv.U);
+  KVM_DISPATCH(dv, accum_kernel, grid, dim3(256), 0, st, dv, src, m_before, m_after);
+  return hipGetLastError();
+}
+
+hipError_t launch_refresh(const Dev &dv, int m, hipStream_t st) {
+  if (m <= 0) return hipSuccess;
+  dim3 grid((m + 3) / 4, dv.U);
+  KVM_DISPATCH(dv, refresh_kernel, grid, dim3(256), 0, st, dv, m);
+  return hipGetLastError();
+}
+
+hipError_t launch_ring_copy(const Dev &dv, const Src &src, int64_t src_t0, int64_t p0, int64_t p1,
+                            hipStream_t st) {
+  if (p1 <= p0) return hipSuccess;
+  dim3 grid((unsigned)(p1 - p0), dv.U);
+  if (dv.io == 0)
+    hipLaunchKernelGGL(ring_copy_kernel<float>, grid, dim3(64), 0, st, dv, src, src_t0, p0);
+  else
+    hipLaunchKernelGGL(ring_copy_kernel<bf16_t>, grid, dim3(64), 0, st, dv, src, src_t0, p0);
+  return hipGetLastError();
+}
+
+}  // namespace kvm

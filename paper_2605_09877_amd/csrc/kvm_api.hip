@@ -1,0 +1,563 @@
+// Host side of the KVM library: the C ABI of include/kvm.h, the state handle, the growth
+// schedule (integer replay of the paper's budget rule) and the per-chunk launch sequence.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/kvm.h"
+#include "kvm_internal.h"
+
+using kvm::AttnArgs;
+using kvm::Dev;
+using kvm::Src;
+
+struct kvm_state {
+  kvm_config cfg;
+  std::vector<int64_t> table;
+  Dev dv;
+  void *buf = nullptr;
+  size_t bytes = 0;
+  int64_t m = 0, tokens = 0, folds = 0;
+  int32_t *trace_assign = nullptr;
+  float *trace_score = nullptr;
+  int64_t trace_max = 0;
+  bool mfma = false;  // bf16, d = 128, C % 64 == 0: matrix-core kernels
+};
+
+namespace {
+
+thread_local std::string g_hip_error;
+
+int hip_fail(hipError_t e, const char *what) {
+  g_hip_error = std::string(what) + ": " + hipGetErrorString(e);
+  return KVM_ERR_HIP;
+}
+#define HIP_TRY(expr)                                  \
+  do {                                                 \
+    hipError_t e__ = (expr);                           \
+    if (e__ != hipSuccess) return hip_fail(e__, #expr); \
+  } while (0)
+
+inline size_t esize(int io) { return io == KVM_BF16 ? 2 : 4; }
+inline size_t up256(size_t x) { return (x + 255) & ~size_t(255); }
+
+int64_t ceil_sqrt(int64_t e) {
+  if (e <= 0) return 0;
+  int64_t n = (int64_t)std::ceil(std::sqrt((double)e));
+  while (n * n < e) ++n;
+  while (n > 0 && (n - 1) * (n - 1) >= e) --n;
+  return n;
+}
+
+int64_t budget_at(const kvm_config &c, const std::vector<int64_t> &table, int64_t e) {
+  switch (c.budget_kind) {
+    case KVM_BUDGET_FIXED: return c.budget_fixed;
+    case KVM_BUDGET_SQRT: return (int64_t)std::floor(c.budget_scale * (double)ceil_sqrt(e));
+    case KVM_BUDGET_TABLE: {
+      if (table.empty()) return 0;
+      int64_t idx = e / c.chunk_len - 1;
+      if (idx < 0) idx = 0;
+      if (idx >= (int64_t)table.size()) idx = (int64_t)table.size() - 1;
+      return table[idx];
+    }
+    default: return 0;
+  }
+}
+
+// Rows after folding one block at chunk end e: creation copies a whole chunk, afterwards
+// M* = max(m, min(B(e), m + C)).
+int64_t rows_after(const kvm_config &c, const std::vector<int64_t> &table, int64_t m, int64_t e) {
+  if (c.budget_kind == KVM_BUDGET_NONE) return 0;
+  if (m == 0) return c.chunk_len;
+  const int64_t B = budget_at(c, table, e);
+  const int64_t capped = B < m + c.chunk_len ? B : m + c.chunk_len;
+  return m > capped ? m : capped;
+}
+
+bool config_ok(const kvm_config *c) {
+  if (!c) return false;
+  if (c->batch <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0) return false;
+  if (c->n_q_heads % c->n_kv_heads) return false;
+  if (c->head_dim != 64 && c->head_dim != 128) return false;
+  if (c->rope_dims < 0 || c->rope_dims > c->head_dim) return false;
+  if (c->chunk_len <= 0 || c->n_bswa_chunks < 1) return false;
+  if (c->n_sink < 0 || c->n_sink >= c->chunk_len) return false;
+  if (c->io_dtype != KVM_F32 && c->io_dtype != KVM_BF16) return false;
+  if (c->budget_kind < KVM_BUDGET_NONE || c->budget_kind > KVM_BUDGET_TABLE) return false;
+  if (c->budget_kind == KVM_BUDGET_TABLE && (!c->budget_table || c->budget_table_len <= 0)) return false;
+  if (c->budget_kind == KVM_BUDGET_SQRT && !(c->budget_scale >= 0.0)) return false;
+  if (c->budget_kind == KVM_BUDGET_FIXED && c->budget_fixed < 0) return false;
+  return true;
+}
+
+std::vector<int64_t> table_of(const kvm_config *c) {
+  if (c->budget_kind == KVM_BUDGET_TABLE)
+    return std::vector<int64_t>(c->budget_table, c->budget_table + c->budget_table_len);
+  return {};
+}
+
+// Rows reached after running from (m, tokens) to `until` tokens.
+int64_t replay_rows(const kvm_config &c, const std::vector<int64_t> &table, int64_t m, int64_t tokens,
+                    int64_t until) {
+  const int64_t C = c.chunk_len, L = C * c.n_bswa_chunks;
+  for (int64_t e = (tokens / C + 1) * C; e <= until; e += C)
+    if (e >= L) m = rows_after(c, table, m, e);
+  return m;
+}
+
+int64_t capacity_rows(const kvm_config &c, const std::vector<int64_t> &table, int64_t max_tokens) {
+  int64_t rows = replay_rows(c, table, 0, 0, max_tokens);
+  if (rows < c.chunk_len) rows = c.chunk_len;
+  return (rows + 63) / 64 * 64;
+}
+
+struct Layout {
+  size_t sK, sV, rho, w, n, khat, vhat, winK, winV, winG, kbar, score, pi, app, creator, total;
+};
+
+Layout layout_of(const kvm_config &c, int64_t Mcap) {
+  const size_t U = (size_t)c.batch * c.n_kv_heads, d = c.head_dim, C = c.chunk_len;
+  const size_t L = C * c.n_bswa_chunks, es = esize(c.io_dtype), M = (size_t)Mcap;
+  Layout l;
+  size_t o = 0;
+  auto take = [&](size_t bytes) {
+    size_t at = o;
+    o += up256(bytes);
+    return at;
+  };
+  l.sK = take(U * M * d * 8);
+  l.sV = take(U * M * d * 4);
+  l.rho = take(U * M * 4);
+  l.w = take(U * M * 4);
+  l.n = take(U * M * 4);
+  l.khat = take(U * M * d * es);
+  l.vhat = take(U * M * d * es);
+  l.winK = take(U * L * d * es);
+  l.winV = take(U * L * d * es);
+  l.winG = take(U * L * 4);
+  l.kbar = take(U * C * d * es);
+  l.score = take(U * C * 8);
+  l.pi = take(U * C * 4);
+  l.app = take(U * C * 4);
+  l.creator = take(U * C * 4);
+  l.total = o;
+  return l;
+}
+
+void bind(Dev &dv, const kvm_config &c, void *buf, int64_t Mcap) {
+  const Layout l = layout_of(c, Mcap);
+  char *p = (char *)buf;
+  dv.sK = (double *)(p + l.sK);
+  dv.sV = (float *)(p + l.sV);
+  dv.rho = (float *)(p + l.rho);
+  dv.w = (float *)(p + l.w);
+  dv.n = (int32_t *)(p + l.n);
+  dv.khat = p + l.khat;
+  dv.vhat = p + l.vhat;
+  dv.winK = p + l.winK;
+  dv.winV = p + l.winV;
+  dv.winG = (float *)(p + l.winG);
+  dv.kbar = p + l.kbar;
+  dv.score = (float2 *)(p + l.score);
+  dv.pi = (int32_t *)(p + l.pi);
+  dv.app = (int32_t *)(p + l.app);
+  dv.creator = (int32_t *)(p + l.creator);
+  dv.gamma = c.ln_gamma;
+  dv.beta = c.ln_beta;
+  dv.tau_state = c.tau_state;
+  dv.tau_bswa = c.tau_bswa;
+  dv.B = c.batch;
+  dv.Hq = c.n_q_heads;
+  dv.Hkv = c.n_kv_heads;
+  dv.U = c.batch * c.n_kv_heads;
+  dv.d = c.head_dim;
+  dv.r = c.rope_dims;
+  dv.C = c.chunk_len;
+  dv.L = c.chunk_len * c.n_bswa_chunks;
+  dv.S = c.n_sink;
+  dv.Mcap = (int32_t)Mcap;
+  dv.ln_eps = c.ln_eps > 0.f ? c.ln_eps : 1e-5f;
+  dv.norm_eps = c.norm_eps > 0.f ? c.norm_eps : 1e-12f;
+  dv.io = c.io_dtype;
+}
+
+Src ring_src(const kvm_state *st) {
+  const Dev &dv = st->dv;
+  Src s;
+  s.k = dv.winK;
+  s.v = dv.winV;
+  s.g = dv.winG;
+  s.k_b = s.v_b = (int64_t)dv.Hkv * dv.L * dv.d;
+  s.k_h = s.v_h = (int64_t)dv.L * dv.d;
+  s.k_t = s.v_t = dv.d;
+  s.g_b = (int64_t)dv.Hkv * dv.L;
+  s.g_h = dv.L;
+  s.g_t = 1;
+  return s;
+}
+
+// `src` with its token origin moved forward by `tok` tokens.
+Src advance(const Src &s, int64_t tok, size_t es) {
+  Src r = s;
+  r.k = (const char *)s.k + tok * s.k_t * (int64_t)es;
+  r.v = (const char *)s.v + tok * s.v_t * (int64_t)es;
+  if (s.g) r.g = s.g + tok * s.g_t;
+  return r;
+}
+
+// Fold the C-token block whose first token is src's token 0.  e = end of the chunk just attended.
+int fold_block(kvm_state *st, const Src &src, int64_t e, int32_t *assign_out, float *score_out,
+               hipStream_t stream) {
+  const kvm_config &c = st->cfg;
+  const Dev &dv = st->dv;
+  if (c.budget_kind == KVM_BUDGET_NONE) return KVM_OK;
+  const int64_t m = st->m;
+  const int64_t m_after = rows_after(c, st->table, m, e);
+  const int n_app = (int)(m_after - m);
+  if (m_after > dv.Mcap) return KVM_ERR_CAPACITY;
+  HIP_TRY(kvm::launch_memkey(dv, src, stream));
+  if (n_app == dv.C) {
+    HIP_TRY(kvm::launch_select(dv, (int)m, n_app, true, stream));
+  } else {
+    if (st->mfma)
+      HIP_TRY(kvm::launch_score_mfma(dv, 0, (int)m, true, stream));
+    else
+      HIP_TRY(kvm::launch_score(dv, 0, (int)m, true, stream));
+    if (n_app > 0) {
+      HIP_TRY(kvm::launch_select(dv, (int)m, n_app, false, stream));
+      if (st->mfma)
+        HIP_TRY(kvm::launch_score_mfma(dv, (int)m, (int)m_after, false, stream));
+      else
+        HIP_TRY(kvm::launch_score(dv, (int)m, (int)m_after, false, stream));
+    }
+  }
+  HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, stream));
+  const size_t ntok = (size_t)dv.U * dv.C;
+  if (assign_out)
+    HIP_TRY(hipMemcpyAsync(assign_out, dv.pi, ntok * 4, hipMemcpyDeviceToDevice, stream));
+  if (score_out)
+    HIP_TRY(hipMemcpyAsync(score_out, dv.score, ntok * 8, hipMemcpyDeviceToDevice, stream));
+  if (st->trace_assign && st->folds < st->trace_max)
+    HIP_TRY(hipMemcpyAsync(st->trace_assign + st->folds * ntok, dv.pi, ntok * 4,
+                           hipMemcpyDeviceToDevice, stream));
+  if (st->trace_score && st->folds < st->trace_max)
+    HIP_TRY(hipMemcpyAsync(st->trace_score + st->folds * ntok * 2, dv.score, ntok * 8,
+                           hipMemcpyDeviceToDevice, stream));
+  st->m = m_after;
+  st->folds += 1;
+  return KVM_OK;
+}
+
+bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+
+}  // namespace
+
+extern "C" {
+
+const char *kvm_strerror(int status) {
+  switch (status) {
+    case KVM_OK: return "ok";
+    case KVM_ERR_ARG: return "bad argument";
+    case KVM_ERR_CAPACITY: return "state buffer too small for the rows the budget asks for";
+    case KVM_ERR_STATE: return "call not valid at the state's current position";
+    case KVM_ERR_HIP: return "HIP runtime error";
+    case KVM_ERR_UNSUPPORTED: return "unsupported shape or dtype";
+    default: return "unknown status";
+  }
+}
+
+const char *kvm_last_hip_error(void) { return g_hip_error.c_str(); }
+
+int64_t kvm_state_rows_for(const kvm_config *cfg, int64_t max_tokens) {
+  if (!config_ok(cfg) || max_tokens < 0) return -1;
+  return replay_rows(*cfg, table_of(cfg), 0, 0, max_tokens);
+}
+
+size_t kvm_state_bytes(const kvm_config *cfg, int64_t max_tokens) {
+  if (!config_ok(cfg) || max_tokens < 0) return 0;
+  return layout_of(*cfg, capacity_rows(*cfg, table_of(cfg), max_tokens)).total;
+}
+
+int kvm_state_init(kvm_state **out, const kvm_config *cfg, void *dev_buf, size_t bytes,
+                   int64_t max_tokens) {
+  if (!out || !config_ok(cfg) || !dev_buf || max_tokens < 0) return KVM_ERR_ARG;
+  if (((uintptr_t)dev_buf & 255) != 0) return KVM_ERR_ARG;
+  std::vector<int64_t> table = table_of(cfg);
+  const int64_t Mcap = capacity_rows(*cfg, table, max_tokens);
+  if (layout_of(*cfg, Mcap).total > bytes) return KVM_ERR_CAPACITY;
+  kvm_state *st = new (std::nothrow) kvm_state();
+  if (!st) return KVM_ERR_ARG;
+  st->cfg = *cfg;
+  st->table = std::move(table);
+  st->cfg.budget_table = st->table.empty() ? nullptr : st->table.data();
+  st->buf = dev_buf;
+  st->bytes = bytes;
+  bind(st->dv, st->cfg, dev_buf, Mcap);
+  st->mfma = cfg->io_dtype == KVM_BF16 && cfg->head_dim == 128 && cfg->chunk_len % 64 == 0;
+  *out = st;
+  return KVM_OK;
+}
+
+int kvm_state_destroy(kvm_state *st) {
+  delete st;
+  return KVM_OK;
+}
+
+int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void *v,
+                        const float *gate, void *out, float *lse, int64_t T,
+                        const kvm_strides *sp, void *stream_) {
+  if (!st || !q || !k || !v || !out || T <= 0) return KVM_ERR_ARG;
+  hipStream_t stream = (hipStream_t)stream_;
+  const kvm_config &c = st->cfg;
+  const Dev &dv = st->dv;
+  const int64_t C = dv.C, L = dv.L, d = dv.d;
+  const size_t es = esize(c.io_dtype);
+  if (st->tokens % C != 0) return KVM_ERR_STATE;
+  kvm_strides s;
+  if (sp) {
+    s = *sp;
+  } else {
+    s.q_b = T * dv.Hq * d; s.q_t = dv.Hq * d; s.q_h = d;
+    s.k_b = T * dv.Hkv * d; s.k_t = dv.Hkv * d; s.k_h = d;
+    s.v_b = s.k_b; s.v_t = s.k_t; s.v_h = s.k_h;
+    s.o_b = s.q_b; s.o_t = s.q_t; s.o_h = s.q_h;
+    s.g_b = T * dv.Hkv; s.g_t = dv.Hkv; s.g_h = 1;
+    s.lse_b = T * dv.Hq; s.lse_t = dv.Hq; s.lse_h = 1;
+  }
+  const int64_t vec = 16 / (int64_t)es;
+  const int64_t strides16[] = {s.q_b, s.q_t, s.q_h, s.k_b, s.k_t, s.k_h, s.v_b, s.v_t, s.v_h, s.o_b, s.o_t, s.o_h};
+  for (int64_t x : strides16)
+    if (x % vec) return KVM_ERR_ARG;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return KVM_ERR_ARG;
+
+  const int64_t t0 = st->tokens, t_end = t0 + T;
+  if (replay_rows(c, st->table, st->m, t0, t_end) > dv.Mcap) return KVM_ERR_CAPACITY;
+
+  Src in;
+  in.k = k; in.v = v; in.g = gate;
+  in.k_b = s.k_b; in.k_h = s.k_h; in.k_t = s.k_t;
+  in.v_b = s.v_b; in.v_h = s.v_h; in.v_t = s.v_t;
+  in.g_b = s.g_b; in.g_h = s.g_h; in.g_t = s.g_t;
+  const Src ring = ring_src(st);
+
+  for (int64_t cs = t0; cs < t_end; cs += C) {
+    const int64_t ce = cs + C < t_end ? cs + C : t_end;
+    AttnArgs a;
+    a.q = (const char *)q + (cs - t0) * s.q_t * (int64_t)es;
+    a.out = (char *)out + (cs - t0) * s.o_t * (int64_t)es;
+    a.lse = lse ? lse + (cs - t0) * s.lse_t : nullptr;
+    a.q_b = s.q_b; a.q_t = s.q_t; a.q_h = s.q_h;
+    a.o_b = s.o_b; a.o_t = s.o_t; a.o_h = s.o_h;
+    a.lse_b = s.lse_b; a.lse_t = s.lse_t; a.lse_h = s.lse_h;
+    a.in = in;
+    a.t0 = t0;
+    a.s = cs;
+    a.nq = (int32_t)(ce - cs);
+    a.b = cs + C - L > 0 ? cs + C - L : 0;
+    a.m = (int32_t)st->m;
+    if (st->mfma)
+      HIP_TRY(kvm::launch_attn_mfma(dv, a, stream));
+    else
+      HIP_TRY(kvm::launch_attn_rows(dv, a, stream));
+    if (ce - cs == C && ce >= L) {
+      const int64_t lo = ce - L;  // first token of the overflow block
+      int rc;
+      if (lo >= t0)
+        rc = fold_block(st, advance(in, lo - t0, es), ce, nullptr, nullptr, stream);
+      else
+        rc = fold_block(st, advance(ring, lo % L, es), ce, nullptr, nullptr, stream);
+      if (rc != KVM_OK) return rc;
+    }
+  }
+  // keep the last L tokens for the calls that follow
+  const int64_t p0 = t_end - L > t0 ? t_end - L : t0;
+  HIP_TRY(kvm::launch_ring_copy(dv, in, t0, p0, t_end, stream));
+  st->tokens = t_end;
+  return KVM_OK;
+}
+
+int kvm_decode_step(kvm_state *st, const void *q, const void *k, const void *v,
+                    const float *gate, void *out, void *stream_) {
+  if (!st || !q || !k || !v || !out) return KVM_ERR_ARG;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return KVM_ERR_ARG;
+  hipStream_t stream = (hipStream_t)stream_;
+  const kvm_config &c = st->cfg;
+  const Dev &dv = st->dv;
+  const int64_t C = dv.C, L = dv.L, d = dv.d;
+  const size_t es = esize(c.io_dtype);
+  const int64_t u = st->tokens;
+  const bool completes = (u + 1) % C == 0 && u + 1 >= L;
+  if (completes && rows_after(c, st->table, st->m, u + 1) > dv.Mcap) return KVM_ERR_CAPACITY;
+
+  Src tok;
+  tok.k = k; tok.v = v; tok.g = gate;
+  tok.k_b = tok.v_b = dv.Hkv * d; tok.k_h = tok.v_h = d; tok.k_t = tok.v_t = 0;
+  tok.g_b = dv.Hkv; tok.g_h = 1; tok.g_t = 0;
+  HIP_TRY(kvm::launch_ring_copy(dv, tok, u, u, u + 1, stream));
+
+  AttnArgs a;
+  a.q = q; a.out = out; a.lse = nullptr;
+  a.q_b = a.o_b = dv.Hq * d; a.q_t = a.o_t = 0; a.q_h = a.o_h = d;
+  a.lse_b = a.lse_t = a.lse_h = 0;
+  a.in = tok;
+  a.t0 = INT64_MAX / 2;  // every window token comes from the ring
+  a.s = u;
+  a.nq = 1;
+  const int64_t cs = u / C * C;
+  a.b = cs + C - L > 0 ? cs + C - L : 0;
+  a.m = (int32_t)st->m;
+  HIP_TRY(kvm::launch_attn_rows(dv, a, stream));
+  st->tokens = u + 1;
+  if (completes) {
+    const int64_t lo = u + 1 - L;
+    int rc = fold_block(st, advance(ring_src(st), lo % L, es), u + 1, nullptr, nullptr, stream);
+    if (rc != KVM_OK) return rc;
+  }
+  return KVM_OK;
+}
+
+int kvm_state_fold(kvm_state *st, const void *k_blk, const void *v_blk, const float *gate_blk,
+                   int32_t n_tokens, int64_t e, int32_t *assign_out, float *score_out,
+                   void *stream_) {
+  if (!st || !k_blk || !v_blk) return KVM_ERR_ARG;
+  if (n_tokens != st->dv.C) return KVM_ERR_ARG;
+  if (!aligned16(k_blk) || !aligned16(v_blk)) return KVM_ERR_ARG;
+  const Dev &dv = st->dv;
+  Src src;
+  src.k = k_blk; src.v = v_blk; src.g = gate_blk;
+  src.k_b = src.v_b = (int64_t)n_tokens * dv.Hkv * dv.d;
+  src.k_t = src.v_t = (int64_t)dv.Hkv * dv.d;
+  src.k_h = src.v_h = dv.d;
+  src.g_b = (int64_t)n_tokens * dv.Hkv; src.g_t = dv.Hkv; src.g_h = 1;
+  if (st->cfg.budget_kind != KVM_BUDGET_NONE &&
+      rows_after(st->cfg, st->table, st->m, e) > dv.Mcap)
+    return KVM_ERR_CAPACITY;
+  return fold_block(st, src, e, assign_out, score_out, (hipStream_t)stream_);
+}
+
+int kvm_state_rows(const kvm_state *st, int64_t *m_out) {
+  if (!st || !m_out) return KVM_ERR_ARG;
+  *m_out = st->m;
+  return KVM_OK;
+}
+int kvm_state_tokens(const kvm_state *st, int64_t *tokens_seen) {
+  if (!st || !tokens_seen) return KVM_ERR_ARG;
+  *tokens_seen = st->tokens;
+  return KVM_OK;
+}
+int kvm_state_capacity(const kvm_state *st, int64_t *rows_out) {
+  if (!st || !rows_out) return KVM_ERR_ARG;
+  *rows_out = st->dv.Mcap;
+  return KVM_OK;
+}
+int kvm_state_folds(const kvm_state *st, int64_t *folds_out) {
+  if (!st || !folds_out) return KVM_ERR_ARG;
+  *folds_out = st->folds;
+  return KVM_OK;
+}
+
+int kvm_state_trace(kvm_state *st, int32_t *assign, float *score, int64_t max_folds) {
+  if (!st || max_folds < 0) return KVM_ERR_ARG;
+  st->trace_assign = assign;
+  st->trace_score = score;
+  st->trace_max = (assign || score) ? max_folds : 0;
+  return KVM_OK;
+}
+
+int kvm_state_grow(kvm_state *st, void *new_buf, size_t new_bytes, int64_t new_max_tokens,
+                   void *stream_) {
+  if (!st || !new_buf || ((uintptr_t)new_buf & 255) != 0) return KVM_ERR_ARG;
+  hipStream_t stream = (hipStream_t)stream_;
+  const kvm_config &c = st->cfg;
+  const int64_t Mnew = capacity_rows(c, st->table, new_max_tokens);
+  if (Mnew < st->m) return KVM_ERR_CAPACITY;
+  if (layout_of(c, Mnew).total > new_bytes) return KVM_ERR_CAPACITY;
+  Dev nd = st->dv;
+  bind(nd, c, new_buf, Mnew);
+  const Dev &od = st->dv;
+  const size_t U = od.U, d = od.d, es = esize(c.io_dtype), m = (size_t)st->m;
+  auto copy2d = [&](void *dst, const void *src, size_t row_bytes) -> hipError_t {
+    if (m == 0) return hipSuccess;
+    return hipMemcpy2DAsync(dst, (size_t)Mnew * row_bytes, src, (size_t)od.Mcap * row_bytes,
+                            m * row_bytes, U, hipMemcpyDeviceToDevice, stream);
+  };
+  HIP_TRY(copy2d(nd.sK, od.sK, d * 8));
+  HIP_TRY(copy2d(nd.sV, od.sV, d * 4));
+  HIP_TRY(copy2d(nd.rho, od.rho, 4));
+  HIP_TRY(copy2d(nd.w, od.w, 4));
+  HIP_TRY(copy2d(nd.n, od.n, 4));
+  HIP_TRY(copy2d(nd.khat, od.khat, d * es));
+  HIP_TRY(copy2d(nd.vhat, od.vhat, d * es));
+  const size_t win = U * od.L * d * es;
+  HIP_TRY(hipMemcpyAsync(nd.winK, od.winK, win, hipMemcpyDeviceToDevice, stream));
+  HIP_TRY(hipMemcpyAsync(nd.winV, od.winV, win, hipMemcpyDeviceToDevice, stream));
+  HIP_TRY(hipMemcpyAsync(nd.winG, od.winG, U * od.L * 4, hipMemcpyDeviceToDevice, stream));
+  st->dv = nd;
+  st->buf = new_buf;
+  st->bytes = new_bytes;
+  return KVM_OK;
+}
+
+int kvm_state_export(const kvm_state *st, double *sK, float *sV, float *rho, float *w,
+                     int32_t *n, void *khat, void *vhat, void *win_k, void *win_v,
+                     float *win_g, void *stream_) {
+  if (!st) return KVM_ERR_ARG;
+  hipStream_t stream = (hipStream_t)stream_;
+  const Dev &dv = st->dv;
+  const size_t U = dv.U, d = dv.d, es = esize(st->cfg.io_dtype), m = (size_t)st->m;
+  auto out2d = [&](void *dst, const void *src, size_t row_bytes) -> hipError_t {
+    if (!dst || m == 0) return hipSuccess;
+    return hipMemcpy2DAsync(dst, m * row_bytes, src, (size_t)dv.Mcap * row_bytes, m * row_bytes, U,
+                            hipMemcpyDeviceToDevice, stream);
+  };
+  HIP_TRY(out2d(sK, dv.sK, d * 8));
+  HIP_TRY(out2d(sV, dv.sV, d * 4));
+  HIP_TRY(out2d(rho, dv.rho, 4));
+  HIP_TRY(out2d(w, dv.w, 4));
+  HIP_TRY(out2d(n, dv.n, 4));
+  HIP_TRY(out2d(khat, dv.khat, d * es));
+  HIP_TRY(out2d(vhat, dv.vhat, d * es));
+  const size_t win = U * dv.L * d * es;
+  if (win_k) HIP_TRY(hipMemcpyAsync(win_k, dv.winK, win, hipMemcpyDeviceToDevice, stream));
+  if (win_v) HIP_TRY(hipMemcpyAsync(win_v, dv.winV, win, hipMemcpyDeviceToDevice, stream));
+  if (win_g) HIP_TRY(hipMemcpyAsync(win_g, dv.winG, U * dv.L * 4, hipMemcpyDeviceToDevice, stream));
+  return KVM_OK;
+}
+
+int kvm_state_import(kvm_state *st, const double *sK, const float *sV, const float *rho,
+                     const float *w, const int32_t *n, const void *win_k, const void *win_v,
+                     const float *win_g, int64_t m, int64_t tokens_seen, int64_t folds,
+                     void *stream_) {
+  if (!st || m < 0 || tokens_seen < 0 || folds < 0) return KVM_ERR_ARG;
+  if (m > 0 && (!sK || !sV || !rho)) return KVM_ERR_ARG;
+  hipStream_t stream = (hipStream_t)stream_;
+  const Dev &dv = st->dv;
+  if (m > dv.Mcap) return KVM_ERR_CAPACITY;
+  const size_t U = dv.U, d = dv.d, es = esize(st->cfg.io_dtype), mm = (size_t)m;
+  auto in2d = [&](void *dst, const void *src, size_t row_bytes) -> hipError_t {
+    if (!src || mm == 0) return hipSuccess;
+    return hipMemcpy2DAsync(dst, (size_t)dv.Mcap * row_bytes, src, mm * row_bytes, mm * row_bytes, U,
+                            hipMemcpyDeviceToDevice, stream);
+  };
+  HIP_TRY(in2d(dv.sK, sK, d * 8));
+  HIP_TRY(in2d(dv.sV, sV, d * 4));
+  HIP_TRY(in2d(dv.rho, rho, 4));
+  HIP_TRY(in2d(dv.w, w, 4));
+  HIP_TRY(in2d(dv.n, n, 4));
+  const size_t win = U * dv.L * d * es;
+  if (win_k) HIP_TRY(hipMemcpyAsync(dv.winK, win_k, win, hipMemcpyDeviceToDevice, stream));
+  if (win_v) HIP_TRY(hipMemcpyAsync(dv.winV, win_v, win, hipMemcpyDeviceToDevice, stream));
+  if (win_g) HIP_TRY(hipMemcpyAsync(dv.winG, win_g, U * dv.L * 4, hipMemcpyDeviceToDevice, stream));
+  HIP_TRY(kvm::launch_refresh(dv, (int)m, stream));
+  st->m = m;
+  st->tokens = tokens_seen;
+  st->folds = folds;
+  return KVM_OK;
+}
+
+}  // extern "C"

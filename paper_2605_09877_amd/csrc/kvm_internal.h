@@ -1,0 +1,76 @@
+// Internal declarations shared by the host side of the KVM library and its HIP kernels.
+// Nothing here is part of the public ABI (see include/kvm.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace kvm {
+
+// A strided source of per-token keys, values and merge gates for all units.
+// Element strides; the head_dim axis is contiguous.  Token index 0 is `k`'s first token.
+struct Src {
+  const void *k, *v;
+  const float *g;  // nullable: g = 1
+  int64_t k_b, k_h, k_t;
+  int64_t v_b, v_h, v_t;
+  int64_t g_b, g_h, g_t;
+};
+
+// Device views of one bound state.  U = B * H_kv units; rows are padded to Mcap.
+struct Dev {
+  // state proper
+  double *sK;    // [U, Mcap, d] running gated sums of memory keys (fp64: feeds the argmax)
+  float *sV;     // [U, Mcap, d] running gated sums of values
+  float *rho;    // [U, Mcap]    radius stored at row creation
+  float *w;      // [U, Mcap]    1 + sum of merged gates (diagnostic)
+  int32_t *n;    // [U, Mcap]    tokens in the row (diagnostic)
+  void *khat;    // [U, Mcap, d] I/O dtype: LN_s(sK)
+  void *vhat;    // [U, Mcap, d] I/O dtype: rho * sV / max(||sV||, eps)
+  // window ring: token p lives in slot p % L
+  void *winK, *winV;  // [U, L, d] I/O dtype
+  float *winG;        // [U, L]
+  // fold scratch, per overflow token
+  void *kbar;        // [U, C, d] I/O dtype memory keys
+  float2 *score;     // [U, C]    x = append score s_j, y = winning merge score
+  int32_t *pi;       // [U, C]    row the token goes to
+  int32_t *app;      // [U, C]    rank among appended tokens, or -1
+  int32_t *creator;  // [U, C]    token that creates new row number a
+  // parameters
+  const float *gamma, *beta;          // [H_kv, d] or null
+  const float *tau_state, *tau_bswa;  // [H_q] or null
+  int32_t B, Hq, Hkv, U, d, r, C, L, S, Mcap;
+  float ln_eps, norm_eps;
+  int32_t io;  // KVM_F32 / KVM_BF16
+};
+
+// One chunk of prefill attention (or one decode token when nq == 1 per sequence).
+struct AttnArgs {
+  const void *q;
+  void *out;
+  float *lse;  // nullable
+  int64_t q_b, q_t, q_h, o_b, o_t, o_h, lse_b, lse_t, lse_h;  // q/out/lse index 0 = position s
+  Src in;        // keys/values of this call: token index 0 = position t0
+  int64_t t0;    // positions below t0 come from the ring
+  int64_t s;     // position of the first query
+  int32_t nq;    // queries in this chunk (<= C)
+  int64_t b;     // first window position
+  int32_t m;     // state rows
+};
+
+// fold.hip
+hipError_t launch_memkey(const Dev &dv, const Src &src, hipStream_t st);
+hipError_t launch_score(const Dev &dv, int row0, int row1, bool first_pass, hipStream_t st);
+hipError_t launch_select(const Dev &dv, int m, int n_app, bool take_all, hipStream_t st);
+hipError_t launch_accum(const Dev &dv, const Src &src, int m_before, int m_after, hipStream_t st);
+hipError_t launch_refresh(const Dev &dv, int m, hipStream_t st);
+hipError_t launch_ring_copy(const Dev &dv, const Src &src, int64_t src_t0, int64_t p0, int64_t p1,
+                            hipStream_t st);
+// score_mfma.hip (bf16, d = 128)
+hipError_t launch_score_mfma(const Dev &dv, int row0, int row1, bool first_pass, hipStream_t st);
+// attn_rows.hip
+hipError_t launch_attn_rows(const Dev &dv, const AttnArgs &a, hipStream_t st);
+// attn_mfma.hip (bf16, d = 128)
+hipError_t launch_attn_mfma(const Dev &dv, const AttnArgs &a, hipStream_t st);
+
+}  // namespace kvm

@@ -27,3 +27,12 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture(scope="session", autouse=True)
+def _library_built():
+    """Tests load the in-tree libkvm.so; it is compiled here only when it does not exist yet."""
+    from paper_2605_09877_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build()
+    yield

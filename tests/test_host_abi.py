@@ -1,0 +1,120 @@
+"""CPU-side checks of the C ABI: the library loads, exports every symbol the header declares,
+and its host logic (growth schedule, sizing, argument and capacity errors) behaves -- without
+launching anything on a GPU.  Error paths return before any kernel or HIP call is made, so a
+placeholder device pointer is enough here."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from oracle import kvm_oracle as ko
+from paper_2605_09877_amd import binding as kb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE_DEV_PTR = 0x10000000  # 256-byte aligned, never dereferenced by the calls below
+
+
+def cfg(**kw):
+    base = dict(batch=2, n_q_heads=4, n_kv_heads=2, head_dim=128, rope_dims=32, chunk_len=256,
+                n_bswa_chunks=2, n_sink=1, io_dtype=kb.KVM_BF16, budget_kind=kb.KVM_BUDGET_FIXED,
+                budget_fixed=512, budget_scale=0.0, budget_table=None, budget_table_len=0,
+                ln_eps=1e-5, norm_eps=1e-12, ln_gamma=None, ln_beta=None, tau_state=None, tau_bswa=None)
+    base.update(kw)
+    return kb.kvm_config(**base)
+
+
+def test_every_declared_symbol_is_exported():
+    header = open(os.path.join(ROOT, "include", "kvm.h")).read()
+    declared = set(re.findall(r"\b(kvm_[a-z_]+)\s*\(", header))
+    declared -= {"kvm_status"}
+    assert declared == set(kb.EXPORTS), declared ^ set(kb.EXPORTS)
+    lib = kb.load_library()
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert lib.kvm_strerror(kb.KVM_ERR_CAPACITY).decode().startswith("state buffer too small")
+    assert lib.kvm_strerror(0).decode() == "ok"
+
+
+@pytest.mark.parametrize("kind,kw,okw", [
+    (kb.KVM_BUDGET_FIXED, dict(budget_fixed=512), dict(budget_kind=ko.BUDGET_FIXED, budget_fixed=512)),
+    (kb.KVM_BUDGET_FIXED, dict(budget_fixed=10), dict(budget_kind=ko.BUDGET_FIXED, budget_fixed=10)),
+    (kb.KVM_BUDGET_SQRT, dict(budget_scale=4.0), dict(budget_kind=ko.BUDGET_SQRT, budget_scale=4.0)),
+    (kb.KVM_BUDGET_SQRT, dict(budget_scale=16.0), dict(budget_kind=ko.BUDGET_SQRT, budget_scale=16.0)),
+    (kb.KVM_BUDGET_SQRT, dict(budget_scale=2.5), dict(budget_kind=ko.BUDGET_SQRT, budget_scale=2.5)),
+    (kb.KVM_BUDGET_NONE, {}, dict(budget_kind=ko.BUDGET_NONE)),
+])
+def test_growth_schedule_matches_oracle_and_closed_forms(kind, kw, okw):
+    lib = kb.load_library()
+    c = cfg(budget_kind=kind, **kw)
+    oc = ko.KVMConfig(head_dim=128, rope_dims=32, chunk_len=256, **okw)
+    for T in (0, 255, 256, 511, 512, 768, 4096, 4352, 16384, 65536, 65537):
+        rows = ko.expected_rows(oc, T)
+        assert lib.kvm_state_rows_for(C.byref(c), T) == (rows[-1] if rows else 0), T
+    if kind == kb.KVM_BUDGET_SQRT and kw["budget_scale"] == 4.0:
+        # worked by hand: 4*ceil(sqrt(e)) <= 256 up to e = 4096; 4*66 at 4352; 512 at 16384; 1024 at 65536
+        got = [lib.kvm_state_rows_for(C.byref(c), T) for T in (4096, 4352, 16384, 65536)]
+        assert got == [256, 264, 512, 1024]
+
+
+def test_table_budget_and_bad_configs():
+    lib = kb.load_library()
+    table = (C.c_int64 * 6)(0, 256, 300, 300, 900, 901)
+    c = cfg(budget_kind=kb.KVM_BUDGET_TABLE, budget_table=C.cast(table, C.POINTER(C.c_int64)), budget_table_len=6)
+    oc = ko.KVMConfig(head_dim=128, rope_dims=32, chunk_len=256, budget_kind=ko.BUDGET_TABLE,
+                      budget_table=list(table))
+    for T in (512, 768, 1024, 1280, 1536, 4096):
+        assert lib.kvm_state_rows_for(C.byref(c), T) == ko.expected_rows(oc, T)[-1]
+    for bad in (dict(head_dim=96), dict(n_q_heads=3), dict(chunk_len=0), dict(n_sink=256), dict(io_dtype=7),
+                dict(rope_dims=129), dict(budget_kind=9), dict(batch=0)):
+        assert lib.kvm_state_bytes(C.byref(cfg(**bad)), 4096) == 0, bad
+        assert lib.kvm_state_rows_for(C.byref(cfg(**bad)), 4096) == -1, bad
+
+
+def test_state_bytes_cover_the_layout():
+    lib = kb.load_library()
+    c = cfg()
+    U, d, C_, L, m = 4, 128, 256, 512, 512
+    need = U * m * d * (8 + 4 + 2 + 2) + U * m * 12 + 2 * U * L * d * 2 + U * L * 4 + U * C_ * d * 2 + U * C_ * 20
+    got = lib.kvm_state_bytes(C.byref(c), 8192)
+    assert need <= got <= need + 16 * 256
+    assert lib.kvm_state_bytes(C.byref(cfg(budget_kind=kb.KVM_BUDGET_SQRT, budget_scale=4.0)), 65536) > \
+        lib.kvm_state_bytes(C.byref(cfg(budget_kind=kb.KVM_BUDGET_SQRT, budget_scale=4.0)), 4096)
+
+
+def test_argument_and_capacity_errors_before_any_launch():
+    lib = kb.load_library()
+    c = cfg(budget_kind=kb.KVM_BUDGET_SQRT, budget_scale=4.0)
+    h = C.c_void_p()
+    nbytes = lib.kvm_state_bytes(C.byref(c), 4096)
+    assert lib.kvm_state_init(C.byref(h), C.byref(c), FAKE_DEV_PTR, nbytes - 1, 4096) == kb.KVM_ERR_CAPACITY
+    assert lib.kvm_state_init(C.byref(h), C.byref(c), FAKE_DEV_PTR + 8, nbytes, 4096) == kb.KVM_ERR_ARG
+    assert lib.kvm_state_init(C.byref(h), C.byref(c), None, nbytes, 4096) == kb.KVM_ERR_ARG
+    assert lib.kvm_state_init(C.byref(h), C.byref(c), FAKE_DEV_PTR, nbytes, 4096) == kb.KVM_OK
+    v = C.c_int64(-1)
+    assert lib.kvm_state_rows(h, C.byref(v)) == 0 and v.value == 0
+    assert lib.kvm_state_capacity(h, C.byref(v)) == 0 and v.value == 256
+    assert lib.kvm_state_tokens(h, C.byref(v)) == 0 and v.value == 0
+    p = FAKE_DEV_PTR
+    # budget over this call (rows 264 at e = 4352) exceeds the 256-row buffer: refused up front
+    assert lib.kvm_prefill_chunked(h, p, p, p, None, p, None, 8192, None, None) == kb.KVM_ERR_CAPACITY
+    assert lib.kvm_state_tokens(h, C.byref(v)) == 0 and v.value == 0
+    assert lib.kvm_prefill_chunked(h, p, p, p, None, p, None, 0, None, None) == kb.KVM_ERR_ARG
+    assert lib.kvm_prefill_chunked(h, None, p, p, None, p, None, 256, None, None) == kb.KVM_ERR_ARG
+    assert lib.kvm_prefill_chunked(h, p + 2, p, p, None, p, None, 256, None, None) == kb.KVM_ERR_ARG
+    st = kb.kvm_strides(*([128] * 18))
+    st.q_t = 100                                         # not a multiple of 8 elements
+    assert lib.kvm_prefill_chunked(h, p, p, p, None, p, None, 256, C.byref(st), None) == kb.KVM_ERR_ARG
+    assert lib.kvm_state_fold(h, p, p, None, 255, 512, None, None, None) == kb.KVM_ERR_ARG
+    assert lib.kvm_decode_step(h, p, None, p, None, p, None) == kb.KVM_ERR_ARG
+    assert lib.kvm_state_grow(h, FAKE_DEV_PTR, 16, 65536, None) == kb.KVM_ERR_CAPACITY
+    assert lib.kvm_state_import(h, None, None, None, None, None, None, None, None, 100000, 0, 0, None) \
+        == kb.KVM_ERR_ARG
+    assert lib.kvm_state_destroy(h) == 0
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(kb, "_lib", None)
+    monkeypatch.setattr(kb, "LIB_PATH", str(tmp_path / "libkvm.so"))
+    with pytest.raises(FileNotFoundError):
+        kb.load_library()
