@@ -386,7 +386,7 @@ class KVMUnit:
     def _maybe_fold(self):
         C, L = self.cfg.chunk_len, self.cfg.window
         e = self.t
-        if e % C != 0 or e < L:
+        if e % C != 0 or e < L or self.cfg.budget_kind == BUDGET_NONE:
             return
         lo = e - L
         idx = len(self.fold_logs)

@@ -187,13 +187,18 @@ __global__ __launch_bounds__(256) void select_kernel(Dev dv, int m, int n_app, i
 }
 
 // ------------------------------------------------------------------ create + merge + readout refresh
-// One wave per state row of the updated state.  Tokens are added in ascending position.
+// One wave per state row in [row_begin, m_after) of the updated state.  Tokens are added in
+// ascending position.  do_create: rows >= m_before are created from their creator token;
+// do_merge: tokens whose target is the row are added.  A fold that appends only part of the
+// block runs create first (so the new rows have a normalised key to score against), then the
+// second scoring pass, then merge.
 template <typename T, int D>
-__global__ __launch_bounds__(256) void accum_kernel(Dev dv, Src src, int m_before, int m_after) {
+__global__ __launch_bounds__(256) void accum_kernel(Dev dv, Src src, int m_before, int m_after,
+                                                    int row_begin, int do_create, int do_merge) {
   constexpr int CPL = D / 64;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int u = blockIdx.y, b = u / dv.Hkv, h = u % dv.Hkv;
-  const int row = blockIdx.x * 4 + wave;
+  const int row = row_begin + blockIdx.x * 4 + wave;
   if (row >= m_after) return;
   const int C = dv.C;
   const int64_t base = (int64_t)u * C;
@@ -207,7 +212,7 @@ __global__ __launch_bounds__(256) void accum_kernel(Dev dv, Src src, int m_befor
   float rho = 0.f, w = 0.f;
   int n = 0;
   bool loaded = false;
-  const bool is_new = row >= m_before;
+  const bool is_new = do_create && row >= m_before;
   if (is_new) {
     const int j0 = dv.creator[base + (row - m_before)];
     float nn = 0.f;
@@ -223,7 +228,7 @@ __global__ __launch_bounds__(256) void accum_kernel(Dev dv, Src src, int m_befor
     n = 1;
     loaded = true;
   }
-  if (row >= dv.S) {
+  if (do_merge && row >= dv.S) {
     for (int j0 = 0; j0 < C; j0 += 64) {
       const int j = j0 + lane;
       const bool mine = j < C && dv.pi[base + j] == row && dv.app[base + j] < 0;
@@ -340,9 +345,12 @@ hipError_t launch_select(const Dev &dv, int m, int n_app, bool take_all, hipStre
   return hipGetLastError();
 }
 
-hipError_t launch_accum(const Dev &dv, const Src &src, int m_before, int m_after, hipStream_t st) {
-  dim3 grid((m_after + 3) / 4, dv.U);
-  KVM_DISPATCH(dv, accum_kernel, grid, dim3(256), 0, st, dv, src, m_before, m_after);
+hipError_t launch_accum(const Dev &dv, const Src &src, int m_before, int m_after, int row_begin,
+                        bool do_create, bool do_merge, hipStream_t st) {
+  if (m_after <= row_begin) return hipSuccess;
+  dim3 grid((m_after - row_begin + 3) / 4, dv.U);
+  KVM_DISPATCH(dv, accum_kernel, grid, dim3(256), 0, st, dv, src, m_before, m_after, row_begin,
+               do_create ? 1 : 0, do_merge ? 1 : 0);
   return hipGetLastError();
 }
 

@@ -222,21 +222,25 @@ int fold_block(kvm_state *st, const Src &src, int64_t e, int32_t *assign_out, fl
   if (m_after > dv.Mcap) return KVM_ERR_CAPACITY;
   HIP_TRY(kvm::launch_memkey(dv, src, stream));
   if (n_app == dv.C) {
+    // room for the whole block (state creation included): no scores are needed
     HIP_TRY(kvm::launch_select(dv, (int)m, n_app, true, stream));
+    HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, 0, true, true, stream));
   } else {
     if (st->mfma)
       HIP_TRY(kvm::launch_score_mfma(dv, 0, (int)m, true, stream));
     else
       HIP_TRY(kvm::launch_score(dv, 0, (int)m, true, stream));
     if (n_app > 0) {
+      // new rows first, so that the remaining tokens can be scored against them too
       HIP_TRY(kvm::launch_select(dv, (int)m, n_app, false, stream));
+      HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, (int)m, true, false, stream));
       if (st->mfma)
         HIP_TRY(kvm::launch_score_mfma(dv, (int)m, (int)m_after, false, stream));
       else
         HIP_TRY(kvm::launch_score(dv, (int)m, (int)m_after, false, stream));
     }
+    HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, 0, false, true, stream));
   }
-  HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, stream));
   const size_t ntok = (size_t)dv.U * dv.C;
   if (assign_out)
     HIP_TRY(hipMemcpyAsync(assign_out, dv.pi, ntok * 4, hipMemcpyDeviceToDevice, stream));

@@ -62,7 +62,8 @@ struct AttnArgs {
 hipError_t launch_memkey(const Dev &dv, const Src &src, hipStream_t st);
 hipError_t launch_score(const Dev &dv, int row0, int row1, bool first_pass, hipStream_t st);
 hipError_t launch_select(const Dev &dv, int m, int n_app, bool take_all, hipStream_t st);
-hipError_t launch_accum(const Dev &dv, const Src &src, int m_before, int m_after, hipStream_t st);
+hipError_t launch_accum(const Dev &dv, const Src &src, int m_before, int m_after, int row_begin,
+                        bool do_create, bool do_merge, hipStream_t st);
 hipError_t launch_refresh(const Dev &dv, int m, hipStream_t st);
 hipError_t launch_ring_copy(const Dev &dv, const Src &src, int64_t src_t0, int64_t p0, int64_t p1,
                             hipStream_t st);
