@@ -1,0 +1,199 @@
+#!/usr/bin/env python3
+"""Benchmark of the KVM layer hot path on one MI355X.
+
+A "step" is one pass of the whole path over one batch of synthetic input: chunk-wise prefill
+of the 32k-context workload (every chunk's attention over [state || window] plus every fold),
+inputs resident in HBM.  One JSON line is printed: prefill tokens/s, the roofline of the
+dominant kernel (fused MFMA attention; kernel time from HIP events recorded by the library on
+the launch stream), the decode leg (us per token on the batched-decode workload, HBM roofline)
+and the CPU oracle timed on the host cores on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E peak
+
+
+def attention_flops(w, T):
+    """Algorithmic attention flops of a T-token prefill: 4*d per visible (query, key) pair, pairs
+    per chunk and query head = C*(m + tokens of earlier window blocks) + C*(C+1)/2."""
+    C, L = w.chunk_len, w.chunk_len * w.n_bswa_chunks
+    kind = w.budget_kind
+    pairs, m, launches = 0, 0, 0
+    for s in range(0, T, C):
+        e = s + C
+        b = max(0, e - L)
+        pairs += C * (m + (s - b)) + C * (C + 1) // 2
+        launches += 1
+        if e >= L and kind != "none":
+            if m == 0:
+                m = C
+            else:
+                import math
+                B = w.budget_fixed if kind == "fixed" else int(w.budget_scale * (math.isqrt(e - 1) + 1))
+                m = max(m, min(B, m + C))
+    return 4.0 * w.head_dim * pairs * w.n_q_heads * w.batch, launches
+
+
+def prefill_leg(args, pkg, synth, dev):
+    import torch
+    w = synth.WORKLOADS[args.workload]
+    q, k, v = synth.make_qkv(w, dev)
+    st = pkg.state_for(w, device=dev)
+    out = torch.empty_like(q)
+    for _ in range(args.warmup):
+        st.reset()
+        st.prefill(q, k, v, out=out)
+    torch.cuda.synchronize()
+    st.profile(True)
+    st.profile_read()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        st.reset()
+        st.prefill(q, k, v, out=out)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = st.profile_read()
+    st.profile(False)
+    tokens = w.batch * w.seq
+    flops, launches = attention_flops(w, w.seq)
+    attn_ms, attn_n = prof["attn"]
+    fold_ms, fold_n = prof["fold"]
+    avg_launch_s = attn_ms / max(attn_n, 1) * 1e-3
+    achieved = flops / launches / avg_launch_s / 1e12 if attn_n else 0.0
+    res = dict(
+        value=tokens * args.steps / dt, ms_per_step=dt / args.steps * 1e3,
+        roofline=dict(bound="mfma", kernel="attn_mfma_kernel", achieved=achieved, peak=MFMA_BF16_PEAK_TFLOPS,
+                      unit="TFLOP/s", frac=achieved / MFMA_BF16_PEAK_TFLOPS, traffic=None,
+                      launches_per_step=launches, avg_launch_us=avg_launch_s * 1e6,
+                      attn_ms_per_step=attn_ms / args.steps, fold_ms_per_step=fold_ms / args.steps,
+                      folds_per_step=fold_n // max(args.steps, 1)),
+        workload=w)
+    return res, (q, k, v)
+
+
+def decode_leg(args, pkg, synth, dev):
+    """Batched decode workload: successive steps against a pre-built state, folds included."""
+    import torch
+    w = synth.WORKLOADS["decode"]
+    pre = synth.make_decode_state(w, dev)
+    steps = w.seq
+    st = pkg.state_for(w, device=dev, max_tokens=pre["tokens"] + 2 * steps)
+    st.import_(pre)
+    n_in = 16                                            # distinct inputs, cycled
+    q, k, v = synth.make_qkv(w, dev, T=n_in, pos0=pre["tokens"])
+    qs = [q[:, t].contiguous() for t in range(n_in)]
+    ks = [k[:, t].contiguous() for t in range(n_in)]
+    vs = [v[:, t].contiguous() for t in range(n_in)]
+    out = torch.empty_like(qs[0])
+    for t in range(20):
+        st.decode(qs[t % n_in], ks[t % n_in], vs[t % n_in], out=out)
+    st.import_(pre)
+    torch.cuda.synchronize()
+    st.profile(True)
+    st.profile_read()
+    t0 = time.perf_counter()
+    for t in range(steps):
+        st.decode(qs[t % n_in], ks[t % n_in], vs[t % n_in], out=out)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = st.profile_read()
+    dec_ms, dec_n = prof["decode"]
+    fold_ms, fold_n = prof["fold"]
+    L, C, m, d = w.chunk_len * w.n_bswa_chunks, w.chunk_len, w.state_rows, w.head_dim
+    mean_w = (L - C + 1 + L) / 2.0                       # window length cycles L-C+1 .. L
+    bytes_per_step = w.batch * w.n_q_heads * ((m + mean_w) * d * 2 * 2 + 2 * d * 2)
+    avg_s = dec_ms / max(dec_n, 1) * 1e-3
+    gbs = bytes_per_step / avg_s / 1e9 if dec_n else 0.0
+    return dict(us_per_token=dt / steps / w.batch * 1e6, us_per_step=dt / steps * 1e6, steps=steps,
+                folds=fold_n, fold_us=fold_ms / max(fold_n, 1) * 1e3,
+                config=dict(workload="decode", batch=w.batch, heads=w.n_q_heads, head_dim=d, state_rows=m,
+                            window=L, chunk_len=C),
+                roofline=dict(bound="hbm", kernel="attn_rows_kernel", achieved=gbs, peak=HBM_PEAK_GBS,
+                              unit="GB/s", frac=gbs / HBM_PEAK_GBS, traffic=None,
+                              avg_launch_us=avg_s * 1e6, bytes_per_launch=bytes_per_step))
+
+
+def cpu_baseline_leg(w, tensors, budget_s):
+    """The oracle, as it stands, on one (batch, KV head) unit of the same inputs, for as many
+    chunks as fit the time budget; scaled to whole-layer tokens/s (units are independent and
+    equal in work)."""
+    import kvm_testlib as tl
+    q, k, v = tensors
+    C = w.chunk_len
+    n_tok = min(w.seq, 16 * C)
+    sub = (q[:1, :n_tok], k[:1, :n_tok], v[:1, :n_tok])
+    u = tl.unit_inputs(w, *sub, {}, 0, 0)
+    unit = tl.make_oracle_unit(w, {}, 0)
+    t0 = time.perf_counter()
+    done = 0
+    while done < n_tok and time.perf_counter() - t0 < budget_s:
+        unit.prefill(u["q"][:, done:done + C], u["k"][done:done + C], u["v"][done:done + C])
+        done += C
+    dt = time.perf_counter() - t0
+    units = w.batch * w.n_kv_heads
+    try:
+        import threadpoolctl
+        cores = max(int(i.get("num_threads", 1)) for i in threadpoolctl.threadpool_info()) \
+            if threadpoolctl.threadpool_info() else os.cpu_count()
+    except Exception:
+        cores = os.cpu_count()
+    # one unit handles `done` tokens of one KV head of one sequence: the layer needs `units` of them
+    return dict(value=done * w.batch / (dt * units), unit="tokens/s", cores=cores, kind="oracle",
+                sample=f"unit (b=0, kv head 0): first {done} of {w.seq} tokens ({done // C} chunks, "
+                       f"{len(unit.fold_logs)} folds) in {dt:.1f} s, scaled by 1/{units} units")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="prefill_gqa_32k")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2605_09877_amd as pkg
+    from paper_2605_09877_amd import synth
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    if not os.path.exists(pkg.binding.LIB_PATH):
+        from paper_2605_09877_amd import build
+        build.build()
+    dev = "cuda:0"
+    res, tensors = prefill_leg(args, pkg, synth, dev)
+    w = res.pop("workload")
+    line = dict(
+        metric="KVM-layer prefill tokens/sec at 32k ctx bf16", value=res["value"], unit="tokens/s",
+        n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=res["ms_per_step"],
+        higher_is_better=True, scaling="weak", vs_baseline=None, dtype="bf16", data="synthetic",
+        config=dict(workload=w.name, batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads,
+                    head_dim=w.head_dim, seq_len=w.seq, chunk_len=w.chunk_len, state_rows=w.budget_fixed,
+                    rope_dims=w.rope_dims, gpu=torch.cuda.get_device_name(0)),
+        roofline=res["roofline"])
+    if not args.no_decode:
+        line["decode"] = decode_leg(args, pkg, synth, dev)
+    if not args.no_cpu:
+        line["cpu_baseline"] = cpu_baseline_leg(w, tensors, args.cpu_seconds)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

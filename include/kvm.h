@@ -25,8 +25,8 @@
  *    H_q/H_kv query heads shares one KV head's state, window, gate and LN_s), d = head_dim
  *    (64 or 128), C = chunk_len, L = n_bswa_chunks * C.  A "unit" is one (batch, KV head).
  *  - I/O dtype: KVM_F32 or KVM_BF16 for q, k, v, out, the memory keys and the normalised
- *    readout rows.  State key sums are fp64, value sums fp32 (see DESIGN notes shipped with
- *    the library sources).
+ *    readout rows.  State key sums are fp64 (they feed the slot argmax, which has to be
+ *    reproducible), value sums and radii fp32.
  */
 #ifndef KVM_H
 #define KVM_H
@@ -168,6 +168,16 @@ int kvm_state_import(kvm_state *st, const double *sK, const float *sV, const flo
                      const float *w, const int32_t *n, const void *win_k, const void *win_v,
                      const float *win_g, int64_t m, int64_t tokens_seen, int64_t folds,
                      void *stream);
+
+/* Kernel timing for benchmarks (no passage of the paper: a measurement aid).  While enabled,
+ * every attention launch and every fold of this state is bracketed by HIP events recorded on
+ * the call's stream.  kvm_state_profile_read waits for the recorded events, adds up the elapsed
+ * milliseconds per class, returns them with the number of launches, and clears the record:
+ *   ms[0], count[0]: prefill attention launches (one per chunk)
+ *   ms[1], count[1]: folds (all kernels of one fold together)
+ *   ms[2], count[2]: decode attention launches */
+int kvm_state_profile(kvm_state *st, int enable);
+int kvm_state_profile_read(kvm_state *st, double ms[3], int64_t count[3]);
 
 #ifdef __cplusplus
 }

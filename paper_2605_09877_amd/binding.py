@@ -22,7 +22,7 @@ EXPORTS = [
     "kvm_strerror", "kvm_last_hip_error", "kvm_state_rows_for", "kvm_state_bytes", "kvm_state_init",
     "kvm_state_destroy", "kvm_prefill_chunked", "kvm_decode_step", "kvm_state_fold", "kvm_state_rows",
     "kvm_state_tokens", "kvm_state_capacity", "kvm_state_folds", "kvm_state_trace", "kvm_state_grow",
-    "kvm_state_export", "kvm_state_import",
+    "kvm_state_export", "kvm_state_import", "kvm_state_profile", "kvm_state_profile_read",
 ]
 
 
@@ -81,6 +81,8 @@ def load_library() -> C.CDLL:
     lib.kvm_state_grow.argtypes = [vp, vp, C.c_size_t, i64, vp]
     lib.kvm_state_export.argtypes = [vp] * 12
     lib.kvm_state_import.argtypes = [vp] * 9 + [i64, i64, i64, vp]
+    lib.kvm_state_profile.argtypes = [vp, C.c_int]
+    lib.kvm_state_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
     _lib = lib
     return lib
 
@@ -269,6 +271,20 @@ class KVMState:
             _check(self.lib.kvm_state_fold(self.handle, k_blk.data_ptr(), v_blk.data_ptr(), _ptr(gate_blk), n, e,
                                            assign.data_ptr(), score.data_ptr(), _stream()), "kvm_state_fold")
         return assign, score
+
+    def reset(self) -> None:
+        """Back to the empty state (m = 0, no tokens seen) in the same buffer; no device work."""
+        _check(self.lib.kvm_state_import(self.handle, *([None] * 8), 0, 0, 0, None), "kvm_state_import")
+
+    def profile(self, enable: bool) -> None:
+        _check(self.lib.kvm_state_profile(self.handle, 1 if enable else 0), "kvm_state_profile")
+
+    def profile_read(self) -> dict:
+        """kvm_state_profile_read: {"attn": (ms, launches), "fold": (...), "decode": (...)}."""
+        ms = (C.c_double * 3)()
+        cnt = (C.c_int64 * 3)()
+        _check(self.lib.kvm_state_profile_read(self.handle, ms, cnt), "kvm_state_profile_read")
+        return {k: (ms[i], cnt[i]) for i, k in enumerate(("attn", "fold", "decode"))}
 
     # ---- tracing, checkpoint
     def trace(self, max_folds: int):

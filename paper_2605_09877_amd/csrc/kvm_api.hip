@@ -27,6 +27,14 @@ struct kvm_state {
   float *trace_score = nullptr;
   int64_t trace_max = 0;
   bool mfma = false;  // bf16, d = 128, C % 64 == 0: matrix-core kernels
+  // optional kernel timing: (start, stop, class) event pairs, events reused across reads
+  bool profile = false;
+  struct Span {
+    hipEvent_t a, b;
+    int kind;
+  };
+  std::vector<Span> spans;
+  std::vector<hipEvent_t> free_events;
 };
 
 namespace {
@@ -259,6 +267,36 @@ int fold_block(kvm_state *st, const Src &src, int64_t e, int32_t *assign_out, fl
 
 bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
 
+// RAII bracket: records a start event now and a stop event when it goes out of scope.
+struct ProfileSpan {
+  kvm_state *st;
+  hipStream_t stream;
+  hipEvent_t a = nullptr, b = nullptr;
+  int kind;
+  ProfileSpan(kvm_state *s, int k, hipStream_t str) : st(s), stream(str), kind(k) {
+    if (!st->profile) return;
+    auto get = [&]() -> hipEvent_t {
+      hipEvent_t e = nullptr;
+      if (!st->free_events.empty()) {
+        e = st->free_events.back();
+        st->free_events.pop_back();
+      } else if (hipEventCreate(&e) != hipSuccess) {
+        e = nullptr;
+      }
+      return e;
+    };
+    a = get();
+    b = get();
+    if (a && b) (void)hipEventRecord(a, stream);
+  }
+  ~ProfileSpan() {
+    if (a && b) {
+      (void)hipEventRecord(b, stream);
+      st->spans.push_back({a, b, kind});
+    }
+  }
+};
+
 }  // namespace
 
 extern "C" {
@@ -308,7 +346,39 @@ int kvm_state_init(kvm_state **out, const kvm_config *cfg, void *dev_buf, size_t
 }
 
 int kvm_state_destroy(kvm_state *st) {
+  if (st) {
+    for (auto &sp : st->spans) {
+      (void)hipEventDestroy(sp.a);
+      (void)hipEventDestroy(sp.b);
+    }
+    for (auto e : st->free_events) (void)hipEventDestroy(e);
+  }
   delete st;
+  return KVM_OK;
+}
+
+int kvm_state_profile(kvm_state *st, int enable) {
+  if (!st) return KVM_ERR_ARG;
+  st->profile = enable != 0;
+  return KVM_OK;
+}
+
+int kvm_state_profile_read(kvm_state *st, double ms[3], int64_t count[3]) {
+  if (!st || !ms || !count) return KVM_ERR_ARG;
+  for (int i = 0; i < 3; ++i) {
+    ms[i] = 0.0;
+    count[i] = 0;
+  }
+  for (auto &sp : st->spans) {
+    HIP_TRY(hipEventSynchronize(sp.b));
+    float t = 0.f;
+    HIP_TRY(hipEventElapsedTime(&t, sp.a, sp.b));
+    ms[sp.kind] += t;
+    count[sp.kind] += 1;
+    st->free_events.push_back(sp.a);
+    st->free_events.push_back(sp.b);
+  }
+  st->spans.clear();
   return KVM_OK;
 }
 
@@ -364,12 +434,16 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
     a.nq = (int32_t)(ce - cs);
     a.b = cs + C - L > 0 ? cs + C - L : 0;
     a.m = (int32_t)st->m;
-    if (st->mfma)
-      HIP_TRY(kvm::launch_attn_mfma(dv, a, stream));
-    else
-      HIP_TRY(kvm::launch_attn_rows(dv, a, stream));
+    {
+      ProfileSpan span(st, 0, stream);
+      if (st->mfma)
+        HIP_TRY(kvm::launch_attn_mfma(dv, a, stream));
+      else
+        HIP_TRY(kvm::launch_attn_rows(dv, a, stream));
+    }
     if (ce - cs == C && ce >= L) {
       const int64_t lo = ce - L;  // first token of the overflow block
+      ProfileSpan span(st, 1, stream);
       int rc;
       if (lo >= t0)
         rc = fold_block(st, advance(in, lo - t0, es), ce, nullptr, nullptr, stream);
@@ -415,10 +489,14 @@ int kvm_decode_step(kvm_state *st, const void *q, const void *k, const void *v,
   const int64_t cs = u / C * C;
   a.b = cs + C - L > 0 ? cs + C - L : 0;
   a.m = (int32_t)st->m;
-  HIP_TRY(kvm::launch_attn_rows(dv, a, stream));
+  {
+    ProfileSpan span(st, 2, stream);
+    HIP_TRY(kvm::launch_attn_rows(dv, a, stream));
+  }
   st->tokens = u + 1;
   if (completes) {
     const int64_t lo = u + 1 - L;
+    ProfileSpan span(st, 1, stream);
     int rc = fold_block(st, advance(ring_src(st), lo % L, es), u + 1, nullptr, nullptr, stream);
     if (rc != KVM_OK) return rc;
   }
