@@ -8,10 +8,13 @@
 //   S^T[key, query] = K_tile . Q^T      16 MFMA 32x32x16, K from LDS, Q^T kept in registers
 //   online softmax down the key axis: a lane holds one query column, so the running max and
 //                                     sum are per-lane scalars plus one exchange with lane^32
-//   O^T[d, query]  += V_tile^T . P^T    16 MFMA; V is stored transposed in LDS so that both
-//                                     operands are key-contiguous; P^T is S^T's own register
-//                                     layout, no shuffle needed
-// The mask is never materialised: it is the tile loop bounds plus a compare on diagonal tiles.
+//   O^T[d, query]  += V_tile^T . P^T    16 MFMA; V^T fragments come out of the row-major V tile
+//                                     through the transposing LDS read; P^T is S^T's own
+//                                     register layout, no shuffle needed
+// K and V tiles go from HBM straight into LDS (global_load_lds, 16 B per lane, swizzled rows),
+// double buffered: the loads of tile i+1 are in flight while tile i is consumed, one barrier
+// per tile.  The mask is never materialised: it is the tile loop bounds plus a compare on
+// diagonal tiles.
 #include "kvm_device.h"
 #include "kvm_internal.h"
 #include "kvm_mfma.h"
@@ -25,8 +28,8 @@ constexpr float kLn2 = 0.6931471805599453f;
 constexpr int kTileQ = 128;
 
 __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
-  __shared__ __attribute__((aligned(16))) uint16_t Ks[kTileKeys * kKStride];
-  __shared__ __attribute__((aligned(16))) uint16_t Vts[kHeadDim * kVtStride];
+  __shared__ __attribute__((aligned(1024))) uint16_t Ks[2][kTileElems];
+  __shared__ __attribute__((aligned(1024))) uint16_t Vs[2][kTileElems];
   constexpr int D = kHeadDim;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 5, l32 = lane & 31;
@@ -52,8 +55,13 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
     }
   }
   const float rs = kLog2e * rsqrtf((float)D);
-  const float c_state = (dv.tau_state ? dv.tau_state[hq] : 1.f) * rs;
-  const float c_bswa = (dv.tau_bswa ? dv.tau_bswa[hq] : 1.f) * rs;
+  float c_state = (dv.tau_state ? dv.tau_state[hq] : 1.f) * rs;
+  float c_bswa = (dv.tau_bswa ? dv.tau_bswa[hq] : 1.f) * rs;
+  // The softmax below takes the row maximum on raw dot products and applies a positive scale
+  // afterwards; for a negative temperature the dot products of that region are negated first.
+  const bool neg_state = c_state < 0.f, neg_bswa = c_bswa < 0.f;
+  c_state = fabsf(c_state);
+  c_bswa = fabsf(c_bswa);
 
   const int n_st = (m + kTileKeys - 1) / kTileKeys;
   const int qend = (Q0 + kTileQ < nq) ? Q0 + kTileQ : nq;  // one past the last valid query here
@@ -68,8 +76,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
   const uint16_t *in_k = (const uint16_t *)a.in.k + b * a.in.k_b + hkv * a.in.k_h;
   const uint16_t *in_v = (const uint16_t *)a.in.v + b * a.in.v_b + hkv * a.in.v_h;
 
-  uint4 kr[4], vr[4];
-  auto issue_loads = [&](int it) {
+  auto issue_tile = [&](int it) {
     const uint16_t *kb_, *vb_;
     int64_t kst, vst;
     int valid;
@@ -95,36 +102,8 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
       }
     }
     valid = valid < kTileKeys ? valid : kTileKeys;
-    tile_rows_load(kb_, kst, valid, tid, kr);
-    // V: thread takes keys 4*(tid/16) .. +3, channels 8*(tid%16) .. +7
-    const int c8 = (tid & 15) * 8;
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      int key = 4 * (tid >> 4) + kk;
-      key = key < valid ? key : valid - 1;
-      vr[kk] = *reinterpret_cast<const uint4 *>(vb_ + (int64_t)key * vst + c8);
-    }
-  };
-  auto store_lds = [&]() {
-    tile_rows_to_lds(Ks, tid, kr);
-    // transpose the 4 keys x 8 channels block in registers: one 8-byte store per channel
-    const uint32_t *w0 = reinterpret_cast<const uint32_t *>(&vr[0]);
-    const uint32_t *w1 = reinterpret_cast<const uint32_t *>(&vr[1]);
-    const uint32_t *w2 = reinterpret_cast<const uint32_t *>(&vr[2]);
-    const uint32_t *w3 = reinterpret_cast<const uint32_t *>(&vr[3]);
-    const int d0 = (tid & 15) * 8, key0 = 4 * (tid >> 4);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      uint32_t lo, hi;
-      if (e & 1) {
-        lo = (w0[e >> 1] >> 16) | (w1[e >> 1] & 0xffff0000u);
-        hi = (w2[e >> 1] >> 16) | (w3[e >> 1] & 0xffff0000u);
-      } else {
-        lo = (w0[e >> 1] & 0xffffu) | (w1[e >> 1] << 16);
-        hi = (w2[e >> 1] & 0xffffu) | (w3[e >> 1] << 16);
-      }
-      *reinterpret_cast<uint2 *>(Vts + (d0 + e) * kVtStride + key0) = make_uint2(lo, hi);
-    }
+    tile_dma<false>(kb_, kst, valid, Ks[it & 1], wave, lane);
+    tile_dma<true>(vb_, vst, valid, Vs[it & 1], wave, lane);
   };
 
   f32x16 oacc[4];
@@ -134,12 +113,13 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
     for (int v = 0; v < 16; ++v) oacc[i][v] = 0.f;
   float m_run = -INFINITY, l_part = 0.f;
 
-  issue_loads(0);
+  issue_tile(0);
   for (int it = 0; it < n_tiles; ++it) {
+    // tile `it` has landed for every wave, and every wave is done reading the other buffer
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
-    store_lds();
-    __syncthreads();
-    if (it + 1 < n_tiles) issue_loads(it + 1);
+    if (it + 1 < n_tiles) issue_tile(it + 1);
+    const uint16_t *Kt = Ks[it & 1], *Vt = Vs[it & 1];
 
     const bool is_state = it < n_st;
     const int row0 = it * kTileKeys;
@@ -160,50 +140,72 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
     for (int i = 0; i < 2; ++i)
 #pragma unroll
       for (int v = 0; v < 16; ++v) sacc[i][v] = 0.f;
+    // S^T = K . Q^T with a rolling window of eight K fragments in flight from LDS, so that a
+    // matrix instruction does not wait for the read issued just before it
+    {
+      bf16x8 kf[8];
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
+      for (int i = 0; i < 8; ++i) kf[i] = ktile_frag(Kt, i & 1, i >> 1, lane);
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk) {
+          const int slot = (2 * ks + blk) & 7;
+          sacc[blk] = mfma32(kf[slot], qreg[ks], sacc[blk]);
+          if (ks + 4 < 8) kf[slot] = ktile_frag(Kt, blk, ks + 4, lane);
+        }
+      }
+      // pin that order: 8 LDS reads up front, then one read behind every matrix instruction
+      __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+    }
+    // first eight V^T fragments: issued now, consumed after the softmax arithmetic
+    bf16x8 vf[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) vf[i] = vtile_frag(Vt, i & 3, i >> 2, lane);
+
+    if (is_state ? neg_state : neg_bswa) {
 #pragma unroll
       for (int blk = 0; blk < 2; ++blk)
-        sacc[blk] = mfma32(tile_rows_frag(Ks, blk, ks, lane), qreg[ks], sacc[blk]);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sacc[blk][v] = -sacc[blk][v];
     }
-
-    float tmax = -INFINITY;
     if (need_mask) {
       // keys up to `lim` (tile-local) are visible to this lane's query
       const int lim = is_state ? (m - row0 - 1) : (int)(a.s + myq - p0);
 #pragma unroll
       for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int key = 32 * blk + mfma_row(v, g);
-          const float t = key <= lim ? sacc[blk][v] * scale : -INFINITY;
-          sacc[blk][v] = t;
-          tmax = fmaxf(tmax, t);
-        }
-    } else {
-#pragma unroll
-      for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const float t = sacc[blk][v] * scale;
-          sacc[blk][v] = t;
-          tmax = fmaxf(tmax, t);
-        }
+        for (int v = 0; v < 16; ++v)
+          sacc[blk][v] = (32 * blk + mfma_row(v, g)) <= lim ? sacc[blk][v] : -INFINITY;
     }
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));
-    const float m_new = fmaxf(m_run, tmax);
-    const float alpha = exp2f(m_run - m_new);
-    m_run = m_new;
-    l_part *= alpha;
+    float smax = sacc[0][0];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) oacc[i][v] *= alpha;
+      for (int v = 0; v < 16; ++v) smax = fmaxf(smax, sacc[blk][v]);
+    smax = fmaxf(smax, __shfl_xor(smax, 32, kWave));
+    const float m_new = fmaxf(m_run, smax * scale);
+    if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
+      // some query of this wave has a new running maximum: rescale what is accumulated
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      m_run = m_new;
+      l_part *= alpha;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) oacc[i][v] *= alpha;
+    }
 #pragma unroll
     for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const float p = exp2f(sacc[blk][v] - m_new);
+        const float p = __builtin_amdgcn_exp2f(fmaf(sacc[blk][v], scale, -m_run));
         l_part += p;
         sacc[blk][v] = p;
       }
@@ -216,11 +218,9 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
       for (int e = 0; e < 4; ++e) pb.w[e] = pack_bf16(sacc[blk][v0 + 2 * e], sacc[blk][v0 + 2 * e + 1]);
 #pragma unroll
       for (int dblk = 0; dblk < 4; ++dblk) {
-        const uint16_t *vrow = Vts + (32 * dblk + l32) * kVtStride + 16 * ks + 4 * g;
-        Frag8 av;
-        av.d[0] = *reinterpret_cast<const uint2 *>(vrow);
-        av.d[1] = *reinterpret_cast<const uint2 *>(vrow + 8);
-        oacc[dblk] = mfma32(av.v, pb.v, oacc[dblk]);
+        const int i = 4 * ks + dblk, slot = i & 7;
+        oacc[dblk] = mfma32(vf[slot], pb.v, oacc[dblk]);
+        if (i + 8 < 16) vf[slot] = vtile_frag(Vt, dblk, ks + 2, lane);
       }
     }
   }

@@ -73,4 +73,65 @@ __device__ __forceinline__ bf16x8 tile_rows_frag(const uint16_t *lds, int blk, i
   return f.v;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Swizzled 64 x 128 bf16 tiles filled by direct global -> LDS loads (no register staging).
+//
+// global_load_lds with 16 bytes per lane writes lane i's chunk to lds_base + 16*i, so one wave
+// instruction fills 1 KiB = four unpadded 256-byte rows.  Which global chunk a lane fetches is
+// free, so a row's sixteen 16-byte chunks are stored permuted: chunk q of row r sits in slot
+// q ^ swz(r).  Rows are 256 B apart (a multiple of the bank cycle), the permutation is what keeps
+// the fragment reads below conflict-free.
+//   K tiles (read with ds_read_b128, lanes walk rows):        swz(r) = r & 15
+//   V tiles (read with ds_read_b64_tr_b16, 4 rows x 32 B):    swz(r) = 2 * (r & 3)
+typedef short v4i16 __attribute__((ext_vector_type(4)));
+#define KVM_LDS_V4(p) ((__attribute__((address_space(3))) v4i16 *)(p))
+#define KVM_LDS_VOID(p) ((__attribute__((address_space(3))) void *)(p))
+
+constexpr int kTileElems = kTileKeys * kHeadDim;  // 8192 bf16 = 16 KiB
+
+// One wave fetches rows 4*bi .. 4*bi+3 (bi = 4*wave + n, n = 0..3) of a tile.  `vswz`: V layout.
+// Rows at or beyond rows_valid repeat the last valid row.
+template <bool kVSwz>
+__device__ __forceinline__ void tile_dma(const uint16_t *base, int64_t stride, int rows_valid,
+                                         uint16_t *lds_tile, int wave, int lane) {
+#pragma unroll
+  for (int n = 0; n < 4; ++n) {
+    const int bi = 4 * wave + n;
+    int r = 4 * bi + (lane >> 4);
+    const int sw = kVSwz ? 2 * (r & 3) : (r & 15);
+    const int q = (lane & 15) ^ sw;
+    r = r < rows_valid ? r : rows_valid - 1;
+    __builtin_amdgcn_global_load_lds(base + (int64_t)r * stride + 8 * q, KVM_LDS_VOID(lds_tile + bi * 512),
+                                     16, 0, 0);
+  }
+}
+
+// A-operand fragment of a swizzled K tile: row = 32*blk + lane%32, channels 16*ks + 8*(lane/32) ..
+__device__ __forceinline__ bf16x8 ktile_frag(const uint16_t *lds_tile, int blk, int ks, int lane) {
+  const int l32 = lane & 31;
+  const int q = (2 * ks + (lane >> 5)) ^ (l32 & 15);
+  Frag8 f;
+  f.q = *reinterpret_cast<const uint4 *>(lds_tile + (32 * blk + l32) * kHeadDim + 8 * q);
+  return f.v;
+}
+
+// A-operand fragment of V^T from a swizzled row-major V tile, through the transposing LDS read:
+// lane gets channel 32*dblk + lane%32 and keys 16*ks + 4*g + {0..3}, 16*ks + 8 + 4*g + {0..3}
+// (g = lane/32) -- the key order in which a lane holds P^T after the first product.
+// ds_read_b64_tr_b16: within 16 lanes, result element t of lane i = element i%4 of the 8 bytes
+// addressed by lane 4*t + i/4.  So lane j addresses key row K0 + j/4, channels dbase + 4*(j%4).
+__device__ __forceinline__ bf16x8 vtile_frag(const uint16_t *lds_tile, int dblk, int ks, int lane) {
+  const int j = lane & 15, t = j >> 2, c = j & 3;
+  const int g = lane >> 5, half = (lane >> 4) & 1;
+  const int q = 4 * dblk + 2 * half + (c >> 1);            // 16-byte chunk of the channel run
+  const int r0 = 16 * ks + 4 * g + t;                        // r0 % 4 == t, (r0 + 8) % 4 == t
+  const int off = 8 * (q ^ (2 * t)) + 4 * (c & 1);
+  const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(KVM_LDS_V4(lds_tile + r0 * kHeadDim + off));
+  const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(KVM_LDS_V4(lds_tile + (r0 + 8) * kHeadDim + off));
+  Frag8 f;
+  f.d[0] = __builtin_bit_cast(uint2, lo);
+  f.d[1] = __builtin_bit_cast(uint2, hi);
+  return f.v;
+}
+
 }  // namespace kvm
