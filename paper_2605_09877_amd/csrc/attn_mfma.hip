@@ -76,9 +76,13 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
   const uint16_t *in_k = (const uint16_t *)a.in.k + b * a.in.k_b + hkv * a.in.k_h;
   const uint16_t *in_v = (const uint16_t *)a.in.v + b * a.in.v_b + hkv * a.in.v_h;
 
+  uint32_t koff[8], voff[2];
+  ktile_offsets(lane, koff);
+  vtile_offsets(lane, voff);
+
   auto issue_tile = [&](int it) {
     const uint16_t *kb_, *vb_;
-    int64_t kst, vst;
+    uint32_t kst, vst;
     int valid;
     if (it < n_st) {
       const int row0 = it * kTileKeys;
@@ -92,8 +96,8 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
       if (p0 >= a.t0) {
         kb_ = in_k + (p0 - a.t0) * a.in.k_t;
         vb_ = in_v + (p0 - a.t0) * a.in.v_t;
-        kst = a.in.k_t;
-        vst = a.in.v_t;
+        kst = (uint32_t)a.in.k_t;
+        vst = (uint32_t)a.in.v_t;
       } else {
         const int slot = (int)(p0 % dv.L);
         kb_ = ring_k + (int64_t)slot * D;
@@ -136,23 +140,20 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
     }
 
     f32x16 sacc[2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) sacc[i][v] = 0.f;
     // S^T = K . Q^T with a rolling window of eight K fragments in flight from LDS, so that a
     // matrix instruction does not wait for the read issued just before it
     {
       bf16x8 kf[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) kf[i] = ktile_frag(Kt, i & 1, i >> 1, lane);
+      for (int i = 0; i < 8; ++i) kf[i] = ktile_frag(Kt, koff, i & 1, i >> 1);
+      const f32x16 zero = {0.f};
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
 #pragma unroll
         for (int blk = 0; blk < 2; ++blk) {
           const int slot = (2 * ks + blk) & 7;
-          sacc[blk] = mfma32(kf[slot], qreg[ks], sacc[blk]);
-          if (ks + 4 < 8) kf[slot] = ktile_frag(Kt, blk, ks + 4, lane);
+          sacc[blk] = mfma32(kf[slot], qreg[ks], ks == 0 ? zero : sacc[blk]);
+          if (ks + 4 < 8) kf[slot] = ktile_frag(Kt, koff, blk, ks + 4);
         }
       }
       // pin that order: 8 LDS reads up front, then one read behind every matrix instruction
@@ -167,7 +168,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
     // first eight V^T fragments: issued now, consumed after the softmax arithmetic
     bf16x8 vf[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) vf[i] = vtile_frag(Vt, i & 3, i >> 2, lane);
+    for (int i = 0; i < 8; ++i) vf[i] = vtile_frag(Vt, voff, i & 3, i >> 2);
 
     if (is_state ? neg_state : neg_bswa) {
 #pragma unroll
@@ -220,7 +221,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
       for (int dblk = 0; dblk < 4; ++dblk) {
         const int i = 4 * ks + dblk, slot = i & 7;
         oacc[dblk] = mfma32(vf[slot], pb.v, oacc[dblk]);
-        if (i + 8 < 16) vf[slot] = vtile_frag(Vt, dblk, ks + 2, lane);
+        if (i + 8 < 16) vf[slot] = vtile_frag(Vt, voff, dblk, ks + 2);
       }
     }
   }

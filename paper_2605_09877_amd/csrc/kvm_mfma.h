@@ -89,29 +89,43 @@ typedef short v4i16 __attribute__((ext_vector_type(4)));
 
 constexpr int kTileElems = kTileKeys * kHeadDim;  // 8192 bf16 = 16 KiB
 
-// One wave fetches rows 4*bi .. 4*bi+3 (bi = 4*wave + n, n = 0..3) of a tile.  `vswz`: V layout.
-// Rows at or beyond rows_valid repeat the last valid row.
+// One wave fetches rows 4*bi .. 4*bi+3 (bi = 4*wave + n, n = 0..3) of a tile; kVSwz: V layout.
+// `base` is wave-uniform, the per-lane part is a 32-bit element offset.  Rows at or beyond
+// rows_valid repeat the last valid row (only looked at when the tile is not full).
 template <bool kVSwz>
-__device__ __forceinline__ void tile_dma(const uint16_t *base, int64_t stride, int rows_valid,
+__device__ __forceinline__ void tile_dma(const uint16_t *base, uint32_t stride, int rows_valid,
                                          uint16_t *lds_tile, int wave, int lane) {
+  const int rl = lane >> 4, c16 = lane & 15;
+  if (rows_valid >= kTileKeys) {
+    const uint32_t row_off = (uint32_t)(16 * wave + rl) * stride;
 #pragma unroll
-  for (int n = 0; n < 4; ++n) {
-    const int bi = 4 * wave + n;
-    int r = 4 * bi + (lane >> 4);
-    const int sw = kVSwz ? 2 * (r & 3) : (r & 15);
-    const int q = (lane & 15) ^ sw;
-    r = r < rows_valid ? r : rows_valid - 1;
-    __builtin_amdgcn_global_load_lds(base + (int64_t)r * stride + 8 * q, KVM_LDS_VOID(lds_tile + bi * 512),
-                                     16, 0, 0);
+    for (int n = 0; n < 4; ++n) {
+      const int q = kVSwz ? (c16 ^ (2 * rl)) : (c16 ^ (4 * n + rl));
+      const uint32_t off = row_off + (uint32_t)(4 * n) * stride + (uint32_t)(8 * q);
+      __builtin_amdgcn_global_load_lds(base + off, KVM_LDS_VOID(lds_tile + (4 * wave + n) * 512), 16, 0, 0);
+    }
+  } else {
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+      int r = 16 * wave + 4 * n + rl;
+      const int q = kVSwz ? (c16 ^ (2 * rl)) : (c16 ^ (4 * n + rl));
+      r = r < rows_valid ? r : rows_valid - 1;
+      const uint32_t off = (uint32_t)r * stride + (uint32_t)(8 * q);
+      __builtin_amdgcn_global_load_lds(base + off, KVM_LDS_VOID(lds_tile + (4 * wave + n) * 512), 16, 0, 0);
+    }
   }
 }
 
-// A-operand fragment of a swizzled K tile: row = 32*blk + lane%32, channels 16*ks + 8*(lane/32) ..
-__device__ __forceinline__ bf16x8 ktile_frag(const uint16_t *lds_tile, int blk, int ks, int lane) {
+// Per-lane LDS element offsets of the K fragments (one per 16-channel step; the row block adds
+// a constant): row = lane%32 (+32*blk), chunk (2*ks + lane/32) ^ (row & 15).
+__device__ __forceinline__ void ktile_offsets(int lane, uint32_t (&off)[8]) {
   const int l32 = lane & 31;
-  const int q = (2 * ks + (lane >> 5)) ^ (l32 & 15);
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) off[ks] = (uint32_t)(l32 * kHeadDim + 8 * ((2 * ks + (lane >> 5)) ^ (l32 & 15)));
+}
+__device__ __forceinline__ bf16x8 ktile_frag(const uint16_t *lds_tile, const uint32_t (&off)[8], int blk, int ks) {
   Frag8 f;
-  f.q = *reinterpret_cast<const uint4 *>(lds_tile + (32 * blk + l32) * kHeadDim + 8 * q);
+  f.q = *reinterpret_cast<const uint4 *>(lds_tile + off[ks] + 32 * blk * kHeadDim);
   return f.v;
 }
 
@@ -120,14 +134,21 @@ __device__ __forceinline__ bf16x8 ktile_frag(const uint16_t *lds_tile, int blk, 
 // (g = lane/32) -- the key order in which a lane holds P^T after the first product.
 // ds_read_b64_tr_b16: within 16 lanes, result element t of lane i = element i%4 of the 8 bytes
 // addressed by lane 4*t + i/4.  So lane j addresses key row K0 + j/4, channels dbase + 4*(j%4).
-__device__ __forceinline__ bf16x8 vtile_frag(const uint16_t *lds_tile, int dblk, int ks, int lane) {
+// The per-lane part of the address depends on dblk only through its low bit (it meets the row
+// swizzle in one bit), so two offsets cover all sixteen fragments; the rest are constants.
+__device__ __forceinline__ void vtile_offsets(int lane, uint32_t (&off)[2]) {
   const int j = lane & 15, t = j >> 2, c = j & 3;
   const int g = lane >> 5, half = (lane >> 4) & 1;
-  const int q = 4 * dblk + 2 * half + (c >> 1);            // 16-byte chunk of the channel run
-  const int r0 = 16 * ks + 4 * g + t;                        // r0 % 4 == t, (r0 + 8) % 4 == t
-  const int off = 8 * (q ^ (2 * t)) + 4 * (c & 1);
-  const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(KVM_LDS_V4(lds_tile + r0 * kHeadDim + off));
-  const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(KVM_LDS_V4(lds_tile + (r0 + 8) * kHeadDim + off));
+#pragma unroll
+  for (int odd = 0; odd < 2; ++odd) {
+    const int q = 4 * odd + 2 * half + (c >> 1);
+    off[odd] = (uint32_t)((4 * g + t) * kHeadDim + 8 * (q ^ (2 * t)) + 4 * (c & 1));
+  }
+}
+__device__ __forceinline__ bf16x8 vtile_frag(const uint16_t *lds_tile, const uint32_t (&off)[2], int dblk, int ks) {
+  const uint16_t *p = lds_tile + off[dblk & 1] + 16 * ks * kHeadDim + 64 * (dblk >> 1);
+  const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(KVM_LDS_V4(p));
+  const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(KVM_LDS_V4(p + 8 * kHeadDim));
   Frag8 f;
   f.d[0] = __builtin_bit_cast(uint2, lo);
   f.d[1] = __builtin_bit_cast(uint2, hi);
