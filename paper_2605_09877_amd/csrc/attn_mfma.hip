@@ -36,17 +36,25 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
   const int hq = blockIdx.y, b = blockIdx.z;
   const int hkv = hq / (dv.Hq / dv.Hkv);
   const int u = b * dv.Hkv + hkv;
-  const int Q0 = blockIdx.x * kTileQ;
+  // blockIdx.x = chunk of the launch, then query tile of the chunk; the tile with the longest
+  // causal part is scheduled first
+  const int tpc = (dv.C + kTileQ - 1) / kTileQ;
+  const int ci = blockIdx.x / tpc;
+  const int Q0 = (tpc - 1 - (int)(blockIdx.x % tpc)) * kTileQ;
+  const int nq = ci == a.n_chunks - 1 ? a.nq_total - ci * dv.C : dv.C;  // queries of this chunk
+  if (Q0 >= nq) return;
+  const int64_t cs = a.s + (int64_t)ci * dv.C;                           // chunk start position
+  const int64_t wb = cs + dv.C - dv.L > 0 ? cs + dv.C - dv.L : 0;        // first window position
   const int wq0 = Q0 + 32 * wave;
   const int myq = wq0 + l32;
-  const int nq = a.nq;
-  const int m = a.m;
+  const int m = a.m[ci];
 
   // Q^T fragments: query myq, channels 16*ks + 8*g .. +7
   bf16x8 qreg[8];
   {
     const int qc = myq < nq ? myq : nq - 1;
-    const uint16_t *qrow = (const uint16_t *)a.q + b * a.q_b + (int64_t)qc * a.q_t + hq * a.q_h;
+    const uint16_t *qrow =
+        (const uint16_t *)a.q + b * a.q_b + ((int64_t)ci * dv.C + qc) * a.q_t + hq * a.q_h;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
       Frag8 f;
@@ -65,12 +73,12 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
 
   const int n_st = (m + kTileKeys - 1) / kTileKeys;
   const int qend = (Q0 + kTileQ < nq) ? Q0 + kTileQ : nq;  // one past the last valid query here
-  const int n_win = (int)((a.s + qend - a.b + kTileKeys - 1) / kTileKeys);
+  const int n_win = (int)((cs + qend - wb + kTileKeys - 1) / kTileKeys);
   const int n_tiles = n_st + n_win;
-  const int64_t last_pos = a.s + nq - 1;
+  const int64_t last_pos = cs + nq - 1;
 
-  const uint16_t *khat = (const uint16_t *)dv.khat + (int64_t)u * dv.Mcap * D;
-  const uint16_t *vhat = (const uint16_t *)dv.vhat + (int64_t)u * dv.Mcap * D;
+  const uint16_t *khat = (const uint16_t *)dv.khat + a.slot[ci] * dv.slot_elems + (int64_t)u * dv.Mcap * D;
+  const uint16_t *vhat = (const uint16_t *)dv.vhat + a.slot[ci] * dv.slot_elems + (int64_t)u * dv.Mcap * D;
   const uint16_t *ring_k = (const uint16_t *)dv.winK + (int64_t)u * dv.L * D;
   const uint16_t *ring_v = (const uint16_t *)dv.winV + (int64_t)u * dv.L * D;
   const uint16_t *in_k = (const uint16_t *)a.in.k + b * a.in.k_b + hkv * a.in.k_h;
@@ -91,7 +99,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
       kst = vst = D;
       valid = m - row0;
     } else {
-      const int64_t p0 = a.b + (int64_t)(it - n_st) * kTileKeys;
+      const int64_t p0 = wb + (int64_t)(it - n_st) * kTileKeys;
       valid = (int)(last_pos - p0 + 1);
       if (p0 >= a.t0) {
         kb_ = in_k + (p0 - a.t0) * a.in.k_t;
@@ -127,7 +135,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
 
     const bool is_state = it < n_st;
     const int row0 = it * kTileKeys;
-    const int64_t p0 = a.b + (int64_t)(it - n_st) * kTileKeys;
+    const int64_t p0 = wb + (int64_t)(it - n_st) * kTileKeys;
     bool need_mask;
     float scale;
     if (is_state) {
@@ -135,8 +143,8 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
       need_mask = m - row0 < kTileKeys;
     } else {
       scale = c_bswa;
-      if (p0 > a.s + wq0 + 31) continue;  // every key of the tile lies after this wave's queries
-      need_mask = p0 + kTileKeys - 1 > a.s + wq0;
+      if (p0 > cs + wq0 + 31) continue;  // every key of the tile lies after this wave's queries
+      need_mask = p0 + kTileKeys - 1 > cs + wq0;
     }
 
     f32x16 sacc[2];
@@ -178,7 +186,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
     }
     if (need_mask) {
       // keys up to `lim` (tile-local) are visible to this lane's query
-      const int lim = is_state ? (m - row0 - 1) : (int)(a.s + myq - p0);
+      const int lim = is_state ? (m - row0 - 1) : (int)(cs + myq - p0);
 #pragma unroll
       for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
@@ -229,7 +237,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
   const float l = l_part + __shfl_xor(l_part, 32, kWave);
   if (myq < nq) {
     const float inv = 1.f / l;
-    uint16_t *orow = (uint16_t *)a.out + b * a.o_b + (int64_t)myq * a.o_t + hq * a.o_h;
+    uint16_t *orow = (uint16_t *)a.out + b * a.o_b + ((int64_t)ci * dv.C + myq) * a.o_t + hq * a.o_h;
 #pragma unroll
     for (int dblk = 0; dblk < 4; ++dblk)
 #pragma unroll
@@ -239,15 +247,15 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
         *reinterpret_cast<uint2 *>(orow + 32 * dblk + 8 * vq + 4 * g) = make_uint2(lo, hi);
       }
     if (a.lse && g == 0)
-      a.lse[b * a.lse_b + (int64_t)myq * a.lse_t + hq * a.lse_h] = (m_run + log2f(l)) * kLn2;
+      a.lse[b * a.lse_b + ((int64_t)ci * dv.C + myq) * a.lse_t + hq * a.lse_h] = (m_run + log2f(l)) * kLn2;
   }
 }
 
 }  // namespace
 
 hipError_t launch_attn_mfma(const Dev &dv, const AttnArgs &a, hipStream_t st) {
-  if (a.nq <= 0) return hipSuccess;
-  dim3 grid((a.nq + kTileQ - 1) / kTileQ, dv.Hq, dv.B);
+  if (a.nq_total <= 0) return hipSuccess;
+  dim3 grid(a.n_chunks * ((dv.C + kTileQ - 1) / kTileQ), dv.Hq, dv.B);
   hipLaunchKernelGGL(attn_mfma_kernel, grid, dim3(256), 0, st, dv, a);
   return hipGetLastError();
 }

@@ -62,6 +62,9 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(Dev dv, AttnArgs a) {
   const int hkv = hq / (dv.Hq / dv.Hkv);
   const int u = b * dv.Hkv + hkv;
   const int64_t pos = a.s + qi;
+  const int ci = (int)(pos / dv.C - a.s / dv.C);            // chunk of this query within the launch
+  const int64_t cs = pos / dv.C * dv.C;                      // its chunk starts here
+  const int64_t wb = cs + dv.C - dv.L > 0 ? cs + dv.C - dv.L : 0;  // first window position
 
   float qf[VEC];
   Frag<T>::load((const T *)a.q + b * a.q_b + (int64_t)qi * a.q_t + hq * a.q_h + cl * VEC, qf);
@@ -69,10 +72,10 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(Dev dv, AttnArgs a) {
   const float c_state = (dv.tau_state ? dv.tau_state[hq] : 1.f) * rs;
   const float c_bswa = (dv.tau_bswa ? dv.tau_bswa[hq] : 1.f) * rs;
 
-  const int m = a.m;
-  const int total = m + (int)(pos - a.b + 1);
-  const T *khat = (const T *)dv.khat + (int64_t)u * dv.Mcap * D;
-  const T *vhat = (const T *)dv.vhat + (int64_t)u * dv.Mcap * D;
+  const int m = a.m[ci];
+  const int total = m + (int)(pos - wb + 1);
+  const T *khat = (const T *)dv.khat + a.slot[ci] * dv.slot_elems + (int64_t)u * dv.Mcap * D;
+  const T *vhat = (const T *)dv.vhat + a.slot[ci] * dv.slot_elems + (int64_t)u * dv.Mcap * D;
   const T *ring_k = (const T *)dv.winK + (int64_t)u * dv.L * D;
   const T *ring_v = (const T *)dv.winV + (int64_t)u * dv.L * D;
   const T *in_k = (const T *)a.in.k + b * a.in.k_b + hkv * a.in.k_h;
@@ -94,7 +97,7 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(Dev dv, AttnArgs a) {
         kp = khat + (int64_t)nc * D;
         vp = vhat + (int64_t)nc * D;
       } else {
-        const int64_t p = a.b + (nc - m);
+        const int64_t p = wb + (nc - m);
         if (p >= a.t0) {
           kp = in_k + (p - a.t0) * a.in.k_t;
           vp = in_v + (p - a.t0) * a.in.v_t;
@@ -184,8 +187,8 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(Dev dv, AttnArgs a) {
 }  // namespace
 
 hipError_t launch_attn_rows(const Dev &dv, const AttnArgs &a, hipStream_t st) {
-  if (a.nq <= 0) return hipSuccess;
-  dim3 grid(a.nq, dv.Hq, dv.B);
+  if (a.nq_total <= 0) return hipSuccess;
+  dim3 grid(a.nq_total, dv.Hq, dv.B);
   if (dv.io == 0 && dv.d == 64)
     hipLaunchKernelGGL((attn_rows_kernel<float, 64>), grid, dim3(256), 0, st, dv, a);
   else if (dv.io == 0 && dv.d == 128)

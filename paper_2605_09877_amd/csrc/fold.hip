@@ -18,7 +18,7 @@ namespace kvm {
 namespace {
 
 template <typename T, int D>
-__device__ __forceinline__ void write_readout(const Dev &dv, int u, int h, int row,
+__device__ __forceinline__ void write_readout(const Dev &dv, int slot, int u, int h, int row,
                                               const double (&sk)[D / 64], const float (&sv)[D / 64],
                                               float rho, int lane) {
   constexpr int CPL = D / 64;
@@ -38,8 +38,8 @@ __device__ __forceinline__ void write_readout(const Dev &dv, int u, int h, int r
   for (int c = 0; c < CPL; ++c) nn += sv[c] * sv[c];
   const float nrm = sqrtf(wave_sum(nn));
   const float vs = rho / fmaxf(nrm, dv.norm_eps);
-  T *kh = (T *)dv.khat + ((int64_t)u * dv.Mcap + row) * D;
-  T *vh = (T *)dv.vhat + ((int64_t)u * dv.Mcap + row) * D;
+  T *kh = (T *)dv.khat + slot * dv.slot_elems + ((int64_t)u * dv.Mcap + row) * D;
+  T *vh = (T *)dv.vhat + slot * dv.slot_elems + ((int64_t)u * dv.Mcap + row) * D;
 #pragma unroll
   for (int c = 0; c < CPL; ++c) {
     const int ch = lane * CPL + c;
@@ -92,7 +92,7 @@ __global__ __launch_bounds__(256) void memkey_kernel(Dev dv, Src src) {
 // and the best eligible row.  Otherwise rows are the ones appended in this fold and only tokens
 // that were not appended themselves may move to them (strictly larger score only).
 template <typename T, int D>
-__global__ __launch_bounds__(256) void score_kernel(Dev dv, int row0, int row1, int first_pass) {
+__global__ __launch_bounds__(256) void score_kernel(Dev dv, int slot, int row0, int row1, int first_pass) {
   __shared__ double kb[4][D];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int u = blockIdx.y;
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(256) void score_kernel(Dev dv, int row0, int row1, 
   if (!active) return;
   double best_all = -INFINITY, best = -INFINITY;
   int best_i = 0x7fffffff;
-  const T *kh = (const T *)dv.khat + (int64_t)u * dv.Mcap * D;
+  const T *kh = (const T *)dv.khat + slot * dv.slot_elems + (int64_t)u * dv.Mcap * D;
   for (int i = row0 + lane; i < row1; i += 64) {
     const T *row = kh + (int64_t)i * D;
     double acc = 0.0;
@@ -194,7 +194,8 @@ __global__ __launch_bounds__(256) void select_kernel(Dev dv, int m, int n_app, i
 // second scoring pass, then merge.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void accum_kernel(Dev dv, Src src, int m_before, int m_after,
-                                                    int row_begin, int do_create, int do_merge) {
+                                                    int row_begin, int do_create, int do_merge,
+                                                    int slot_old, int slot_new) {
   constexpr int CPL = D / 64;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int u = blockIdx.y, b = u / dv.Hkv, h = u % dv.Hkv;
@@ -259,7 +260,23 @@ __global__ __launch_bounds__(256) void accum_kernel(Dev dv, Src src, int m_befor
       }
     }
   }
-  if (!loaded) return;  // untouched row: sums and readout stay as they are
+  if (!loaded) {
+    // untouched row: the sums stay; the new state version gets a copy of its readout (rows
+    // created earlier in this fold are in the new slot already)
+    if (do_merge && row < m_before) {
+      constexpr int kVecs = D * (int)sizeof(T) / 16;
+      const int64_t eo = ro * D * (int64_t)sizeof(T);
+      if (lane < kVecs) {
+        const char *ko = (const char *)dv.khat + slot_old * dv.slot_elems * (int64_t)sizeof(T) + eo;
+        const char *vo = (const char *)dv.vhat + slot_old * dv.slot_elems * (int64_t)sizeof(T) + eo;
+        char *kn = (char *)dv.khat + slot_new * dv.slot_elems * (int64_t)sizeof(T) + eo;
+        char *vn = (char *)dv.vhat + slot_new * dv.slot_elems * (int64_t)sizeof(T) + eo;
+        reinterpret_cast<uint4 *>(kn)[lane] = reinterpret_cast<const uint4 *>(ko)[lane];
+        reinterpret_cast<uint4 *>(vn)[lane] = reinterpret_cast<const uint4 *>(vo)[lane];
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int c = 0; c < CPL; ++c) {
     dv.sK[ro * D + lane * CPL + c] = sk[c];
@@ -270,12 +287,12 @@ __global__ __launch_bounds__(256) void accum_kernel(Dev dv, Src src, int m_befor
     dv.w[ro] = w;
     dv.n[ro] = n;
   }
-  write_readout<T, D>(dv, u, h, row, sk, sv, rho, lane);
+  write_readout<T, D>(dv, slot_new, u, h, row, sk, sv, rho, lane);
 }
 
 // Recompute the normalised readout of rows [0, m) from the stored sums (after an import).
 template <typename T, int D>
-__global__ __launch_bounds__(256) void refresh_kernel(Dev dv, int m) {
+__global__ __launch_bounds__(256) void refresh_kernel(Dev dv, int m, int slot) {
   constexpr int CPL = D / 64;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int u = blockIdx.y, h = u % dv.Hkv;
@@ -289,7 +306,7 @@ __global__ __launch_bounds__(256) void refresh_kernel(Dev dv, int m) {
     sk[c] = dv.sK[ro * D + lane * CPL + c];
     sv[c] = dv.sV[ro * D + lane * CPL + c];
   }
-  write_readout<T, D>(dv, u, h, row, sk, sv, dv.rho[ro], lane);
+  write_readout<T, D>(dv, slot, u, h, row, sk, sv, dv.rho[ro], lane);
 }
 
 // Copy positions [p0, p1) of a token source (its token 0 is position src_t0) into the ring.
@@ -333,9 +350,9 @@ hipError_t launch_memkey(const Dev &dv, const Src &src, hipStream_t st) {
   return hipGetLastError();
 }
 
-hipError_t launch_score(const Dev &dv, int row0, int row1, bool first_pass, hipStream_t st) {
+hipError_t launch_score(const Dev &dv, int slot, int row0, int row1, bool first_pass, hipStream_t st) {
   dim3 grid((dv.C + 3) / 4, dv.U);
-  KVM_DISPATCH(dv, score_kernel, grid, dim3(256), 0, st, dv, row0, row1, first_pass ? 1 : 0);
+  KVM_DISPATCH(dv, score_kernel, grid, dim3(256), 0, st, dv, slot, row0, row1, first_pass ? 1 : 0);
   return hipGetLastError();
 }
 
@@ -346,18 +363,18 @@ hipError_t launch_select(const Dev &dv, int m, int n_app, bool take_all, hipStre
 }
 
 hipError_t launch_accum(const Dev &dv, const Src &src, int m_before, int m_after, int row_begin,
-                        bool do_create, bool do_merge, hipStream_t st) {
+                        bool do_create, bool do_merge, int slot_old, int slot_new, hipStream_t st) {
   if (m_after <= row_begin) return hipSuccess;
   dim3 grid((m_after - row_begin + 3) / 4, dv.U);
   KVM_DISPATCH(dv, accum_kernel, grid, dim3(256), 0, st, dv, src, m_before, m_after, row_begin,
-               do_create ? 1 : 0, do_merge ? 1 : 0);
+               do_create ? 1 : 0, do_merge ? 1 : 0, slot_old, slot_new);
   return hipGetLastError();
 }
 
-hipError_t launch_refresh(const Dev &dv, int m, hipStream_t st) {
+hipError_t launch_refresh(const Dev &dv, int m, int slot, hipStream_t st) {
   if (m <= 0) return hipSuccess;
   dim3 grid((m + 3) / 4, dv.U);
-  KVM_DISPATCH(dv, refresh_kernel, grid, dim3(256), 0, st, dv, m);
+  KVM_DISPATCH(dv, refresh_kernel, grid, dim3(256), 0, st, dv, m, slot);
   return hipGetLastError();
 }
 

@@ -27,6 +27,11 @@ struct kvm_state {
   float *trace_score = nullptr;
   int64_t trace_max = 0;
   bool mfma = false;  // bf16, d = 128, C % 64 == 0: matrix-core kernels
+  int group = 1;      // chunks per attention launch in prefill; the readout has 2 * group slots
+  // prefill pipeline: folds run ahead on a library-owned stream, attention follows in groups
+  hipStream_t fold_stream = nullptr;
+  std::vector<hipEvent_t> sync_events;  // untimed events, reused call after call
+  size_t sync_used = 0;
   // optional kernel timing: (start, stop, class) event pairs, events reused across reads
   bool profile = false;
   struct Span {
@@ -128,6 +133,13 @@ struct Layout {
   size_t sK, sV, rho, w, n, khat, vhat, winK, winV, winG, kbar, score, pi, app, creator, total;
 };
 
+bool use_mfma(const kvm_config &c) {
+  return c.io_dtype == KVM_BF16 && c.head_dim == 128 && c.chunk_len % 64 == 0;
+}
+// Chunks per prefill attention launch.  The matrix-core path launches groups of chunks so that
+// a launch has thousands of workgroups; the generic path launches chunk by chunk.
+int group_of(const kvm_config &c) { return use_mfma(c) ? 8 : 1; }
+
 Layout layout_of(const kvm_config &c, int64_t Mcap) {
   const size_t U = (size_t)c.batch * c.n_kv_heads, d = c.head_dim, C = c.chunk_len;
   const size_t L = C * c.n_bswa_chunks, es = esize(c.io_dtype), M = (size_t)Mcap;
@@ -143,8 +155,9 @@ Layout layout_of(const kvm_config &c, int64_t Mcap) {
   l.rho = take(U * M * 4);
   l.w = take(U * M * 4);
   l.n = take(U * M * 4);
-  l.khat = take(U * M * d * es);
-  l.vhat = take(U * M * d * es);
+  const size_t NS = 2 * (size_t)group_of(c);
+  l.khat = take(NS * U * M * d * es);
+  l.vhat = take(NS * U * M * d * es);
   l.winK = take(U * L * d * es);
   l.winV = take(U * L * d * es);
   l.winG = take(U * L * 4);
@@ -189,6 +202,8 @@ void bind(Dev &dv, const kvm_config &c, void *buf, int64_t Mcap) {
   dv.L = c.chunk_len * c.n_bswa_chunks;
   dv.S = c.n_sink;
   dv.Mcap = (int32_t)Mcap;
+  dv.NS = 2 * group_of(c);
+  dv.slot_elems = (int64_t)dv.U * Mcap * dv.d;
   dv.ln_eps = c.ln_eps > 0.f ? c.ln_eps : 1e-5f;
   dv.norm_eps = c.norm_eps > 0.f ? c.norm_eps : 1e-12f;
   dv.io = c.io_dtype;
@@ -219,6 +234,7 @@ Src advance(const Src &s, int64_t tok, size_t es) {
 }
 
 // Fold the C-token block whose first token is src's token 0.  e = end of the chunk just attended.
+// Reads readout version `folds` (slot folds % NS), writes version folds + 1 into the next slot.
 int fold_block(kvm_state *st, const Src &src, int64_t e, int32_t *assign_out, float *score_out,
                hipStream_t stream) {
   const kvm_config &c = st->cfg;
@@ -228,26 +244,27 @@ int fold_block(kvm_state *st, const Src &src, int64_t e, int32_t *assign_out, fl
   const int64_t m_after = rows_after(c, st->table, m, e);
   const int n_app = (int)(m_after - m);
   if (m_after > dv.Mcap) return KVM_ERR_CAPACITY;
+  const int so = (int)(st->folds % dv.NS), sn = (int)((st->folds + 1) % dv.NS);
   HIP_TRY(kvm::launch_memkey(dv, src, stream));
   if (n_app == dv.C) {
     // room for the whole block (state creation included): no scores are needed
     HIP_TRY(kvm::launch_select(dv, (int)m, n_app, true, stream));
-    HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, 0, true, true, stream));
+    HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, 0, true, true, so, sn, stream));
   } else {
     if (st->mfma)
-      HIP_TRY(kvm::launch_score_mfma(dv, 0, (int)m, true, stream));
+      HIP_TRY(kvm::launch_score_mfma(dv, so, 0, (int)m, true, stream));
     else
-      HIP_TRY(kvm::launch_score(dv, 0, (int)m, true, stream));
+      HIP_TRY(kvm::launch_score(dv, so, 0, (int)m, true, stream));
     if (n_app > 0) {
       // new rows first, so that the remaining tokens can be scored against them too
       HIP_TRY(kvm::launch_select(dv, (int)m, n_app, false, stream));
-      HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, (int)m, true, false, stream));
+      HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, (int)m, true, false, so, sn, stream));
       if (st->mfma)
-        HIP_TRY(kvm::launch_score_mfma(dv, (int)m, (int)m_after, false, stream));
+        HIP_TRY(kvm::launch_score_mfma(dv, sn, (int)m, (int)m_after, false, stream));
       else
-        HIP_TRY(kvm::launch_score(dv, (int)m, (int)m_after, false, stream));
+        HIP_TRY(kvm::launch_score(dv, sn, (int)m, (int)m_after, false, stream));
     }
-    HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, 0, false, true, stream));
+    HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, 0, false, true, so, sn, stream));
   }
   const size_t ntok = (size_t)dv.U * dv.C;
   if (assign_out)
@@ -263,6 +280,18 @@ int fold_block(kvm_state *st, const Src &src, int64_t e, int32_t *assign_out, fl
   st->m = m_after;
   st->folds += 1;
   return KVM_OK;
+}
+
+// An untimed event from the state's pool (for ordering between the two streams).
+hipError_t next_sync_event(kvm_state *st, hipEvent_t *out) {
+  if (st->sync_used == st->sync_events.size()) {
+    hipEvent_t e;
+    hipError_t rc = hipEventCreateWithFlags(&e, hipEventDisableTiming);
+    if (rc != hipSuccess) return rc;
+    st->sync_events.push_back(e);
+  }
+  *out = st->sync_events[st->sync_used++];
+  return hipSuccess;
 }
 
 bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
@@ -340,7 +369,8 @@ int kvm_state_init(kvm_state **out, const kvm_config *cfg, void *dev_buf, size_t
   st->buf = dev_buf;
   st->bytes = bytes;
   bind(st->dv, st->cfg, dev_buf, Mcap);
-  st->mfma = cfg->io_dtype == KVM_BF16 && cfg->head_dim == 128 && cfg->chunk_len % 64 == 0;
+  st->mfma = use_mfma(*cfg);
+  st->group = group_of(*cfg);
   *out = st;
   return KVM_OK;
 }
@@ -352,6 +382,8 @@ int kvm_state_destroy(kvm_state *st) {
       (void)hipEventDestroy(sp.b);
     }
     for (auto e : st->free_events) (void)hipEventDestroy(e);
+    for (auto e : st->sync_events) (void)hipEventDestroy(e);
+    if (st->fold_stream) (void)hipStreamDestroy(st->fold_stream);
   }
   delete st;
   return KVM_OK;
@@ -419,9 +451,73 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
   in.g_b = s.g_b; in.g_h = s.g_h; in.g_t = s.g_t;
   const Src ring = ring_src(st);
 
-  for (int64_t cs = t0; cs < t_end; cs += C) {
-    const int64_t ce = cs + C < t_end ? cs + C : t_end;
+  // Plan.  The schedule is data independent: which state version (and how many rows) each chunk
+  // sees, and which chunks are followed by a fold, is integer arithmetic.
+  struct Chunk {
+    int64_t s;
+    int32_t nq, m;
+    int64_t ver;
+    bool folds;
+  };
+  std::vector<Chunk> plan;
+  {
+    int64_t m = st->m, ver = st->folds;
+    for (int64_t cs = t0; cs < t_end; cs += C) {
+      const int64_t ce = cs + C < t_end ? cs + C : t_end;
+      Chunk ch{cs, (int32_t)(ce - cs), (int32_t)m, ver, false};
+      if (ce - cs == C && ce >= L && c.budget_kind != KVM_BUDGET_NONE) {
+        ch.folds = true;
+        m = rows_after(c, st->table, m, ce);
+        ver += 1;
+      }
+      plan.push_back(ch);
+    }
+  }
+  // Folds depend only on k, v, g and the previous fold, so they run ahead on their own stream,
+  // each writing a fresh readout version; attention follows on the caller's stream in groups
+  // of chunks, each group waiting for the last version it reads.  A slot is rewritten only
+  // after the attention launch that read its previous version has finished.
+  if (!st->fold_stream) HIP_TRY(hipStreamCreateWithFlags(&st->fold_stream, hipStreamNonBlocking));
+  hipStream_t fstream = st->fold_stream;
+  st->sync_used = 0;
+  std::vector<hipEvent_t> slot_busy(dv.NS, nullptr);
+  hipEvent_t ev;
+  HIP_TRY(next_sync_event(st, &ev));
+  HIP_TRY(hipEventRecord(ev, stream));
+  HIP_TRY(hipStreamWaitEvent(fstream, ev, 0));
+  const int G = st->group;
+  const int n_chunks = (int)plan.size();
+  int next_fold = 0;                 // folds of chunks < next_fold are enqueued
+  hipEvent_t last_fold_ev = nullptr;
+  auto enqueue_folds_through = [&](int last_chunk) -> int {
+    for (; next_fold <= last_chunk && next_fold < n_chunks; ++next_fold) {
+      const Chunk &ch = plan[next_fold];
+      if (!ch.folds) continue;
+      const int sn = (int)((st->folds + 1) % dv.NS);
+      if (slot_busy[sn]) HIP_TRY(hipStreamWaitEvent(fstream, slot_busy[sn], 0));
+      const int64_t ce = ch.s + C, lo = ce - L;  // first token of the overflow block
+      int rc;
+      {
+        ProfileSpan span(st, 1, fstream);
+        if (lo >= t0)
+          rc = fold_block(st, advance(in, lo - t0, es), ce, nullptr, nullptr, fstream);
+        else
+          rc = fold_block(st, advance(ring, lo % L, es), ce, nullptr, nullptr, fstream);
+      }
+      if (rc != KVM_OK) return rc;
+      HIP_TRY(next_sync_event(st, &last_fold_ev));
+      HIP_TRY(hipEventRecord(last_fold_ev, fstream));
+    }
+    return KVM_OK;
+  };
+  for (int g0 = 0; g0 < n_chunks; g0 += G) {
+    const int g1 = g0 + G < n_chunks ? g0 + G : n_chunks;
+    // the last chunk of the group reads the version written by the fold after chunk g1 - 2
+    int rc = enqueue_folds_through(g1 - 2);
+    if (rc != KVM_OK) return rc;
+    if (last_fold_ev) HIP_TRY(hipStreamWaitEvent(stream, last_fold_ev, 0));
     AttnArgs a;
+    const int64_t cs = plan[g0].s;
     a.q = (const char *)q + (cs - t0) * s.q_t * (int64_t)es;
     a.out = (char *)out + (cs - t0) * s.o_t * (int64_t)es;
     a.lse = lse ? lse + (cs - t0) * s.lse_t : nullptr;
@@ -431,9 +527,12 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
     a.in = in;
     a.t0 = t0;
     a.s = cs;
-    a.nq = (int32_t)(ce - cs);
-    a.b = cs + C - L > 0 ? cs + C - L : 0;
-    a.m = (int32_t)st->m;
+    a.n_chunks = g1 - g0;
+    a.nq_total = (int32_t)((g1 - 1 - g0) * C + plan[g1 - 1].nq);
+    for (int i = 0; i < kvm::kMaxGroup; ++i) {
+      a.m[i] = i < g1 - g0 ? plan[g0 + i].m : 0;
+      a.slot[i] = i < g1 - g0 ? (int32_t)(plan[g0 + i].ver % dv.NS) : 0;
+    }
     {
       ProfileSpan span(st, 0, stream);
       if (st->mfma)
@@ -441,16 +540,14 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
       else
         HIP_TRY(kvm::launch_attn_rows(dv, a, stream));
     }
-    if (ce - cs == C && ce >= L) {
-      const int64_t lo = ce - L;  // first token of the overflow block
-      ProfileSpan span(st, 1, stream);
-      int rc;
-      if (lo >= t0)
-        rc = fold_block(st, advance(in, lo - t0, es), ce, nullptr, nullptr, stream);
-      else
-        rc = fold_block(st, advance(ring, lo % L, es), ce, nullptr, nullptr, stream);
-      if (rc != KVM_OK) return rc;
-    }
+    HIP_TRY(next_sync_event(st, &ev));
+    HIP_TRY(hipEventRecord(ev, stream));
+    for (int i = g0; i < g1; ++i) slot_busy[plan[i].ver % dv.NS] = ev;
+  }
+  {
+    int rc = enqueue_folds_through(n_chunks - 1);
+    if (rc != KVM_OK) return rc;
+    if (last_fold_ev) HIP_TRY(hipStreamWaitEvent(stream, last_fold_ev, 0));
   }
   // keep the last L tokens for the calls that follow
   const int64_t p0 = t_end - L > t0 ? t_end - L : t0;
@@ -485,10 +582,12 @@ int kvm_decode_step(kvm_state *st, const void *q, const void *k, const void *v,
   a.in = tok;
   a.t0 = INT64_MAX / 2;  // every window token comes from the ring
   a.s = u;
-  a.nq = 1;
-  const int64_t cs = u / C * C;
-  a.b = cs + C - L > 0 ? cs + C - L : 0;
-  a.m = (int32_t)st->m;
+  a.n_chunks = 1;
+  a.nq_total = 1;
+  for (int i = 0; i < kvm::kMaxGroup; ++i) {
+    a.m[i] = (int32_t)st->m;
+    a.slot[i] = (int32_t)(st->folds % dv.NS);
+  }
   {
     ProfileSpan span(st, 2, stream);
     HIP_TRY(kvm::launch_attn_rows(dv, a, stream));
@@ -573,8 +672,11 @@ int kvm_state_grow(kvm_state *st, void *new_buf, size_t new_bytes, int64_t new_m
   HIP_TRY(copy2d(nd.rho, od.rho, 4));
   HIP_TRY(copy2d(nd.w, od.w, 4));
   HIP_TRY(copy2d(nd.n, od.n, 4));
-  HIP_TRY(copy2d(nd.khat, od.khat, d * es));
-  HIP_TRY(copy2d(nd.vhat, od.vhat, d * es));
+  const int64_t slot = st->folds % od.NS;  // only the current version is live
+  HIP_TRY(copy2d((char *)nd.khat + slot * nd.slot_elems * (int64_t)es,
+                 (const char *)od.khat + slot * od.slot_elems * (int64_t)es, d * es));
+  HIP_TRY(copy2d((char *)nd.vhat + slot * nd.slot_elems * (int64_t)es,
+                 (const char *)od.vhat + slot * od.slot_elems * (int64_t)es, d * es));
   const size_t win = U * od.L * d * es;
   HIP_TRY(hipMemcpyAsync(nd.winK, od.winK, win, hipMemcpyDeviceToDevice, stream));
   HIP_TRY(hipMemcpyAsync(nd.winV, od.winV, win, hipMemcpyDeviceToDevice, stream));
@@ -602,8 +704,9 @@ int kvm_state_export(const kvm_state *st, double *sK, float *sV, float *rho, flo
   HIP_TRY(out2d(rho, dv.rho, 4));
   HIP_TRY(out2d(w, dv.w, 4));
   HIP_TRY(out2d(n, dv.n, 4));
-  HIP_TRY(out2d(khat, dv.khat, d * es));
-  HIP_TRY(out2d(vhat, dv.vhat, d * es));
+  const int64_t slot_off = (st->folds % dv.NS) * dv.slot_elems * (int64_t)es;
+  HIP_TRY(out2d(khat, (const char *)dv.khat + slot_off, d * es));
+  HIP_TRY(out2d(vhat, (const char *)dv.vhat + slot_off, d * es));
   const size_t win = U * dv.L * d * es;
   if (win_k) HIP_TRY(hipMemcpyAsync(win_k, dv.winK, win, hipMemcpyDeviceToDevice, stream));
   if (win_v) HIP_TRY(hipMemcpyAsync(win_v, dv.winV, win, hipMemcpyDeviceToDevice, stream));
@@ -635,7 +738,7 @@ int kvm_state_import(kvm_state *st, const double *sK, const float *sV, const flo
   if (win_k) HIP_TRY(hipMemcpyAsync(dv.winK, win_k, win, hipMemcpyDeviceToDevice, stream));
   if (win_v) HIP_TRY(hipMemcpyAsync(dv.winV, win_v, win, hipMemcpyDeviceToDevice, stream));
   if (win_g) HIP_TRY(hipMemcpyAsync(dv.winG, win_g, U * dv.L * 4, hipMemcpyDeviceToDevice, stream));
-  HIP_TRY(kvm::launch_refresh(dv, (int)m, stream));
+  HIP_TRY(kvm::launch_refresh(dv, (int)m, (int)(folds % dv.NS), stream));
   st->m = m;
   st->tokens = tokens_seen;
   st->folds = folds;

@@ -25,8 +25,13 @@ struct Dev {
   float *rho;    // [U, Mcap]    radius stored at row creation
   float *w;      // [U, Mcap]    1 + sum of merged gates (diagnostic)
   int32_t *n;    // [U, Mcap]    tokens in the row (diagnostic)
-  void *khat;    // [U, Mcap, d] I/O dtype: LN_s(sK)
-  void *vhat;    // [U, Mcap, d] I/O dtype: rho * sV / max(||sV||, eps)
+  // Normalised readout, one copy ("slot") per recent state version: version v (= number of
+  // folds done) lives in slot v % NS.  A fold reads the old version and writes the new one in
+  // full, so attention over earlier chunks can still be running on the old slots.
+  void *khat;    // [NS, U, Mcap, d] I/O dtype: LN_s(sK)
+  void *vhat;    // [NS, U, Mcap, d] I/O dtype: rho * sV / max(||sV||, eps)
+  int64_t slot_elems;  // U * Mcap * d
+  int32_t NS;
   // window ring: token p lives in slot p % L
   void *winK, *winV;  // [U, L, d] I/O dtype
   float *winG;        // [U, L]
@@ -44,31 +49,34 @@ struct Dev {
   int32_t io;  // KVM_F32 / KVM_BF16
 };
 
-// One chunk of prefill attention (or one decode token when nq == 1 per sequence).
+// One attention launch: the queries of up to kMaxGroup consecutive chunks (prefill), or one
+// query per sequence (decode).  Chunk boundaries are absolute multiples of C.
+constexpr int kMaxGroup = 16;
 struct AttnArgs {
   const void *q;
   void *out;
   float *lse;  // nullable
   int64_t q_b, q_t, q_h, o_b, o_t, o_h, lse_b, lse_t, lse_h;  // q/out/lse index 0 = position s
-  Src in;        // keys/values of this call: token index 0 = position t0
-  int64_t t0;    // positions below t0 come from the ring
-  int64_t s;     // position of the first query
-  int32_t nq;    // queries in this chunk (<= C)
-  int64_t b;     // first window position
-  int32_t m;     // state rows
+  Src in;            // keys/values of this call: token index 0 = position t0
+  int64_t t0;        // positions below t0 come from the ring
+  int64_t s;         // position of the first query of the launch
+  int32_t n_chunks;  // chunks covered
+  int32_t nq_total;  // queries covered (all chunks but the last are full)
+  int32_t m[kMaxGroup];     // state rows each chunk sees
+  int32_t slot[kMaxGroup];  // readout slot of that state version
 };
 
 // fold.hip
 hipError_t launch_memkey(const Dev &dv, const Src &src, hipStream_t st);
-hipError_t launch_score(const Dev &dv, int row0, int row1, bool first_pass, hipStream_t st);
+hipError_t launch_score(const Dev &dv, int slot, int row0, int row1, bool first_pass, hipStream_t st);
 hipError_t launch_select(const Dev &dv, int m, int n_app, bool take_all, hipStream_t st);
 hipError_t launch_accum(const Dev &dv, const Src &src, int m_before, int m_after, int row_begin,
-                        bool do_create, bool do_merge, hipStream_t st);
-hipError_t launch_refresh(const Dev &dv, int m, hipStream_t st);
+                        bool do_create, bool do_merge, int slot_old, int slot_new, hipStream_t st);
+hipError_t launch_refresh(const Dev &dv, int m, int slot, hipStream_t st);
 hipError_t launch_ring_copy(const Dev &dv, const Src &src, int64_t src_t0, int64_t p0, int64_t p1,
                             hipStream_t st);
 // score_mfma.hip (bf16, d = 128)
-hipError_t launch_score_mfma(const Dev &dv, int row0, int row1, bool first_pass, hipStream_t st);
+hipError_t launch_score_mfma(const Dev &dv, int slot, int row0, int row1, bool first_pass, hipStream_t st);
 // attn_rows.hip
 hipError_t launch_attn_rows(const Dev &dv, const AttnArgs &a, hipStream_t st);
 // attn_mfma.hip (bf16, d = 128)

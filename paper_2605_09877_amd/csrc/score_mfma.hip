@@ -16,7 +16,7 @@ namespace {
 
 constexpr int kTileTok = 128;  // tokens per workgroup (32 per wave)
 
-__global__ __launch_bounds__(256, 2) void score_mfma_kernel(Dev dv, int row0, int row1, int first_pass) {
+__global__ __launch_bounds__(256, 2) void score_mfma_kernel(Dev dv, int slot, int row0, int row1, int first_pass) {
   __shared__ __attribute__((aligned(16))) uint16_t Ks[kTileKeys * kKStride];
   constexpr int D = kHeadDim;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -40,7 +40,7 @@ __global__ __launch_bounds__(256, 2) void score_mfma_kernel(Dev dv, int row0, in
   float best_all = -INFINITY, best = -INFINITY;
   int best_i = 0x7fffffff;
 
-  const uint16_t *khat = (const uint16_t *)dv.khat + (int64_t)u * dv.Mcap * D;
+  const uint16_t *khat = (const uint16_t *)dv.khat + slot * dv.slot_elems + (int64_t)u * dv.Mcap * D;
   const int n_tiles = (row1 - row0 + kTileKeys - 1) / kTileKeys;
   uint4 kr[4];
   tile_rows_load(khat + (int64_t)row0 * D, D, min(kTileKeys, row1 - row0), tid, kr);
@@ -119,10 +119,10 @@ __global__ __launch_bounds__(256, 2) void score_mfma_kernel(Dev dv, int row0, in
 
 }  // namespace
 
-hipError_t launch_score_mfma(const Dev &dv, int row0, int row1, bool first_pass, hipStream_t st) {
+hipError_t launch_score_mfma(const Dev &dv, int slot, int row0, int row1, bool first_pass, hipStream_t st) {
   if (row1 <= row0) return hipSuccess;
   dim3 grid((dv.C + kTileTok - 1) / kTileTok, dv.U);
-  hipLaunchKernelGGL(score_mfma_kernel, grid, dim3(256), 0, st, dv, row0, row1, first_pass ? 1 : 0);
+  hipLaunchKernelGGL(score_mfma_kernel, grid, dim3(256), 0, st, dv, slot, row0, row1, first_pass ? 1 : 0);
   return hipGetLastError();
 }
 
