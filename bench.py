@@ -66,9 +66,10 @@ def prefill_leg(args, pkg, synth, dev):
     prof = st.profile_read()
     st.profile(False)
     tokens = w.batch * w.seq
-    flops, launches = attention_flops(w, w.seq)
+    flops, _ = attention_flops(w, w.seq)
     attn_ms, attn_n = prof["attn"]
     fold_ms, fold_n = prof["fold"]
+    launches = max(attn_n // max(args.steps, 1), 1)      # attention launches per step (groups of chunks)
     avg_launch_s = attn_ms / max(attn_n, 1) * 1e-3
     achieved = flops / launches / avg_launch_s / 1e12 if attn_n else 0.0
     res = dict(

@@ -5,6 +5,7 @@
 //   memkey : k-bar_j = LN_s(k_j with the rotary channels zeroed), materialised in the I/O dtype
 //   score  : s_j = max_i k-bar_j . s-hat^K_i and pi(j) = argmax_{i >= S}   (generic, fp64 dot)
 //   select : the n_append smallest s_j become new rows, in position order
+//   index  : merged tokens are sorted by (target row, position); per-row counts and offsets
 //   accum  : new rows are created, merged tokens are added to their row in position order,
 //            touched rows get their normalised readout (LN_s on keys, stored radius on values)
 //
@@ -52,13 +53,15 @@ __device__ __forceinline__ void write_readout(const Dev &dv, int slot, int u, in
 }
 
 // ------------------------------------------------------------------ memory keys
+// Covers n_blocks consecutive C-token blocks of `src`; block i goes to the i-th [U, C, d] slab
+// after dv.kbar (memory keys depend on k alone, so a prefill computes them a group at a time).
 template <typename T, int D>
-__global__ __launch_bounds__(256) void memkey_kernel(Dev dv, Src src) {
+__global__ __launch_bounds__(256) void memkey_kernel(Dev dv, Src src, int n_blocks) {
   constexpr int CPL = D / 64;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int u = blockIdx.y, b = u / dv.Hkv, h = u % dv.Hkv;
   const int j = blockIdx.x * 4 + wave;
-  if (j >= dv.C) return;
+  if (j >= dv.C * n_blocks) return;
   const T *krow = (const T *)src.k + b * src.k_b + h * src.k_h + (int64_t)j * src.k_t;
   double x[CPL];
   double s = 0.0;
@@ -76,7 +79,7 @@ __global__ __launch_bounds__(256) void memkey_kernel(Dev dv, Src src) {
     q += dl * dl;
   }
   const double den = sqrt(wave_sum(q) / (double)D + (double)dv.ln_eps);
-  T *out = (T *)dv.kbar + ((int64_t)u * dv.C + j) * D;
+  T *out = (T *)dv.kbar + ((int64_t)(j / dv.C) * dv.U * dv.C + (int64_t)u * dv.C + j % dv.C) * D;
 #pragma unroll
   for (int c = 0; c < CPL; ++c) {
     const int ch = lane * CPL + c;
@@ -186,16 +189,86 @@ __global__ __launch_bounds__(256) void select_kernel(Dev dv, int m, int n_app, i
   }
 }
 
+// ------------------------------------------------------------------ winners of split scoring + merge index
+// One workgroup per unit.  n_splits > 0: the scoring pass left one candidate per row split and
+// token; they are merged here in ascending row order (a later split wins only with a strictly
+// larger score, so ties keep the lowest row).  do_index: tokens that merge are counting-sorted
+// by target row, stably in position, so that the accumulate pass can walk each row's tokens in
+// ascending position without searching.
+__global__ __launch_bounds__(512) void index_kernel(Dev dv, int m_after, int n_splits, int do_index) {
+  extern __shared__ int shi[];  // m_after counters, then C targets
+  int *cnt = shi;
+  int *tgt = shi + m_after;
+  const int u = blockIdx.x, C = dv.C;
+  const int64_t base = (int64_t)u * C;
+  if (n_splits > 0) {
+    for (int j = threadIdx.x; j < C; j += blockDim.x) {
+      float best_all = -INFINITY, best = -INFINITY;
+      int best_i = 0x7fffffff;
+      for (int r = 0; r < n_splits; ++r) {
+        const float4 cd = dv.cand[(base + j) * kScoreSplits + r];
+        best_all = fmaxf(best_all, cd.x);
+        if (cd.y > best) {
+          best = cd.y;
+          best_i = __float_as_int(cd.z);
+        }
+      }
+      dv.score[base + j] = make_float2(best_all, best);
+      dv.pi[base + j] = best_i;
+      dv.app[base + j] = -1;
+      tgt[j] = best_i;
+    }
+  } else if (do_index) {
+    for (int j = threadIdx.x; j < C; j += blockDim.x) tgt[j] = dv.app[base + j] < 0 ? dv.pi[base + j] : -1;
+  }
+  if (!do_index) return;
+  for (int i = threadIdx.x; i < m_after; i += blockDim.x) cnt[i] = 0;
+  __syncthreads();
+  for (int j = threadIdx.x; j < C; j += blockDim.x)
+    if (tgt[j] >= 0) atomicAdd(&cnt[tgt[j]], 1);
+  __syncthreads();
+  // exclusive scan of the counters by one wave (m_after is a few thousand at most)
+  if (threadIdx.x < 64) {
+    const int lane = threadIdx.x;
+    const int per = (m_after + 63) / 64;
+    const int lo = lane * per, hi = min(lo + per, m_after);
+    int sum = 0;
+    for (int i = lo; i < hi; ++i) sum += cnt[i];
+    int incl = sum;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int v = __shfl_up(incl, o, kWave);
+      if (lane >= o) incl += v;
+    }
+    int run = incl - sum;
+    for (int i = lo; i < hi; ++i) {
+      const int c = cnt[i];
+      dv.row_cnt[(int64_t)u * dv.Mcap + i] = c;
+      dv.row_start[(int64_t)u * dv.Mcap + i] = run;
+      cnt[i] = run;  // becomes the row's start offset
+      run += c;
+    }
+  }
+  __syncthreads();
+  for (int j = threadIdx.x; j < C; j += blockDim.x) {
+    const int t = tgt[j];
+    if (t < 0) continue;
+    int rank = 0;
+    for (int i = 0; i < j; ++i) rank += tgt[i] == t ? 1 : 0;
+    dv.order[base + cnt[t] + rank] = j;
+  }
+}
+
 // ------------------------------------------------------------------ create + merge + readout refresh
-// One wave per state row in [row_begin, m_after) of the updated state.  Tokens are added in
-// ascending position.  do_create: rows >= m_before are created from their creator token;
-// do_merge: tokens whose target is the row are added.  A fold that appends only part of the
-// block runs create first (so the new rows have a normalised key to score against), then the
-// second scoring pass, then merge.
+// One wave per state row in [row_begin, m_after) of the updated state.  do_create: rows >=
+// m_before are created from their creator token; do_merge: the row's tokens (index_kernel) are
+// added in ascending position; do_copy: an untouched row's readout is copied to the new state
+// version.  A fold that appends only part of the block runs create first (so the new rows have
+// a normalised key to score against), then the second scoring pass, then merge.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void accum_kernel(Dev dv, Src src, int m_before, int m_after,
                                                     int row_begin, int do_create, int do_merge,
-                                                    int slot_old, int slot_new) {
+                                                    int do_copy, int slot_old, int slot_new) {
   constexpr int CPL = D / 64;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int u = blockIdx.y, b = u / dv.Hkv, h = u % dv.Hkv;
@@ -229,25 +302,25 @@ __global__ __launch_bounds__(256) void accum_kernel(Dev dv, Src src, int m_befor
     n = 1;
     loaded = true;
   }
-  if (do_merge && row >= dv.S) {
-    for (int j0 = 0; j0 < C; j0 += 64) {
-      const int j = j0 + lane;
-      const bool mine = j < C && dv.pi[base + j] == row && dv.app[base + j] < 0;
-      uint64_t mask = __ballot(mine);
-      if (mask && !loaded) {
+  const int cnt = (do_merge && row >= dv.S) ? dv.row_cnt[ro] : 0;
+  if (cnt > 0) {
+    if (!loaded) {
 #pragma unroll
-        for (int c = 0; c < CPL; ++c) {
-          sk[c] = dv.sK[ro * D + lane * CPL + c];
-          sv[c] = dv.sV[ro * D + lane * CPL + c];
-        }
-        rho = dv.rho[ro];
-        w = dv.w[ro];
-        n = dv.n[ro];
-        loaded = true;
+      for (int c = 0; c < CPL; ++c) {
+        sk[c] = dv.sK[ro * D + lane * CPL + c];
+        sv[c] = dv.sV[ro * D + lane * CPL + c];
       }
-      while (mask) {
-        const int t = j0 + __builtin_ctzll(mask);
-        mask &= mask - 1;
+      rho = dv.rho[ro];
+      w = dv.w[ro];
+      n = dv.n[ro];
+      loaded = true;
+    }
+    const int32_t *ord = dv.order + base + dv.row_start[ro];
+    for (int i0 = 0; i0 < cnt; i0 += 64) {
+      const int mine = i0 + lane < cnt ? ord[i0 + lane] : 0;   // this row's tokens, ascending position
+      const int nb = min(64, cnt - i0);
+      for (int i = 0; i < nb; ++i) {
+        const int t = __shfl(mine, i, kWave);
         const float g = gsrc ? gsrc[(int64_t)t * src.g_t] : 1.f;
 #pragma unroll
         for (int c = 0; c < CPL; ++c) {
@@ -261,9 +334,8 @@ __global__ __launch_bounds__(256) void accum_kernel(Dev dv, Src src, int m_befor
     }
   }
   if (!loaded) {
-    // untouched row: the sums stay; the new state version gets a copy of its readout (rows
-    // created earlier in this fold are in the new slot already)
-    if (do_merge && row < m_before) {
+    // untouched row: the sums stay; the new state version gets a copy of its readout
+    if (do_copy && row < m_before) {
       constexpr int kVecs = D * (int)sizeof(T) / 16;
       const int64_t eo = ro * D * (int64_t)sizeof(T);
       if (lane < kVecs) {
@@ -344,9 +416,9 @@ __global__ __launch_bounds__(64) void ring_copy_kernel(Dev dv, Src src, int64_t 
 
 }  // namespace
 
-hipError_t launch_memkey(const Dev &dv, const Src &src, hipStream_t st) {
-  dim3 grid((dv.C + 3) / 4, dv.U);
-  KVM_DISPATCH(dv, memkey_kernel, grid, dim3(256), 0, st, dv, src);
+hipError_t launch_memkey(const Dev &dv, const Src &src, int n_blocks, hipStream_t st) {
+  dim3 grid((dv.C * n_blocks + 3) / 4, dv.U);
+  KVM_DISPATCH(dv, memkey_kernel, grid, dim3(256), 0, st, dv, src, n_blocks);
   return hipGetLastError();
 }
 
@@ -362,12 +434,19 @@ hipError_t launch_select(const Dev &dv, int m, int n_app, bool take_all, hipStre
   return hipGetLastError();
 }
 
+hipError_t launch_index(const Dev &dv, int m_after, int n_splits, bool do_index, hipStream_t st) {
+  hipLaunchKernelGGL(index_kernel, dim3(dv.U), dim3(512), (size_t)(m_after + dv.C) * 4, st, dv, m_after,
+                     n_splits, do_index ? 1 : 0);
+  return hipGetLastError();
+}
+
 hipError_t launch_accum(const Dev &dv, const Src &src, int m_before, int m_after, int row_begin,
-                        bool do_create, bool do_merge, int slot_old, int slot_new, hipStream_t st) {
+                        bool do_create, bool do_merge, bool do_copy, int slot_old, int slot_new,
+                        hipStream_t st) {
   if (m_after <= row_begin) return hipSuccess;
   dim3 grid((m_after - row_begin + 3) / 4, dv.U);
   KVM_DISPATCH(dv, accum_kernel, grid, dim3(256), 0, st, dv, src, m_before, m_after, row_begin,
-               do_create ? 1 : 0, do_merge ? 1 : 0, slot_old, slot_new);
+               do_create ? 1 : 0, do_merge ? 1 : 0, do_copy ? 1 : 0, slot_old, slot_new);
   return hipGetLastError();
 }
 

@@ -130,7 +130,8 @@ int64_t capacity_rows(const kvm_config &c, const std::vector<int64_t> &table, in
 }
 
 struct Layout {
-  size_t sK, sV, rho, w, n, khat, vhat, winK, winV, winG, kbar, score, pi, app, creator, total;
+  size_t sK, sV, rho, w, n, khat, vhat, winK, winV, winG, kbar, score, pi, app, creator, cand, row_cnt,
+      row_start, order, total;
 };
 
 bool use_mfma(const kvm_config &c) {
@@ -161,11 +162,15 @@ Layout layout_of(const kvm_config &c, int64_t Mcap) {
   l.winK = take(U * L * d * es);
   l.winV = take(U * L * d * es);
   l.winG = take(U * L * 4);
-  l.kbar = take(U * C * d * es);
+  l.kbar = take((size_t)group_of(c) * U * C * d * es);
   l.score = take(U * C * 8);
   l.pi = take(U * C * 4);
   l.app = take(U * C * 4);
   l.creator = take(U * C * 4);
+  l.cand = take(U * C * kvm::kScoreSplits * 16);
+  l.row_cnt = take(U * M * 4);
+  l.row_start = take(U * M * 4);
+  l.order = take(U * C * 4);
   l.total = o;
   return l;
 }
@@ -188,6 +193,10 @@ void bind(Dev &dv, const kvm_config &c, void *buf, int64_t Mcap) {
   dv.pi = (int32_t *)(p + l.pi);
   dv.app = (int32_t *)(p + l.app);
   dv.creator = (int32_t *)(p + l.creator);
+  dv.cand = (float4 *)(p + l.cand);
+  dv.row_cnt = (int32_t *)(p + l.row_cnt);
+  dv.row_start = (int32_t *)(p + l.row_start);
+  dv.order = (int32_t *)(p + l.order);
   dv.gamma = c.ln_gamma;
   dv.beta = c.ln_beta;
   dv.tau_state = c.tau_state;
@@ -235,36 +244,45 @@ Src advance(const Src &s, int64_t tok, size_t es) {
 
 // Fold the C-token block whose first token is src's token 0.  e = end of the chunk just attended.
 // Reads readout version `folds` (slot folds % NS), writes version folds + 1 into the next slot.
+// kbar_block >= 0: the block's memory keys were already computed into that slab of the scratch.
 int fold_block(kvm_state *st, const Src &src, int64_t e, int32_t *assign_out, float *score_out,
-               hipStream_t stream) {
+               hipStream_t stream, int kbar_block = -1) {
   const kvm_config &c = st->cfg;
-  const Dev &dv = st->dv;
   if (c.budget_kind == KVM_BUDGET_NONE) return KVM_OK;
   const int64_t m = st->m;
   const int64_t m_after = rows_after(c, st->table, m, e);
   const int n_app = (int)(m_after - m);
-  if (m_after > dv.Mcap) return KVM_ERR_CAPACITY;
+  if (m_after > st->dv.Mcap) return KVM_ERR_CAPACITY;
+  Dev dv = st->dv;
+  if (kbar_block < 0) {
+    HIP_TRY(kvm::launch_memkey(dv, src, 1, stream));
+  } else {
+    dv.kbar = (char *)dv.kbar + (size_t)kbar_block * dv.U * dv.C * dv.d * esize(c.io_dtype);
+  }
   const int so = (int)(st->folds % dv.NS), sn = (int)((st->folds + 1) % dv.NS);
-  HIP_TRY(kvm::launch_memkey(dv, src, stream));
   if (n_app == dv.C) {
     // room for the whole block (state creation included): no scores are needed
     HIP_TRY(kvm::launch_select(dv, (int)m, n_app, true, stream));
-    HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, 0, true, true, so, sn, stream));
+    HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, 0, true, false, true, so, sn, stream));
   } else {
+    int splits = 0;  // > 0: candidates per row split wait in dv.cand for index_kernel
     if (st->mfma)
-      HIP_TRY(kvm::launch_score_mfma(dv, so, 0, (int)m, true, stream));
+      HIP_TRY(kvm::launch_score_mfma(dv, so, 0, (int)m, true, &splits, stream));
     else
       HIP_TRY(kvm::launch_score(dv, so, 0, (int)m, true, stream));
     if (n_app > 0) {
       // new rows first, so that the remaining tokens can be scored against them too
+      if (splits > 0) HIP_TRY(kvm::launch_index(dv, (int)m_after, splits, false, stream));
       HIP_TRY(kvm::launch_select(dv, (int)m, n_app, false, stream));
-      HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, (int)m, true, false, so, sn, stream));
+      HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, (int)m, true, false, false, so, sn, stream));
       if (st->mfma)
-        HIP_TRY(kvm::launch_score_mfma(dv, sn, (int)m, (int)m_after, false, stream));
+        HIP_TRY(kvm::launch_score_mfma(dv, sn, (int)m, (int)m_after, false, nullptr, stream));
       else
         HIP_TRY(kvm::launch_score(dv, sn, (int)m, (int)m_after, false, stream));
+      splits = 0;
     }
-    HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, 0, false, true, so, sn, stream));
+    HIP_TRY(kvm::launch_index(dv, (int)m_after, splits, true, stream));
+    HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, 0, false, true, true, so, sn, stream));
   }
   const size_t ntok = (size_t)dv.U * dv.C;
   if (assign_out)
@@ -490,23 +508,39 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
   int next_fold = 0;                 // folds of chunks < next_fold are enqueued
   hipEvent_t last_fold_ev = nullptr;
   auto enqueue_folds_through = [&](int last_chunk) -> int {
-    for (; next_fold <= last_chunk && next_fold < n_chunks; ++next_fold) {
-      const Chunk &ch = plan[next_fold];
-      if (!ch.folds) continue;
-      const int sn = (int)((st->folds + 1) % dv.NS);
-      if (slot_busy[sn]) HIP_TRY(hipStreamWaitEvent(fstream, slot_busy[sn], 0));
-      const int64_t ce = ch.s + C, lo = ce - L;  // first token of the overflow block
-      int rc;
-      {
-        ProfileSpan span(st, 1, fstream);
-        if (lo >= t0)
-          rc = fold_block(st, advance(in, lo - t0, es), ce, nullptr, nullptr, fstream);
-        else
-          rc = fold_block(st, advance(ring, lo % L, es), ce, nullptr, nullptr, fstream);
+    while (next_fold <= last_chunk && next_fold < n_chunks) {
+      if (!plan[next_fold].folds) {
+        ++next_fold;
+        continue;
       }
-      if (rc != KVM_OK) return rc;
-      HIP_TRY(next_sync_event(st, &last_fold_ev));
-      HIP_TRY(hipEventRecord(last_fold_ev, fstream));
+      // a run of folds whose overflow blocks are consecutive in this call's k: their memory
+      // keys are computed by one launch (blocks taken from the ring go one at a time)
+      const int64_t lo0 = plan[next_fold].s + C - L;
+      int run = 1;
+      if (lo0 >= t0)
+        while (run < G && next_fold + run <= last_chunk && next_fold + run < n_chunks &&
+               plan[next_fold + run].folds)
+          ++run;
+      const bool batched = lo0 >= t0;
+      for (int i = 0; i < run; ++i) {
+        const Chunk &ch = plan[next_fold + i];
+        const int sn = (int)((st->folds + 1) % dv.NS);
+        if (slot_busy[sn]) HIP_TRY(hipStreamWaitEvent(fstream, slot_busy[sn], 0));
+        const int64_t ce = ch.s + C, lo = ce - L;  // first token of the overflow block
+        int rc;
+        {
+          ProfileSpan span(st, 1, fstream);
+          if (batched && i == 0) HIP_TRY(kvm::launch_memkey(dv, advance(in, lo0 - t0, es), run, fstream));
+          if (batched)
+            rc = fold_block(st, advance(in, lo - t0, es), ce, nullptr, nullptr, fstream, i);
+          else
+            rc = fold_block(st, advance(ring, lo % L, es), ce, nullptr, nullptr, fstream);
+        }
+        if (rc != KVM_OK) return rc;
+        HIP_TRY(next_sync_event(st, &last_fold_ev));
+        HIP_TRY(hipEventRecord(last_fold_ev, fstream));
+      }
+      next_fold += run;
     }
     return KVM_OK;
   };

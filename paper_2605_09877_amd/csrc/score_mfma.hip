@@ -5,7 +5,9 @@
 // D[row, token] = K-hat_tile . K-bar^T: a lane holds one token column, so the running maximum
 // and its row index are per-lane scalars scanned in ascending row order (ties keep the lowest
 // row); the two lane halves of a token are merged once at the end.  Each wave keeps the memory
-// keys of its 32 tokens in registers; state rows stream through LDS in 64-row tiles.
+// keys of its 32 tokens in registers; state rows stream HBM -> LDS (direct loads, swizzled,
+// double buffered) in 64-row tiles.  The rows are split over gridDim.y workgroups so that one
+// fold fills the chip; each split leaves a candidate per token and index_kernel merges them.
 #include "kvm_device.h"
 #include "kvm_internal.h"
 #include "kvm_mfma.h"
@@ -17,15 +19,21 @@ namespace {
 constexpr int kTileTok = 128;  // tokens per workgroup (32 per wave)
 
 __global__ __launch_bounds__(256, 2) void score_mfma_kernel(Dev dv, int slot, int row0, int row1, int first_pass) {
-  __shared__ __attribute__((aligned(16))) uint16_t Ks[kTileKeys * kKStride];
+  __shared__ __attribute__((aligned(1024))) uint16_t Ks[2][kTileElems];
   constexpr int D = kHeadDim;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 5, l32 = lane & 31;
-  const int u = blockIdx.y;
+  const int u = blockIdx.z;
   const int tok0 = blockIdx.x * kTileTok + 32 * wave;
   const bool wave_active = tok0 < dv.C;  // C is a multiple of 32: a wave is all in or all out
   const int j = tok0 + l32;
   const int64_t tj = (int64_t)u * dv.C + (wave_active ? j : 0);
+
+  // this workgroup's share of the row tiles
+  const int tiles_all = (row1 - row0 + kTileKeys - 1) / kTileKeys;
+  const int per_split = (tiles_all + (int)gridDim.y - 1) / (int)gridDim.y;
+  const int t_begin = (int)blockIdx.y * per_split;
+  const int t_end = min(t_begin + per_split, tiles_all);
 
   bf16x8 kreg[8];
   if (wave_active) {
@@ -39,31 +47,46 @@ __global__ __launch_bounds__(256, 2) void score_mfma_kernel(Dev dv, int slot, in
   }
   float best_all = -INFINITY, best = -INFINITY;
   int best_i = 0x7fffffff;
+  uint32_t koff[8];
+  ktile_offsets(lane, koff);
 
-  const uint16_t *khat = (const uint16_t *)dv.khat + slot * dv.slot_elems + (int64_t)u * dv.Mcap * D;
-  const int n_tiles = (row1 - row0 + kTileKeys - 1) / kTileKeys;
-  uint4 kr[4];
-  tile_rows_load(khat + (int64_t)row0 * D, D, min(kTileKeys, row1 - row0), tid, kr);
-  for (int it = 0; it < n_tiles; ++it) {
+  const uint16_t *khat = (const uint16_t *)dv.khat + slot * dv.slot_elems + ((int64_t)u * dv.Mcap + row0) * D;
+  auto issue_tile = [&](int t) {
+    const int base = t * kTileKeys;
+    tile_dma<false>(khat + (int64_t)base * D, D, min(kTileKeys, row1 - row0 - base), Ks[t & 1], wave, lane);
+  };
+  if (t_begin < t_end) issue_tile(t_begin);
+  for (int t = t_begin; t < t_end; ++t) {
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
-    tile_rows_to_lds(Ks, tid, kr);
-    __syncthreads();
-    const int base = row0 + it * kTileKeys;
-    if (it + 1 < n_tiles)
-      tile_rows_load(khat + (int64_t)(base + kTileKeys) * D, D, min(kTileKeys, row1 - base - kTileKeys),
-                     tid, kr);
+    if (t + 1 < t_end) issue_tile(t + 1);
     if (!wave_active) continue;
+    const uint16_t *Kt = Ks[t & 1];
     f32x16 acc[2];
+    {
+      bf16x8 kf[8];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < 8; ++i) kf[i] = ktile_frag(Kt, koff, i & 1, i >> 1);
+      const f32x16 zero = {0.f};
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+      for (int ks = 0; ks < 8; ++ks) {
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks)
+        for (int blk = 0; blk < 2; ++blk) {
+          const int sl = (2 * ks + blk) & 7;
+          acc[blk] = mfma32(kf[sl], kreg[ks], ks == 0 ? zero : acc[blk]);
+          if (ks + 4 < 8) kf[sl] = ktile_frag(Kt, koff, blk, ks + 4);
+        }
+      }
+      __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
 #pragma unroll
-      for (int blk = 0; blk < 2; ++blk)
-        acc[blk] = mfma32(tile_rows_frag(Ks, blk, ks, lane), kreg[ks], acc[blk]);
+      for (int i = 0; i < 8; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+    }
     // rows this lane sees, ascending: blk, then v
+    const int base = row0 + t * kTileKeys;
     const bool edge = base < dv.S || base + kTileKeys > row1;
     if (edge) {
 #pragma unroll
@@ -107,9 +130,7 @@ __global__ __launch_bounds__(256, 2) void score_mfma_kernel(Dev dv, int slot, in
   }
   if (g == 0) {
     if (first_pass) {
-      dv.score[tj] = make_float2(best_all, best);
-      dv.pi[tj] = best_i;
-      dv.app[tj] = -1;
+      dv.cand[tj * kScoreSplits + blockIdx.y] = make_float4(best_all, best, __int_as_float(best_i), 0.f);
     } else if (dv.app[tj] < 0 && best_i != 0x7fffffff && best > dv.score[tj].y) {
       dv.score[tj].y = best;
       dv.pi[tj] = best_i;
@@ -119,9 +140,15 @@ __global__ __launch_bounds__(256, 2) void score_mfma_kernel(Dev dv, int slot, in
 
 }  // namespace
 
-hipError_t launch_score_mfma(const Dev &dv, int slot, int row0, int row1, bool first_pass, hipStream_t st) {
+// first_pass: returns the number of row splits used through *n_splits (candidates are left in
+// dv.cand for index_kernel); otherwise one split updates score/pi in place.
+hipError_t launch_score_mfma(const Dev &dv, int slot, int row0, int row1, bool first_pass, int *n_splits,
+                             hipStream_t st) {
   if (row1 <= row0) return hipSuccess;
-  dim3 grid((dv.C + kTileTok - 1) / kTileTok, dv.U);
+  const int tiles = (row1 - row0 + kTileKeys - 1) / kTileKeys;
+  int splits = first_pass ? (tiles >= kScoreSplits ? kScoreSplits : 1) : 1;
+  if (n_splits) *n_splits = splits;
+  dim3 grid((dv.C + kTileTok - 1) / kTileTok, splits, dv.U);
   hipLaunchKernelGGL(score_mfma_kernel, grid, dim3(256), 0, st, dv, slot, row0, row1, first_pass ? 1 : 0);
   return hipGetLastError();
 }
