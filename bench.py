@@ -64,6 +64,13 @@ def prefill_leg(args, pkg, synth, dev):
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     prof = st.profile_read()
+    # the same step with folds and attention kept apart: each kernel's time without the other
+    st.profile(2)
+    for _ in range(2):
+        st.reset()
+        st.prefill(q, k, v, out=out)
+    torch.cuda.synchronize()
+    iso = st.profile_read()
     st.profile(False)
     tokens = w.batch * w.seq
     flops, _ = attention_flops(w, w.seq)
@@ -72,13 +79,16 @@ def prefill_leg(args, pkg, synth, dev):
     launches = max(attn_n // max(args.steps, 1), 1)      # attention launches per step (groups of chunks)
     avg_launch_s = attn_ms / max(attn_n, 1) * 1e-3
     achieved = flops / launches / avg_launch_s / 1e12 if attn_n else 0.0
+    iso_tflops = flops / launches / (iso["attn"][0] / max(iso["attn"][1], 1) * 1e-3) / 1e12
     res = dict(
         value=tokens * args.steps / dt, ms_per_step=dt / args.steps * 1e3,
         roofline=dict(bound="mfma", kernel="attn_mfma_kernel", achieved=achieved, peak=MFMA_BF16_PEAK_TFLOPS,
                       unit="TFLOP/s", frac=achieved / MFMA_BF16_PEAK_TFLOPS, traffic=None,
                       launches_per_step=launches, avg_launch_us=avg_launch_s * 1e6,
                       attn_ms_per_step=attn_ms / args.steps, fold_ms_per_step=fold_ms / args.steps,
-                      folds_per_step=fold_n // max(args.steps, 1)),
+                      folds_per_step=fold_n // max(args.steps, 1),
+                      isolated=dict(achieved=iso_tflops, frac=iso_tflops / MFMA_BF16_PEAK_TFLOPS,
+                                    attn_ms_per_step=iso["attn"][0] / 2, fold_ms_per_step=iso["fold"][0] / 2)),
         workload=w)
     return res, (q, k, v)
 

@@ -175,7 +175,9 @@ int kvm_state_import(kvm_state *st, const double *sK, const float *sV, const flo
  * milliseconds per class, returns them with the number of launches, and clears the record:
  *   ms[0], count[0]: prefill attention launches (one per chunk)
  *   ms[1], count[1]: folds (all kernels of one fold together)
- *   ms[2], count[2]: decode attention launches */
+ *   ms[2], count[2]: decode attention launches
+ * enable = 2 additionally keeps the prefill's fold stream from overlapping its attention
+ * launches, so that each kernel is timed alone (slower overall; for kernel rooflines). */
 int kvm_state_profile(kvm_state *st, int enable);
 int kvm_state_profile_read(kvm_state *st, double ms[3], int64_t count[3]);
 

@@ -276,8 +276,9 @@ class KVMState:
         """Back to the empty state (m = 0, no tokens seen) in the same buffer; no device work."""
         _check(self.lib.kvm_state_import(self.handle, *([None] * 8), 0, 0, 0, None), "kvm_state_import")
 
-    def profile(self, enable: bool) -> None:
-        _check(self.lib.kvm_state_profile(self.handle, 1 if enable else 0), "kvm_state_profile")
+    def profile(self, enable) -> None:
+        """kvm_state_profile: False/0 off, True/1 on, 2 on with folds and attention kept apart."""
+        _check(self.lib.kvm_state_profile(self.handle, int(enable)), "kvm_state_profile")
 
     def profile_read(self) -> dict:
         """kvm_state_profile_read: {"attn": (ms, launches), "fold": (...), "decode": (...)}."""

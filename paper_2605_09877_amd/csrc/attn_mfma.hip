@@ -31,7 +31,8 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
   __shared__ __attribute__((aligned(1024))) uint16_t Ks[2][kTileElems];
   __shared__ __attribute__((aligned(1024))) uint16_t Vs[2][kTileElems];
   constexpr int D = kHeadDim;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction
   const int g = lane >> 5, l32 = lane & 31;
   const int hq = blockIdx.y, b = blockIdx.z;
   const int hkv = hq / (dv.Hq / dv.Hkv);
@@ -75,47 +76,56 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
   const int qend = (Q0 + kTileQ < nq) ? Q0 + kTileQ : nq;  // one past the last valid query here
   const int n_win = (int)((cs + qend - wb + kTileKeys - 1) / kTileKeys);
   const int n_tiles = n_st + n_win;
-  const int64_t last_pos = cs + nq - 1;
 
-  const uint16_t *khat = (const uint16_t *)dv.khat + a.slot[ci] * dv.slot_elems + (int64_t)u * dv.Mcap * D;
-  const uint16_t *vhat = (const uint16_t *)dv.vhat + a.slot[ci] * dv.slot_elems + (int64_t)u * dv.Mcap * D;
-  const uint16_t *ring_k = (const uint16_t *)dv.winK + (int64_t)u * dv.L * D;
-  const uint16_t *ring_v = (const uint16_t *)dv.winV + (int64_t)u * dv.L * D;
-  const uint16_t *in_k = (const uint16_t *)a.in.k + b * a.in.k_b + hkv * a.in.k_h;
-  const uint16_t *in_v = (const uint16_t *)a.in.v + b * a.in.v_b + hkv * a.in.v_h;
+  // Tile sources, all wave-uniform: state rows of this chunk's version; window positions from the
+  // call's own k/v (at or after t0) or from the ring (before t0).  Positions are kept relative
+  // to the chunk start so that the per-tile arithmetic is 32-bit.
+  const char *khat = (const char *)dv.khat + (a.slot[ci] * dv.slot_elems + (int64_t)u * dv.Mcap * D) * 2;
+  const char *vhat = (const char *)dv.vhat + (a.slot[ci] * dv.slot_elems + (int64_t)u * dv.Mcap * D) * 2;
+  const char *ring_k = (const char *)dv.winK + (int64_t)u * dv.L * D * 2;
+  const char *ring_v = (const char *)dv.winV + (int64_t)u * dv.L * D * 2;
+  const uint32_t kst_in = (uint32_t)a.in.k_t * 2, vst_in = (uint32_t)a.in.v_t * 2;
+  const char *in_k = (const char *)a.in.k + (b * a.in.k_b + hkv * a.in.k_h + (cs - a.t0) * a.in.k_t) * 2;
+  const char *in_v = (const char *)a.in.v + (b * a.in.v_b + hkv * a.in.v_h + (cs - a.t0) * a.in.v_t) * 2;
+  const int wrel = (int)(wb - cs);                                   // first window position (<= 0)
+  const int t0rel = a.t0 - cs < -(1 << 30) ? -(1 << 30) : (int)(a.t0 - cs);
+  const int ring_slot0 = (int)(wb % dv.L);
+  const int last_rel = nq - 1;
 
   uint32_t koff[8], voff[2];
   ktile_offsets(lane, koff);
   vtile_offsets(lane, voff);
+  const DmaLane dl = dma_lane(lane);
 
   auto issue_tile = [&](int it) {
-    const uint16_t *kb_, *vb_;
+    const char *kb_, *vb_;
     uint32_t kst, vst;
     int valid;
     if (it < n_st) {
       const int row0 = it * kTileKeys;
-      kb_ = khat + (int64_t)row0 * D;
-      vb_ = vhat + (int64_t)row0 * D;
-      kst = vst = D;
+      kb_ = khat + (uint32_t)row0 * (D * 2);
+      vb_ = vhat + (uint32_t)row0 * (D * 2);
+      kst = vst = D * 2;
       valid = m - row0;
     } else {
-      const int64_t p0 = wb + (int64_t)(it - n_st) * kTileKeys;
-      valid = (int)(last_pos - p0 + 1);
-      if (p0 >= a.t0) {
-        kb_ = in_k + (p0 - a.t0) * a.in.k_t;
-        vb_ = in_v + (p0 - a.t0) * a.in.v_t;
-        kst = (uint32_t)a.in.k_t;
-        vst = (uint32_t)a.in.v_t;
+      const int w = it - n_st;
+      const int prel = wrel + w * kTileKeys;
+      valid = last_rel - prel + 1;
+      if (prel >= t0rel) {
+        kb_ = in_k + (int64_t)prel * (int64_t)kst_in;
+        vb_ = in_v + (int64_t)prel * (int64_t)vst_in;
+        kst = kst_in;
+        vst = vst_in;
       } else {
-        const int slot = (int)(p0 % dv.L);
-        kb_ = ring_k + (int64_t)slot * D;
-        vb_ = ring_v + (int64_t)slot * D;
-        kst = vst = D;
+        int slot = ring_slot0 + w * kTileKeys;
+        slot = slot >= dv.L ? slot - dv.L : slot;   // a window is at most L long: one wrap
+        kb_ = ring_k + (uint32_t)slot * (D * 2);
+        vb_ = ring_v + (uint32_t)slot * (D * 2);
+        kst = vst = D * 2;
       }
     }
-    valid = valid < kTileKeys ? valid : kTileKeys;
-    tile_dma<false>(kb_, kst, valid, Ks[it & 1], wave, lane);
-    tile_dma<true>(vb_, vst, valid, Vs[it & 1], wave, lane);
+    tile_dma<false>(kb_, kst, valid, Ks[it & 1], wave, dl);
+    tile_dma<true>(vb_, vst, valid, Vs[it & 1], wave, dl);
   };
 
   f32x16 oacc[4];

@@ -34,6 +34,7 @@ struct kvm_state {
   size_t sync_used = 0;
   // optional kernel timing: (start, stop, class) event pairs, events reused across reads
   bool profile = false;
+  bool isolate = false;  // profiling aid: never let folds and attention share the chip
   struct Span {
     hipEvent_t a, b;
     int kind;
@@ -410,6 +411,7 @@ int kvm_state_destroy(kvm_state *st) {
 int kvm_state_profile(kvm_state *st, int enable) {
   if (!st) return KVM_ERR_ARG;
   st->profile = enable != 0;
+  st->isolate = enable == 2;
   return KVM_OK;
 }
 
@@ -507,7 +509,9 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
   const int n_chunks = (int)plan.size();
   int next_fold = 0;                 // folds of chunks < next_fold are enqueued
   hipEvent_t last_fold_ev = nullptr;
+  hipEvent_t last_att_ev = nullptr;
   auto enqueue_folds_through = [&](int last_chunk) -> int {
+    if (st->isolate && last_att_ev) HIP_TRY(hipStreamWaitEvent(fstream, last_att_ev, 0));
     while (next_fold <= last_chunk && next_fold < n_chunks) {
       if (!plan[next_fold].folds) {
         ++next_fold;
@@ -577,6 +581,7 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
     HIP_TRY(next_sync_event(st, &ev));
     HIP_TRY(hipEventRecord(ev, stream));
     for (int i = g0; i < g1; ++i) slot_busy[plan[i].ver % dv.NS] = ev;
+    last_att_ev = ev;
   }
   {
     int rc = enqueue_folds_through(n_chunks - 1);

@@ -89,28 +89,44 @@ typedef short v4i16 __attribute__((ext_vector_type(4)));
 
 constexpr int kTileElems = kTileKeys * kHeadDim;  // 8192 bf16 = 16 KiB
 
-// One wave fetches rows 4*bi .. 4*bi+3 (bi = 4*wave + n, n = 0..3) of a tile; kVSwz: V layout.
-// `base` is wave-uniform, the per-lane part is a 32-bit element offset.  Rows at or beyond
-// rows_valid repeat the last valid row (only looked at when the tile is not full).
-template <bool kVSwz>
-__device__ __forceinline__ void tile_dma(const uint16_t *base, uint32_t stride, int rows_valid,
-                                         uint16_t *lds_tile, int wave, int lane) {
+// Per-lane byte offsets of a lane's 16-byte chunk within its row, for the four loads a wave
+// issues per tile (the chunk permutation depends on the row, see above).
+struct DmaLane {
+  uint32_t rl;       // row of the lane within a 4-row block
+  uint32_t kcol[4];  // K layout, loads n = 0..3
+  uint32_t vcol;     // V layout, same for all four loads
+};
+__device__ __forceinline__ DmaLane dma_lane(int lane) {
+  DmaLane d;
   const int rl = lane >> 4, c16 = lane & 15;
+  d.rl = (uint32_t)rl;
+#pragma unroll
+  for (int n = 0; n < 4; ++n) d.kcol[n] = (uint32_t)(16 * (c16 ^ (4 * n + rl)));
+  d.vcol = (uint32_t)(16 * (c16 ^ (2 * rl)));
+  return d;
+}
+
+// One wave fetches rows 4*bi .. 4*bi+3 (bi = 4*wave + n, n = 0..3) of a tile; kVSwz: V layout.
+// `base` (bytes) and `stride` (bytes between rows) are wave-uniform; the per-lane part is a
+// 32-bit byte offset, so each load is scalar base + vector offset.  Rows at or beyond rows_valid
+// repeat the last valid row (only looked at when the tile is not full).
+template <bool kVSwz>
+__device__ __forceinline__ void tile_dma(const char *base, uint32_t stride, int rows_valid,
+                                         uint16_t *lds_tile, int wave, const DmaLane &dl) {
   if (rows_valid >= kTileKeys) {
-    const uint32_t row_off = (uint32_t)(16 * wave + rl) * stride;
+    const uint32_t lane_row = dl.rl * stride;
 #pragma unroll
     for (int n = 0; n < 4; ++n) {
-      const int q = kVSwz ? (c16 ^ (2 * rl)) : (c16 ^ (4 * n + rl));
-      const uint32_t off = row_off + (uint32_t)(4 * n) * stride + (uint32_t)(8 * q);
-      __builtin_amdgcn_global_load_lds(base + off, KVM_LDS_VOID(lds_tile + (4 * wave + n) * 512), 16, 0, 0);
+      const char *sb = base + (uint32_t)(16 * wave + 4 * n) * stride;
+      const uint32_t off = lane_row + (kVSwz ? dl.vcol : dl.kcol[n]);
+      __builtin_amdgcn_global_load_lds(sb + off, KVM_LDS_VOID(lds_tile + (4 * wave + n) * 512), 16, 0, 0);
     }
   } else {
 #pragma unroll
     for (int n = 0; n < 4; ++n) {
-      int r = 16 * wave + 4 * n + rl;
-      const int q = kVSwz ? (c16 ^ (2 * rl)) : (c16 ^ (4 * n + rl));
+      int r = 16 * wave + 4 * n + (int)dl.rl;
       r = r < rows_valid ? r : rows_valid - 1;
-      const uint32_t off = (uint32_t)r * stride + (uint32_t)(8 * q);
+      const uint32_t off = (uint32_t)r * stride + (kVSwz ? dl.vcol : dl.kcol[n]);
       __builtin_amdgcn_global_load_lds(base + off, KVM_LDS_VOID(lds_tile + (4 * wave + n) * 512), 16, 0, 0);
     }
   }

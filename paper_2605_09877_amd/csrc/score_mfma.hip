@@ -21,7 +21,8 @@ constexpr int kTileTok = 128;  // tokens per workgroup (32 per wave)
 __global__ __launch_bounds__(256, 2) void score_mfma_kernel(Dev dv, int slot, int row0, int row1, int first_pass) {
   __shared__ __attribute__((aligned(1024))) uint16_t Ks[2][kTileElems];
   constexpr int D = kHeadDim;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 5, l32 = lane & 31;
   const int u = blockIdx.z;
   const int tok0 = blockIdx.x * kTileTok + 32 * wave;
@@ -50,10 +51,11 @@ __global__ __launch_bounds__(256, 2) void score_mfma_kernel(Dev dv, int slot, in
   uint32_t koff[8];
   ktile_offsets(lane, koff);
 
-  const uint16_t *khat = (const uint16_t *)dv.khat + slot * dv.slot_elems + ((int64_t)u * dv.Mcap + row0) * D;
+  const char *khat = (const char *)dv.khat + (slot * dv.slot_elems + ((int64_t)u * dv.Mcap + row0) * D) * 2;
+  const DmaLane dl = dma_lane(lane);
   auto issue_tile = [&](int t) {
     const int base = t * kTileKeys;
-    tile_dma<false>(khat + (int64_t)base * D, D, min(kTileKeys, row1 - row0 - base), Ks[t & 1], wave, lane);
+    tile_dma<false>(khat + (uint32_t)base * (D * 2), D * 2, row1 - row0 - base, Ks[t & 1], wave, dl);
   };
   if (t_begin < t_end) issue_tile(t_begin);
   for (int t = t_begin; t < t_end; ++t) {
