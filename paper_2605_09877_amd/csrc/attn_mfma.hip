@@ -26,22 +26,38 @@ namespace {
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr int kTileQ = 128;
+constexpr int kXcds = 8;  // accelerator dies, each with its own L2
 
 __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
-  __shared__ __attribute__((aligned(1024))) uint16_t Ks[2][kTileElems];
-  __shared__ __attribute__((aligned(1024))) uint16_t Vs[2][kTileElems];
+  // Two tile buffers per operand, as separate arrays: the compiler can then tell that the loads
+  // filling one buffer do not alias the fragment reads of the other and does not wait for them.
+  __shared__ __attribute__((aligned(1024))) uint16_t Ks0[kTileElems];
+  __shared__ __attribute__((aligned(1024))) uint16_t Ks1[kTileElems];
+  __shared__ __attribute__((aligned(1024))) uint16_t Vs0[kTileElems];
+  __shared__ __attribute__((aligned(1024))) uint16_t Vs1[kTileElems];
   constexpr int D = kHeadDim;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction
   const int g = lane >> 5, l32 = lane & 31;
-  const int hq = blockIdx.y, b = blockIdx.z;
-  const int hkv = hq / (dv.Hq / dv.Hkv);
-  const int u = b * dv.Hkv + hkv;
-  // blockIdx.x = chunk of the launch, then query tile of the chunk; the tile with the longest
-  // causal part is scheduled first
+  // Workgroup -> work item.  The tpc * Gq workgroups that read the same K and V (query tiles of one
+  // chunk x query heads of one KV group) are given to one XCD, whose L2 then serves all but the
+  // first read of every tile: consecutive workgroup ids go round-robin over the 8 XCDs, so id % 8
+  // picks the XCD and id / 8 walks that XCD's own sequence of (group, member) pairs.
   const int tpc = (dv.C + kTileQ - 1) / kTileQ;
-  const int ci = blockIdx.x / tpc;
-  const int Q0 = (tpc - 1 - (int)(blockIdx.x % tpc)) * kTileQ;
+  const int Gq = dv.Hq / dv.Hkv;
+  const int per_group = tpc * Gq;
+  const int n_groups = a.n_chunks * dv.Hkv * dv.B;
+  const int xcd = blockIdx.x % kXcds, seq = blockIdx.x / kXcds;
+  const int group = (seq / per_group) * kXcds + xcd;
+  if (group >= n_groups) return;
+  const int member = seq % per_group;
+  const int qt = member % tpc, gq = member / tpc;
+  const int ci = group % a.n_chunks;
+  const int hkv = (group / a.n_chunks) % dv.Hkv;
+  const int b = group / (a.n_chunks * dv.Hkv);
+  const int hq = hkv * Gq + gq;
+  const int u = b * dv.Hkv + hkv;
+  const int Q0 = (tpc - 1 - qt) * kTileQ;                                // longest causal part first
   const int nq = ci == a.n_chunks - 1 ? a.nq_total - ci * dv.C : dv.C;  // queries of this chunk
   if (Q0 >= nq) return;
   const int64_t cs = a.s + (int64_t)ci * dv.C;                           // chunk start position
@@ -97,7 +113,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
   vtile_offsets(lane, voff);
   const DmaLane dl = dma_lane(lane);
 
-  auto issue_tile = [&](int it) {
+  auto issue_tile = [&](int it, uint16_t *Kdst, uint16_t *Vdst) {
     const char *kb_, *vb_;
     uint32_t kst, vst;
     int valid;
@@ -124,8 +140,8 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
         kst = vst = D * 2;
       }
     }
-    tile_dma<false>(kb_, kst, valid, Ks[it & 1], wave, dl);
-    tile_dma<true>(vb_, vst, valid, Vs[it & 1], wave, dl);
+    tile_dma<false>(kb_, kst, valid, Kdst, wave, dl);
+    tile_dma<true>(vb_, vst, valid, Vdst, wave, dl);
   };
 
   f32x16 oacc[4];
@@ -135,13 +151,12 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
     for (int v = 0; v < 16; ++v) oacc[i][v] = 0.f;
   float m_run = -INFINITY, l_part = 0.f;
 
-  issue_tile(0);
-  for (int it = 0; it < n_tiles; ++it) {
-    // tile `it` has landed for every wave, and every wave is done reading the other buffer
+  // One tile: wait for it, start the loads of the next one into the other buffers, consume it.
+  auto do_tile = [&](int it, const uint16_t *Kt, const uint16_t *Vt, uint16_t *Knext, uint16_t *Vnext) {
+    // tile `it` has landed for every wave, and every wave is done reading the other buffers
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
-    if (it + 1 < n_tiles) issue_tile(it + 1);
-    const uint16_t *Kt = Ks[it & 1], *Vt = Vs[it & 1];
+    if (it + 1 < n_tiles) issue_tile(it + 1, Knext, Vnext);
 
     const bool is_state = it < n_st;
     const int row0 = it * kTileKeys;
@@ -153,7 +168,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
       need_mask = m - row0 < kTileKeys;
     } else {
       scale = c_bswa;
-      if (p0 > cs + wq0 + 31) continue;  // every key of the tile lies after this wave's queries
+      if (p0 > cs + wq0 + 31) return;  // every key of the tile lies after this wave's queries
       need_mask = p0 + kTileKeys - 1 > cs + wq0;
     }
 
@@ -242,6 +257,11 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
         if (i + 8 < 16) vf[slot] = vtile_frag(Vt, voff, dblk, ks + 2);
       }
     }
+  };
+  issue_tile(0, Ks0, Vs0);
+  for (int it = 0; it < n_tiles; it += 2) {
+    do_tile(it, Ks0, Vs0, Ks1, Vs1);
+    if (it + 1 < n_tiles) do_tile(it + 1, Ks1, Vs1, Ks0, Vs0);
   }
 
   const float l = l_part + __shfl_xor(l_part, 32, kWave);
@@ -265,7 +285,9 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
 
 hipError_t launch_attn_mfma(const Dev &dv, const AttnArgs &a, hipStream_t st) {
   if (a.nq_total <= 0) return hipSuccess;
-  dim3 grid(a.n_chunks * ((dv.C + kTileQ - 1) / kTileQ), dv.Hq, dv.B);
+  const int per_group = ((dv.C + kTileQ - 1) / kTileQ) * (dv.Hq / dv.Hkv);
+  const int n_groups = a.n_chunks * dv.Hkv * dv.B;
+  dim3 grid((unsigned)((n_groups + kXcds - 1) / kXcds * kXcds * per_group));
   hipLaunchKernelGGL(attn_mfma_kernel, grid, dim3(256), 0, st, dv, a);
   return hipGetLastError();
 }

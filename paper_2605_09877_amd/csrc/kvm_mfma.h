@@ -106,6 +106,24 @@ __device__ __forceinline__ DmaLane dma_lane(int lane) {
   return d;
 }
 
+// One 16-byte-per-lane direct load: lane i's chunk from sbase + voff lands at lds_addr + 16*i.
+// Written as an instruction sequence of its own rather than through the compiler's builtin: the
+// compiler cannot see that such a load into one tile buffer leaves the other buffer alone, and
+// puts a full wait for it in front of the next LDS read, which would undo the prefetch.  The
+// kernels wait themselves (s_waitcnt vmcnt(0) ahead of the barrier that publishes a tile).
+__device__ __forceinline__ void dma16(const char *sbase, uint32_t voff, uint32_t lds_addr) {
+  asm volatile(
+      "s_mov_b32 m0, %2\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %0, %1"
+      :
+      : "v"(voff), "s"(sbase), "s"(lds_addr)
+      : "memory", "m0");
+}
+__device__ __forceinline__ uint32_t lds_addr_of(const void *p) {
+  return (uint32_t)(uintptr_t)KVM_LDS_VOID(p);
+}
+
 // One wave fetches rows 4*bi .. 4*bi+3 (bi = 4*wave + n, n = 0..3) of a tile; kVSwz: V layout.
 // `base` (bytes) and `stride` (bytes between rows) are wave-uniform; the per-lane part is a
 // 32-bit byte offset, so each load is scalar base + vector offset.  Rows at or beyond rows_valid
@@ -119,7 +137,7 @@ __device__ __forceinline__ void tile_dma(const char *base, uint32_t stride, int 
     for (int n = 0; n < 4; ++n) {
       const char *sb = base + (uint32_t)(16 * wave + 4 * n) * stride;
       const uint32_t off = lane_row + (kVSwz ? dl.vcol : dl.kcol[n]);
-      __builtin_amdgcn_global_load_lds(sb + off, KVM_LDS_VOID(lds_tile + (4 * wave + n) * 512), 16, 0, 0);
+      dma16(sb, off, lds_addr_of(lds_tile + (4 * wave + n) * 512));
     }
   } else {
 #pragma unroll
@@ -127,7 +145,7 @@ __device__ __forceinline__ void tile_dma(const char *base, uint32_t stride, int 
       int r = 16 * wave + 4 * n + (int)dl.rl;
       r = r < rows_valid ? r : rows_valid - 1;
       const uint32_t off = (uint32_t)r * stride + (kVSwz ? dl.vcol : dl.kcol[n]);
-      __builtin_amdgcn_global_load_lds(base + off, KVM_LDS_VOID(lds_tile + (4 * wave + n) * 512), 16, 0, 0);
+      dma16(base, off, lds_addr_of(lds_tile + (4 * wave + n) * 512));
     }
   }
 }
