@@ -37,7 +37,7 @@ struct kvm_state {
   bool isolate = false;  // profiling aid: never let folds and attention share the chip
   struct Span {
     hipEvent_t a, b;
-    int kind;
+    int kind, count;  // count: how many launches (or folds) the bracket covers
   };
   std::vector<Span> spans;
   std::vector<hipEvent_t> free_events;
@@ -320,8 +320,8 @@ struct ProfileSpan {
   kvm_state *st;
   hipStream_t stream;
   hipEvent_t a = nullptr, b = nullptr;
-  int kind;
-  ProfileSpan(kvm_state *s, int k, hipStream_t str) : st(s), stream(str), kind(k) {
+  int kind, count;
+  ProfileSpan(kvm_state *s, int k, hipStream_t str, int n = 1) : st(s), stream(str), kind(k), count(n) {
     if (!st->profile) return;
     auto get = [&]() -> hipEvent_t {
       hipEvent_t e = nullptr;
@@ -340,7 +340,7 @@ struct ProfileSpan {
   ~ProfileSpan() {
     if (a && b) {
       (void)hipEventRecord(b, stream);
-      st->spans.push_back({a, b, kind});
+      st->spans.push_back({a, b, kind, count});
     }
   }
 };
@@ -426,7 +426,7 @@ int kvm_state_profile_read(kvm_state *st, double ms[3], int64_t count[3]) {
     float t = 0.f;
     HIP_TRY(hipEventElapsedTime(&t, sp.a, sp.b));
     ms[sp.kind] += t;
-    count[sp.kind] += 1;
+    count[sp.kind] += sp.count;
     st->free_events.push_back(sp.a);
     st->free_events.push_back(sp.b);
   }
@@ -526,24 +526,29 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
                plan[next_fold + run].folds)
           ++run;
       const bool batched = lo0 >= t0;
-      for (int i = 0; i < run; ++i) {
-        const Chunk &ch = plan[next_fold + i];
-        const int sn = (int)((st->folds + 1) % dv.NS);
-        if (slot_busy[sn]) HIP_TRY(hipStreamWaitEvent(fstream, slot_busy[sn], 0));
-        const int64_t ce = ch.s + C, lo = ce - L;  // first token of the overflow block
-        int rc;
-        {
-          ProfileSpan span(st, 1, fstream);
+      {
+        // events cost microseconds each on the queue: one bracket and one ordering event per
+        // run of folds, not per fold
+        ProfileSpan span(st, 1, fstream, run);
+        for (int i = 0; i < run; ++i) {
+          const Chunk &ch = plan[next_fold + i];
+          const int sn = (int)((st->folds + 1) % dv.NS);
+          if (slot_busy[sn]) {
+            HIP_TRY(hipStreamWaitEvent(fstream, slot_busy[sn], 0));
+            slot_busy[sn] = nullptr;
+          }
+          const int64_t ce = ch.s + C, lo = ce - L;  // first token of the overflow block
+          int rc;
           if (batched && i == 0) HIP_TRY(kvm::launch_memkey(dv, advance(in, lo0 - t0, es), run, fstream));
           if (batched)
             rc = fold_block(st, advance(in, lo - t0, es), ce, nullptr, nullptr, fstream, i);
           else
             rc = fold_block(st, advance(ring, lo % L, es), ce, nullptr, nullptr, fstream);
+          if (rc != KVM_OK) return rc;
         }
-        if (rc != KVM_OK) return rc;
-        HIP_TRY(next_sync_event(st, &last_fold_ev));
-        HIP_TRY(hipEventRecord(last_fold_ev, fstream));
       }
+      HIP_TRY(next_sync_event(st, &last_fold_ev));
+      HIP_TRY(hipEventRecord(last_fold_ev, fstream));
       next_fold += run;
     }
     return KVM_OK;
