@@ -33,7 +33,9 @@ __device__ __forceinline__ void write_readout(const Dev &dv, int slot, int u, in
     const double dl = sk[c] - mean;
     q += dl * dl;
   }
-  const double den = sqrt(wave_sum(q) / (double)D + (double)dv.ln_eps);
+  // one fp64 reciprocal per row; (x - mean) * rden differs from (x - mean) / den by an ulp of
+  // fp64 at most, far below what the rounding to the I/O dtype can see
+  const double rden = 1.0 / sqrt(wave_sum(q) / (double)D + (double)dv.ln_eps);
   float nn = 0.f;
 #pragma unroll
   for (int c = 0; c < CPL; ++c) nn += sv[c] * sv[c];
@@ -46,7 +48,7 @@ __device__ __forceinline__ void write_readout(const Dev &dv, int slot, int u, in
     const int ch = lane * CPL + c;
     const double ga = dv.gamma ? (double)dv.gamma[h * D + ch] : 1.0;
     const double be = dv.beta ? (double)dv.beta[h * D + ch] : 0.0;
-    const double y = (sk[c] - mean) / den * ga + be;
+    const double y = (sk[c] - mean) * rden * ga + be;
     Io<T>::store(kh + ch, Io<T>::round_from(y));
     Io<T>::store(vh + ch, sv[c] * vs);
   }
@@ -78,14 +80,14 @@ __global__ __launch_bounds__(256) void memkey_kernel(Dev dv, Src src, int n_bloc
     const double dl = x[c] - mean;
     q += dl * dl;
   }
-  const double den = sqrt(wave_sum(q) / (double)D + (double)dv.ln_eps);
+  const double rden = 1.0 / sqrt(wave_sum(q) / (double)D + (double)dv.ln_eps);
   T *out = (T *)dv.kbar + ((int64_t)(j / dv.C) * dv.U * dv.C + (int64_t)u * dv.C + j % dv.C) * D;
 #pragma unroll
   for (int c = 0; c < CPL; ++c) {
     const int ch = lane * CPL + c;
     const double ga = dv.gamma ? (double)dv.gamma[h * D + ch] : 1.0;
     const double be = dv.beta ? (double)dv.beta[h * D + ch] : 0.0;
-    Io<T>::store(out + ch, Io<T>::round_from((x[c] - mean) / den * ga + be));
+    Io<T>::store(out + ch, Io<T>::round_from((x[c] - mean) * rden * ga + be));
   }
 }
 
