@@ -1,20 +1,23 @@
 // Fused prefill attention for bf16, head_dim 128 on the gfx950 matrix cores.
 //
-// One workgroup (4 waves) owns 128 consecutive queries of one chunk for one query head; each
+// A workgroup of NW waves owns 32*NW consecutive queries of one chunk for one query head; each
 // wave owns 32 of them.  Keys are visited in 64-key tiles through three regions that share one
 // online softmax ("Readout" equations of the paper): normalised state rows (scale tau_state,
 // all visible), window tokens before the chunk (scale tau_bswa, all visible), and the chunk's
 // own tokens (causal).  Per tile and wave:
-//   S^T[key, query] = K_tile . Q^T      16 MFMA 32x32x16, K from LDS, Q^T kept in registers
-//   online softmax down the key axis: a lane holds one query column, so the running max and
-//                                     sum are per-lane scalars plus one exchange with lane^32
-//   O^T[d, query]  += V_tile^T . P^T    16 MFMA; V^T fragments come out of the row-major V tile
-//                                     through the transposing LDS read; P^T is S^T's own
-//                                     register layout, no shuffle needed
-// K and V tiles go from HBM straight into LDS (global_load_lds, 16 B per lane, swizzled rows),
-// double buffered: the loads of tile i+1 are in flight while tile i is consumed, one barrier
-// per tile.  The mask is never materialised: it is the tile loop bounds plus a compare on
-// diagonal tiles.
+//   QK : S^T[key, query] = K_tile . Q^T   16 MFMA 32x32x16, K from LDS, Q^T kept in registers
+//   SM : online softmax down the key axis; a lane holds one query column, so the running max and
+//        sum are per-lane scalars plus one exchange with lane^32
+//   PV : O^T[d, query] += V_tile^T . P^T  16 MFMA; V^T fragments come out of the row-major V
+//        tile through the transposing LDS read; P^T is S^T's own register layout, no shuffle
+// K and V tiles go from HBM/L2 straight into LDS (16 B per lane, swizzled rows) ahead of use,
+// one barrier per tile.  The mask is never materialised: it is the tile loop bounds plus a
+// compare on diagonal tiles.
+//
+// NW = 8 (256 queries; chunks that are a multiple of 256): half the tile bytes per flop, which
+// matters because the direct-to-LDS path, not the matrix cores, saturates first; one workgroup
+// per CU.  NW = 4 (128 queries): two workgroups per CU.  Either way the four tile buffers (two K,
+// two V) fill exactly the first 64 KiB of LDS.
 #include "kvm_device.h"
 #include "kvm_internal.h"
 #include "kvm_mfma.h"
@@ -25,17 +28,13 @@ namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
-constexpr int kTileQ = 128;
 constexpr int kXcds = 8;  // accelerator dies, each with its own L2
 
-__global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
-  // Two tile buffers per operand, as separate arrays: the compiler can then tell that the loads
-  // filling one buffer do not alias the fragment reads of the other and does not wait for them.
-  __shared__ __attribute__((aligned(1024))) uint16_t Ks0[kTileElems];
-  __shared__ __attribute__((aligned(1024))) uint16_t Ks1[kTileElems];
-  __shared__ __attribute__((aligned(1024))) uint16_t Vs0[kTileElems];
-  __shared__ __attribute__((aligned(1024))) uint16_t Vs1[kTileElems];
+template <int NW>
+__device__ __forceinline__ void attn_body(const Dev &dv, const AttnArgs &a, uint16_t *Ks, uint16_t *Vs) {
   constexpr int D = kHeadDim;
+  constexpr int kTileQ = 32 * NW;
+  constexpr int kVBufs = 2;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction
   const int g = lane >> 5, l32 = lane & 31;
@@ -108,12 +107,14 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
   const int ring_slot0 = (int)(wb % dv.L);
   const int last_rel = nq - 1;
 
+  // Per-lane fragment offsets (elements) from the start of the K / V buffers.  K has two buffers
+  // and its offsets flip after every tile; V buffers are addressed by tile number.
   uint32_t koff[8], voff[2];
   ktile_offsets(lane, koff);
   vtile_offsets(lane, voff);
   const DmaLane dl = dma_lane(lane);
 
-  auto issue_tile = [&](int it, uint16_t *Kdst, uint16_t *Vdst) {
+  auto issue_tile = [&](int it) {
     const char *kb_, *vb_;
     uint32_t kst, vst;
     int valid;
@@ -140,8 +141,8 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
         kst = vst = D * 2;
       }
     }
-    tile_dma<false>(kb_, kst, valid, Kdst, wave, dl);
-    tile_dma<true>(vb_, vst, valid, Vdst, wave, dl);
+    tile_dma<false, NW>(kb_, kst, valid, Ks + (it & 1) * kTileElems, wave, dl);
+    tile_dma<true, NW>(vb_, vst, valid, Vs + (it % kVBufs) * kTileElems, wave, dl);
   };
 
   f32x16 oacc[4];
@@ -150,35 +151,35 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) oacc[i][v] = 0.f;
   float m_run = -INFINITY, l_part = 0.f;
+  Frag8 pb[4];  // P^T of the tile just scored, packed for the second product
 
-  // One tile: wait for it, start the loads of the next one into the other buffers, consume it.
-  auto do_tile = [&](int it, const uint16_t *Kt, const uint16_t *Vt, uint16_t *Knext, uint16_t *Vnext) {
-    // tile `it` has landed for every wave, and every wave is done reading the other buffers
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
-    if (it + 1 < n_tiles) issue_tile(it + 1, Knext, Vnext);
+  // O^T += V^T . P^T for the tile whose P^T is in pb.
+  auto do_pv = [&](int tile) {
+    const uint16_t *Vt = Vs + (tile % kVBufs) * kTileElems;
+    bf16x8 vf[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) vf[i] = vtile_frag(Vt, voff, i & 3, i >> 2);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+      for (int dblk = 0; dblk < 4; ++dblk) {
+        const int i = 4 * ks + dblk, slot = i & 7;
+        oacc[dblk] = mfma32(vf[slot], pb[ks].v, oacc[dblk]);
+        if (i + 8 < 16) vf[slot] = vtile_frag(Vt, voff, dblk, ks + 2);
+      }
+  };
 
-    const bool is_state = it < n_st;
-    const int row0 = it * kTileKeys;
-    const int64_t p0 = wb + (int64_t)(it - n_st) * kTileKeys;
-    bool need_mask;
-    float scale;
-    if (is_state) {
-      scale = c_state;
-      need_mask = m - row0 < kTileKeys;
-    } else {
-      scale = c_bswa;
-      if (p0 > cs + wq0 + 31) return;  // every key of the tile lies after this wave's queries
-      need_mask = p0 + kTileKeys - 1 > cs + wq0;
-    }
-
+  // S^T = K . Q^T and the online softmax for the tile in the current K buffer; leaves P^T in pb.
+  auto do_qk_softmax = [&](bool is_state, int row0, int64_t p0) {
+    const float scale = is_state ? c_state : c_bswa;
+    const bool need_mask = is_state ? (m - row0 < kTileKeys) : (p0 + kTileKeys - 1 > cs + wq0);
     f32x16 sacc[2];
-    // S^T = K . Q^T with a rolling window of eight K fragments in flight from LDS, so that a
-    // matrix instruction does not wait for the read issued just before it
+    // a rolling window of eight K fragments in flight from LDS, so that a matrix instruction does
+    // not wait for the read issued just before it
     {
       bf16x8 kf[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) kf[i] = ktile_frag(Kt, koff, i & 1, i >> 1);
+      for (int i = 0; i < 8; ++i) kf[i] = ktile_frag(Ks, koff, i & 1, i >> 1);
       const f32x16 zero = {0.f};
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
@@ -186,7 +187,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
         for (int blk = 0; blk < 2; ++blk) {
           const int slot = (2 * ks + blk) & 7;
           sacc[blk] = mfma32(kf[slot], qreg[ks], ks == 0 ? zero : sacc[blk]);
-          if (ks + 4 < 8) kf[slot] = ktile_frag(Kt, koff, blk, ks + 4);
+          if (ks + 4 < 8) kf[slot] = ktile_frag(Ks, koff, blk, ks + 4);
         }
       }
       // pin that order: 8 LDS reads up front, then one read behind every matrix instruction
@@ -198,11 +199,6 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
       }
       __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
     }
-    // first eight V^T fragments: issued now, consumed after the softmax arithmetic
-    bf16x8 vf[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) vf[i] = vtile_frag(Vt, voff, i & 3, i >> 2);
-
     if (is_state ? neg_state : neg_bswa) {
 #pragma unroll
       for (int blk = 0; blk < 2; ++blk)
@@ -243,25 +239,29 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
         l_part += p;
         sacc[blk][v] = p;
       }
-
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      const int blk = ks >> 1, v0 = (ks & 1) * 8;
-      Frag8 pb;
+    for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) pb.w[e] = pack_bf16(sacc[blk][v0 + 2 * e], sacc[blk][v0 + 2 * e + 1]);
-#pragma unroll
-      for (int dblk = 0; dblk < 4; ++dblk) {
-        const int i = 4 * ks + dblk, slot = i & 7;
-        oacc[dblk] = mfma32(vf[slot], pb.v, oacc[dblk]);
-        if (i + 8 < 16) vf[slot] = vtile_frag(Vt, voff, dblk, ks + 2);
-      }
-    }
+      for (int e = 0; e < 4; ++e)
+        pb[ks].w[e] = pack_bf16(sacc[ks >> 1][(ks & 1) * 8 + 2 * e], sacc[ks >> 1][(ks & 1) * 8 + 2 * e + 1]);
   };
-  issue_tile(0, Ks0, Vs0);
-  for (int it = 0; it < n_tiles; it += 2) {
-    do_tile(it, Ks0, Vs0, Ks1, Vs1);
-    if (it + 1 < n_tiles) do_tile(it + 1, Ks1, Vs1, Ks0, Vs0);
+
+  issue_tile(0);
+  for (int it = 0; it < n_tiles; ++it) {
+    // tile `it` has landed for every wave, and every wave is done reading the other buffers
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    if (it + 1 < n_tiles) issue_tile(it + 1);
+    const bool is_state = it < n_st;
+    const int64_t p0 = wb + (int64_t)(it - n_st) * kTileKeys;
+    // skip tiles whose keys all lie after this wave's queries
+    if (is_state || p0 <= cs + wq0 + 31) {
+      do_qk_softmax(is_state, it * kTileKeys, p0);
+      do_pv(it);
+    }
+    // the next tile's K sits in the other buffer
+#pragma unroll
+    for (int i = 0; i < 8; ++i) koff[i] ^= (uint32_t)kTileElems;
   }
 
   const float l = l_part + __shfl_xor(l_part, 32, kWave);
@@ -281,14 +281,33 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(Dev dv, AttnArgs a) {
   }
 }
 
+// Static LDS only: 2 K + 2 V buffers = 64 KiB, so every direct-to-LDS destination is below
+// 64 KiB.
+__global__ __launch_bounds__(256, 2) void attn_mfma_kernel_q128(Dev dv, AttnArgs a) {
+  __shared__ __attribute__((aligned(32768))) uint16_t Ks[2 * kTileElems];
+  __shared__ __attribute__((aligned(1024))) uint16_t Vs[2 * kTileElems];
+  attn_body<4>(dv, a, Ks, Vs);
+}
+__global__ __launch_bounds__(512, 2) void attn_mfma_kernel_q256(Dev dv, AttnArgs a) {
+  __shared__ __attribute__((aligned(32768))) uint16_t Ks[2 * kTileElems];
+  __shared__ __attribute__((aligned(1024))) uint16_t Vs[2 * kTileElems];
+  attn_body<8>(dv, a, Ks, Vs);
+}
+
 }  // namespace
 
 hipError_t launch_attn_mfma(const Dev &dv, const AttnArgs &a, hipStream_t st) {
   if (a.nq_total <= 0) return hipSuccess;
-  const int per_group = ((dv.C + kTileQ - 1) / kTileQ) * (dv.Hq / dv.Hkv);
+  const bool wide = dv.C % 256 == 0;
+  const int tile_q = wide ? 256 : 128;
+  const int per_group = ((dv.C + tile_q - 1) / tile_q) * (dv.Hq / dv.Hkv);
   const int n_groups = a.n_chunks * dv.Hkv * dv.B;
   dim3 grid((unsigned)((n_groups + kXcds - 1) / kXcds * kXcds * per_group));
-  hipLaunchKernelGGL(attn_mfma_kernel, grid, dim3(256), 0, st, dv, a);
+  if (wide) {
+    hipLaunchKernelGGL(attn_mfma_kernel_q256, grid, dim3(512), 0, st, dv, a);
+  } else {
+    hipLaunchKernelGGL(attn_mfma_kernel_q128, grid, dim3(256), 0, st, dv, a);
+  }
   return hipGetLastError();
 }
 

@@ -112,6 +112,14 @@ __device__ __forceinline__ DmaLane dma_lane(int lane) {
 // puts a full wait for it in front of the next LDS read, which would undo the prefetch.  The
 // kernels wait themselves (s_waitcnt vmcnt(0) ahead of the barrier that publishes a tile).
 __device__ __forceinline__ void dma16(const char *sbase, uint32_t voff, uint32_t lds_addr) {
+  // Both are wave-uniform by construction; say so where the compiler cannot prove it.  The
+  // builtin returns a signed int: each half goes through uint32_t, or a low half with its top
+  // bit set would be sign-extended over the high half and the load would go astray.
+  lds_addr = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_addr);
+  const uint64_t sb = (uint64_t)sbase;
+  const uint32_t sb_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)sb);
+  const uint32_t sb_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(sb >> 32));
+  sbase = (const char *)(((uint64_t)sb_hi << 32) | (uint64_t)sb_lo);
   asm volatile(
       "s_mov_b32 m0, %2\n\t"
       "s_nop 0\n\t"
@@ -124,28 +132,30 @@ __device__ __forceinline__ uint32_t lds_addr_of(const void *p) {
   return (uint32_t)(uintptr_t)KVM_LDS_VOID(p);
 }
 
-// One wave fetches rows 4*bi .. 4*bi+3 (bi = 4*wave + n, n = 0..3) of a tile; kVSwz: V layout.
-// `base` (bytes) and `stride` (bytes between rows) are wave-uniform; the per-lane part is a
-// 32-bit byte offset, so each load is scalar base + vector offset.  Rows at or beyond rows_valid
-// repeat the last valid row (only looked at when the tile is not full).
-template <bool kVSwz>
+// The kNW waves of a workgroup share a tile's sixteen 1-KiB loads: wave w issues loads
+// bi = (16/kNW)*w + n, each fetching rows 4*bi .. 4*bi+3; kVSwz: V layout.  `base` (bytes) and
+// `stride` (bytes between rows) are wave-uniform; the per-lane part is a 32-bit byte offset, so
+// each load is scalar base + vector offset.  Rows at or beyond rows_valid repeat the last valid
+// row (only looked at when the tile is not full).
+template <bool kVSwz, int kNW>
 __device__ __forceinline__ void tile_dma(const char *base, uint32_t stride, int rows_valid,
                                          uint16_t *lds_tile, int wave, const DmaLane &dl) {
-  if (rows_valid >= kTileKeys) {
-    const uint32_t lane_row = dl.rl * stride;
+  constexpr int kPer = 16 / kNW;
+  const bool full = rows_valid >= kTileKeys;
+  const uint32_t lane_row = dl.rl * stride;
 #pragma unroll
-    for (int n = 0; n < 4; ++n) {
-      const char *sb = base + (uint32_t)(16 * wave + 4 * n) * stride;
-      const uint32_t off = lane_row + (kVSwz ? dl.vcol : dl.kcol[n]);
-      dma16(sb, off, lds_addr_of(lds_tile + (4 * wave + n) * 512));
-    }
-  } else {
-#pragma unroll
-    for (int n = 0; n < 4; ++n) {
-      int r = 16 * wave + 4 * n + (int)dl.rl;
+  for (int n = 0; n < kPer; ++n) {
+    const int bi = kPer * wave + n;
+    // the K chunk permutation depends on bi % 4, which is n for four waves and
+    // 2*(wave%2) + n for eight (a wave-uniform choice between two precomputed values)
+    const uint32_t kcol = kPer == 4 ? dl.kcol[n] : ((wave & 1) ? dl.kcol[2 + n] : dl.kcol[n]);
+    const uint32_t col = kVSwz ? dl.vcol : kcol;
+    if (full) {
+      dma16(base + (uint32_t)(4 * bi) * stride, lane_row + col, lds_addr_of(lds_tile + bi * 512));
+    } else {
+      int r = 4 * bi + (int)dl.rl;
       r = r < rows_valid ? r : rows_valid - 1;
-      const uint32_t off = (uint32_t)r * stride + (kVSwz ? dl.vcol : dl.kcol[n]);
-      dma16(base, off, lds_addr_of(lds_tile + (4 * wave + n) * 512));
+      dma16(base, (uint32_t)r * stride + col, lds_addr_of(lds_tile + bi * 512));
     }
   }
 }

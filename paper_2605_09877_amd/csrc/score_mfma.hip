@@ -55,7 +55,7 @@ __global__ __launch_bounds__(256, 2) void score_mfma_kernel(Dev dv, int slot, in
   const DmaLane dl = dma_lane(lane);
   auto issue_tile = [&](int t) {
     const int base = t * kTileKeys;
-    tile_dma<false>(khat + (uint32_t)base * (D * 2), D * 2, row1 - row0 - base, Ks[t & 1], wave, dl);
+    tile_dma<false, 4>(khat + (uint32_t)base * (D * 2), D * 2, row1 - row0 - base, Ks[t & 1], wave, dl);
   };
   if (t_begin < t_end) issue_tile(t_begin);
   for (int t = t_begin; t < t_end; ++t) {
