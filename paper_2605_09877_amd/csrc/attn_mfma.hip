@@ -14,10 +14,11 @@
 // one barrier per tile.  The mask is never materialised: it is the tile loop bounds plus a
 // compare on diagonal tiles.
 //
-// NW = 8 (256 queries; chunks that are a multiple of 256): half the tile bytes per flop, which
-// matters because the direct-to-LDS path, not the matrix cores, saturates first; one workgroup
-// per CU.  NW = 4 (128 queries): two workgroups per CU.  Either way the four tile buffers (two K,
-// two V) fill exactly the first 64 KiB of LDS.
+// The kernel runs NW = 4 (128 queries per workgroup, two workgroups per CU; the four tile buffers,
+// two K and two V, fill 64 KiB of LDS).  Eight waves on 256 queries halve the tile bytes per flop
+// but measured slower, both with one barrier per tile and with the two halves of the workgroup
+// running half a tile apart: the waves of one workgroup then move in step and their matrix and
+// softmax phases coincide instead of overlapping.
 #include "kvm_device.h"
 #include "kvm_internal.h"
 #include "kvm_mfma.h"
@@ -82,30 +83,42 @@ __device__ __forceinline__ void attn_body(const Dev &dv, const AttnArgs &a, uint
   float c_state = (dv.tau_state ? dv.tau_state[hq] : 1.f) * rs;
   float c_bswa = (dv.tau_bswa ? dv.tau_bswa[hq] : 1.f) * rs;
   // The softmax below takes the row maximum on raw dot products and applies a positive scale
-  // afterwards; for a negative temperature the dot products of that region are negated first.
-  const bool neg_state = c_state < 0.f, neg_bswa = c_bswa < 0.f;
+  // afterwards; for a negative temperature the region's dot products are negated, by flipping
+  // the sign of Q^T when the tile loop enters the region (exact in bf16, and K . (-Q) = -(K . Q)
+  // bit for bit).  Two bits of one wave-uniform scalar, so that the test is a scalar one.
+  const int neg_bits = __builtin_amdgcn_readfirstlane((c_state < 0.f ? 1 : 0) | (c_bswa < 0.f ? 2 : 0));
   c_state = fabsf(c_state);
   c_bswa = fabsf(c_bswa);
 
-  const int n_st = (m + kTileKeys - 1) / kTileKeys;
+  const int n_st = __builtin_amdgcn_readfirstlane((m + kTileKeys - 1) / kTileKeys);
   const int qend = (Q0 + kTileQ < nq) ? Q0 + kTileQ : nq;  // one past the last valid query here
   const int n_win = (int)((cs + qend - wb + kTileKeys - 1) / kTileKeys);
-  const int n_tiles = n_st + n_win;
+  const int n_tiles = __builtin_amdgcn_readfirstlane(n_st + n_win);
 
   // Tile sources, all wave-uniform: state rows of this chunk's version; window positions from the
   // call's own k/v (at or after t0) or from the ring (before t0).  Positions are kept relative
   // to the chunk start so that the per-tile arithmetic is 32-bit.
-  const char *khat = (const char *)dv.khat + (a.slot[ci] * dv.slot_elems + (int64_t)u * dv.Mcap * D) * 2;
-  const char *vhat = (const char *)dv.vhat + (a.slot[ci] * dv.slot_elems + (int64_t)u * dv.Mcap * D) * 2;
-  const char *ring_k = (const char *)dv.winK + (int64_t)u * dv.L * D * 2;
-  const char *ring_v = (const char *)dv.winV + (int64_t)u * dv.L * D * 2;
-  const uint32_t kst_in = (uint32_t)a.in.k_t * 2, vst_in = (uint32_t)a.in.v_t * 2;
-  const char *in_k = (const char *)a.in.k + (b * a.in.k_b + hkv * a.in.k_h + (cs - a.t0) * a.in.k_t) * 2;
-  const char *in_v = (const char *)a.in.v + (b * a.in.v_b + hkv * a.in.v_h + (cs - a.t0) * a.in.v_t) * 2;
-  const int wrel = (int)(wb - cs);                                   // first window position (<= 0)
-  const int t0rel = a.t0 - cs < -(1 << 30) ? -(1 << 30) : (int)(a.t0 - cs);
-  const int ring_slot0 = (int)(wb % dv.L);
-  const int last_rel = nq - 1;
+  // All of it is wave-uniform, which the compiler cannot see through the 64-bit divisions above:
+  // each value is pinned to scalar registers once, so that the per-tile address arithmetic and
+  // the loads' base operands are scalar instructions.
+  auto uni = [](int x) { return __builtin_amdgcn_readfirstlane(x); };
+  auto uni_ptr = [](const char *p_) {
+    const uint64_t x = (uint64_t)p_;
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)x);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(x >> 32));
+    return (const char *)(((uint64_t)hi << 32) | (uint64_t)lo);
+  };
+  const char *khat = uni_ptr((const char *)dv.khat + (a.slot[ci] * dv.slot_elems + (int64_t)u * dv.Mcap * D) * 2);
+  const char *vhat = uni_ptr((const char *)dv.vhat + (a.slot[ci] * dv.slot_elems + (int64_t)u * dv.Mcap * D) * 2);
+  const char *ring_k = uni_ptr((const char *)dv.winK + (int64_t)u * dv.L * D * 2);
+  const char *ring_v = uni_ptr((const char *)dv.winV + (int64_t)u * dv.L * D * 2);
+  const uint32_t kst_in = (uint32_t)uni((int)(a.in.k_t * 2)), vst_in = (uint32_t)uni((int)(a.in.v_t * 2));
+  const char *in_k = uni_ptr((const char *)a.in.k + (b * a.in.k_b + hkv * a.in.k_h + (cs - a.t0) * a.in.k_t) * 2);
+  const char *in_v = uni_ptr((const char *)a.in.v + (b * a.in.v_b + hkv * a.in.v_h + (cs - a.t0) * a.in.v_t) * 2);
+  const int wrel = uni((int)(wb - cs));                              // first window position (<= 0)
+  const int t0rel = uni(a.t0 - cs < -(1 << 30) ? -(1 << 30) : (int)(a.t0 - cs));
+  const int ring_slot0 = uni((int)(wb % dv.L));
+  const int last_rel = uni(nq - 1);
 
   // Per-lane fragment offsets (elements) from the start of the K / V buffers.  K has two buffers
   // and its offsets flip after every tile; V buffers are addressed by tile number.
@@ -113,36 +126,44 @@ __device__ __forceinline__ void attn_body(const Dev &dv, const AttnArgs &a, uint
   ktile_offsets(lane, koff);
   vtile_offsets(lane, voff);
   const DmaLane dl = dma_lane(lane);
+  const uint32_t ks_addr = lds_addr_of(Ks), vs_addr = lds_addr_of(Vs);
 
-  auto issue_tile = [&](int it) {
-    const char *kb_, *vb_;
+  struct TileSrc {
+    const char *k, *v;
     uint32_t kst, vst;
     int valid;
+  };
+  auto tile_src = [&](int it) {
+    TileSrc t;
     if (it < n_st) {
       const int row0 = it * kTileKeys;
-      kb_ = khat + (uint32_t)row0 * (D * 2);
-      vb_ = vhat + (uint32_t)row0 * (D * 2);
-      kst = vst = D * 2;
-      valid = m - row0;
+      t.k = khat + (uint32_t)row0 * (D * 2);
+      t.v = vhat + (uint32_t)row0 * (D * 2);
+      t.kst = t.vst = D * 2;
+      t.valid = m - row0;
     } else {
       const int w = it - n_st;
       const int prel = wrel + w * kTileKeys;
-      valid = last_rel - prel + 1;
+      t.valid = last_rel - prel + 1;
       if (prel >= t0rel) {
-        kb_ = in_k + (int64_t)prel * (int64_t)kst_in;
-        vb_ = in_v + (int64_t)prel * (int64_t)vst_in;
-        kst = kst_in;
-        vst = vst_in;
+        t.k = in_k + (int64_t)prel * (int64_t)kst_in;
+        t.v = in_v + (int64_t)prel * (int64_t)vst_in;
+        t.kst = kst_in;
+        t.vst = vst_in;
       } else {
         int slot = ring_slot0 + w * kTileKeys;
         slot = slot >= dv.L ? slot - dv.L : slot;   // a window is at most L long: one wrap
-        kb_ = ring_k + (uint32_t)slot * (D * 2);
-        vb_ = ring_v + (uint32_t)slot * (D * 2);
-        kst = vst = D * 2;
+        t.k = ring_k + (uint32_t)slot * (D * 2);
+        t.v = ring_v + (uint32_t)slot * (D * 2);
+        t.kst = t.vst = D * 2;
       }
     }
-    tile_dma<false, NW>(kb_, kst, valid, Ks + (it & 1) * kTileElems, wave, dl);
-    tile_dma<true, NW>(vb_, vst, valid, Vs + (it % kVBufs) * kTileElems, wave, dl);
+    return t;
+  };
+  auto issue_tile = [&](int it) {
+    const TileSrc t = tile_src(it);
+    tile_dma<false, NW>(t.k, t.kst, t.valid, ks_addr + (uint32_t)(it & 1) * (kTileElems * 2), wave, dl);
+    tile_dma<true, NW>(t.v, t.vst, t.valid, vs_addr + (uint32_t)(it % kVBufs) * (kTileElems * 2), wave, dl);
   };
 
   f32x16 oacc[4];
@@ -199,12 +220,6 @@ __device__ __forceinline__ void attn_body(const Dev &dv, const AttnArgs &a, uint
       }
       __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
     }
-    if (is_state ? neg_state : neg_bswa) {
-#pragma unroll
-      for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) sacc[blk][v] = -sacc[blk][v];
-    }
     if (need_mask) {
       // keys up to `lim` (tile-local) are visible to this lane's query
       const int lim = is_state ? (m - row0 - 1) : (int)(cs + myq - p0);
@@ -246,13 +261,32 @@ __device__ __forceinline__ void attn_body(const Dev &dv, const AttnArgs &a, uint
         pb[ks].w[e] = pack_bf16(sacc[ks >> 1][(ks & 1) * 8 + 2 * e], sacc[ks >> 1][(ks & 1) * 8 + 2 * e + 1]);
   };
 
+  // One barrier per tile: it publishes tile `it` (every wave has waited for its own share of the
+  // loads) and frees the buffers of tile it - 1 for the loads of tile it + 1.  (Measured and
+  // dropped: a second barrier per tile that lets K and V loads run a tile and a half ahead, and
+  // touching the lines of later tiles to pull them into L2 early; neither beat this loop.)
+  bool q_negated = false;
+  // Q^T is in registers from here on: said explicitly, or the compiler, which does not count the
+  // tile loads, would wait for "its" loads inside the loop and drain the tile loads with them
+  __builtin_amdgcn_s_waitcnt(0);
   issue_tile(0);
   for (int it = 0; it < n_tiles; ++it) {
-    // tile `it` has landed for every wave, and every wave is done reading the other buffers
+    const bool is_state = it < n_st;
+    if (((neg_bits & (is_state ? 1 : 2)) != 0) != q_negated) {
+      asm volatile("" ::: "memory");  // stays a (rarely taken) branch
+      q_negated = !q_negated;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        Frag8 f;
+        f.v = qreg[ks];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) f.w[e] ^= 0x80008000u;
+        qreg[ks] = f.v;
+      }
+    }
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     if (it + 1 < n_tiles) issue_tile(it + 1);
-    const bool is_state = it < n_st;
     const int64_t p0 = wb + (int64_t)(it - n_st) * kTileKeys;
     // skip tiles whose keys all lie after this wave's queries
     if (is_state || p0 <= cs + wq0 + 31) {
@@ -263,7 +297,6 @@ __device__ __forceinline__ void attn_body(const Dev &dv, const AttnArgs &a, uint
 #pragma unroll
     for (int i = 0; i < 8; ++i) koff[i] ^= (uint32_t)kTileElems;
   }
-
   const float l = l_part + __shfl_xor(l_part, 32, kWave);
   if (myq < nq) {
     const float inv = 1.f / l;
@@ -281,33 +314,22 @@ __device__ __forceinline__ void attn_body(const Dev &dv, const AttnArgs &a, uint
   }
 }
 
-// Static LDS only: 2 K + 2 V buffers = 64 KiB, so every direct-to-LDS destination is below
-// 64 KiB.
+// Static LDS: 2 K + 2 V tile buffers = 64 KiB, two workgroups per CU.
 __global__ __launch_bounds__(256, 2) void attn_mfma_kernel_q128(Dev dv, AttnArgs a) {
   __shared__ __attribute__((aligned(32768))) uint16_t Ks[2 * kTileElems];
   __shared__ __attribute__((aligned(1024))) uint16_t Vs[2 * kTileElems];
   attn_body<4>(dv, a, Ks, Vs);
-}
-__global__ __launch_bounds__(512, 2) void attn_mfma_kernel_q256(Dev dv, AttnArgs a) {
-  __shared__ __attribute__((aligned(32768))) uint16_t Ks[2 * kTileElems];
-  __shared__ __attribute__((aligned(1024))) uint16_t Vs[2 * kTileElems];
-  attn_body<8>(dv, a, Ks, Vs);
 }
 
 }  // namespace
 
 hipError_t launch_attn_mfma(const Dev &dv, const AttnArgs &a, hipStream_t st) {
   if (a.nq_total <= 0) return hipSuccess;
-  const bool wide = dv.C % 256 == 0;
-  const int tile_q = wide ? 256 : 128;
+  const int tile_q = 128;
   const int per_group = ((dv.C + tile_q - 1) / tile_q) * (dv.Hq / dv.Hkv);
   const int n_groups = a.n_chunks * dv.Hkv * dv.B;
   dim3 grid((unsigned)((n_groups + kXcds - 1) / kXcds * kXcds * per_group));
-  if (wide) {
-    hipLaunchKernelGGL(attn_mfma_kernel_q256, grid, dim3(512), 0, st, dv, a);
-  } else {
-    hipLaunchKernelGGL(attn_mfma_kernel_q128, grid, dim3(256), 0, st, dv, a);
-  }
+  hipLaunchKernelGGL(attn_mfma_kernel_q128, grid, dim3(256), 0, st, dv, a);
   return hipGetLastError();
 }
 

@@ -135,27 +135,31 @@ __device__ __forceinline__ uint32_t lds_addr_of(const void *p) {
 // The kNW waves of a workgroup share a tile's sixteen 1-KiB loads: wave w issues loads
 // bi = (16/kNW)*w + n, each fetching rows 4*bi .. 4*bi+3; kVSwz: V layout.  `base` (bytes) and
 // `stride` (bytes between rows) are wave-uniform; the per-lane part is a 32-bit byte offset, so
-// each load is scalar base + vector offset.  Rows at or beyond rows_valid repeat the last valid
+// each load is scalar base + vector offset.  lds_tile_addr: LDS byte address of the tile buffer.  Rows at or beyond rows_valid repeat the last valid
 // row (only looked at when the tile is not full).
 template <bool kVSwz, int kNW>
 __device__ __forceinline__ void tile_dma(const char *base, uint32_t stride, int rows_valid,
-                                         uint16_t *lds_tile, int wave, const DmaLane &dl) {
+                                         uint32_t lds_tile_addr, int wave, const DmaLane &dl) {
   constexpr int kPer = 16 / kNW;
-  const bool full = rows_valid >= kTileKeys;
-  const uint32_t lane_row = dl.rl * stride;
+  if (rows_valid >= kTileKeys) {
+    const uint32_t lane_row = dl.rl * stride;
 #pragma unroll
-  for (int n = 0; n < kPer; ++n) {
-    const int bi = kPer * wave + n;
-    // the K chunk permutation depends on bi % 4, which is n for four waves and
-    // 2*(wave%2) + n for eight (a wave-uniform choice between two precomputed values)
-    const uint32_t kcol = kPer == 4 ? dl.kcol[n] : ((wave & 1) ? dl.kcol[2 + n] : dl.kcol[n]);
-    const uint32_t col = kVSwz ? dl.vcol : kcol;
-    if (full) {
-      dma16(base + (uint32_t)(4 * bi) * stride, lane_row + col, lds_addr_of(lds_tile + bi * 512));
-    } else {
+    for (int n = 0; n < kPer; ++n) {
+      const int bi = kPer * wave + n;
+      // the K chunk permutation depends on bi % 4, which is n for four waves and
+      // 2*(wave%2) + n for eight (a wave-uniform choice between two precomputed values)
+      const uint32_t kcol = kPer == 4 ? dl.kcol[n] : ((wave & 1) ? dl.kcol[2 + n] : dl.kcol[n]);
+      dma16(base + (uint32_t)(4 * bi) * stride, lane_row + (kVSwz ? dl.vcol : kcol),
+            lds_tile_addr + (uint32_t)bi * 1024u);
+    }
+  } else {
+#pragma unroll
+    for (int n = 0; n < kPer; ++n) {
+      const int bi = kPer * wave + n;
+      const uint32_t kcol = kPer == 4 ? dl.kcol[n] : ((wave & 1) ? dl.kcol[2 + n] : dl.kcol[n]);
       int r = 4 * bi + (int)dl.rl;
       r = r < rows_valid ? r : rows_valid - 1;
-      dma16(base, (uint32_t)r * stride + col, lds_addr_of(lds_tile + bi * 512));
+      dma16(base, (uint32_t)r * stride + (kVSwz ? dl.vcol : kcol), lds_tile_addr + (uint32_t)bi * 1024u);
     }
   }
 }

@@ -53,9 +53,11 @@ __global__ __launch_bounds__(256, 2) void score_mfma_kernel(Dev dv, int slot, in
 
   const char *khat = (const char *)dv.khat + (slot * dv.slot_elems + ((int64_t)u * dv.Mcap + row0) * D) * 2;
   const DmaLane dl = dma_lane(lane);
+  const uint32_t ks_addr = lds_addr_of(&Ks[0][0]);
   auto issue_tile = [&](int t) {
     const int base = t * kTileKeys;
-    tile_dma<false, 4>(khat + (uint32_t)base * (D * 2), D * 2, row1 - row0 - base, Ks[t & 1], wave, dl);
+    tile_dma<false, 4>(khat + (uint32_t)base * (D * 2), D * 2, row1 - row0 - base,
+                       ks_addr + (uint32_t)(t & 1) * (kTileElems * 2), wave, dl);
   };
   if (t_begin < t_end) issue_tile(t_begin);
   for (int t = t_begin; t < t_end; ++t) {

@@ -25,12 +25,14 @@ def synth():
     return s
 
 
-def run_prefill_case(w, plain, split=None, decode_tail=0, check_lse=True, units=None):
+def run_prefill_case(w, plain, split=None, decode_tail=0, check_lse=True, units=None, tweak=None):
     """Prefill (optionally in two calls, optionally finishing with decode steps) on the GPU and in
     the oracle; compare sizes, assignments, scores, outputs, lse and the final state."""
     pkg, sy = kvm(), synth()
     q, k, v = sy.make_qkv(w, DEV)
     params = sy.make_params(w, DEV, plain=plain)
+    if tweak is not None:
+        tweak(params)
     gate = params["gate"]
     st = pkg.state_for(w, device=DEV, **params)
     T = w.seq
@@ -116,6 +118,18 @@ def test_bf16_fixed_budget_prefill(plain):
     w = synth().shrink(synth().WORKLOADS["prefill_fixed"], batch=2, n_q_heads=2, n_kv_heads=2, seq=2560 + 77)
     ties, st = run_prefill_case(w, plain=plain)
     assert st.rows == 512
+
+
+def test_bf16_negative_temperatures():
+    """Learned temperatures may be negative: one sign per region and head, in every combination
+    (the matrix-core kernel flips the sign of its query fragments when it changes region)."""
+    w = synth().shrink(synth().WORKLOADS["prefill_fixed"], batch=1, n_q_heads=4, n_kv_heads=2, seq=1536 + 40)
+
+    def tweak(params):
+        params["tau_state"] *= torch.tensor([1.0, -1.0, 1.0, -1.0], device=DEV)
+        params["tau_bswa"] *= torch.tensor([1.0, 1.0, -1.0, -1.0], device=DEV)
+
+    run_prefill_case(w, plain=False, tweak=tweak)
 
 
 def test_bf16_sqrt_growth_prefill():
