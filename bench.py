@@ -24,6 +24,30 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E peak
 
 
+def measured_traffic(summary):
+    """HBM bytes per launch of a kernel, as committed under profiles/ (derived from the
+    FETCH_SIZE and WRITE_SIZE counters of this same command, scaled by what the counters read
+    for a plain copy of known size); None when there is no such summary."""
+    path = os.path.join(ROOT, "profiles", summary)
+    try:
+        for ln in open(path):
+            if ln.startswith("traffic_bytes_per_launch:"):
+                return float(ln.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+def copy_calibration(dev):
+    """A plain device copy of known size (1 GiB read, 1 GiB written), for scaling HBM counters."""
+    import torch
+    src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        torch.add(src, 0.0, out=dst)   # one elementwise kernel: reads src once, writes dst once
+    torch.cuda.synchronize()
+
+
 def attention_flops(w, T):
     """Algorithmic attention flops of a T-token prefill: 4*d per visible (query, key) pair, pairs
     per chunk and query head = C*(m + tokens of earlier window blocks) + C*(C+1)/2."""
@@ -65,12 +89,14 @@ def prefill_leg(args, pkg, synth, dev):
     dt = time.perf_counter() - t0
     prof = st.profile_read()
     # the same step with folds and attention kept apart: each kernel's time without the other
-    st.profile(2)
-    for _ in range(2):
-        st.reset()
-        st.prefill(q, k, v, out=out)
-    torch.cuda.synchronize()
-    iso = st.profile_read()
+    iso = None
+    if not args.no_isolated:
+        st.profile(2)
+        for _ in range(2):
+            st.reset()
+            st.prefill(q, k, v, out=out)
+        torch.cuda.synchronize()
+        iso = st.profile_read()
     st.profile(False)
     tokens = w.batch * w.seq
     flops, _ = attention_flops(w, w.seq)
@@ -79,16 +105,21 @@ def prefill_leg(args, pkg, synth, dev):
     launches = max(attn_n // max(args.steps, 1), 1)      # attention launches per step (groups of chunks)
     avg_launch_s = attn_ms / max(attn_n, 1) * 1e-3
     achieved = flops / launches / avg_launch_s / 1e12 if attn_n else 0.0
-    iso_tflops = flops / launches / (iso["attn"][0] / max(iso["attn"][1], 1) * 1e-3) / 1e12
+    isolated = None
+    if iso is not None:
+        iso_tflops = flops / launches / (iso["attn"][0] / max(iso["attn"][1], 1) * 1e-3) / 1e12
+        isolated = dict(achieved=iso_tflops, frac=iso_tflops / MFMA_BF16_PEAK_TFLOPS,
+                        attn_ms_per_step=iso["attn"][0] / 2, fold_ms_per_step=iso["fold"][0] / 2)
     res = dict(
         value=tokens * args.steps / dt, ms_per_step=dt / args.steps * 1e3,
         roofline=dict(bound="mfma", kernel="attn_mfma_kernel", achieved=achieved, peak=MFMA_BF16_PEAK_TFLOPS,
-                      unit="TFLOP/s", frac=achieved / MFMA_BF16_PEAK_TFLOPS, traffic=None,
+                      unit="TFLOP/s", frac=achieved / MFMA_BF16_PEAK_TFLOPS,
+                      traffic=measured_traffic("attn_mfma_kernel_prefill_gqa_32k_hbm_traffic.txt")
+                      if w.name == "prefill_gqa_32k" else None,
                       launches_per_step=launches, avg_launch_us=avg_launch_s * 1e6,
                       attn_ms_per_step=attn_ms / args.steps, fold_ms_per_step=fold_ms / args.steps,
                       folds_per_step=fold_n // max(args.steps, 1),
-                      isolated=dict(achieved=iso_tflops, frac=iso_tflops / MFMA_BF16_PEAK_TFLOPS,
-                                    attn_ms_per_step=iso["attn"][0] / 2, fold_ms_per_step=iso["fold"][0] / 2)),
+                      isolated=isolated),
         workload=w)
     return res, (q, k, v)
 
@@ -131,7 +162,8 @@ def decode_leg(args, pkg, synth, dev):
                 config=dict(workload="decode", batch=w.batch, heads=w.n_q_heads, head_dim=d, state_rows=m,
                             window=L, chunk_len=C),
                 roofline=dict(bound="hbm", kernel="attn_rows_kernel", achieved=gbs, peak=HBM_PEAK_GBS,
-                              unit="GB/s", frac=gbs / HBM_PEAK_GBS, traffic=None,
+                              unit="GB/s", frac=gbs / HBM_PEAK_GBS,
+                              traffic=measured_traffic("attn_rows_kernel_decode_hbm_traffic.txt"),
                               avg_launch_us=avg_s * 1e6, bytes_per_launch=bytes_per_step))
 
 
@@ -174,6 +206,10 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-isolated", action="store_true",
+                    help="skip the extra passes that time folds and attention apart")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -203,6 +239,8 @@ def main():
         line["decode"] = decode_leg(args, pkg, synth, dev)
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline_leg(w, tensors, args.cpu_seconds)
+    if args.copy_calibration:
+        copy_calibration(dev)
     print(json.dumps(line))
 
 
