@@ -5,8 +5,8 @@
 //   memkey : k-bar_j = LN_s(k_j with the rotary channels zeroed), materialised in the I/O dtype
 //   score  : s_j = max_i k-bar_j . s-hat^K_i and pi(j) = argmax_{i >= S}   (generic, fp64 dot)
 //   select : the n_append smallest s_j become new rows, in position order
-//   index  : merged tokens are sorted by (target row, position); per-row counts and offsets
-//   accum  : new rows are created, merged tokens are added to their row in position order,
+//   accum  : new rows are created, each row finds the tokens that merge into it and adds them in
+//            position order,
 //            touched rows get their normalised readout (LN_s on keys, stored radius on values)
 //
 // Everything that decides an integer (LN_s of keys, the key sums) is computed in fp64 so that
@@ -191,86 +191,39 @@ __global__ __launch_bounds__(256) void select_kernel(Dev dv, int m, int n_app, i
   }
 }
 
-// ------------------------------------------------------------------ winners of split scoring + merge index
-// One workgroup per unit.  n_splits > 0: the scoring pass left one candidate per row split and
-// token; they are merged here in ascending row order (a later split wins only with a strictly
-// larger score, so ties keep the lowest row).  do_index: tokens that merge are counting-sorted
-// by target row, stably in position, so that the accumulate pass can walk each row's tokens in
-// ascending position without searching.
-__global__ __launch_bounds__(512) void index_kernel(Dev dv, int m_after, int n_splits, int do_index) {
-  extern __shared__ int shi[];  // m_after counters, then C targets
-  int *cnt = shi;
-  int *tgt = shi + m_after;
-  const int u = blockIdx.x, C = dv.C;
-  const int64_t base = (int64_t)u * C;
-  if (n_splits > 0) {
-    for (int j = threadIdx.x; j < C; j += blockDim.x) {
-      float best_all = -INFINITY, best = -INFINITY;
-      int best_i = 0x7fffffff;
-      for (int r = 0; r < n_splits; ++r) {
-        const float4 cd = dv.cand[(base + j) * kScoreSplits + r];
-        best_all = fmaxf(best_all, cd.x);
-        if (cd.y > best) {
-          best = cd.y;
-          best_i = __float_as_int(cd.z);
-        }
-      }
-      dv.score[base + j] = make_float2(best_all, best);
-      dv.pi[base + j] = best_i;
-      dv.app[base + j] = -1;
-      tgt[j] = best_i;
-    }
-  } else if (do_index) {
-    for (int j = threadIdx.x; j < C; j += blockDim.x) tgt[j] = dv.app[base + j] < 0 ? dv.pi[base + j] : -1;
-  }
-  if (!do_index) return;
-  for (int i = threadIdx.x; i < m_after; i += blockDim.x) cnt[i] = 0;
-  __syncthreads();
-  for (int j = threadIdx.x; j < C; j += blockDim.x)
-    if (tgt[j] >= 0) atomicAdd(&cnt[tgt[j]], 1);
-  __syncthreads();
-  // exclusive scan of the counters by one wave (m_after is a few thousand at most)
-  if (threadIdx.x < 64) {
-    const int lane = threadIdx.x;
-    const int per = (m_after + 63) / 64;
-    const int lo = lane * per, hi = min(lo + per, m_after);
-    int sum = 0;
-    for (int i = lo; i < hi; ++i) sum += cnt[i];
-    int incl = sum;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const int v = __shfl_up(incl, o, kWave);
-      if (lane >= o) incl += v;
-    }
-    int run = incl - sum;
-    for (int i = lo; i < hi; ++i) {
-      const int c = cnt[i];
-      dv.row_cnt[(int64_t)u * dv.Mcap + i] = c;
-      dv.row_start[(int64_t)u * dv.Mcap + i] = run;
-      cnt[i] = run;  // becomes the row's start offset
-      run += c;
+// ------------------------------------------------------------------ winners of split scoring
+// The matrix-core scoring pass leaves one candidate per row split and token; they are merged in
+// ascending row order (a later split wins only with a strictly larger score, so ties keep the
+// lowest row).
+__global__ __launch_bounds__(256) void winners_kernel(Dev dv, int n_splits) {
+  const int64_t tj = (int64_t)blockIdx.y * dv.C + blockIdx.x * 256 + threadIdx.x;
+  if (blockIdx.x * 256 + threadIdx.x >= dv.C) return;
+  float best_all = -INFINITY, best = -INFINITY;
+  int best_i = 0x7fffffff;
+  for (int r = 0; r < n_splits; ++r) {
+    const float4 cd = dv.cand[tj * kScoreSplits + r];
+    best_all = fmaxf(best_all, cd.x);
+    if (cd.y > best) {
+      best = cd.y;
+      best_i = __float_as_int(cd.z);
     }
   }
-  __syncthreads();
-  for (int j = threadIdx.x; j < C; j += blockDim.x) {
-    const int t = tgt[j];
-    if (t < 0) continue;
-    int rank = 0;
-    for (int i = 0; i < j; ++i) rank += tgt[i] == t ? 1 : 0;
-    dv.order[base + cnt[t] + rank] = j;
-  }
+  dv.score[tj] = make_float2(best_all, best);
+  dv.pi[tj] = best_i;
+  dv.app[tj] = -1;
 }
 
 // ------------------------------------------------------------------ create + merge + readout refresh
 // One wave per state row in [row_begin, m_after) of the updated state.  do_create: rows >=
-// m_before are created from their creator token; do_merge: the row's tokens (index_kernel) are
-// added in ascending position; do_copy: an untouched row's readout is copied to the new state
+// m_before are created from their creator token; do_merge: the tokens whose target is this row
+// are added in ascending position; do_copy: an untouched row's readout is copied to the new state
 // version.  A fold that appends only part of the block runs create first (so the new rows have
 // a normalised key to score against), then the second scoring pass, then merge.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void accum_kernel(Dev dv, Src src, int m_before, int m_after,
                                                     int row_begin, int do_create, int do_merge,
-                                                    int do_copy, int slot_old, int slot_new) {
+                                                    int do_copy, int check_app, int slot_old,
+                                                    int slot_new) {
   constexpr int CPL = D / 64;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int u = blockIdx.y, b = u / dv.Hkv, h = u % dv.Hkv;
@@ -304,34 +257,51 @@ __global__ __launch_bounds__(256) void accum_kernel(Dev dv, Src src, int m_befor
     n = 1;
     loaded = true;
   }
-  const int cnt = (do_merge && row >= dv.S) ? dv.row_cnt[ro] : 0;
-  if (cnt > 0) {
-    if (!loaded) {
+  if (do_merge && row >= dv.S) {
+    // The tokens that merge into this row, in ascending position: every wave scans the block's
+    // targets itself (C integers from L2), 64 tokens per ballot, eight ballots per round trip.
+    // check_app: tokens appended in this fold carry their own new row in pi and do not merge.
+    for (int j0 = 0; j0 < C; j0 += 512) {
+      int tg[8];
 #pragma unroll
-      for (int c = 0; c < CPL; ++c) {
-        sk[c] = dv.sK[ro * D + lane * CPL + c];
-        sv[c] = dv.sV[ro * D + lane * CPL + c];
+      for (int bk = 0; bk < 8; ++bk) {
+        const int j = j0 + 64 * bk + lane;
+        tg[bk] = j < C ? dv.pi[base + j] : -1;
       }
-      rho = dv.rho[ro];
-      w = dv.w[ro];
-      n = dv.n[ro];
-      loaded = true;
-    }
-    const int32_t *ord = dv.order + base + dv.row_start[ro];
-    for (int i0 = 0; i0 < cnt; i0 += 64) {
-      const int mine = i0 + lane < cnt ? ord[i0 + lane] : 0;   // this row's tokens, ascending position
-      const int nb = min(64, cnt - i0);
-      for (int i = 0; i < nb; ++i) {
-        const int t = __shfl(mine, i, kWave);
-        const float g = gsrc ? gsrc[(int64_t)t * src.g_t] : 1.f;
+      if (check_app) {
 #pragma unroll
-        for (int c = 0; c < CPL; ++c) {
-          const int ch = lane * CPL + c;
-          sk[c] = fma((double)g, (double)Io<T>::load(kbar + (int64_t)t * D + ch), sk[c]);
-          sv[c] = fmaf(g, Io<T>::load(vsrc + (int64_t)t * src.v_t + ch), sv[c]);
+        for (int bk = 0; bk < 8; ++bk) {
+          const int j = j0 + 64 * bk + lane;
+          if (j < C && dv.app[base + j] >= 0) tg[bk] = -1;
         }
-        w += g;
-        n += 1;
+      }
+#pragma unroll
+      for (int bk = 0; bk < 8; ++bk) {
+        uint64_t hits = __builtin_amdgcn_ballot_w64(tg[bk] == row);
+        while (hits) {
+          const int t = j0 + 64 * bk + __builtin_ctzll(hits);
+          hits &= hits - 1;
+          if (!loaded) {
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) {
+              sk[c] = dv.sK[ro * D + lane * CPL + c];
+              sv[c] = dv.sV[ro * D + lane * CPL + c];
+            }
+            rho = dv.rho[ro];
+            w = dv.w[ro];
+            n = dv.n[ro];
+            loaded = true;
+          }
+          const float g = gsrc ? gsrc[(int64_t)t * src.g_t] : 1.f;
+#pragma unroll
+          for (int c = 0; c < CPL; ++c) {
+            const int ch = lane * CPL + c;
+            sk[c] = fma((double)g, (double)Io<T>::load(kbar + (int64_t)t * D + ch), sk[c]);
+            sv[c] = fmaf(g, Io<T>::load(vsrc + (int64_t)t * src.v_t + ch), sv[c]);
+          }
+          w += g;
+          n += 1;
+        }
       }
     }
   }
@@ -436,19 +406,18 @@ hipError_t launch_select(const Dev &dv, int m, int n_app, bool take_all, hipStre
   return hipGetLastError();
 }
 
-hipError_t launch_index(const Dev &dv, int m_after, int n_splits, bool do_index, hipStream_t st) {
-  hipLaunchKernelGGL(index_kernel, dim3(dv.U), dim3(512), (size_t)(m_after + dv.C) * 4, st, dv, m_after,
-                     n_splits, do_index ? 1 : 0);
+hipError_t launch_winners(const Dev &dv, int n_splits, hipStream_t st) {
+  hipLaunchKernelGGL(winners_kernel, dim3((dv.C + 255) / 256, dv.U), dim3(256), 0, st, dv, n_splits);
   return hipGetLastError();
 }
 
 hipError_t launch_accum(const Dev &dv, const Src &src, int m_before, int m_after, int row_begin,
-                        bool do_create, bool do_merge, bool do_copy, int slot_old, int slot_new,
-                        hipStream_t st) {
+                        bool do_create, bool do_merge, bool do_copy, bool check_app, int slot_old,
+                        int slot_new, hipStream_t st) {
   if (m_after <= row_begin) return hipSuccess;
   dim3 grid((m_after - row_begin + 3) / 4, dv.U);
   KVM_DISPATCH(dv, accum_kernel, grid, dim3(256), 0, st, dv, src, m_before, m_after, row_begin,
-               do_create ? 1 : 0, do_merge ? 1 : 0, do_copy ? 1 : 0, slot_old, slot_new);
+               do_create ? 1 : 0, do_merge ? 1 : 0, do_copy ? 1 : 0, check_app ? 1 : 0, slot_old, slot_new);
   return hipGetLastError();
 }
 

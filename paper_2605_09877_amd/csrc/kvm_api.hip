@@ -131,8 +131,7 @@ int64_t capacity_rows(const kvm_config &c, const std::vector<int64_t> &table, in
 }
 
 struct Layout {
-  size_t sK, sV, rho, w, n, khat, vhat, winK, winV, winG, kbar, score, pi, app, creator, cand, row_cnt,
-      row_start, order, total;
+  size_t sK, sV, rho, w, n, khat, vhat, winK, winV, winG, kbar, score, pi, app, creator, cand, total;
 };
 
 bool use_mfma(const kvm_config &c) {
@@ -169,9 +168,6 @@ Layout layout_of(const kvm_config &c, int64_t Mcap) {
   l.app = take(U * C * 4);
   l.creator = take(U * C * 4);
   l.cand = take(U * C * kvm::kScoreSplits * 16);
-  l.row_cnt = take(U * M * 4);
-  l.row_start = take(U * M * 4);
-  l.order = take(U * C * 4);
   l.total = o;
   return l;
 }
@@ -195,9 +191,6 @@ void bind(Dev &dv, const kvm_config &c, void *buf, int64_t Mcap) {
   dv.app = (int32_t *)(p + l.app);
   dv.creator = (int32_t *)(p + l.creator);
   dv.cand = (float4 *)(p + l.cand);
-  dv.row_cnt = (int32_t *)(p + l.row_cnt);
-  dv.row_start = (int32_t *)(p + l.row_start);
-  dv.order = (int32_t *)(p + l.order);
   dv.gamma = c.ln_gamma;
   dv.beta = c.ln_beta;
   dv.tau_state = c.tau_state;
@@ -264,26 +257,26 @@ int fold_block(kvm_state *st, const Src &src, int64_t e, int32_t *assign_out, fl
   if (n_app == dv.C) {
     // room for the whole block (state creation included): no scores are needed
     HIP_TRY(kvm::launch_select(dv, (int)m, n_app, true, stream));
-    HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, 0, true, false, true, so, sn, stream));
+    HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, 0, true, false, true, false, so, sn, stream));
   } else {
-    int splits = 0;  // > 0: candidates per row split wait in dv.cand for index_kernel
+    int splits = 0;  // > 0: candidates per row split wait in dv.cand for winners_kernel
     if (st->mfma)
       HIP_TRY(kvm::launch_score_mfma(dv, so, 0, (int)m, true, &splits, stream));
     else
       HIP_TRY(kvm::launch_score(dv, so, 0, (int)m, true, stream));
     if (n_app > 0) {
       // new rows first, so that the remaining tokens can be scored against them too
-      if (splits > 0) HIP_TRY(kvm::launch_index(dv, (int)m_after, splits, false, stream));
+      if (splits > 0) HIP_TRY(kvm::launch_winners(dv, splits, stream));
       HIP_TRY(kvm::launch_select(dv, (int)m, n_app, false, stream));
-      HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, (int)m, true, false, false, so, sn, stream));
+      HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, (int)m, true, false, false, false, so, sn, stream));
       if (st->mfma)
         HIP_TRY(kvm::launch_score_mfma(dv, sn, (int)m, (int)m_after, false, nullptr, stream));
       else
         HIP_TRY(kvm::launch_score(dv, sn, (int)m, (int)m_after, false, stream));
       splits = 0;
     }
-    HIP_TRY(kvm::launch_index(dv, (int)m_after, splits, true, stream));
-    HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, 0, false, true, true, so, sn, stream));
+    if (splits > 0) HIP_TRY(kvm::launch_winners(dv, splits, stream));
+    HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, 0, false, true, true, n_app > 0, so, sn, stream));
   }
   const size_t ntok = (size_t)dv.U * dv.C;
   if (assign_out)

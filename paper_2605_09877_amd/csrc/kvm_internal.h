@@ -43,9 +43,6 @@ struct Dev {
   int32_t *app;      // [U, C]    rank among appended tokens, or -1
   int32_t *creator;  // [U, C]    token that creates new row number a
   float4 *cand;      // [U, C, kScoreSplits] per row-split: (max over all rows, best eligible, row bits, -)
-  int32_t *row_cnt;  // [U, Mcap] merged tokens per row in this fold
-  int32_t *row_start;  // [U, Mcap] first entry of the row in `order`
-  int32_t *order;    // [U, C]    merged tokens sorted by (row, position)
   // parameters
   const float *gamma, *beta;          // [H_kv, d] or null
   const float *tau_state, *tau_bswa;  // [H_q] or null
@@ -77,10 +74,10 @@ struct AttnArgs {
 hipError_t launch_memkey(const Dev &dv, const Src &src, int n_blocks, hipStream_t st);
 hipError_t launch_score(const Dev &dv, int slot, int row0, int row1, bool first_pass, hipStream_t st);
 hipError_t launch_select(const Dev &dv, int m, int n_app, bool take_all, hipStream_t st);
-hipError_t launch_index(const Dev &dv, int m_after, int n_splits, bool do_index, hipStream_t st);
+hipError_t launch_winners(const Dev &dv, int n_splits, hipStream_t st);
 hipError_t launch_accum(const Dev &dv, const Src &src, int m_before, int m_after, int row_begin,
-                        bool do_create, bool do_merge, bool do_copy, int slot_old, int slot_new,
-                        hipStream_t st);
+                        bool do_create, bool do_merge, bool do_copy, bool check_app, int slot_old,
+                        int slot_new, hipStream_t st);
 hipError_t launch_refresh(const Dev &dv, int m, int slot, hipStream_t st);
 hipError_t launch_ring_copy(const Dev &dv, const Src &src, int64_t src_t0, int64_t p0, int64_t p1,
                             hipStream_t st);
