@@ -16,43 +16,9 @@ namespace {
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
-template <typename T>
-struct Frag;
-template <>
-struct Frag<float> {
-  static constexpr int kVec = 4;
-  __device__ static __forceinline__ void load(const float *p, float (&f)[4]) {
-    const float4 x = *reinterpret_cast<const float4 *>(p);
-    f[0] = x.x; f[1] = x.y; f[2] = x.z; f[3] = x.w;
-  }
-  __device__ static __forceinline__ void store(float *p, const float (&f)[4]) {
-    *reinterpret_cast<float4 *>(p) = make_float4(f[0], f[1], f[2], f[3]);
-  }
-};
-template <>
-struct Frag<bf16_t> {
-  static constexpr int kVec = 8;
-  __device__ static __forceinline__ void load(const bf16_t *p, float (&f)[8]) {
-    const uint4 x = *reinterpret_cast<const uint4 *>(p);
-    const uint32_t wds[4] = {x.x, x.y, x.z, x.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      f[2 * i] = __uint_as_float(wds[i] << 16);
-      f[2 * i + 1] = __uint_as_float(wds[i] & 0xffff0000u);
-    }
-  }
-  __device__ static __forceinline__ void store(bf16_t *p, const float (&f)[8]) {
-    uint32_t wds[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      wds[i] = (uint32_t)float_to_bf16_bits(f[2 * i]) | ((uint32_t)float_to_bf16_bits(f[2 * i + 1]) << 16);
-    *reinterpret_cast<uint4 *>(p) = make_uint4(wds[0], wds[1], wds[2], wds[3]);
-  }
-};
-
 template <typename T, int D>
 __global__ __launch_bounds__(256) void attn_rows_kernel(Dev dv, AttnArgs a) {
-  constexpr int VEC = Frag<T>::kVec;
+  constexpr int VEC = Vec16<T>::kN;
   constexpr int LPR = D / VEC;   // lanes per key row
   constexpr int RPW = 64 / LPR;  // key rows per wave step
   constexpr int KB = 4;          // rows in flight per lane group
@@ -67,7 +33,7 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(Dev dv, AttnArgs a) {
   const int64_t wb = cs + dv.C - dv.L > 0 ? cs + dv.C - dv.L : 0;  // first window position
 
   float qf[VEC];
-  Frag<T>::load((const T *)a.q + b * a.q_b + (int64_t)qi * a.q_t + hq * a.q_h + cl * VEC, qf);
+  Vec16<T>::load((const T *)a.q + b * a.q_b + (int64_t)qi * a.q_t + hq * a.q_h + cl * VEC, qf);
   const float rs = kLog2e * rsqrtf((float)D);
   const float c_state = (dv.tau_state ? dv.tau_state[hq] : 1.f) * rs;
   const float c_bswa = (dv.tau_bswa ? dv.tau_bswa[hq] : 1.f) * rs;
@@ -107,8 +73,8 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(Dev dv, AttnArgs a) {
           vp = ring_v + (int64_t)slot * D;
         }
       }
-      Frag<T>::load(kp + cl * VEC, kf[kb]);
-      Frag<T>::load(vp + cl * VEC, vf[kb]);
+      Vec16<T>::load(kp + cl * VEC, kf[kb]);
+      Vec16<T>::load(vp + cl * VEC, vf[kb]);
       t[kb] = (n < total) ? (nc < m ? c_state : c_bswa) : 0.f;  // holds the scale for now
     }
     float m_new = m_run;
@@ -178,7 +144,7 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(Dev dv, AttnArgs a) {
     const float inv = 1.f / l;
 #pragma unroll
     for (int i = 0; i < VEC; ++i) o[i] *= inv;
-    Frag<T>::store((T *)a.out + b * a.o_b + (int64_t)qi * a.o_t + hq * a.o_h + cl * VEC, o);
+    Vec16<T>::store((T *)a.out + b * a.o_b + (int64_t)qi * a.o_t + hq * a.o_h + cl * VEC, o);
     if (a.lse && cl == 0)
       a.lse[b * a.lse_b + (int64_t)qi * a.lse_t + hq * a.lse_h] = (mm + log2f(l)) * kLn2;
   }

@@ -57,37 +57,47 @@ __device__ __forceinline__ void write_readout(const Dev &dv, int slot, int u, in
 // ------------------------------------------------------------------ memory keys
 // Covers n_blocks consecutive C-token blocks of `src`; block i goes to the i-th [U, C, d] slab
 // after dv.kbar (memory keys depend on k alone, so a prefill computes them a group at a time).
+// A token takes D / kN adjacent lanes, 16 bytes of channels each, so a wave handles several tokens.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void memkey_kernel(Dev dv, Src src, int n_blocks) {
-  constexpr int CPL = D / 64;
+  constexpr int VEC = Vec16<T>::kN;
+  constexpr int LPT = D / VEC;   // lanes per token
+  constexpr int TPW = 64 / LPT;  // tokens per wave
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane / LPT, cl = lane % LPT;
   const int u = blockIdx.y, b = u / dv.Hkv, h = u % dv.Hkv;
-  const int j = blockIdx.x * 4 + wave;
-  if (j >= dv.C * n_blocks) return;
-  const T *krow = (const T *)src.k + b * src.k_b + h * src.k_h + (int64_t)j * src.k_t;
-  double x[CPL];
+  const int n_tok = dv.C * n_blocks;
+  const int j = (blockIdx.x * 4 + wave) * TPW + sub;
+  const int jc = j < n_tok ? j : n_tok - 1;  // lanes past the end repeat the last token, store nothing
+  const T *krow = (const T *)src.k + b * src.k_b + h * src.k_h + (int64_t)jc * src.k_t;
+  float raw[VEC];
+  Vec16<T>::load(krow + cl * VEC, raw);
+  double x[VEC];
   double s = 0.0;
 #pragma unroll
-  for (int c = 0; c < CPL; ++c) {
-    const int ch = lane * CPL + c;
-    x[c] = ch < dv.r ? 0.0 : (double)Io<T>::load(krow + ch);
+  for (int c = 0; c < VEC; ++c) {
+    x[c] = cl * VEC + c < dv.r ? 0.0 : (double)raw[c];
     s += x[c];
   }
-  const double mean = wave_sum(s) / (double)D;
+  const double mean = group_sum<LPT>(s) / (double)D;
   double q = 0.0;
 #pragma unroll
-  for (int c = 0; c < CPL; ++c) {
+  for (int c = 0; c < VEC; ++c) {
     const double dl = x[c] - mean;
     q += dl * dl;
   }
-  const double rden = 1.0 / sqrt(wave_sum(q) / (double)D + (double)dv.ln_eps);
-  T *out = (T *)dv.kbar + ((int64_t)(j / dv.C) * dv.U * dv.C + (int64_t)u * dv.C + j % dv.C) * D;
+  const double rden = 1.0 / sqrt(group_sum<LPT>(q) / (double)D + (double)dv.ln_eps);
+  float y[VEC];
 #pragma unroll
-  for (int c = 0; c < CPL; ++c) {
-    const int ch = lane * CPL + c;
+  for (int c = 0; c < VEC; ++c) {
+    const int ch = cl * VEC + c;
     const double ga = dv.gamma ? (double)dv.gamma[h * D + ch] : 1.0;
     const double be = dv.beta ? (double)dv.beta[h * D + ch] : 0.0;
-    Io<T>::store(out + ch, Io<T>::round_from((x[c] - mean) * rden * ga + be));
+    y[c] = Io<T>::round_from((x[c] - mean) * rden * ga + be);
+  }
+  if (j < n_tok) {
+    T *out = (T *)dv.kbar + ((int64_t)(j / dv.C) * dv.U * dv.C + (int64_t)u * dv.C + j % dv.C) * D;
+    Vec16<T>::store(out + cl * VEC, y);
   }
 }
 
@@ -189,28 +199,6 @@ __global__ __launch_bounds__(256) void select_kernel(Dev dv, int m, int n_app, i
       dv.app[base + j] = -1;
     }
   }
-}
-
-// ------------------------------------------------------------------ winners of split scoring
-// The matrix-core scoring pass leaves one candidate per row split and token; they are merged in
-// ascending row order (a later split wins only with a strictly larger score, so ties keep the
-// lowest row).
-__global__ __launch_bounds__(256) void winners_kernel(Dev dv, int n_splits) {
-  const int64_t tj = (int64_t)blockIdx.y * dv.C + blockIdx.x * 256 + threadIdx.x;
-  if (blockIdx.x * 256 + threadIdx.x >= dv.C) return;
-  float best_all = -INFINITY, best = -INFINITY;
-  int best_i = 0x7fffffff;
-  for (int r = 0; r < n_splits; ++r) {
-    const float4 cd = dv.cand[tj * kScoreSplits + r];
-    best_all = fmaxf(best_all, cd.x);
-    if (cd.y > best) {
-      best = cd.y;
-      best_i = __float_as_int(cd.z);
-    }
-  }
-  dv.score[tj] = make_float2(best_all, best);
-  dv.pi[tj] = best_i;
-  dv.app[tj] = -1;
 }
 
 // ------------------------------------------------------------------ create + merge + readout refresh
@@ -389,7 +377,8 @@ __global__ __launch_bounds__(64) void ring_copy_kernel(Dev dv, Src src, int64_t 
 }  // namespace
 
 hipError_t launch_memkey(const Dev &dv, const Src &src, int n_blocks, hipStream_t st) {
-  dim3 grid((dv.C * n_blocks + 3) / 4, dv.U);
+  const int per_wg = 4 * 64 / (dv.d * (dv.io == 0 ? 4 : 2) / 16);  // tokens per workgroup
+  dim3 grid((dv.C * n_blocks + per_wg - 1) / per_wg, dv.U);
   KVM_DISPATCH(dv, memkey_kernel, grid, dim3(256), 0, st, dv, src, n_blocks);
   return hipGetLastError();
 }
@@ -403,11 +392,6 @@ hipError_t launch_score(const Dev &dv, int slot, int row0, int row1, bool first_
 hipError_t launch_select(const Dev &dv, int m, int n_app, bool take_all, hipStream_t st) {
   hipLaunchKernelGGL(select_kernel, dim3(dv.U), dim3(256), (size_t)dv.C * 8, st, dv, m, n_app,
                      take_all ? 1 : 0);
-  return hipGetLastError();
-}
-
-hipError_t launch_winners(const Dev &dv, int n_splits, hipStream_t st) {
-  hipLaunchKernelGGL(winners_kernel, dim3((dv.C + 255) / 256, dv.U), dim3(256), 0, st, dv, n_splits);
   return hipGetLastError();
 }
 

@@ -131,7 +131,7 @@ int64_t capacity_rows(const kvm_config &c, const std::vector<int64_t> &table, in
 }
 
 struct Layout {
-  size_t sK, sV, rho, w, n, khat, vhat, winK, winV, winG, kbar, score, pi, app, creator, cand, total;
+  size_t sK, sV, rho, w, n, khat, vhat, winK, winV, winG, kbar, score, pi, app, creator, total;
 };
 
 bool use_mfma(const kvm_config &c) {
@@ -167,7 +167,6 @@ Layout layout_of(const kvm_config &c, int64_t Mcap) {
   l.pi = take(U * C * 4);
   l.app = take(U * C * 4);
   l.creator = take(U * C * 4);
-  l.cand = take(U * C * kvm::kScoreSplits * 16);
   l.total = o;
   return l;
 }
@@ -190,7 +189,6 @@ void bind(Dev &dv, const kvm_config &c, void *buf, int64_t Mcap) {
   dv.pi = (int32_t *)(p + l.pi);
   dv.app = (int32_t *)(p + l.app);
   dv.creator = (int32_t *)(p + l.creator);
-  dv.cand = (float4 *)(p + l.cand);
   dv.gamma = c.ln_gamma;
   dv.beta = c.ln_beta;
   dv.tau_state = c.tau_state;
@@ -259,23 +257,19 @@ int fold_block(kvm_state *st, const Src &src, int64_t e, int32_t *assign_out, fl
     HIP_TRY(kvm::launch_select(dv, (int)m, n_app, true, stream));
     HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, 0, true, false, true, false, so, sn, stream));
   } else {
-    int splits = 0;  // > 0: candidates per row split wait in dv.cand for winners_kernel
     if (st->mfma)
-      HIP_TRY(kvm::launch_score_mfma(dv, so, 0, (int)m, true, &splits, stream));
+      HIP_TRY(kvm::launch_score_mfma(dv, so, 0, (int)m, true, stream));
     else
       HIP_TRY(kvm::launch_score(dv, so, 0, (int)m, true, stream));
     if (n_app > 0) {
       // new rows first, so that the remaining tokens can be scored against them too
-      if (splits > 0) HIP_TRY(kvm::launch_winners(dv, splits, stream));
       HIP_TRY(kvm::launch_select(dv, (int)m, n_app, false, stream));
       HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, (int)m, true, false, false, false, so, sn, stream));
       if (st->mfma)
-        HIP_TRY(kvm::launch_score_mfma(dv, sn, (int)m, (int)m_after, false, nullptr, stream));
+        HIP_TRY(kvm::launch_score_mfma(dv, sn, (int)m, (int)m_after, false, stream));
       else
         HIP_TRY(kvm::launch_score(dv, sn, (int)m, (int)m_after, false, stream));
-      splits = 0;
     }
-    if (splits > 0) HIP_TRY(kvm::launch_winners(dv, splits, stream));
     HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, 0, false, true, true, n_app > 0, so, sn, stream));
   }
   const size_t ntok = (size_t)dv.U * dv.C;
@@ -520,16 +514,27 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
           ++run;
       const bool batched = lo0 >= t0;
       {
-        // events cost microseconds each on the queue: one bracket and one ordering event per
-        // run of folds, not per fold
+        // Events cost microseconds each on the queue: one bracket and one ordering event per
+        // run of folds, not per fold.  The slots this run rewrites must have been read to the end: one wait per distinct
+        // attention launch (usually one), ahead of the run rather than between its folds
+        {
+          hipEvent_t waited[2 * kvm::kMaxGroup];
+          int n_waited = 0;
+          for (int i = 0; i < run; ++i) {
+            const int sn = (int)((st->folds + 1 + i) % dv.NS);
+            hipEvent_t e = slot_busy[sn];
+            slot_busy[sn] = nullptr;
+            bool seen = e == nullptr;
+            for (int k2 = 0; k2 < n_waited && !seen; ++k2) seen = waited[k2] == e;
+            if (!seen) {
+              HIP_TRY(hipStreamWaitEvent(fstream, e, 0));
+              waited[n_waited++] = e;
+            }
+          }
+        }
         ProfileSpan span(st, 1, fstream, run);
         for (int i = 0; i < run; ++i) {
           const Chunk &ch = plan[next_fold + i];
-          const int sn = (int)((st->folds + 1) % dv.NS);
-          if (slot_busy[sn]) {
-            HIP_TRY(hipStreamWaitEvent(fstream, slot_busy[sn], 0));
-            slot_busy[sn] = nullptr;
-          }
           const int64_t ce = ch.s + C, lo = ce - L;  // first token of the overflow block
           int rc;
           if (batched && i == 0) HIP_TRY(kvm::launch_memkey(dv, advance(in, lo0 - t0, es), run, fstream));

@@ -43,6 +43,49 @@ struct Io<bf16_t> {
   }
 };
 
+// 16 bytes of consecutive elements as floats (4 fp32 or 8 bf16); p is 16-byte aligned.
+template <typename T>
+struct Vec16;
+template <>
+struct Vec16<float> {
+  static constexpr int kN = 4;
+  __device__ static __forceinline__ void load(const float *p, float (&f)[4]) {
+    const float4 x = *reinterpret_cast<const float4 *>(p);
+    f[0] = x.x; f[1] = x.y; f[2] = x.z; f[3] = x.w;
+  }
+  __device__ static __forceinline__ void store(float *p, const float (&f)[4]) {
+    *reinterpret_cast<float4 *>(p) = make_float4(f[0], f[1], f[2], f[3]);
+  }
+};
+template <>
+struct Vec16<bf16_t> {
+  static constexpr int kN = 8;
+  __device__ static __forceinline__ void load(const bf16_t *p, float (&f)[8]) {
+    const uint4 x = *reinterpret_cast<const uint4 *>(p);
+    const uint32_t wds[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      f[2 * i] = __uint_as_float(wds[i] << 16);
+      f[2 * i + 1] = __uint_as_float(wds[i] & 0xffff0000u);
+    }
+  }
+  __device__ static __forceinline__ void store(bf16_t *p, const float (&f)[8]) {
+    uint32_t wds[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      wds[i] = (uint32_t)float_to_bf16_bits(f[2 * i]) | ((uint32_t)float_to_bf16_bits(f[2 * i + 1]) << 16);
+    *reinterpret_cast<uint4 *>(p) = make_uint4(wds[0], wds[1], wds[2], wds[3]);
+  }
+};
+
+// Sum over groups of kLanes adjacent lanes (a power of two).
+template <int kLanes, typename V>
+__device__ __forceinline__ V group_sum(V x) {
+#pragma unroll
+  for (int o = kLanes / 2; o > 0; o >>= 1) x += __shfl_xor(x, o, kWave);
+  return x;
+}
+
 template <typename V>
 __device__ __forceinline__ V wave_sum(V x) {
 #pragma unroll

@@ -42,7 +42,6 @@ struct Dev {
   int32_t *pi;       // [U, C]    row the token goes to
   int32_t *app;      // [U, C]    rank among appended tokens, or -1
   int32_t *creator;  // [U, C]    token that creates new row number a
-  float4 *cand;      // [U, C, kScoreSplits] per row-split: (max over all rows, best eligible, row bits, -)
   // parameters
   const float *gamma, *beta;          // [H_kv, d] or null
   const float *tau_state, *tau_bswa;  // [H_q] or null
@@ -51,7 +50,6 @@ struct Dev {
   int32_t io;  // KVM_F32 / KVM_BF16
 };
 
-constexpr int kScoreSplits = 4;  // workgroups sharing the state rows of one token tile
 
 // One attention launch: the queries of up to kMaxGroup consecutive chunks (prefill), or one
 // query per sequence (decode).  Chunk boundaries are absolute multiples of C.
@@ -74,7 +72,6 @@ struct AttnArgs {
 hipError_t launch_memkey(const Dev &dv, const Src &src, int n_blocks, hipStream_t st);
 hipError_t launch_score(const Dev &dv, int slot, int row0, int row1, bool first_pass, hipStream_t st);
 hipError_t launch_select(const Dev &dv, int m, int n_app, bool take_all, hipStream_t st);
-hipError_t launch_winners(const Dev &dv, int n_splits, hipStream_t st);
 hipError_t launch_accum(const Dev &dv, const Src &src, int m_before, int m_after, int row_begin,
                         bool do_create, bool do_merge, bool do_copy, bool check_app, int slot_old,
                         int slot_new, hipStream_t st);
@@ -82,8 +79,7 @@ hipError_t launch_refresh(const Dev &dv, int m, int slot, hipStream_t st);
 hipError_t launch_ring_copy(const Dev &dv, const Src &src, int64_t src_t0, int64_t p0, int64_t p1,
                             hipStream_t st);
 // score_mfma.hip (bf16, d = 128)
-hipError_t launch_score_mfma(const Dev &dv, int slot, int row0, int row1, bool first_pass, int *n_splits,
-                             hipStream_t st);
+hipError_t launch_score_mfma(const Dev &dv, int slot, int row0, int row1, bool first_pass, hipStream_t st);
 // attn_rows.hip
 hipError_t launch_attn_rows(const Dev &dv, const AttnArgs &a, hipStream_t st);
 // attn_mfma.hip (bf16, d = 128)

@@ -4,10 +4,14 @@
 //
 // D[row, token] = K-hat_tile . K-bar^T: a lane holds one token column, so the running maximum
 // and its row index are per-lane scalars scanned in ascending row order (ties keep the lowest
-// row); the two lane halves of a token are merged once at the end.  Each wave keeps the memory
-// keys of its 32 tokens in registers; state rows stream HBM -> LDS (direct loads, swizzled,
-// double buffered) in 64-row tiles.  The rows are split over gridDim.y workgroups so that one
-// fold fills the chip; each split leaves a candidate per token and index_kernel merges them.
+// row).  A workgroup owns 64 tokens and walks all state rows in stages of two 64-row tiles,
+// which stream HBM/L2 -> LDS (direct loads, swizzled, one stage ahead).  Its eight waves split
+// a stage as (token half) x (row half of a tile) x (which tile of the stage): a wave keeps the
+// memory keys of its 32 tokens in registers and multiplies them with 32 rows per stage.  The
+// kernel is bound by latencies (a wave's matrix instructions form one dependent chain per
+// tile), so the point of the split is to have four waves per SIMD in flight.  The two lane
+// halves of a token and then the four waves that share it are merged once at the end.  One fold
+// launches (C / 64) x units workgroups: for the 32k-context workload 512, one resident round.
 #include "kvm_device.h"
 #include "kvm_internal.h"
 #include "kvm_mfma.h"
@@ -16,25 +20,34 @@ namespace kvm {
 
 namespace {
 
-constexpr int kTileTok = 128;  // tokens per workgroup (32 per wave)
+constexpr int kTileTok = 64;  // tokens per workgroup (32 per wave)
+constexpr int kXcds = 8;
 
-__global__ __launch_bounds__(256, 2) void score_mfma_kernel(Dev dv, int slot, int row0, int row1, int first_pass) {
-  __shared__ __attribute__((aligned(1024))) uint16_t Ks[2][kTileElems];
+// best eligible candidate a against b: larger score wins, equal scores keep the lower row
+__device__ __forceinline__ bool beats(float sa, int ia, float sb, int ib) {
+  return sa > sb || (sa == sb && ia < ib);
+}
+
+__global__ __launch_bounds__(512, 2) void score_mfma_kernel(Dev dv, int slot, int row0, int row1, int first_pass) {
+  __shared__ __attribute__((aligned(1024))) uint16_t Ks[2][2][kTileElems];  // [stage parity][tile of the stage]
   constexpr int D = kHeadDim;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int th = wave & 1, rh = (wave >> 1) & 1, tp = wave >> 2;  // token half, row half, tile of the stage
   const int g = lane >> 5, l32 = lane & 31;
-  const int u = blockIdx.z;
-  const int tok0 = blockIdx.x * kTileTok + 32 * wave;
+  // Workgroup -> (unit, token tile).  Consecutive workgroup ids go round-robin over the 8 XCDs,
+  // each with its own L2: id % 8 picks the XCD and id / 8 walks that XCD's own units, so that
+  // all the workgroups that stream one unit's state rows share one L2.
+  const int tpu = (dv.C + kTileTok - 1) / kTileTok;
+  const int seq = blockIdx.x / kXcds;
+  const int u = (seq / tpu) * kXcds + blockIdx.x % kXcds;
+  if (u >= dv.U) return;
+  const int tok0 = (seq % tpu) * kTileTok + 32 * th;
   const bool wave_active = tok0 < dv.C;  // C is a multiple of 32: a wave is all in or all out
   const int j = tok0 + l32;
   const int64_t tj = (int64_t)u * dv.C + (wave_active ? j : 0);
-
-  // this workgroup's share of the row tiles
-  const int tiles_all = (row1 - row0 + kTileKeys - 1) / kTileKeys;
-  const int per_split = (tiles_all + (int)gridDim.y - 1) / (int)gridDim.y;
-  const int t_begin = (int)blockIdx.y * per_split;
-  const int t_end = min(t_begin + per_split, tiles_all);
+  const int n_tiles = (row1 - row0 + kTileKeys - 1) / kTileKeys;
+  const int n_stages = (n_tiles + 1) / 2;
 
   bf16x8 kreg[8];
   if (wave_active) {
@@ -53,88 +66,110 @@ __global__ __launch_bounds__(256, 2) void score_mfma_kernel(Dev dv, int slot, in
 
   const char *khat = (const char *)dv.khat + (slot * dv.slot_elems + ((int64_t)u * dv.Mcap + row0) * D) * 2;
   const DmaLane dl = dma_lane(lane);
-  const uint32_t ks_addr = lds_addr_of(&Ks[0][0]);
-  auto issue_tile = [&](int t) {
-    const int base = t * kTileKeys;
-    tile_dma<false, 4>(khat + (uint32_t)base * (D * 2), D * 2, row1 - row0 - base,
-                       ks_addr + (uint32_t)(t & 1) * (kTileElems * 2), wave, dl);
+  const uint32_t ks_addr = lds_addr_of(&Ks[0][0][0]);
+  auto issue_stage = [&](int sg) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int t = 2 * sg + i;
+      if (t < n_tiles) {
+        const int base = t * kTileKeys;
+        tile_dma<false, 8>(khat + (uint32_t)base * (D * 2), D * 2, row1 - row0 - base,
+                           ks_addr + (uint32_t)(2 * (sg & 1) + i) * (kTileElems * 2), wave, dl);
+      }
+    }
   };
-  if (t_begin < t_end) issue_tile(t_begin);
-  for (int t = t_begin; t < t_end; ++t) {
+  // the memory keys are in registers before the tile loads start, so that the waits below
+  // count tile loads only
+  __builtin_amdgcn_s_waitcnt(0);
+  if (n_stages > 0) issue_stage(0);
+  for (int sg = 0; sg < n_stages; ++sg) {
+    // stage sg has landed for every wave, and every wave is done reading stage sg - 1
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
-    if (t + 1 < t_end) issue_tile(t + 1);
-    if (!wave_active) continue;
-    const uint16_t *Kt = Ks[t & 1];
-    f32x16 acc[2];
+    if (sg + 1 < n_stages) issue_stage(sg + 1);
+    const int t = 2 * sg + tp;
+    if (!wave_active || t >= n_tiles) continue;
+    const uint16_t *Kt = Ks[sg & 1][tp];
+    // two accumulation chains (channels 0..63 and 64..127), so that consecutive matrix
+    // instructions do not wait for each other
+    f32x16 acc0, acc1;
     {
       bf16x8 kf[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) kf[i] = ktile_frag(Kt, koff, i & 1, i >> 1);
+      for (int i = 0; i < 8; ++i) kf[i] = ktile_frag(Kt, koff, rh, i);
       const f32x16 zero = {0.f};
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-#pragma unroll
-        for (int blk = 0; blk < 2; ++blk) {
-          const int sl = (2 * ks + blk) & 7;
-          acc[blk] = mfma32(kf[sl], kreg[ks], ks == 0 ? zero : acc[blk]);
-          if (ks + 4 < 8) kf[sl] = ktile_frag(Kt, koff, blk, ks + 4);
-        }
+      for (int ks = 0; ks < 4; ++ks) {
+        acc0 = mfma32(kf[ks], kreg[ks], ks == 0 ? zero : acc0);
+        acc1 = mfma32(kf[ks + 4], kreg[ks + 4], ks == 0 ? zero : acc1);
       }
-      __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      }
-      __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
     }
-    // rows this lane sees, ascending: blk, then v
-    const int base = row0 + t * kTileKeys;
-    const bool edge = base < dv.S || base + kTileKeys > row1;
+    // rows this lane sees, ascending in v
+    const int base = row0 + t * kTileKeys + 32 * rh;
+    const bool edge = base < dv.S || base + 32 > row1;
     if (edge) {
 #pragma unroll
-      for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int i = base + 32 * blk + mfma_row(v, g);
-          const float sc = acc[blk][v];
-          if (i < row1) {
-            best_all = fmaxf(best_all, sc);
-            if (i >= dv.S && sc > best) {
-              best = sc;
-              best_i = i;
-            }
+      for (int v = 0; v < 16; ++v) {
+        const int i = base + mfma_row(v, g);
+        const float sc = acc0[v] + acc1[v];
+        if (i < row1) {
+          best_all = fmaxf(best_all, sc);
+          if (i >= dv.S && sc > best) {
+            best = sc;
+            best_i = i;
           }
         }
+      }
     } else {
 #pragma unroll
-      for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const float sc = acc[blk][v];
-          if (sc > best) {
-            best = sc;
-            best_i = base + 32 * blk + mfma_row(v, g);
-          }
+      for (int v = 0; v < 16; ++v) {
+        const float sc = acc0[v] + acc1[v];
+        if (sc > best) {
+          best = sc;
+          best_i = base + mfma_row(v, g);
         }
+      }
     }
   }
-  if (!wave_active) return;
   best_all = fmaxf(best_all, best);
   {
+    // the other lane half holds the other rows of the same token
     const float ob = __shfl_xor(best, 32, kWave);
     const int oi = __shfl_xor(best_i, 32, kWave);
     const float oa = __shfl_xor(best_all, 32, kWave);
-    if (ob > best || (ob == best && oi < best_i)) {
+    if (beats(ob, oi, best, best_i)) {
       best = ob;
       best_i = oi;
     }
     best_all = fmaxf(best_all, oa);
   }
-  if (g == 0) {
+  // and the three other waves with the same tokens, through LDS: the tile buffers are free once
+  // every wave has left the loop
+  __syncthreads();
+  float *x_all = reinterpret_cast<float *>(&Ks[0][0][0]), *x_best = x_all + 256;
+  int *x_idx = reinterpret_cast<int *>(x_all + 512);
+  const int part = 2 * tp + rh;  // 0..3: which share of the rows this wave looked at
+  if (part != 0 && g == 0) {
+    const int xi = 64 * part + 32 * th + l32;
+    x_all[xi] = best_all;
+    x_best[xi] = best;
+    x_idx[xi] = best_i;
+  }
+  __syncthreads();
+  if (part == 0 && g == 0 && wave_active) {
+#pragma unroll
+    for (int o = 1; o < 4; ++o) {
+      const int xi = 64 * o + 32 * th + l32;
+      best_all = fmaxf(best_all, x_all[xi]);
+      if (beats(x_best[xi], x_idx[xi], best, best_i)) {
+        best = x_best[xi];
+        best_i = x_idx[xi];
+      }
+    }
     if (first_pass) {
-      dv.cand[tj * kScoreSplits + blockIdx.y] = make_float4(best_all, best, __int_as_float(best_i), 0.f);
+      dv.score[tj] = make_float2(best_all, best);
+      dv.pi[tj] = best_i;
+      dv.app[tj] = -1;
     } else if (dv.app[tj] < 0 && best_i != 0x7fffffff && best > dv.score[tj].y) {
       dv.score[tj].y = best;
       dv.pi[tj] = best_i;
@@ -144,16 +179,13 @@ __global__ __launch_bounds__(256, 2) void score_mfma_kernel(Dev dv, int slot, in
 
 }  // namespace
 
-// first_pass: returns the number of row splits used through *n_splits (candidates are left in
-// dv.cand for index_kernel); otherwise one split updates score/pi in place.
-hipError_t launch_score_mfma(const Dev &dv, int slot, int row0, int row1, bool first_pass, int *n_splits,
-                             hipStream_t st) {
+// first_pass: rows are the pre-append state, every token gets s_j and its best eligible row.
+// Otherwise rows are the ones appended in this fold and only tokens that were not appended
+// themselves may move to them (strictly larger score only).
+hipError_t launch_score_mfma(const Dev &dv, int slot, int row0, int row1, bool first_pass, hipStream_t st) {
   if (row1 <= row0) return hipSuccess;
-  const int tiles = (row1 - row0 + kTileKeys - 1) / kTileKeys;
-  int splits = first_pass ? (tiles >= kScoreSplits ? kScoreSplits : 1) : 1;
-  if (n_splits) *n_splits = splits;
-  dim3 grid((dv.C + kTileTok - 1) / kTileTok, splits, dv.U);
-  hipLaunchKernelGGL(score_mfma_kernel, grid, dim3(256), 0, st, dv, slot, row0, row1, first_pass ? 1 : 0);
+  dim3 grid((unsigned)((dv.U + kXcds - 1) / kXcds * kXcds * ((dv.C + kTileTok - 1) / kTileTok)));
+  hipLaunchKernelGGL(score_mfma_kernel, grid, dim3(512), 0, st, dv, slot, row0, row1, first_pass ? 1 : 0);
   return hipGetLastError();
 }
 
