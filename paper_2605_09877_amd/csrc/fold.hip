@@ -18,6 +18,16 @@ namespace kvm {
 
 namespace {
 
+// An unsigned type of the given size in bytes.
+template <int kBytes>
+struct PieceOf;
+template <>
+struct PieceOf<4> { using type = uint32_t; };
+template <>
+struct PieceOf<8> { using type = uint2; };
+template <>
+struct PieceOf<16> { using type = uint4; };
+
 template <typename T, int D>
 __device__ __forceinline__ void write_readout(const Dev &dv, int slot, int u, int h, int row,
                                               const double (&sk)[D / 64], const float (&sv)[D / 64],
@@ -202,11 +212,14 @@ __global__ __launch_bounds__(256) void select_kernel(Dev dv, int m, int n_app, i
 }
 
 // ------------------------------------------------------------------ create + merge + readout refresh
-// One wave per state row in [row_begin, m_after) of the updated state.  do_create: rows >=
+// A wave takes kAccumRows consecutive rows of [row_begin, m_after) of the updated state, one
+// after the other.  do_create: rows >=
 // m_before are created from their creator token; do_merge: the tokens whose target is this row
 // are added in ascending position; do_copy: an untouched row's readout is copied to the new state
 // version.  A fold that appends only part of the block runs create first (so the new rows have
 // a normalised key to score against), then the second scoring pass, then merge.
+constexpr int kAccumRows = 4;  // consecutive rows per wave: they share one scan of the targets
+
 template <typename T, int D>
 __global__ __launch_bounds__(256) void accum_kernel(Dev dv, Src src, int m_before, int m_after,
                                                     int row_begin, int do_create, int do_merge,
@@ -215,111 +228,130 @@ __global__ __launch_bounds__(256) void accum_kernel(Dev dv, Src src, int m_befor
   constexpr int CPL = D / 64;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int u = blockIdx.y, b = u / dv.Hkv, h = u % dv.Hkv;
-  const int row = row_begin + blockIdx.x * 4 + wave;
-  if (row >= m_after) return;
+  const int row_first = row_begin + (blockIdx.x * 4 + wave) * kAccumRows;
+  if (row_first >= m_after) return;
   const int C = dv.C;
   const int64_t base = (int64_t)u * C;
-  const int64_t ro = (int64_t)u * dv.Mcap + row;
   const T *vsrc = (const T *)src.v + b * src.v_b + h * src.v_h;
   const float *gsrc = src.g ? src.g + b * src.g_b + h * src.g_h : nullptr;
   const T *kbar = (const T *)dv.kbar + base * D;
 
-  double sk[CPL];
-  float sv[CPL];
-  float rho = 0.f, w = 0.f;
-  int n = 0;
-  bool loaded = false;
-  const bool is_new = do_create && row >= m_before;
-  if (is_new) {
-    const int j0 = dv.creator[base + (row - m_before)];
-    float nn = 0.f;
+  // Most rows of a fold are not touched and only need their readout copied to the new state
+  // version: those copies are requested first, so that they travel while the targets are
+  // scanned.  The wave moves a row's k-hat and v-hat (2 * D elements) as 64 equal pieces.
+  using Piece = typename PieceOf<2 * D * (int)sizeof(T) / 64>::type;
+  Piece piece[kAccumRows] = {};
+  if (do_copy) {
 #pragma unroll
-    for (int c = 0; c < CPL; ++c) {
-      const int ch = lane * CPL + c;
-      sk[c] = (double)Io<T>::load(kbar + (int64_t)j0 * D + ch);
-      sv[c] = Io<T>::load(vsrc + (int64_t)j0 * src.v_t + ch);
-      nn += sv[c] * sv[c];
+    for (int rr = 0; rr < kAccumRows; ++rr) {
+      const int row = row_first + rr;
+      if (row < m_before && row < m_after) {
+        const int64_t eo = (slot_old * dv.slot_elems + ((int64_t)u * dv.Mcap + row) * D) * (int64_t)sizeof(T);
+        const char *from = (lane < 32 ? (const char *)dv.khat : (const char *)dv.vhat) + eo;
+        piece[rr] = reinterpret_cast<const Piece *>(from)[lane & 31];
+      }
     }
-    rho = sqrtf(wave_sum(nn));
-    w = 1.f;
-    n = 1;
-    loaded = true;
   }
-  if (do_merge && row >= dv.S) {
-    // The tokens that merge into this row, in ascending position: every wave scans the block's
-    // targets itself (C integers from L2), 64 tokens per ballot, eight ballots per round trip.
-    // check_app: tokens appended in this fold carry their own new row in pi and do not merge.
-    for (int j0 = 0; j0 < C; j0 += 512) {
-      int tg[8];
+  // The block's merge targets, 64 tokens per register (blocks longer than 512 tokens take
+  // further rounds below).  check_app: tokens appended in this fold carry their own new row in
+  // pi and do not merge.
+  int tg[8];
+  auto load_targets = [&](int j0) {
+#pragma unroll
+    for (int bk = 0; bk < 8; ++bk) {
+      const int j = j0 + 64 * bk + lane;
+      tg[bk] = j < C ? dv.pi[base + j] : -1;
+    }
+    if (check_app) {
 #pragma unroll
       for (int bk = 0; bk < 8; ++bk) {
         const int j = j0 + 64 * bk + lane;
-        tg[bk] = j < C ? dv.pi[base + j] : -1;
+        if (j < C && dv.app[base + j] >= 0) tg[bk] = -1;
       }
-      if (check_app) {
+    }
+  };
+  if (do_merge) load_targets(0);
+
+#pragma unroll
+  for (int rr = 0; rr < kAccumRows; ++rr) {
+    const int row = row_first + rr;
+    if (row >= m_after) break;
+    const int64_t ro = (int64_t)u * dv.Mcap + row;
+    double sk[CPL];
+    float sv[CPL];
+    float rho = 0.f, w = 0.f;
+    int n = 0;
+    bool loaded = false;
+    if (do_create && row >= m_before) {
+      const int j0 = dv.creator[base + (row - m_before)];
+      float nn = 0.f;
+#pragma unroll
+      for (int c = 0; c < CPL; ++c) {
+        const int ch = lane * CPL + c;
+        sk[c] = (double)Io<T>::load(kbar + (int64_t)j0 * D + ch);
+        sv[c] = Io<T>::load(vsrc + (int64_t)j0 * src.v_t + ch);
+        nn += sv[c] * sv[c];
+      }
+      rho = sqrtf(wave_sum(nn));
+      w = 1.f;
+      n = 1;
+      loaded = true;
+    }
+    if (do_merge && row >= dv.S) {
+      // the tokens that merge into this row, in ascending position: 64 tokens per ballot
+      for (int j0 = 0; j0 < C; j0 += 512) {
+        if (C > 512) load_targets(j0);
 #pragma unroll
         for (int bk = 0; bk < 8; ++bk) {
-          const int j = j0 + 64 * bk + lane;
-          if (j < C && dv.app[base + j] >= 0) tg[bk] = -1;
-        }
-      }
+          uint64_t hits = __builtin_amdgcn_ballot_w64(tg[bk] == row);
+          while (hits) {
+            const int t = j0 + 64 * bk + __builtin_ctzll(hits);
+            hits &= hits - 1;
+            if (!loaded) {
 #pragma unroll
-      for (int bk = 0; bk < 8; ++bk) {
-        uint64_t hits = __builtin_amdgcn_ballot_w64(tg[bk] == row);
-        while (hits) {
-          const int t = j0 + 64 * bk + __builtin_ctzll(hits);
-          hits &= hits - 1;
-          if (!loaded) {
+              for (int c = 0; c < CPL; ++c) {
+                sk[c] = dv.sK[ro * D + lane * CPL + c];
+                sv[c] = dv.sV[ro * D + lane * CPL + c];
+              }
+              rho = dv.rho[ro];
+              w = dv.w[ro];
+              n = dv.n[ro];
+              loaded = true;
+            }
+            const float g = gsrc ? gsrc[(int64_t)t * src.g_t] : 1.f;
 #pragma unroll
             for (int c = 0; c < CPL; ++c) {
-              sk[c] = dv.sK[ro * D + lane * CPL + c];
-              sv[c] = dv.sV[ro * D + lane * CPL + c];
+              const int ch = lane * CPL + c;
+              sk[c] = fma((double)g, (double)Io<T>::load(kbar + (int64_t)t * D + ch), sk[c]);
+              sv[c] = fmaf(g, Io<T>::load(vsrc + (int64_t)t * src.v_t + ch), sv[c]);
             }
-            rho = dv.rho[ro];
-            w = dv.w[ro];
-            n = dv.n[ro];
-            loaded = true;
+            w += g;
+            n += 1;
           }
-          const float g = gsrc ? gsrc[(int64_t)t * src.g_t] : 1.f;
-#pragma unroll
-          for (int c = 0; c < CPL; ++c) {
-            const int ch = lane * CPL + c;
-            sk[c] = fma((double)g, (double)Io<T>::load(kbar + (int64_t)t * D + ch), sk[c]);
-            sv[c] = fmaf(g, Io<T>::load(vsrc + (int64_t)t * src.v_t + ch), sv[c]);
-          }
-          w += g;
-          n += 1;
         }
       }
     }
-  }
-  if (!loaded) {
-    // untouched row: the sums stay; the new state version gets a copy of its readout
-    if (do_copy && row < m_before) {
-      constexpr int kVecs = D * (int)sizeof(T) / 16;
-      const int64_t eo = ro * D * (int64_t)sizeof(T);
-      if (lane < kVecs) {
-        const char *ko = (const char *)dv.khat + slot_old * dv.slot_elems * (int64_t)sizeof(T) + eo;
-        const char *vo = (const char *)dv.vhat + slot_old * dv.slot_elems * (int64_t)sizeof(T) + eo;
-        char *kn = (char *)dv.khat + slot_new * dv.slot_elems * (int64_t)sizeof(T) + eo;
-        char *vn = (char *)dv.vhat + slot_new * dv.slot_elems * (int64_t)sizeof(T) + eo;
-        reinterpret_cast<uint4 *>(kn)[lane] = reinterpret_cast<const uint4 *>(ko)[lane];
-        reinterpret_cast<uint4 *>(vn)[lane] = reinterpret_cast<const uint4 *>(vo)[lane];
+    if (!loaded) {
+      // untouched row: the sums stay; the new state version gets the copy of its readout
+      if (do_copy && row < m_before) {
+        const int64_t eo = (slot_new * dv.slot_elems + ro * D) * (int64_t)sizeof(T);
+        char *to = (lane < 32 ? (char *)dv.khat : (char *)dv.vhat) + eo;
+        reinterpret_cast<Piece *>(to)[lane & 31] = piece[rr];
       }
+      continue;
     }
-    return;
-  }
 #pragma unroll
-  for (int c = 0; c < CPL; ++c) {
-    dv.sK[ro * D + lane * CPL + c] = sk[c];
-    dv.sV[ro * D + lane * CPL + c] = sv[c];
+    for (int c = 0; c < CPL; ++c) {
+      dv.sK[ro * D + lane * CPL + c] = sk[c];
+      dv.sV[ro * D + lane * CPL + c] = sv[c];
+    }
+    if (lane == 0) {
+      dv.rho[ro] = rho;
+      dv.w[ro] = w;
+      dv.n[ro] = n;
+    }
+    write_readout<T, D>(dv, slot_new, u, h, row, sk, sv, rho, lane);
   }
-  if (lane == 0) {
-    dv.rho[ro] = rho;
-    dv.w[ro] = w;
-    dv.n[ro] = n;
-  }
-  write_readout<T, D>(dv, slot_new, u, h, row, sk, sv, rho, lane);
 }
 
 // Recompute the normalised readout of rows [0, m) from the stored sums (after an import).
@@ -399,7 +431,7 @@ hipError_t launch_accum(const Dev &dv, const Src &src, int m_before, int m_after
                         bool do_create, bool do_merge, bool do_copy, bool check_app, int slot_old,
                         int slot_new, hipStream_t st) {
   if (m_after <= row_begin) return hipSuccess;
-  dim3 grid((m_after - row_begin + 3) / 4, dv.U);
+  dim3 grid((m_after - row_begin + 4 * kAccumRows - 1) / (4 * kAccumRows), dv.U);
   KVM_DISPATCH(dv, accum_kernel, grid, dim3(256), 0, st, dv, src, m_before, m_after, row_begin,
                do_create ? 1 : 0, do_merge ? 1 : 0, do_copy ? 1 : 0, check_app ? 1 : 0, slot_old, slot_new);
   return hipGetLastError();
