@@ -354,6 +354,97 @@ __global__ __launch_bounds__(256) void accum_kernel(Dev dv, Src src, int m_befor
   }
 }
 
+// The merge pass of a fold done in place (nothing else reads the readout meanwhile, so untouched
+// rows need no work at all): one wave per token.  The earliest token of each target row does the
+// row: it adds every token with that target, in ascending position, and rewrites the row's
+// readout; the other waves leave at once.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void merge_inplace_kernel(Dev dv, Src src, int check_app, int slot) {
+  constexpr int CPL = D / 64;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int u = blockIdx.y, b = u / dv.Hkv, h = u % dv.Hkv;
+  const int C = dv.C;
+  const int j = blockIdx.x * 4 + wave;
+  if (j >= C) return;
+  const int64_t base = (int64_t)u * C;
+  const int row = dv.pi[base + j];
+  if (row < dv.S || row == 0x7fffffff) return;
+  if (check_app && dv.app[base + j] >= 0) return;
+  const T *vsrc = (const T *)src.v + b * src.v_b + h * src.v_h;
+  const float *gsrc = src.g ? src.g + b * src.g_b + h * src.g_h : nullptr;
+  const T *kbar = (const T *)dv.kbar + base * D;
+  int tg[8];
+  auto load_targets = [&](int j0) {
+#pragma unroll
+    for (int bk = 0; bk < 8; ++bk) {
+      const int t = j0 + 64 * bk + lane;
+      tg[bk] = t < C ? dv.pi[base + t] : -1;
+    }
+    if (check_app) {
+#pragma unroll
+      for (int bk = 0; bk < 8; ++bk) {
+        const int t = j0 + 64 * bk + lane;
+        if (t < C && dv.app[base + t] >= 0) tg[bk] = -1;
+      }
+    }
+  };
+  // The row's sums are requested before it is known whether this wave is the one that does the
+  // row: in decode-sized folds (few tokens, many rows) it almost always is, and the loads then
+  // travel together with the scan of the targets.
+  const int64_t ro = (int64_t)u * dv.Mcap + row;
+  double sk[CPL];
+  float sv[CPL];
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) {
+    sk[c] = dv.sK[ro * D + lane * CPL + c];
+    sv[c] = dv.sV[ro * D + lane * CPL + c];
+  }
+  const float rho = dv.rho[ro];
+  float w = dv.w[ro];
+  int n = dv.n[ro];
+  // is an earlier token bound for the same row?
+  for (int j0 = 0; j0 <= j; j0 += 512) {
+    load_targets(j0);
+#pragma unroll
+    for (int bk = 0; bk < 8; ++bk) {
+      const int t0 = j0 + 64 * bk;
+      uint64_t hits = __builtin_amdgcn_ballot_w64(tg[bk] == row);
+      if (t0 + 64 > j) hits &= t0 > j ? 0ull : ((1ull << (j - t0)) - 1ull);
+      if (hits) return;
+    }
+  }
+  for (int j0 = j / 512 * 512; j0 < C; j0 += 512) {
+    if (C > 512) load_targets(j0);
+#pragma unroll
+    for (int bk = 0; bk < 8; ++bk) {
+      uint64_t hits = __builtin_amdgcn_ballot_w64(tg[bk] == row);
+      while (hits) {
+        const int t = j0 + 64 * bk + __builtin_ctzll(hits);
+        hits &= hits - 1;
+        const float g = gsrc ? gsrc[(int64_t)t * src.g_t] : 1.f;
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) {
+          const int ch = lane * CPL + c;
+          sk[c] = fma((double)g, (double)Io<T>::load(kbar + (int64_t)t * D + ch), sk[c]);
+          sv[c] = fmaf(g, Io<T>::load(vsrc + (int64_t)t * src.v_t + ch), sv[c]);
+        }
+        w += g;
+        n += 1;
+      }
+    }
+  }
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) {
+    dv.sK[ro * D + lane * CPL + c] = sk[c];
+    dv.sV[ro * D + lane * CPL + c] = sv[c];
+  }
+  if (lane == 0) {
+    dv.w[ro] = w;
+    dv.n[ro] = n;
+  }
+  write_readout<T, D>(dv, slot, u, h, row, sk, sv, rho, lane);
+}
+
 // Recompute the normalised readout of rows [0, m) from the stored sums (after an import).
 template <typename T, int D>
 __global__ __launch_bounds__(256) void refresh_kernel(Dev dv, int m, int slot) {
@@ -434,6 +525,12 @@ hipError_t launch_accum(const Dev &dv, const Src &src, int m_before, int m_after
   dim3 grid((m_after - row_begin + 4 * kAccumRows - 1) / (4 * kAccumRows), dv.U);
   KVM_DISPATCH(dv, accum_kernel, grid, dim3(256), 0, st, dv, src, m_before, m_after, row_begin,
                do_create ? 1 : 0, do_merge ? 1 : 0, do_copy ? 1 : 0, check_app ? 1 : 0, slot_old, slot_new);
+  return hipGetLastError();
+}
+
+hipError_t launch_merge_inplace(const Dev &dv, const Src &src, bool check_app, int slot, hipStream_t st) {
+  dim3 grid((dv.C + 3) / 4, dv.U);
+  KVM_DISPATCH(dv, merge_inplace_kernel, grid, dim3(256), 0, st, dv, src, check_app ? 1 : 0, slot);
   return hipGetLastError();
 }
 

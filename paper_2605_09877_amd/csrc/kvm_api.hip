@@ -29,6 +29,7 @@ struct kvm_state {
   bool mfma = false;  // bf16, d = 128, C % 64 == 0: matrix-core kernels
   int group = 1;      // chunks per attention launch in prefill; the readout has 2 * group slots
   // prefill pipeline: folds run ahead on a library-owned stream, attention follows in groups
+  int64_t inplace = 0;  // folds done in place so far: version v lives in slot (v - inplace) mod NS
   hipStream_t fold_stream = nullptr;
   std::vector<hipEvent_t> sync_events;  // untimed events, reused call after call
   size_t sync_used = 0;
@@ -234,11 +235,19 @@ Src advance(const Src &s, int64_t tok, size_t es) {
   return r;
 }
 
+// Readout slot of state version `ver` (versions are numbered by the folds done).
+int slot_of(const kvm_state *st, int64_t ver) {
+  const int64_t ns = st->dv.NS;
+  return (int)(((ver - st->inplace) % ns + ns) % ns);
+}
+
 // Fold the C-token block whose first token is src's token 0.  e = end of the chunk just attended.
-// Reads readout version `folds` (slot folds % NS), writes version folds + 1 into the next slot.
+// Reads readout version `folds` and writes version folds + 1: into the next slot, with untouched
+// rows copied over (prefill, where attention launches still read the older versions), or, in_place,
+// over the version it read (decode and the fold entry point: nothing else is in flight).
 // kbar_block >= 0: the block's memory keys were already computed into that slab of the scratch.
 int fold_block(kvm_state *st, const Src &src, int64_t e, int32_t *assign_out, float *score_out,
-               hipStream_t stream, int kbar_block = -1) {
+               hipStream_t stream, bool in_place, int kbar_block = -1) {
   const kvm_config &c = st->cfg;
   if (c.budget_kind == KVM_BUDGET_NONE) return KVM_OK;
   const int64_t m = st->m;
@@ -251,11 +260,12 @@ int fold_block(kvm_state *st, const Src &src, int64_t e, int32_t *assign_out, fl
   } else {
     dv.kbar = (char *)dv.kbar + (size_t)kbar_block * dv.U * dv.C * dv.d * esize(c.io_dtype);
   }
-  const int so = (int)(st->folds % dv.NS), sn = (int)((st->folds + 1) % dv.NS);
+  const int so = slot_of(st, st->folds), sn = in_place ? so : slot_of(st, st->folds + 1);
+  const bool copy = !in_place;
   if (n_app == dv.C) {
     // room for the whole block (state creation included): no scores are needed
     HIP_TRY(kvm::launch_select(dv, (int)m, n_app, true, stream));
-    HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, 0, true, false, true, false, so, sn, stream));
+    HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, 0, true, false, copy, false, so, sn, stream));
   } else {
     if (st->mfma)
       HIP_TRY(kvm::launch_score_mfma(dv, so, 0, (int)m, true, stream));
@@ -270,7 +280,10 @@ int fold_block(kvm_state *st, const Src &src, int64_t e, int32_t *assign_out, fl
       else
         HIP_TRY(kvm::launch_score(dv, sn, (int)m, (int)m_after, false, stream));
     }
-    HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, 0, false, true, true, n_app > 0, so, sn, stream));
+    if (in_place)
+      HIP_TRY(kvm::launch_merge_inplace(dv, src, n_app > 0, sn, stream));
+    else
+      HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, 0, false, true, true, n_app > 0, so, sn, stream));
   }
   const size_t ntok = (size_t)dv.U * dv.C;
   if (assign_out)
@@ -285,6 +298,7 @@ int fold_block(kvm_state *st, const Src &src, int64_t e, int32_t *assign_out, fl
                            hipMemcpyDeviceToDevice, stream));
   st->m = m_after;
   st->folds += 1;
+  if (in_place) st->inplace += 1;
   return KVM_OK;
 }
 
@@ -521,7 +535,7 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
           hipEvent_t waited[2 * kvm::kMaxGroup];
           int n_waited = 0;
           for (int i = 0; i < run; ++i) {
-            const int sn = (int)((st->folds + 1 + i) % dv.NS);
+            const int sn = slot_of(st, st->folds + 1 + i);
             hipEvent_t e = slot_busy[sn];
             slot_busy[sn] = nullptr;
             bool seen = e == nullptr;
@@ -539,9 +553,9 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
           int rc;
           if (batched && i == 0) HIP_TRY(kvm::launch_memkey(dv, advance(in, lo0 - t0, es), run, fstream));
           if (batched)
-            rc = fold_block(st, advance(in, lo - t0, es), ce, nullptr, nullptr, fstream, i);
+            rc = fold_block(st, advance(in, lo - t0, es), ce, nullptr, nullptr, fstream, false, i);
           else
-            rc = fold_block(st, advance(ring, lo % L, es), ce, nullptr, nullptr, fstream);
+            rc = fold_block(st, advance(ring, lo % L, es), ce, nullptr, nullptr, fstream, false);
           if (rc != KVM_OK) return rc;
         }
       }
@@ -572,7 +586,7 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
     a.nq_total = (int32_t)((g1 - 1 - g0) * C + plan[g1 - 1].nq);
     for (int i = 0; i < kvm::kMaxGroup; ++i) {
       a.m[i] = i < g1 - g0 ? plan[g0 + i].m : 0;
-      a.slot[i] = i < g1 - g0 ? (int32_t)(plan[g0 + i].ver % dv.NS) : 0;
+      a.slot[i] = i < g1 - g0 ? (int32_t)slot_of(st, plan[g0 + i].ver) : 0;
     }
     {
       ProfileSpan span(st, 0, stream);
@@ -583,7 +597,7 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
     }
     HIP_TRY(next_sync_event(st, &ev));
     HIP_TRY(hipEventRecord(ev, stream));
-    for (int i = g0; i < g1; ++i) slot_busy[plan[i].ver % dv.NS] = ev;
+    for (int i = g0; i < g1; ++i) slot_busy[slot_of(st, plan[i].ver)] = ev;
     last_att_ev = ev;
   }
   {
@@ -628,7 +642,7 @@ int kvm_decode_step(kvm_state *st, const void *q, const void *k, const void *v,
   a.nq_total = 1;
   for (int i = 0; i < kvm::kMaxGroup; ++i) {
     a.m[i] = (int32_t)st->m;
-    a.slot[i] = (int32_t)(st->folds % dv.NS);
+    a.slot[i] = (int32_t)slot_of(st, st->folds);
   }
   {
     ProfileSpan span(st, 2, stream);
@@ -638,7 +652,7 @@ int kvm_decode_step(kvm_state *st, const void *q, const void *k, const void *v,
   if (completes) {
     const int64_t lo = u + 1 - L;
     ProfileSpan span(st, 1, stream);
-    int rc = fold_block(st, advance(ring_src(st), lo % L, es), u + 1, nullptr, nullptr, stream);
+    int rc = fold_block(st, advance(ring_src(st), lo % L, es), u + 1, nullptr, nullptr, stream, true);
     if (rc != KVM_OK) return rc;
   }
   return KVM_OK;
@@ -660,7 +674,7 @@ int kvm_state_fold(kvm_state *st, const void *k_blk, const void *v_blk, const fl
   if (st->cfg.budget_kind != KVM_BUDGET_NONE &&
       rows_after(st->cfg, st->table, st->m, e) > dv.Mcap)
     return KVM_ERR_CAPACITY;
-  return fold_block(st, src, e, assign_out, score_out, (hipStream_t)stream_);
+  return fold_block(st, src, e, assign_out, score_out, (hipStream_t)stream_, true);
 }
 
 int kvm_state_rows(const kvm_state *st, int64_t *m_out) {
@@ -714,7 +728,7 @@ int kvm_state_grow(kvm_state *st, void *new_buf, size_t new_bytes, int64_t new_m
   HIP_TRY(copy2d(nd.rho, od.rho, 4));
   HIP_TRY(copy2d(nd.w, od.w, 4));
   HIP_TRY(copy2d(nd.n, od.n, 4));
-  const int64_t slot = st->folds % od.NS;  // only the current version is live
+  const int64_t slot = slot_of(st, st->folds);  // only the current version is live
   HIP_TRY(copy2d((char *)nd.khat + slot * nd.slot_elems * (int64_t)es,
                  (const char *)od.khat + slot * od.slot_elems * (int64_t)es, d * es));
   HIP_TRY(copy2d((char *)nd.vhat + slot * nd.slot_elems * (int64_t)es,
@@ -746,7 +760,7 @@ int kvm_state_export(const kvm_state *st, double *sK, float *sV, float *rho, flo
   HIP_TRY(out2d(rho, dv.rho, 4));
   HIP_TRY(out2d(w, dv.w, 4));
   HIP_TRY(out2d(n, dv.n, 4));
-  const int64_t slot_off = (st->folds % dv.NS) * dv.slot_elems * (int64_t)es;
+  const int64_t slot_off = slot_of(st, st->folds) * dv.slot_elems * (int64_t)es;
   HIP_TRY(out2d(khat, (const char *)dv.khat + slot_off, d * es));
   HIP_TRY(out2d(vhat, (const char *)dv.vhat + slot_off, d * es));
   const size_t win = U * dv.L * d * es;
@@ -780,7 +794,7 @@ int kvm_state_import(kvm_state *st, const double *sK, const float *sV, const flo
   if (win_k) HIP_TRY(hipMemcpyAsync(dv.winK, win_k, win, hipMemcpyDeviceToDevice, stream));
   if (win_v) HIP_TRY(hipMemcpyAsync(dv.winV, win_v, win, hipMemcpyDeviceToDevice, stream));
   if (win_g) HIP_TRY(hipMemcpyAsync(dv.winG, win_g, U * dv.L * 4, hipMemcpyDeviceToDevice, stream));
-  HIP_TRY(kvm::launch_refresh(dv, (int)m, (int)(folds % dv.NS), stream));
+  HIP_TRY(kvm::launch_refresh(dv, (int)m, slot_of(st, folds), stream));
   st->m = m;
   st->tokens = tokens_seen;
   st->folds = folds;

@@ -75,6 +75,7 @@ hipError_t launch_select(const Dev &dv, int m, int n_app, bool take_all, hipStre
 hipError_t launch_accum(const Dev &dv, const Src &src, int m_before, int m_after, int row_begin,
                         bool do_create, bool do_merge, bool do_copy, bool check_app, int slot_old,
                         int slot_new, hipStream_t st);
+hipError_t launch_merge_inplace(const Dev &dv, const Src &src, bool check_app, int slot, hipStream_t st);
 hipError_t launch_refresh(const Dev &dv, int m, int slot, hipStream_t st);
 hipError_t launch_ring_copy(const Dev &dv, const Src &src, int64_t src_t0, int64_t p0, int64_t p1,
                             hipStream_t st);
