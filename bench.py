@@ -197,6 +197,90 @@ def cpu_baseline_leg(w, tensors, budget_s):
                        f"{len(unit.fold_logs)} folds) in {dt:.1f} s, scaled by 1/{units} units")
 
 
+def rows_after_prefill(w, T):
+    """State rows after a T-token prefill (the data-independent schedule)."""
+    import math
+    C, L, m = w.chunk_len, w.chunk_len * w.n_bswa_chunks, 0
+    for e in range(C, T + 1, C):
+        if e >= L and w.budget_kind != "none":
+            B = w.budget_fixed if w.budget_kind == "fixed" else int(w.budget_scale * (math.isqrt(e - 1) + 1))
+            m = C if m == 0 else max(m, min(B, m + C))
+    return m
+
+
+def sweep(args, pkg, synth, dev):
+    """The paper's speed-benchmark shape ("Speed Benchmarks": one layer, 32 heads of dimension
+    128, batch 8, bf16, context 512 .. 32768) for a 256-row state and for a 16*sqrt(N) state:
+    prefill ms and decode us/step, with PyTorch's causal SDPA on the same tensors beside them as
+    the full-attention reference.  One JSON line per point."""
+    import statistics
+    import torch
+    import torch.nn.functional as F
+
+    def timed(fn, reps):
+        ts = []
+        for _ in range(reps):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            fn()
+            torch.cuda.synchronize()
+            ts.append((time.perf_counter() - t0) * 1e3)
+        return statistics.median(ts), min(ts), max(ts)
+
+    variants = {"kvm_256": dict(budget_kind="fixed", budget_fixed=256),
+                "kvm_sqrt": dict(budget_kind="sqrt", budget_scale=16.0)}
+    base = synth.WORKLOADS["prefill_fixed"]
+    for T in [512, 1024, 2048, 4096, 8192, 16384, 32768]:
+        shape = dict(batch=8, n_q_heads=32, n_kv_heads=32, head_dim=128, chunk_len=256, rope_dims=32, seq=T)
+        w0 = synth.shrink(base, **shape)
+        q, k, v = synth.make_qkv(w0, dev)
+        out = torch.empty_like(q)
+        row = dict(T=T)
+        # full causal attention through torch (layout [B, H, T, d])
+        try:
+            qh, kh, vh = (x.permute(0, 2, 1, 3) for x in (q, k, v))
+            F.scaled_dot_product_attention(qh, kh, vh, is_causal=True)
+            row["sdpa_prefill_ms"] = timed(lambda: F.scaled_dot_product_attention(qh, kh, vh, is_causal=True),
+                                           args.steps)[0]
+            q1 = qh[:, :, -1:].contiguous()
+            F.scaled_dot_product_attention(q1, kh, vh)
+            row["sdpa_decode_us"] = timed(lambda: [F.scaled_dot_product_attention(q1, kh, vh) for _ in range(20)],
+                                          args.steps)[0] * 1e3 / 20
+        except Exception as exc:  # the reference is optional
+            row["sdpa_error"] = str(exc)[:80]
+        for name, bud in variants.items():
+            w = synth.shrink(w0, name=name, **bud)
+            st = pkg.state_for(w, device=dev, max_tokens=T + 2 * w.chunk_len)
+
+            def prefill():
+                st.reset()
+                st.prefill(q, k, v, out=out)
+            for _ in range(args.warmup):
+                prefill()
+            med, lo, hi = timed(prefill, args.steps)
+            # decode: one chunk of single-token steps from the state that prefill left (one fold)
+            n_dec = w.chunk_len
+            qd, kd, vd = synth.make_qkv(w, dev, T=16, pos0=T)
+            qs = [qd[:, t].contiguous() for t in range(16)]
+            ks = [kd[:, t].contiguous() for t in range(16)]
+            vs = [vd[:, t].contiguous() for t in range(16)]
+            od = torch.empty_like(qs[0])
+            prefill()
+            for t in range(8):
+                st.decode(qs[t], ks[t], vs[t], out=od)
+            prefill()
+            dmed = timed(lambda: [st.decode(qs[t % 16], ks[t % 16], vs[t % 16], out=od) for t in range(n_dec)], 1)[0]
+            row[name] = dict(prefill_ms=med, prefill_ms_min=lo, prefill_ms_max=hi, rows=rows_after_prefill(w, T),
+                             tokens_per_s=w.batch * T / (med * 1e-3), decode_us_per_step=dmed * 1e3 / n_dec)
+            if "sdpa_prefill_ms" in row:
+                row[name]["prefill_speedup_vs_sdpa"] = row["sdpa_prefill_ms"] / med
+                row[name]["decode_speedup_vs_sdpa"] = row["sdpa_decode_us"] / (dmed * 1e3 / n_dec)
+            del st
+        print(json.dumps(dict(sweep="paper_shape_B8_H32_d128_C256_bf16", **row)), flush=True)
+        del q, k, v, out
+        torch.cuda.empty_cache()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -208,6 +292,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-isolated", action="store_true",
                     help="skip the extra passes that time folds and attention apart")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the benchmark line: the paper's speed-benchmark shape over context lengths")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -225,6 +311,9 @@ def main():
         from paper_2605_09877_amd import build
         build.build()
     dev = "cuda:0"
+    if args.sweep:
+        sweep(args, pkg, synth, dev)
+        return
     res, tensors = prefill_leg(args, pkg, synth, dev)
     w = res.pop("workload")
     line = dict(

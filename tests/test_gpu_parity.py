@@ -132,6 +132,14 @@ def test_bf16_negative_temperatures():
     run_prefill_case(w, plain=False, tweak=tweak)
 
 
+def test_bf16_long_chunks_prefill():
+    """C = 1024: a block's merge targets no longer fit one scan round of the accumulate pass."""
+    w = synth().shrink(synth().WORKLOADS["prefill_fixed"], batch=1, n_q_heads=2, n_kv_heads=2, chunk_len=1024,
+                       budget_fixed=1536, seq=6 * 1024 + 50)
+    ties, st = run_prefill_case(w, plain=False)
+    assert st.rows == 1536
+
+
 def test_bf16_sqrt_growth_prefill():
     """Workload 3 shape, shrunk: rows stay 256 until e = 4096, then grow by a few rows per fold
     (partial appends + re-scoring against the new rows); needle duplicates in the data."""
@@ -183,7 +191,8 @@ def test_bf16_head_dim_64_generic_kernels():
 
 # ----------------------------------------------------------------------------- fold alone
 @pytest.mark.parametrize("io,d,C,m0,budget", [("f32", 64, 64, 64, 80), ("bf16", 128, 256, 300, 340),
-                                               ("bf16", 128, 128, 128, 128), ("bf16", 64, 64, 100, 130)])
+                                               ("bf16", 128, 128, 128, 128), ("bf16", 64, 64, 100, 130),
+                                               ("bf16", 128, 1024, 700, 900), ("f32", 128, 576, 200, 200)])
 def test_state_fold_entry_point(io, d, C, m0, budget):
     """kvm_state_fold on an imported state: partial append + re-score + merge in one call."""
     pkg, sy = kvm(), synth()
