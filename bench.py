@@ -324,8 +324,14 @@ def main():
                     head_dim=w.head_dim, seq_len=w.seq, chunk_len=w.chunk_len, state_rows=w.budget_fixed,
                     rope_dims=w.rope_dims, gpu=torch.cuda.get_device_name(0)),
         roofline=res["roofline"])
+    # what this GPU reaches in the library's own microkernels (registers-only bf16 MFMA; 1 GiB copy)
+    peaks = pkg.binding.measure_peaks(dev)
+    line["measured_peaks"] = dict(mfma_bf16_tflops=peaks["mfma_bf16_tflops"], copy_gbs=peaks["copy_gbs"],
+                                  attn_frac_of_measured=res["roofline"]["achieved"] / peaks["mfma_bf16_tflops"])
     if not args.no_decode:
         line["decode"] = decode_leg(args, pkg, synth, dev)
+        line["decode"]["roofline"]["frac_of_measured_copy"] = \
+            line["decode"]["roofline"]["achieved"] / peaks["copy_gbs"]
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline_leg(w, tensors, args.cpu_seconds)
     if args.copy_calibration:

@@ -181,6 +181,18 @@ int kvm_state_import(kvm_state *st, const double *sK, const float *sV, const flo
 int kvm_state_profile(kvm_state *st, int enable);
 int kvm_state_profile_read(kvm_state *st, double ms[3], int64_t count[3]);
 
+/* Measured peaks of the GPU, for rooflines (no passage of the paper: measurement aids).  Both
+ * calls enqueue a microkernel on `stream`, wait for it (they block the host) and report its rate.
+ *   kvm_measure_mfma_bf16_peak: 2048 workgroups x 4 waves issue `iters` x 4 independent
+ *     32x32x16 bf16 matrix instructions on register operands; scratch: device, >= 4 bytes
+ *     (never written in practice); *tflops (host) receives TFLOP/s.
+ *   kvm_measure_copy_peak: copies `bytes` (a multiple of 16; src, dst device, 16-byte aligned,
+ *     not overlapping) five times with 16-byte accesses; *gbs (host) receives GB/s counting
+ *     bytes read plus bytes written.
+ * Errors: KVM_ERR_ARG for bad arguments, KVM_ERR_HIP when a runtime call fails. */
+int kvm_measure_mfma_bf16_peak(int iters, void *scratch, double *tflops, void *stream);
+int kvm_measure_copy_peak(const void *src, void *dst, size_t bytes, double *gbs, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

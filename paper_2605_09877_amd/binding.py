@@ -23,6 +23,7 @@ EXPORTS = [
     "kvm_state_destroy", "kvm_prefill_chunked", "kvm_decode_step", "kvm_state_fold", "kvm_state_rows",
     "kvm_state_tokens", "kvm_state_capacity", "kvm_state_folds", "kvm_state_trace", "kvm_state_grow",
     "kvm_state_export", "kvm_state_import", "kvm_state_profile", "kvm_state_profile_read",
+    "kvm_measure_mfma_bf16_peak", "kvm_measure_copy_peak",
 ]
 
 
@@ -83,6 +84,8 @@ def load_library() -> C.CDLL:
     lib.kvm_state_import.argtypes = [vp] * 9 + [i64, i64, i64, vp]
     lib.kvm_state_profile.argtypes = [vp, C.c_int]
     lib.kvm_state_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
+    lib.kvm_measure_mfma_bf16_peak.argtypes = [C.c_int, vp, C.POINTER(C.c_double), vp]
+    lib.kvm_measure_copy_peak.argtypes = [vp, vp, C.c_size_t, C.POINTER(C.c_double), vp]
     _lib = lib
     return lib
 
@@ -102,6 +105,21 @@ def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
 
 def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
+
+
+def measure_peaks(device="cuda:0", copy_bytes: int = 1 << 30, iters: int = 20000) -> dict:
+    """kvm_measure_mfma_bf16_peak and kvm_measure_copy_peak on `device`: {"mfma_bf16_tflops", "copy_gbs"}."""
+    lib = load_library()
+    with torch.cuda.device(device):
+        src = torch.ones(copy_bytes // 4, dtype=torch.float32, device=device)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        tf, gb = C.c_double(), C.c_double()
+        _check(lib.kvm_measure_mfma_bf16_peak(iters, dst.data_ptr(), C.byref(tf), _stream()),
+               "kvm_measure_mfma_bf16_peak")
+        _check(lib.kvm_measure_copy_peak(src.data_ptr(), dst.data_ptr(), copy_bytes, C.byref(gb), _stream()),
+               "kvm_measure_copy_peak")
+    return dict(mfma_bf16_tflops=tf.value, copy_gbs=gb.value)
 
 
 def _io_dtype(io: int) -> torch.dtype:
