@@ -174,12 +174,16 @@ __device__ __forceinline__ void attn_body(const Dev &dv, const AttnArgs &a, uint
   float m_run = -INFINITY, l_part = 0.f;
   Frag8 pb[4];  // P^T of the tile just scored, packed for the second product
 
-  // O^T += V^T . P^T for the tile whose P^T is in pb.
-  auto do_pv = [&](int tile) {
+  // O^T += V^T . P^T for the tile whose P^T is in pb.  The first eight V^T fragments are asked
+  // for ahead of the softmax (pv_fetch), so that their LDS latency is not waited for here.
+  bf16x8 vf[8];
+  auto pv_fetch = [&](int tile) {
     const uint16_t *Vt = Vs + (tile % kVBufs) * kTileElems;
-    bf16x8 vf[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) vf[i] = vtile_frag(Vt, voff, i & 3, i >> 2);
+  };
+  auto do_pv = [&](int tile) {
+    const uint16_t *Vt = Vs + (tile % kVBufs) * kTileElems;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
@@ -191,7 +195,7 @@ __device__ __forceinline__ void attn_body(const Dev &dv, const AttnArgs &a, uint
   };
 
   // S^T = K . Q^T and the online softmax for the tile in the current K buffer; leaves P^T in pb.
-  auto do_qk_softmax = [&](bool is_state, int row0, int64_t p0) {
+  auto do_qk_softmax = [&](bool is_state, int row0, int64_t p0, int tile) {
     const float scale = is_state ? c_state : c_bswa;
     const bool need_mask = is_state ? (m - row0 < kTileKeys) : (p0 + kTileKeys - 1 > cs + wq0);
     f32x16 sacc[2];
@@ -220,6 +224,7 @@ __device__ __forceinline__ void attn_body(const Dev &dv, const AttnArgs &a, uint
       }
       __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
     }
+    pv_fetch(tile);
     if (need_mask) {
       // keys up to `lim` (tile-local) are visible to this lane's query
       const int lim = is_state ? (m - row0 - 1) : (int)(cs + myq - p0);
@@ -234,7 +239,7 @@ __device__ __forceinline__ void attn_body(const Dev &dv, const AttnArgs &a, uint
     for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
       for (int v = 0; v < 16; ++v) smax = fmaxf(smax, sacc[blk][v]);
-    smax = fmaxf(smax, __shfl_xor(smax, 32, kWave));
+    smax = xhalf_max(smax);  // the other lane half holds the other 32 keys of the same query
     const float m_new = fmaxf(m_run, smax * scale);
     if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
       // some query of this wave has a new running maximum: rescale what is accumulated
@@ -290,14 +295,14 @@ __device__ __forceinline__ void attn_body(const Dev &dv, const AttnArgs &a, uint
     const int64_t p0 = wb + (int64_t)(it - n_st) * kTileKeys;
     // skip tiles whose keys all lie after this wave's queries
     if (is_state || p0 <= cs + wq0 + 31) {
-      do_qk_softmax(is_state, it * kTileKeys, p0);
+      do_qk_softmax(is_state, it * kTileKeys, p0, it);
       do_pv(it);
     }
     // the next tile's K sits in the other buffer
 #pragma unroll
     for (int i = 0; i < 8; ++i) koff[i] ^= (uint32_t)kTileElems;
   }
-  const float l = l_part + __shfl_xor(l_part, 32, kWave);
+  const float l = xhalf_sum(l_part);
   if (myq < nq) {
     const float inv = 1.f / l;
     uint16_t *orow = (uint16_t *)a.out + b * a.o_b + ((int64_t)ci * dv.C + myq) * a.o_t + hq * a.o_h;

@@ -37,6 +37,18 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, h);
 }
 
+// Exchange between lanes i and i + 32 on the vector ALU (v_permlane32_swap; no LDS round trip):
+// of the two results one is the lane's own value and the other its partner's, so a commutative
+// combination of both is the combination of own and partner for every lane.
+__device__ __forceinline__ float xhalf_max(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float xhalf_sum(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 union Frag8 {
   bf16x8 v;
   uint4 q;
