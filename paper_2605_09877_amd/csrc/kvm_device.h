@@ -78,19 +78,58 @@ struct Vec16<bf16_t> {
   }
 };
 
-// Sum over groups of kLanes adjacent lanes (a power of two).
+// All-reduce sums on the vector ALU, without the LDS crossbar: four DPP steps inside a row of 16
+// lanes (partners lane^1, lane^2, then the mirror images within 8 and within 16 lanes, which pair
+// up the partial sums just as well), then the row exchanges v_permlane16_swap and
+// v_permlane32_swap.  A swap of a register with itself returns the lane's own value and its
+// partner's; their sum is the same number, added in the same order, in both lanes, so every lane
+// of a group ends with the identical result.
+template <int kCtrl>
+__device__ __forceinline__ float dpp_get(float x) {
+  return __uint_as_float(__builtin_amdgcn_mov_dpp(__float_as_uint(x), kCtrl, 0xF, 0xF, true));
+}
+template <int kCtrl>
+__device__ __forceinline__ double dpp_get(double x) {
+  const uint64_t b = (uint64_t)__double_as_longlong(x);
+  const uint32_t lo = __builtin_amdgcn_mov_dpp((uint32_t)b, kCtrl, 0xF, 0xF, true);
+  const uint32_t hi = __builtin_amdgcn_mov_dpp((uint32_t)(b >> 32), kCtrl, 0xF, 0xF, true);
+  return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+}
+template <bool k32>
+__device__ __forceinline__ float swap_sum(float x) {
+  const uint32_t u = __float_as_uint(x);
+  const auto r = k32 ? __builtin_amdgcn_permlane32_swap(u, u, false, false)
+                     : __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+template <bool k32>
+__device__ __forceinline__ double swap_sum(double x) {
+  const uint64_t b = (uint64_t)__double_as_longlong(x);
+  const uint32_t lo = (uint32_t)b, hi = (uint32_t)(b >> 32);
+  const auto l = k32 ? __builtin_amdgcn_permlane32_swap(lo, lo, false, false)
+                     : __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
+  const auto h = k32 ? __builtin_amdgcn_permlane32_swap(hi, hi, false, false)
+                     : __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
+  return __longlong_as_double((long long)(((uint64_t)h[0] << 32) | l[0])) +
+         __longlong_as_double((long long)(((uint64_t)h[1] << 32) | l[1]));
+}
+
+// Sum over aligned groups of kLanes adjacent lanes (8, 16, 32 or 64), in every lane of the group.
 template <int kLanes, typename V>
 __device__ __forceinline__ V group_sum(V x) {
-#pragma unroll
-  for (int o = kLanes / 2; o > 0; o >>= 1) x += __shfl_xor(x, o, kWave);
+  static_assert(kLanes == 8 || kLanes == 16 || kLanes == 32 || kLanes == 64, "group size");
+  x += dpp_get<0xB1>(x);   // quad_perm [1,0,3,2]
+  x += dpp_get<0x4E>(x);   // quad_perm [2,3,0,1]
+  x += dpp_get<0x141>(x);  // row_half_mirror
+  if (kLanes >= 16) x += dpp_get<0x140>(x);  // row_mirror
+  if (kLanes >= 32) x = swap_sum<false>(x);
+  if (kLanes >= 64) x = swap_sum<true>(x);
   return x;
 }
 
 template <typename V>
 __device__ __forceinline__ V wave_sum(V x) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, kWave);
-  return x;
+  return group_sum<64>(x);
 }
 
 template <typename V>
