@@ -168,33 +168,38 @@ def decode_leg(args, pkg, synth, dev):
 
 
 def cpu_baseline_leg(w, tensors, budget_s):
-    """The oracle, as it stands, on one (batch, KV head) unit of the same inputs, for as many
-    chunks as fit the time budget; scaled to whole-layer tokens/s (units are independent and
-    equal in work)."""
+    """The oracle, as it stands, on (batch, KV head) units of the same inputs, one after the other,
+    for as many chunks as fit the time budget; scaled to whole-layer tokens/s (units are
+    independent and equal in work: a layer token is one position of every KV head)."""
     import kvm_testlib as tl
     q, k, v = tensors
     C = w.chunk_len
-    n_tok = w.seq
-    sub = (q[:1, :n_tok], k[:1, :n_tok], v[:1, :n_tok])
-    u = tl.unit_inputs(w, *sub, {}, 0, 0)
-    unit = tl.make_oracle_unit(w, {}, 0)
     t0 = time.perf_counter()
-    done = 0
-    while done < n_tok and time.perf_counter() - t0 < budget_s:
-        unit.prefill(u["q"][:, done:done + C], u["k"][done:done + C], u["v"][done:done + C])
-        done += C
+    done, units_done, folds = 0, 0, 0
+    for b in range(w.batch):
+        for h in range(w.n_kv_heads):
+            if time.perf_counter() - t0 >= budget_s:
+                break
+            u = tl.unit_inputs(w, q[b:b + 1], k[b:b + 1], v[b:b + 1], {}, 0, h)
+            unit = tl.make_oracle_unit(w, {}, h)
+            pos = 0
+            while pos < w.seq and time.perf_counter() - t0 < budget_s:
+                unit.prefill(u["q"][:, pos:pos + C], u["k"][pos:pos + C], u["v"][pos:pos + C])
+                pos += C
+            done += pos
+            folds += len(unit.fold_logs)
+            units_done += 1
     dt = time.perf_counter() - t0
-    units = w.batch * w.n_kv_heads
     try:
         import threadpoolctl
         cores = max(int(i.get("num_threads", 1)) for i in threadpoolctl.threadpool_info()) \
             if threadpoolctl.threadpool_info() else os.cpu_count()
     except Exception:
         cores = os.cpu_count()
-    # one unit handles `done` tokens of one KV head of one sequence: the layer needs `units` of them
-    return dict(value=done * w.batch / (dt * units), unit="tokens/s", cores=cores, kind="oracle",
-                sample=f"unit (b=0, kv head 0): first {done} of {w.seq} tokens ({done // C} chunks, "
-                       f"{len(unit.fold_logs)} folds) in {dt:.1f} s, scaled by 1/{units} units")
+    return dict(value=done / (dt * w.n_kv_heads), unit="tokens/s", cores=cores, kind="oracle",
+                sample=f"{units_done} of {w.batch * w.n_kv_heads} (sequence, KV head) units in order from "
+                       f"(0, 0): {done} unit-tokens ({done // C} chunks, {folds} folds) in {dt:.1f} s; "
+                       f"one layer token = {w.n_kv_heads} unit-tokens")
 
 
 def rows_after_prefill(w, T):
