@@ -81,12 +81,16 @@ def prefill_leg(args, pkg, synth, dev):
     torch.cuda.synchronize()
     st.profile(True)
     st.profile_read()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for i in range(args.steps):
+        marks[i].record()          # on the stream the library is called on; each call joins back to it
         st.reset()
         st.prefill(q, k, v, out=out)
+    marks[args.steps].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
     prof = st.profile_read()
     # the same step with folds and attention kept apart: each kernel's time without the other
     iso = None
@@ -112,6 +116,7 @@ def prefill_leg(args, pkg, synth, dev):
                         attn_ms_per_step=iso["attn"][0] / 2, fold_ms_per_step=iso["fold"][0] / 2)
     res = dict(
         value=tokens * args.steps / dt, ms_per_step=dt / args.steps * 1e3,
+        step_ms=dict(median=step_ms[len(step_ms) // 2], min=step_ms[0], max=step_ms[-1]),
         roofline=dict(bound="mfma", kernel="attn_mfma_kernel", achieved=achieved, peak=MFMA_BF16_PEAK_TFLOPS,
                       unit="TFLOP/s", frac=achieved / MFMA_BF16_PEAK_TFLOPS,
                       traffic=measured_traffic("attn_mfma_kernel_prefill_gqa_32k_hbm_traffic.txt")
@@ -295,6 +300,7 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-others", action="store_true", help="skip the two other prefill workloads")
     ap.add_argument("--no-isolated", action="store_true",
                     help="skip the extra passes that time folds and attention apart")
     ap.add_argument("--sweep", action="store_true",
@@ -328,16 +334,35 @@ def main():
         config=dict(workload=w.name, batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads,
                     head_dim=w.head_dim, seq_len=w.seq, chunk_len=w.chunk_len, state_rows=w.budget_fixed,
                     rope_dims=w.rope_dims, gpu=torch.cuda.get_device_name(0)),
-        roofline=res["roofline"])
+        step_ms=res["step_ms"], roofline=res["roofline"])
     # what this GPU reaches in the library's own microkernels (registers-only bf16 MFMA; 1 GiB copy)
     peaks = pkg.binding.measure_peaks(dev)
     line["measured_peaks"] = dict(mfma_bf16_tflops=peaks["mfma_bf16_tflops"], copy_gbs=peaks["copy_gbs"],
                                   attn_frac_of_measured=res["roofline"]["achieved"] / peaks["mfma_bf16_tflops"])
+    if not args.no_others and args.workload == "prefill_gqa_32k":
+        # the two other prefill configurations (fixed 512-row state; ~sqrt growth): step time only
+        del tensors
+        torch.cuda.empty_cache()
+        line["other_workloads"] = {}
+        for name in ("prefill_fixed", "prefill_sqrt"):
+            a2 = argparse.Namespace(**{**vars(args), "workload": name, "no_isolated": True})
+            r2, t2 = prefill_leg(a2, pkg, synth, dev)
+            w2 = r2["workload"]
+            line["other_workloads"][name] = dict(
+                tokens_per_s=r2["value"], ms_per_step=r2["ms_per_step"], step_ms=r2["step_ms"],
+                attn_tflops=r2["roofline"]["achieved"], folds_per_step=r2["roofline"]["folds_per_step"],
+                config=dict(batch=w2.batch, heads=w2.n_q_heads, seq_len=w2.seq, chunk_len=w2.chunk_len,
+                            budget=w2.budget_kind))
+            del t2
+            torch.cuda.empty_cache()
+        tensors = None
     if not args.no_decode:
         line["decode"] = decode_leg(args, pkg, synth, dev)
         line["decode"]["roofline"]["frac_of_measured_copy"] = \
             line["decode"]["roofline"]["achieved"] / peaks["copy_gbs"]
     if not args.no_cpu:
+        if tensors is None:
+            tensors = synth.make_qkv(w, dev)     # same seed, same tensors as the timed run
         line["cpu_baseline"] = cpu_baseline_leg(w, tensors, args.cpu_seconds)
     if args.copy_calibration:
         copy_calibration(dev)
