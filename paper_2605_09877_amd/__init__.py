@@ -24,10 +24,12 @@ def kvm_state_fold(state: KVMState, k_blk, v_blk, gate_blk=None, *, e: int):
 
 def state_for(w, *, max_tokens=None, device="cuda:0", **params) -> KVMState:
     """A state configured like synth.Workload `w`; params: ln_gamma, ln_beta, tau_state, tau_bswa."""
-    kind = {"none": KVM_BUDGET_NONE, "fixed": KVM_BUDGET_FIXED, "sqrt": KVM_BUDGET_SQRT}[w.budget_kind]
+    kind = {"none": KVM_BUDGET_NONE, "fixed": KVM_BUDGET_FIXED, "sqrt": KVM_BUDGET_SQRT,
+            "table": KVM_BUDGET_TABLE}[w.budget_kind]
     return KVMState(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
                     rope_dims=w.rope_dims, chunk_len=w.chunk_len, n_bswa_chunks=w.n_bswa_chunks,
                     n_sink=w.n_sink, io_dtype=KVM_BF16 if w.io == "bf16" else KVM_F32, budget_kind=kind,
                     budget_fixed=w.budget_fixed, budget_scale=w.budget_scale,
+                    budget_table=list(w.budget_table) if w.budget_kind == "table" else None,
                     max_tokens=w.seq if max_tokens is None else max_tokens, device=device,
                     **{k: v for k, v in params.items() if k in ("ln_gamma", "ln_beta", "tau_state", "tau_bswa")})

@@ -36,9 +36,10 @@ class Workload:
     seq: int                # prefill length T (decode: steps)
     chunk_len: int
     rope_dims: int
-    budget_kind: str        # "none" | "fixed" | "sqrt"
+    budget_kind: str        # "none" | "fixed" | "sqrt" | "table"
     budget_fixed: int = 0
     budget_scale: float = 0.0
+    budget_table: tuple = ()  # "table": budget per chunk index, last entry repeats
     n_bswa_chunks: int = 2
     n_sink: int = 1
     gen: str = "mog"        # "mog" | "needle" | "normal"

@@ -16,14 +16,16 @@ import torch
 from oracle import kvm_oracle as ko
 
 F32_EPS = dict(ln_eps=float(np.float32(1e-5)), norm_eps=float(np.float32(1e-12)))
-ORACLE_BUDGET = {"none": ko.BUDGET_NONE, "fixed": ko.BUDGET_FIXED, "sqrt": ko.BUDGET_SQRT}
+ORACLE_BUDGET = {"none": ko.BUDGET_NONE, "fixed": ko.BUDGET_FIXED, "sqrt": ko.BUDGET_SQRT,
+                 "table": ko.BUDGET_TABLE}
 
 
 def oracle_cfg(w) -> ko.KVMConfig:
     return ko.KVMConfig(head_dim=w.head_dim, rope_dims=w.rope_dims, chunk_len=w.chunk_len,
                         n_bswa_chunks=w.n_bswa_chunks, n_sink=w.n_sink, io=w.io,
                         budget_kind=ORACLE_BUDGET[w.budget_kind], budget_fixed=w.budget_fixed,
-                        budget_scale=w.budget_scale, **F32_EPS)
+                        budget_scale=w.budget_scale,
+                        budget_table=list(w.budget_table) if w.budget_kind == "table" else None, **F32_EPS)
 
 
 def f64(t) -> np.ndarray:

@@ -140,6 +140,24 @@ def test_bf16_long_chunks_prefill():
     assert st.rows == 1536
 
 
+def test_bf16_three_window_blocks_with_state():
+    """n_bswa = 3: a 768-token window over a 512-row state on the matrix-core path."""
+    w = synth().shrink(synth().WORKLOADS["prefill_fixed"], batch=1, n_q_heads=2, n_kv_heads=2, n_bswa_chunks=3,
+                       seq=3072 + 45)
+    ties, st = run_prefill_case(w, plain=False)
+    assert st.rows == 512
+
+
+def test_bf16_saturating_budget_table():
+    """A saturating schedule given as a table (one budget per chunk; the last entry repeats):
+    growth by whole blocks, then by a few rows, then none."""
+    table = (256, 256, 512, 640, 700, 720, 730, 736, 736)
+    w = synth().shrink(synth().WORKLOADS["prefill_fixed"], batch=1, n_q_heads=2, n_kv_heads=2,
+                       budget_kind="table", budget_table=table, seq=12 * 256 + 19)
+    ties, st = run_prefill_case(w, plain=False)
+    assert st.rows == 736
+
+
 def test_bf16_sqrt_growth_prefill():
     """Workload 3 shape, shrunk: rows stay 256 until e = 4096, then grow by a few rows per fold
     (partial appends + re-scoring against the new rows); needle duplicates in the data."""
