@@ -172,6 +172,42 @@ def decode_leg(args, pkg, synth, dev):
                               avg_launch_us=avg_s * 1e6, bytes_per_launch=bytes_per_step))
 
 
+def prep_leg(args, pkg, synth, dev):
+    """The weight preparation in front of the layer (value residual, token shift, LN_q/LN_k, partial
+    RoPE, merge gate) on the headline workload's shape, every feature on: HBM roofline of the call."""
+    import torch
+    w = synth.WORKLOADS[args.workload]
+    B, T, Hq, Hkv, d = w.batch, w.seq, w.n_q_heads, w.n_kv_heads, w.head_dim
+    dm = Hq * d
+    dt = synth.torch_dtype(w.io)
+    gen = torch.Generator(device=dev).manual_seed(w.seed + 31)
+    rnd = lambda *s: torch.randn(*s, generator=gen, device=dev)
+    q, k, v, vf = (rnd(B, T, H, d).to(dt) for H in (Hq, Hkv, Hkv, Hkv))
+    x = rnd(B, T, dm).to(dt)
+    P = dict(alpha_q=torch.rand(Hq, d, device=dev), alpha_k=torch.rand(Hkv, d, device=dev),
+             alpha_v=torch.rand(Hkv, d, device=dev), lambda_v=torch.rand(Hkv, d, device=dev),
+             lnq_gamma=torch.ones(Hq, d, device=dev), lnq_beta=torch.zeros(Hq, d, device=dev),
+             lnk_gamma=torch.ones(Hkv, d, device=dev), lnk_beta=torch.zeros(Hkv, d, device=dev),
+             w_gate=rnd(dm, Hkv) / dm ** 0.5)
+    run = lambda: pkg.binding.prepare_qkv(q, k, v, rope_dims=w.rope_dims, v_first=vf, x=x, **P)
+    run()
+    reps = 5
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+    for i in range(reps):
+        marks[i].record()
+        run()
+    marks[reps].record()
+    torch.cuda.synchronize()
+    ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(reps))[reps // 2]
+    es = 2 if w.io == "bf16" else 4
+    nbytes = B * T * (2 * Hq * d * es + 5 * Hkv * d * es + dm * es + Hkv * 4)   # q r+w, k r+w, v r+w + v_first, x, gate
+    gbs = nbytes / (ms * 1e-3) / 1e9
+    return dict(ms=ms, bytes=nbytes, config=dict(batch=B, seq_len=T, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d,
+                                                 d_model=dm, rope_dims=w.rope_dims),
+                roofline=dict(bound="hbm", kernel="prep_rows_kernel + gate_kernel", achieved=gbs, peak=HBM_PEAK_GBS,
+                              unit="GB/s", frac=gbs / HBM_PEAK_GBS, traffic=None))
+
+
 def cpu_baseline_leg(w, tensors, budget_s):
     """The oracle, as it stands, on (batch, KV head) units of the same inputs, one after the other,
     for as many chunks as fit the time budget; scaled to whole-layer tokens/s (units are
@@ -356,6 +392,9 @@ def main():
             del t2
             torch.cuda.empty_cache()
         tensors = None
+    if not args.no_others:
+        line["prep"] = prep_leg(args, pkg, synth, dev)
+        torch.cuda.empty_cache()
     if not args.no_decode:
         line["decode"] = decode_leg(args, pkg, synth, dev)
         line["decode"]["roofline"]["frac_of_measured_copy"] = \

@@ -181,6 +181,49 @@ int kvm_state_import(kvm_state *st, const double *sK, const float *sV, const flo
 int kvm_state_profile(kvm_state *st, int enable);
 int kvm_state_profile_read(kvm_state *st, double ms[3], int64_t count[3]);
 
+/* ---- Attention weight preparation in front of the layer -------------------------------------
+ * The paper's appendix "GPTAlpha-2 Attention weight preparation" (value residual, token shift,
+ * LN_q / LN_k, rotary embedding on the first r channels) and the merge gate of the Method section
+ * ("KVM weight preparation": g_t = 1 + ELU(x_t W_g)), applied to the "simple" q~, k~, v~ that the
+ * input projections produced; its outputs are what kvm_prefill_chunked / kvm_decode_step take.
+ *   v~ <- (1 - lambda) v~ + lambda v~first;  a_t = a~_t + alpha (a~_{t-1} - a~_t) for a in {q, k, v};
+ *   q <- RoPE_r(LN_q(q)),  k <- RoPE_r(LN_k(k));  rotary pairs are channels (c, c + r/2),
+ *   angle = position * base^(-2c/r).
+ * All parameter arrays are device fp32, 16-byte aligned; NULL selects the neutral value (alpha = 0: no shift,
+ * lambda = 0, gamma = 1, beta = 0).  rope_dims: 0, or an even number whose half is 8, 16, 32 or 64
+ * channels (bf16) / 4 ... 64 (fp32).  d_model: width of x (a multiple of 8 for bf16, 4 for fp32). */
+typedef struct kvm_prep_params {
+  int32_t batch, n_q_heads, n_kv_heads, head_dim; /* d_h: 64 or 128 */
+  int32_t rope_dims;                               /* r */
+  int32_t io_dtype;                                /* KVM_F32 | KVM_BF16: q~, k~, v~, x and the outputs */
+  int32_t d_model;                                 /* 0 when no gate is computed */
+  float ln_eps;                                    /* 0 selects 1e-5 */
+  double rope_base;                                /* 0 selects 10000 */
+  const float *alpha_q;                            /* [H_q, d_h] */
+  const float *alpha_k, *alpha_v, *lambda_v;       /* [H_kv, d_h] */
+  const float *lnq_gamma, *lnq_beta;               /* [H_q, d_h] */
+  const float *lnk_gamma, *lnk_beta;               /* [H_kv, d_h] */
+  const float *w_gate;                             /* [d_model, H_kv] */
+} kvm_prep_params;
+
+/* Bytes of device scratch kvm_prepare_qkv needs for T tokens (the rotation table); 0 on bad arguments. */
+size_t kvm_prepare_scratch_bytes(const kvm_prep_params *p, int64_t T);
+
+/* Prepares T tokens at absolute positions pos0 .. pos0 + T - 1 for every sequence of the batch.
+ *   q_raw [B, T, H_q, d_h], k_raw, v_raw [B, T, H_kv, d_h]: I/O dtype, contiguous, device;
+ *   v_first: same shape as v_raw, or NULL (no value residual);
+ *   x [B, T, d_model] I/O dtype, or NULL (no gate; then gate_out is not written);
+ *   prev_q [B, H_q, d_h], prev_k, prev_v [B, H_kv, d_h]: the simple rows of the token before this
+ *     call (prev_v after its own value residual), or NULL: the first token is then not shifted;
+ *   q_out, k_out, v_out: shaped like the inputs, must not alias them; gate_out fp32 [B, T, H_kv];
+ *   scratch: kvm_prepare_scratch_bytes(p, T) bytes, 16-byte aligned like every other pointer.
+ * Work is enqueued on `stream`; the host is not blocked.  Buffers stay the caller's.
+ * Errors: KVM_ERR_ARG (shapes, alignment, aliasing, missing gate arguments), KVM_ERR_HIP. */
+int kvm_prepare_qkv(const kvm_prep_params *p, const void *q_raw, const void *k_raw, const void *v_raw,
+                    const void *v_first, const void *x, const void *prev_q, const void *prev_k,
+                    const void *prev_v, void *q_out, void *k_out, void *v_out, float *gate_out,
+                    void *scratch, int64_t T, int64_t pos0, void *stream);
+
 /* Measured peaks of the GPU, for rooflines (no passage of the paper: measurement aids).  Both
  * calls enqueue a microkernel on `stream`, wait for it (they block the host) and report its rate.
  *   kvm_measure_mfma_bf16_peak: 2048 workgroups x 4 waves issue `iters` x 4 independent

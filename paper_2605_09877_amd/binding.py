@@ -23,7 +23,7 @@ EXPORTS = [
     "kvm_state_destroy", "kvm_prefill_chunked", "kvm_decode_step", "kvm_state_fold", "kvm_state_rows",
     "kvm_state_tokens", "kvm_state_capacity", "kvm_state_folds", "kvm_state_trace", "kvm_state_grow",
     "kvm_state_export", "kvm_state_import", "kvm_state_profile", "kvm_state_profile_read",
-    "kvm_measure_mfma_bf16_peak", "kvm_measure_copy_peak",
+    "kvm_measure_mfma_bf16_peak", "kvm_measure_copy_peak", "kvm_prepare_scratch_bytes", "kvm_prepare_qkv",
 ]
 
 
@@ -36,6 +36,17 @@ class kvm_config(C.Structure):
         ("budget_table", C.POINTER(C.c_int64)), ("budget_table_len", C.c_int64),
         ("ln_eps", C.c_float), ("norm_eps", C.c_float),
         ("ln_gamma", C.c_void_p), ("ln_beta", C.c_void_p), ("tau_state", C.c_void_p), ("tau_bswa", C.c_void_p),
+    ]
+
+
+class kvm_prep_params(C.Structure):
+    _fields_ = [
+        ("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+        ("rope_dims", C.c_int32), ("io_dtype", C.c_int32), ("d_model", C.c_int32), ("ln_eps", C.c_float),
+        ("rope_base", C.c_double),
+        ("alpha_q", C.c_void_p), ("alpha_k", C.c_void_p), ("alpha_v", C.c_void_p), ("lambda_v", C.c_void_p),
+        ("lnq_gamma", C.c_void_p), ("lnq_beta", C.c_void_p), ("lnk_gamma", C.c_void_p), ("lnk_beta", C.c_void_p),
+        ("w_gate", C.c_void_p),
     ]
 
 
@@ -84,6 +95,9 @@ def load_library() -> C.CDLL:
     lib.kvm_state_import.argtypes = [vp] * 9 + [i64, i64, i64, vp]
     lib.kvm_state_profile.argtypes = [vp, C.c_int]
     lib.kvm_state_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
+    lib.kvm_prepare_scratch_bytes.restype = C.c_size_t
+    lib.kvm_prepare_scratch_bytes.argtypes = [C.POINTER(kvm_prep_params), i64]
+    lib.kvm_prepare_qkv.argtypes = [C.POINTER(kvm_prep_params)] + [vp] * 13 + [i64, i64, vp]
     lib.kvm_measure_mfma_bf16_peak.argtypes = [C.c_int, vp, C.POINTER(C.c_double), vp]
     lib.kvm_measure_copy_peak.argtypes = [vp, vp, C.c_size_t, C.POINTER(C.c_double), vp]
     _lib = lib
@@ -105,6 +119,31 @@ def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
 
 def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
+
+
+def prepare_qkv(q_raw, k_raw, v_raw, *, rope_dims: int, pos0: int = 0, v_first=None, x=None, prev_q=None,
+                prev_k=None, prev_v=None, alpha_q=None, alpha_k=None, alpha_v=None, lambda_v=None,
+                lnq_gamma=None, lnq_beta=None, lnk_gamma=None, lnk_beta=None, w_gate=None,
+                ln_eps: float = 0.0, rope_base: float = 0.0):
+    """kvm_prepare_qkv on [B, T, H, d] tensors: returns (q, k, v, gate or None)."""
+    lib = load_library()
+    B, T, Hq, d = q_raw.shape
+    Hkv = k_raw.shape[2]
+    io = KVM_BF16 if q_raw.dtype == torch.bfloat16 else KVM_F32
+    f32 = lambda t: None if t is None else t.to(torch.float32).contiguous()
+    prm = [f32(t) for t in (alpha_q, alpha_k, alpha_v, lambda_v, lnq_gamma, lnq_beta, lnk_gamma, lnk_beta, w_gate)]
+    p = kvm_prep_params(B, Hq, Hkv, d, rope_dims, io, 0 if x is None else x.shape[-1], ln_eps, rope_base,
+                        *[_ptr(t) for t in prm])
+    tens = [t if t is None else t.contiguous() for t in (q_raw, k_raw, v_raw, v_first, x, prev_q, prev_k, prev_v)]
+    q, k, v = torch.empty_like(tens[0]), torch.empty_like(tens[1]), torch.empty_like(tens[2])
+    gate = None if x is None else torch.empty(B, T, Hkv, dtype=torch.float32, device=q_raw.device)
+    nbytes = lib.kvm_prepare_scratch_bytes(C.byref(p), T)
+    if nbytes == 0:
+        raise KVMError(KVM_ERR_ARG, "kvm_prepare_scratch_bytes: invalid preparation parameters")
+    scratch = torch.empty(nbytes, dtype=torch.uint8, device=q_raw.device)
+    _check(lib.kvm_prepare_qkv(C.byref(p), *[_ptr(t) for t in tens], _ptr(q), _ptr(k), _ptr(v), _ptr(gate),
+                               _ptr(scratch), T, pos0, _stream()), "kvm_prepare_qkv")
+    return q, k, v, gate
 
 
 def measure_peaks(device="cuda:0", copy_bytes: int = 1 << 30, iters: int = 20000) -> dict:

@@ -1,0 +1,297 @@
+// Attention weight preparation in front of the KVM layer (the paper's appendix "GPTAlpha-2
+// Attention weight preparation"; merge gate: Method, "KVM weight preparation"), memory bound:
+//   v~ <- (1 - lambda) v~ + lambda v~first          value residual
+//   a  =  a~_t + alpha * (a~_{t-1} - a~_t)          token shift of q, k, v (first token unshifted)
+//   q, k <- RoPE_r(LN(q)), RoPE_r(LN(k))            LayerNorm with bias per head, rotary on r channels
+//   g  =  1 + ELU(x W_g)                            merge gate, one scalar per KV head
+// One row (token, head) is handled by d_h / kN adjacent lanes, 16 bytes of channels each, so a
+// wave takes several rows; statistics and the rotation partner come through lane exchanges.
+// Arithmetic is fp32; the rotation angles are evaluated in fp64 once per position (a table),
+// because position * frequency loses its low bits in fp32 at 32k tokens.
+#include "../../include/kvm.h"
+#include "kvm_device.h"
+
+namespace kvm {
+namespace {
+
+__global__ __launch_bounds__(256) void rope_table_kernel(float2 *tab, int64_t n_pos, int64_t pos0, int half,
+                                                         double base) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n_pos * half) return;
+  const int64_t t = i / half;
+  const int c = (int)(i % half);
+  const double ang = (double)(pos0 + t) * pow(base, -(double)c / (double)half);  // base^(-2c/r)
+  tab[i] = make_float2((float)cos(ang), (float)sin(ang));
+}
+
+struct RowArgs {
+  const void *in;       // [B, T, H, d] simple q, k or v
+  const void *first;    // [B, T, H, d] first-layer value, or null (value residual)
+  const void *prev;     // [B, H, d] row of the token before this call, or null
+  void *out;            // [B, T, H, d]
+  const float *alpha;   // [H, d] or null
+  const float *lambda;  // [H, d] or null
+  const float *gamma, *beta;  // [H, d] or null
+  const float2 *tab;    // [T, r/2] (cos, sin)
+  int64_t T;
+  int H, r, normalise;
+  float eps;
+};
+
+// kN fp32 parameters starting at p (16-byte aligned), or the neutral value when p is null.
+template <int kN>
+__device__ __forceinline__ void load_params(const float *p, float neutral, float (&f)[kN]) {
+  if (p) {
+#pragma unroll
+    for (int i = 0; i < kN; i += 4) {
+      const float4 x = *reinterpret_cast<const float4 *>(p + i);
+      f[i] = x.x; f[i + 1] = x.y; f[i + 2] = x.z; f[i + 3] = x.w;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < kN; ++i) f[i] = neutral;
+  }
+}
+
+// kNorm: LayerNorm + rotation (q, k); kResidual: value residual (v).
+template <typename T, int D, bool kNorm, bool kResidual>
+__global__ __launch_bounds__(256) void prep_rows_kernel(RowArgs a, uint32_t n_rows) {
+  constexpr int VEC = Vec16<T>::kN;
+  constexpr int LPT = D / VEC;   // lanes per row
+  constexpr int RPW = 64 / LPT;  // rows per wave
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane / LPT, cl = lane % LPT;
+  const uint32_t row_raw = (blockIdx.x * 4u + wave) * RPW + sub;
+  const bool live = row_raw < n_rows;
+  const uint32_t row = live ? row_raw : n_rows - 1;  // idle lane groups repeat the last row, store nothing
+  const uint32_t H = (uint32_t)a.H, bt = row / H, h = row - bt * H;
+  const uint32_t T_ = (uint32_t)a.T, b = bt / T_, t = bt - b * T_;
+  const int c0 = cl * VEC;
+  const int64_t off = (int64_t)row * D + c0;
+  const int pc = (int)h * D + c0;  // offset into the per-head parameter arrays
+
+  float y[VEC], p[VEC];
+  Vec16<T>::load((const T *)a.in + off, y);
+  const bool shift = a.alpha && (t > 0 || a.prev);
+  if (shift) {
+    if (t > 0)
+      Vec16<T>::load((const T *)a.in + off - (int64_t)H * D, p);
+    else
+      Vec16<T>::load((const T *)a.prev + (int64_t)(b * H + h) * D + c0, p);  // already residual-mixed
+  }
+  if (kResidual && a.first && a.lambda) {
+    float lm[VEC], f[VEC];
+    load_params<VEC>(a.lambda + pc, 0.f, lm);
+    Vec16<T>::load((const T *)a.first + off, f);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) y[i] = (1.f - lm[i]) * y[i] + lm[i] * f[i];
+    if (shift && t > 0) {
+      Vec16<T>::load((const T *)a.first + off - (int64_t)H * D, f);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) p[i] = (1.f - lm[i]) * p[i] + lm[i] * f[i];
+    }
+  }
+  if (shift) {
+    float al[VEC];
+    load_params<VEC>(a.alpha + pc, 0.f, al);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) y[i] += al[i] * (p[i] - y[i]);
+  }
+  if (kNorm) {
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) s += y[i];
+    const float mean = group_sum<LPT>(s) * (1.f / (float)D);
+    float q = 0.f;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) {
+      y[i] -= mean;
+      q += y[i] * y[i];
+    }
+    const float rstd = rsqrtf(group_sum<LPT>(q) * (1.f / (float)D) + a.eps);
+    float ga[VEC], be[VEC];
+    load_params<VEC>(a.gamma ? a.gamma + pc : nullptr, 1.f, ga);
+    load_params<VEC>(a.beta ? a.beta + pc : nullptr, 0.f, be);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) y[i] = y[i] * rstd * ga[i] + be[i];
+    if (a.r > 0) {
+      // channel c < r/2 pairs with c + r/2, which sits r/2/VEC lanes away (a power of two)
+      const int half = a.r / 2, hop = half / VEC;
+      float o[VEC];
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) o[i] = __shfl_xor(y[i], hop, kWave);
+      if (c0 < a.r) {
+        const bool lower = c0 < half;
+        float cs[2 * VEC];  // (cos, sin) of this lane's channels
+        load_params<2 * VEC>((const float *)(a.tab + (int64_t)t * half + (lower ? c0 : c0 - half)), 0.f, cs);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i)
+          y[i] = lower ? y[i] * cs[2 * i] - o[i] * cs[2 * i + 1] : y[i] * cs[2 * i] + o[i] * cs[2 * i + 1];
+      }
+    }
+  }
+  if (live) Vec16<T>::store((T *)a.out + off, y);
+}
+
+// Merge gate: a wave takes kGateTok tokens; lanes stride over the model width, 16 bytes of x each,
+// heads in blocks of eight; the per-lane partial dot products are summed across the wave at the
+// end.  kFull: the number of KV heads is a multiple of 8, so a row of eight gate weights is two
+// aligned 16-byte loads.
+constexpr int kGateTok = 4;
+template <typename T, bool kFull>
+__global__ __launch_bounds__(256) void gate_kernel(const T *x, const float *w, float *gate, int64_t n_tok,
+                                                   int dm, int Hkv) {
+  constexpr int VEC = Vec16<T>::kN;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t tok0 = ((int64_t)blockIdx.x * 4 + wave) * kGateTok;
+  if (tok0 >= n_tok) return;
+  const T *xr[kGateTok];
+#pragma unroll
+  for (int k = 0; k < kGateTok; ++k) xr[k] = x + (tok0 + k < n_tok ? tok0 + k : n_tok - 1) * dm;
+  for (int h0 = 0; h0 < Hkv; h0 += 8) {
+    float acc[kGateTok][8];
+#pragma unroll
+    for (int k = 0; k < kGateTok; ++k)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[k][j] = 0.f;
+    for (int c0 = lane * VEC; c0 < dm; c0 += 64 * VEC) {
+      float xv[kGateTok][VEC];
+#pragma unroll
+      for (int k = 0; k < kGateTok; ++k) Vec16<T>::load(xr[k] + c0, xv[k]);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) {
+        float wv[8];
+        const float *wrow = w + (int64_t)(c0 + i) * Hkv + h0;
+        if (kFull) {
+          load_params<8>(wrow, 0.f, wv);
+        } else {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) wv[j] = h0 + j < Hkv ? wrow[j] : 0.f;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+          for (int k = 0; k < kGateTok; ++k) acc[k][j] = fmaf(xv[k][i], wv[j], acc[k][j]);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < kGateTok; ++k)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float z = wave_sum(acc[k][j]);
+        if (lane == 0 && tok0 + k < n_tok && h0 + j < Hkv)
+          gate[(tok0 + k) * Hkv + h0 + j] = 1.f + (z > 0.f ? z : expm1f(z));
+      }
+  }
+}
+
+template <typename T, bool kNorm, bool kResidual>
+hipError_t launch_rows(const RowArgs &a, int d, int64_t n_rows, hipStream_t st) {
+  const int rows_per_wg = 4 * 64 / (d / Vec16<T>::kN);
+  dim3 grid((unsigned)((n_rows + rows_per_wg - 1) / rows_per_wg));
+  if (d == 64)
+    hipLaunchKernelGGL((prep_rows_kernel<T, 64, kNorm, kResidual>), grid, dim3(256), 0, st, a, (uint32_t)n_rows);
+  else
+    hipLaunchKernelGGL((prep_rows_kernel<T, 128, kNorm, kResidual>), grid, dim3(256), 0, st, a, (uint32_t)n_rows);
+  return hipGetLastError();
+}
+
+bool al16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+
+bool valid(const kvm_prep_params *p) {
+  if (!p || p->batch <= 0 || p->n_q_heads <= 0 || p->n_kv_heads <= 0) return false;
+  if (p->head_dim != 64 && p->head_dim != 128) return false;
+  if (p->io_dtype != KVM_F32 && p->io_dtype != KVM_BF16) return false;
+  const int vec = p->io_dtype == KVM_F32 ? 4 : 8;
+  const int r = p->rope_dims;
+  if (r < 0 || r > p->head_dim) return false;
+  if (r > 0) {
+    const int half = r / 2;
+    if (r % 2 || half % vec) return false;
+    const int hop = half / vec;
+    if (hop & (hop - 1)) return false;  // the rotation partner must be a power-of-two lane hop away
+  }
+  if (p->d_model < 0 || p->d_model % vec) return false;
+  return true;
+}
+
+}  // namespace
+}  // namespace kvm
+
+extern "C" size_t kvm_prepare_scratch_bytes(const kvm_prep_params *p, int64_t T) {
+  if (!kvm::valid(p) || T <= 0) return 0;
+  const size_t n = (size_t)T * (size_t)(p->rope_dims / 2) * sizeof(float2);
+  return n ? n : 16;
+}
+
+extern "C" int kvm_prepare_qkv(const kvm_prep_params *p, const void *q_raw, const void *k_raw,
+                               const void *v_raw, const void *v_first, const void *x, const void *prev_q,
+                               const void *prev_k, const void *prev_v, void *q_out, void *k_out,
+                               void *v_out, float *gate_out, void *scratch, int64_t T, int64_t pos0,
+                               void *stream_) {
+  using namespace kvm;
+  if (!valid(p) || T <= 0 || pos0 < 0) return KVM_ERR_ARG;
+  if (!q_raw || !k_raw || !v_raw || !q_out || !k_out || !v_out || !scratch) return KVM_ERR_ARG;
+  if (q_raw == q_out || k_raw == k_out || v_raw == v_out) return KVM_ERR_ARG;  // the shift reads token t - 1
+  const void *ptrs[] = {q_raw, k_raw, v_raw, v_first, x, prev_q, prev_k, prev_v, q_out, k_out, v_out, scratch};
+  for (const void *q : ptrs)
+    if (!al16(q)) return KVM_ERR_ARG;
+  const void *prm[] = {p->alpha_q, p->alpha_k, p->alpha_v, p->lambda_v, p->lnq_gamma, p->lnq_beta,
+                       p->lnk_gamma, p->lnk_beta, p->w_gate};
+  for (const void *q : prm)
+    if (!al16(q)) return KVM_ERR_ARG;
+  const bool gate = x != nullptr;
+  if (gate && (!p->w_gate || !gate_out || p->d_model <= 0)) return KVM_ERR_ARG;
+  hipStream_t st = (hipStream_t)stream_;
+  const int d = p->head_dim, r = p->rope_dims, half = r / 2;
+  const float eps = p->ln_eps > 0.f ? p->ln_eps : 1e-5f;
+  float2 *tab = (float2 *)scratch;
+  if (half > 0) {
+    const int64_t n = T * half;
+    hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, tab, T, pos0, half,
+                       p->rope_base > 0.0 ? p->rope_base : 10000.0);
+    if (hipGetLastError() != hipSuccess) return KVM_ERR_HIP;
+  }
+  auto rows = [&](const void *in, const void *first, const void *prev, void *out, const float *alpha,
+                  const float *lambda, const float *gamma, const float *beta, int H, int normalise) -> int {
+    RowArgs a;
+    a.in = in; a.first = first; a.prev = prev; a.out = out;
+    a.alpha = alpha; a.lambda = lambda; a.gamma = gamma; a.beta = beta;
+    a.tab = tab; a.T = T; a.H = H; a.r = r; a.normalise = normalise; a.eps = eps;
+    const int64_t n_rows = (int64_t)p->batch * T * H;
+    if (n_rows >= (1ll << 31)) return KVM_ERR_ARG;  // rows are indexed with 32 bits
+    hipError_t e;
+    if (p->io_dtype == KVM_F32)
+      e = normalise ? launch_rows<float, true, false>(a, d, n_rows, st) : launch_rows<float, false, true>(a, d, n_rows, st);
+    else
+      e = normalise ? launch_rows<bf16_t, true, false>(a, d, n_rows, st)
+                    : launch_rows<bf16_t, false, true>(a, d, n_rows, st);
+    return e == hipSuccess ? KVM_OK : KVM_ERR_HIP;
+  };
+  int rc = rows(q_raw, nullptr, prev_q, q_out, p->alpha_q, nullptr, p->lnq_gamma, p->lnq_beta, p->n_q_heads, 1);
+  if (rc != KVM_OK) return rc;
+  rc = rows(k_raw, nullptr, prev_k, k_out, p->alpha_k, nullptr, p->lnk_gamma, p->lnk_beta, p->n_kv_heads, 1);
+  if (rc != KVM_OK) return rc;
+  rc = rows(v_raw, v_first, prev_v, v_out, p->alpha_v, p->lambda_v, nullptr, nullptr, p->n_kv_heads, 0);
+  if (rc != KVM_OK) return rc;
+  if (gate) {
+    const int64_t n_tok = (int64_t)p->batch * T;
+    dim3 grid((unsigned)((n_tok + 4 * kGateTok - 1) / (4 * kGateTok)));
+    const bool full = p->n_kv_heads % 8 == 0;
+    const float *wg = p->w_gate;
+    const int dm = p->d_model, hk = p->n_kv_heads;
+    if (p->io_dtype == KVM_F32) {
+      if (full)
+        hipLaunchKernelGGL((gate_kernel<float, true>), grid, dim3(256), 0, st, (const float *)x, wg, gate_out, n_tok, dm, hk);
+      else
+        hipLaunchKernelGGL((gate_kernel<float, false>), grid, dim3(256), 0, st, (const float *)x, wg, gate_out, n_tok, dm, hk);
+    } else {
+      if (full)
+        hipLaunchKernelGGL((gate_kernel<bf16_t, true>), grid, dim3(256), 0, st, (const bf16_t *)x, wg, gate_out, n_tok, dm, hk);
+      else
+        hipLaunchKernelGGL((gate_kernel<bf16_t, false>), grid, dim3(256), 0, st, (const bf16_t *)x, wg, gate_out, n_tok, dm, hk);
+    }
+    if (hipGetLastError() != hipSuccess) return KVM_ERR_HIP;
+  }
+  return KVM_OK;
+}
