@@ -23,6 +23,15 @@ __device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {
   return (uint16_t)(u >> 16);
 }
 
+// Two floats to a pair of bf16 (round to nearest even) with the hardware conversion.
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  f32x2 f = {lo, hi};
+  bf16x2 h = __builtin_convertvector(f, bf16x2);
+  return __builtin_bit_cast(uint32_t, h);
+}
+
 template <typename T>
 struct Io;
 template <>
@@ -72,8 +81,7 @@ struct Vec16<bf16_t> {
   __device__ static __forceinline__ void store(bf16_t *p, const float (&f)[8]) {
     uint32_t wds[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      wds[i] = (uint32_t)float_to_bf16_bits(f[2 * i]) | ((uint32_t)float_to_bf16_bits(f[2 * i + 1]) << 16);
+    for (int i = 0; i < 4; ++i) wds[i] = pack_bf16(f[2 * i], f[2 * i + 1]);
     *reinterpret_cast<uint4 *>(p) = make_uint4(wds[0], wds[1], wds[2], wds[3]);
   }
 };

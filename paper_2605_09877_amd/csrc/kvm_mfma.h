@@ -12,12 +12,12 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "kvm_device.h"
+
 namespace kvm {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
-typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
 
 constexpr int kHeadDim = 128;
 constexpr int kTileKeys = 64;   // keys (or state rows) per LDS tile
@@ -30,12 +30,6 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 
 // row of D held in element v by lane half g
 __device__ __forceinline__ int mfma_row(int v, int g) { return 8 * (v >> 2) + 4 * g + (v & 3); }
-
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-  f32x2 f = {lo, hi};
-  bf16x2 h = __builtin_convertvector(f, bf16x2);
-  return __builtin_bit_cast(uint32_t, h);
-}
 
 // Exchange between lanes i and i + 32 on the vector ALU (v_permlane32_swap; no LDS round trip):
 // of the two results one is the lane's own value and the other its partner's, so a commutative
