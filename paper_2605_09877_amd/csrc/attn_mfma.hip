@@ -240,9 +240,16 @@ __device__ __forceinline__ void attn_body(const Dev &dv, const AttnArgs &a, uint
 #pragma unroll
       for (int v = 0; v < 16; ++v) smax = fmaxf(smax, sacc[blk][v]);
     smax = xhalf_max(smax);  // the other lane half holds the other 32 keys of the same query
+    // m_run is the reference point of the exponentials rather than the running maximum itself: it
+    // moves, and what is accumulated is rescaled, only when the maximum of some query of the wave
+    // has risen more than kSlack (log2 units) above it.  Until then p = 2^(s - m_run) may exceed
+    // 1, by at most 2^kSlack: harmless in fp32 and in bf16 (same relative precision at any
+    // magnitude), and the division by the sum, taken against the same reference, is unchanged.
+    // Some maximum among 32 queries creeps up in most tiles; a jump of this size is rare after
+    // the first.
+    constexpr float kSlack = 8.f;
     const float m_new = fmaxf(m_run, smax * scale);
-    if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
-      // some query of this wave has a new running maximum: rescale what is accumulated
+    if (__builtin_amdgcn_ballot_w64(m_new > m_run + kSlack) != 0) {
       const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
       m_run = m_new;
       l_part *= alpha;
@@ -255,15 +262,19 @@ __device__ __forceinline__ void attn_body(const Dev &dv, const AttnArgs &a, uint
     for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const float p = __builtin_amdgcn_exp2f(fmaf(sacc[blk][v], scale, -m_run));
-        l_part += p;
-        sacc[blk][v] = p;
+        sacc[blk][v] = __builtin_amdgcn_exp2f(fmaf(sacc[blk][v], scale, -m_run));
       }
+    // The row sum is taken over the probabilities as rounded to bf16 for the second product, two
+    // per instruction (v_dot2c_f32_bf16 with a pair of ones): numerator and denominator of the
+    // output then see the same rounded values.
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-      for (int e = 0; e < 4; ++e)
+      for (int e = 0; e < 4; ++e) {
         pb[ks].w[e] = pack_bf16(sacc[ks >> 1][(ks & 1) * 8 + 2 * e], sacc[ks >> 1][(ks & 1) * 8 + 2 * e + 1]);
+        l_part = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pb[ks].w[e]), ones, l_part, false);
+      }
   };
 
   // One barrier per tile: it publishes tile `it` (every wave has waited for its own share of the
