@@ -11,6 +11,8 @@
 //
 // Everything that decides an integer (LN_s of keys, the key sums) is computed in fp64 so that
 // the decision can be reproduced on a CPU; values and radii are fp32.
+#include <type_traits>
+
 #include "kvm_device.h"
 #include "kvm_internal.h"
 
@@ -31,7 +33,7 @@ struct PieceOf<16> { using type = uint4; };
 template <typename T, int D>
 __device__ __forceinline__ void write_readout(const Dev &dv, int slot, int u, int h, int row,
                                               const double (&sk)[D / 64], const float (&sv)[D / 64],
-                                              float rho, int lane) {
+                                              float rho, int lane, float *khat_copy = nullptr) {
   constexpr int CPL = D / 64;
   double s = 0.0;
 #pragma unroll
@@ -61,6 +63,7 @@ __device__ __forceinline__ void write_readout(const Dev &dv, int slot, int u, in
     const double y = (sk[c] - mean) * rden * ga + be;
     Io<T>::store(kh + ch, Io<T>::round_from(y));
     Io<T>::store(vh + ch, sv[c] * vs);
+    if (khat_copy) khat_copy[ch] = Io<T>::round_from(y);  // the stored value, for a reader in the same workgroup
   }
 }
 
@@ -207,6 +210,169 @@ __global__ __launch_bounds__(256) void select_kernel(Dev dv, int m, int n_app, i
       dv.score[base + j].y = __uint_as_float(0x7fc00000u);
     } else {
       dv.app[base + j] = -1;
+    }
+  }
+}
+
+// ------------------------------------------------------------------ a small append in one launch
+// A fold that appends only a few rows (n_app <= kAppendMax) does its selection, the creation of
+// the new rows and the second scoring pass (the block's other tokens against the new rows) here,
+// one workgroup per unit, instead of in three dependent launches: each of those is a few
+// microseconds of work behind ten of latency, and a growing state appends at almost every fold.
+//   1. selection as in select_kernel;
+//   2. a wave per new row: sums, radius, readout into slot_new (as accum_kernel's creation);
+//   3. a lane per remaining token: its dot products with the new rows' normalised keys (staged
+//      in LDS), summed in fp64 over the I/O-dtype operands; a strictly larger score moves the
+//      token to the new row, the lowest row winning ties, compared in the stored fp32 precision
+//      as in score_kernel's second pass.
+constexpr int kAppendMax = 16;
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void append_kernel(Dev dv, Src src, int m, int n_app, int slot_new) {
+  // C sort keys (8 bytes each), kAppendMax creators, 4 wave counts, n_app x D new keys
+  extern __shared__ __attribute__((aligned(16))) unsigned long long sh64[];
+  const int C = dv.C;
+  unsigned long long *key = sh64;
+  int *cr = (int *)(sh64 + C);
+  int *wcnt = cr + kAppendMax;
+  float *kn = (float *)(wcnt + 4);
+  const int u = blockIdx.x, b = u / dv.Hkv, h = u % dv.Hkv;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t base = (int64_t)u * C;
+  const T *vsrc = (const T *)src.v + b * src.v_b + h * src.v_h;
+  const T *kbar = (const T *)dv.kbar + base * D;
+  constexpr int VEC = Vec16<T>::kN, NCH = D / VEC;
+
+  // The (score, position) order as one unsigned 64-bit order: the float's bits made monotonic
+  // (sign flipped for positives, all bits for negatives) above the token index.
+  for (int j = threadIdx.x; j < C; j += blockDim.x) {
+    uint32_t f = __float_as_uint(dv.score[base + j].x);
+    f = f == 0x80000000u ? 0u : f;  // -0 and +0 are one score
+    const uint32_t mono = (f & 0x80000000u) ? ~f : (f | 0x80000000u);
+    key[j] = ((unsigned long long)mono << 32) | (uint32_t)j;
+  }
+  __syncthreads();
+  {  // a thread per token: the host sends only blocks of at most 256 tokens here
+    const int j = threadIdx.x;
+    const bool on = j < C;
+    // the second pass's operand: the token's whole memory key, asked for before anything else
+    // waits (the rows of 64 tokens are 64 separate cache lines per load)
+    uint4 raw[NCH];
+    if (on) {
+#pragma unroll
+      for (int q = 0; q < NCH; ++q) raw[q] = *reinterpret_cast<const uint4 *>(kbar + (int64_t)j * D + q * VEC);
+    }
+    // rank of a token = how many precede it; the n_app first are taken
+    bool take = false;
+    if (on) {
+      const unsigned long long kj = key[j];
+      int rank = 0;
+      for (int t = 0; t < C; t += 2) {
+        const ulonglong2 k2 = *reinterpret_cast<const ulonglong2 *>(key + t);
+        rank += k2.x < kj ? 1 : 0;
+        rank += k2.y < kj ? 1 : 0;
+      }
+      take = rank < n_app;
+    }
+    // position of a taken token among the taken ones, in token order: ballot within the wave,
+    // wave counts through LDS
+    const uint64_t bal = __builtin_amdgcn_ballot_w64(take);
+    if (lane == 0) wcnt[wave] = __builtin_popcountll(bal);
+    __syncthreads();
+    int a = __builtin_popcountll(bal & ((1ull << lane) - 1ull));
+    for (int w = 0; w < wave; ++w) a += wcnt[w];
+    if (on) {
+      if (take) {
+        dv.app[base + j] = a;
+        dv.pi[base + j] = m + a;
+        dv.creator[base + a] = j;
+        cr[a] = j;
+        dv.score[base + j].y = __uint_as_float(0x7fc00000u);
+      } else {
+        dv.app[base + j] = -1;
+      }
+    }
+    __syncthreads();
+
+    // creation: a wave per new row, two rows of a wave in flight together
+    constexpr int CPL = D / 64;
+    for (int a0 = wave; a0 < n_app; a0 += 8) {
+      double sk[2][CPL];
+      float sv[2][CPL];
+      float nn[2] = {0.f, 0.f};
+      const bool two = a0 + 4 < n_app;
+#pragma unroll
+      for (int r = 0; r < 2; ++r) {
+        if (r == 1 && !two) break;
+        const int j0c = cr[a0 + 4 * r];
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) {
+          const int ch = lane * CPL + c;
+          sk[r][c] = (double)Io<T>::load(kbar + (int64_t)j0c * D + ch);
+          sv[r][c] = Io<T>::load(vsrc + (int64_t)j0c * src.v_t + ch);
+          nn[r] += sv[r][c] * sv[r][c];
+        }
+      }
+#pragma unroll
+      for (int r = 0; r < 2; ++r) {
+        if (r == 1 && !two) break;
+        const int an = a0 + 4 * r, row = m + an;
+        const int64_t ro = (int64_t)u * dv.Mcap + row;
+        const float rho = sqrtf(wave_sum(nn[r]));
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) {
+          dv.sK[ro * D + lane * CPL + c] = sk[r][c];
+          dv.sV[ro * D + lane * CPL + c] = sv[r][c];
+        }
+        if (lane == 0) {
+          dv.rho[ro] = rho;
+          dv.w[ro] = 1.f;
+          dv.n[ro] = 1;
+        }
+        write_readout<T, D>(dv, slot_new, u, h, row, sk[r], sv[r], rho, lane, kn + an * D);
+      }
+    }
+    __syncthreads();  // the new rows' normalised keys are in LDS
+
+    // second pass: this lane's token against the new rows, eight at a time.  bf16 operands: the
+    // products are exact in fp32 and so is most of the sum; fp32 operands take the fp64 sum the
+    // generic scoring kernel takes.
+    using Acc = typename std::conditional<std::is_same<T, float>::value, double, float>::type;
+    if (on && !take) {
+      Acc best = -INFINITY;
+      int best_a = 0;
+      for (int a0 = 0; a0 < n_app; a0 += 8) {
+        Acc acc[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) acc[q] = (Acc)0;
+#pragma unroll
+        for (int q = 0; q < NCH; ++q) {
+          float x[VEC];
+          unpack16<T>(raw[q], x);
+#pragma unroll
+          for (int an = 0; an < 8; ++an)
+            if (a0 + an < n_app) {
+#pragma unroll
+              for (int e = 0; e < VEC; e += 4) {
+                const float4 k4 = *reinterpret_cast<const float4 *>(kn + (a0 + an) * D + q * VEC + e);
+                acc[an] += (Acc)x[e] * (Acc)k4.x;
+                acc[an] += (Acc)x[e + 1] * (Acc)k4.y;
+                acc[an] += (Acc)x[e + 2] * (Acc)k4.z;
+                acc[an] += (Acc)x[e + 3] * (Acc)k4.w;
+              }
+            }
+        }
+#pragma unroll
+        for (int an = 0; an < 8; ++an)
+          if (a0 + an < n_app && acc[an] > best) {
+            best = acc[an];
+            best_a = a0 + an;
+          }
+      }
+      if (m + best_a >= dv.S && (float)best > dv.score[base + j].y) {
+        dv.score[base + j].y = (float)best;
+        dv.pi[base + j] = m + best_a;
+      }
     }
   }
 }
@@ -515,6 +681,16 @@ hipError_t launch_score(const Dev &dv, int slot, int row0, int row1, bool first_
 hipError_t launch_select(const Dev &dv, int m, int n_app, bool take_all, hipStream_t st) {
   hipLaunchKernelGGL(select_kernel, dim3(dv.U), dim3(256), (size_t)dv.C * 8, st, dv, m, n_app,
                      take_all ? 1 : 0);
+  return hipGetLastError();
+}
+
+bool append_fits(const Dev &dv, int n_app) {
+  return n_app > 0 && n_app <= kAppendMax && dv.C % 2 == 0 && dv.C <= 256;
+}
+
+hipError_t launch_append(const Dev &dv, const Src &src, int m, int n_app, int slot_new, hipStream_t st) {
+  const size_t lds = (size_t)dv.C * 8 + (kAppendMax + 4) * 4 + (size_t)n_app * dv.d * 4;
+  KVM_DISPATCH(dv, append_kernel, dim3(dv.U), dim3(256), lds, st, dv, src, m, n_app, slot_new);
   return hipGetLastError();
 }
 

@@ -271,7 +271,9 @@ int fold_block(kvm_state *st, const Src &src, int64_t e, int32_t *assign_out, fl
       HIP_TRY(kvm::launch_score_mfma(dv, so, 0, (int)m, true, stream));
     else
       HIP_TRY(kvm::launch_score(dv, so, 0, (int)m, true, stream));
-    if (n_app > 0) {
+    if (kvm::append_fits(dv, n_app)) {
+      HIP_TRY(kvm::launch_append(dv, src, (int)m, n_app, sn, stream));
+    } else if (n_app > 0) {
       // new rows first, so that the remaining tokens can be scored against them too
       HIP_TRY(kvm::launch_select(dv, (int)m, n_app, false, stream));
       HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, (int)m, true, false, false, false, so, sn, stream));

@@ -86,6 +86,23 @@ struct Vec16<bf16_t> {
   }
 };
 
+// The floats of 16 bytes already in registers (4 fp32 or 8 bf16).
+template <typename T>
+__device__ __forceinline__ void unpack16(const uint4 &x, float (&f)[Vec16<T>::kN]);
+template <>
+__device__ __forceinline__ void unpack16<float>(const uint4 &x, float (&f)[4]) {
+  f[0] = __uint_as_float(x.x); f[1] = __uint_as_float(x.y); f[2] = __uint_as_float(x.z); f[3] = __uint_as_float(x.w);
+}
+template <>
+__device__ __forceinline__ void unpack16<bf16_t>(const uint4 &x, float (&f)[8]) {
+  const uint32_t wds[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    f[2 * i] = __uint_as_float(wds[i] << 16);
+    f[2 * i + 1] = __uint_as_float(wds[i] & 0xffff0000u);
+  }
+}
+
 // All-reduce sums on the vector ALU, without the LDS crossbar: four DPP steps inside a row of 16
 // lanes (partners lane^1, lane^2, then the mirror images within 8 and within 16 lanes, which pair
 // up the partial sums just as well), then the row exchanges v_permlane16_swap and

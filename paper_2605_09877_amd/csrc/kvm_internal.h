@@ -75,6 +75,9 @@ hipError_t launch_select(const Dev &dv, int m, int n_app, bool take_all, hipStre
 hipError_t launch_accum(const Dev &dv, const Src &src, int m_before, int m_after, int row_begin,
                         bool do_create, bool do_merge, bool do_copy, bool check_app, int slot_old,
                         int slot_new, hipStream_t st);
+// selection + creation + second scoring pass of a small append, one launch
+bool append_fits(const Dev &dv, int n_app);
+hipError_t launch_append(const Dev &dv, const Src &src, int m, int n_app, int slot_new, hipStream_t st);
 hipError_t launch_merge_inplace(const Dev &dv, const Src &src, bool check_app, int slot, hipStream_t st);
 hipError_t launch_refresh(const Dev &dv, int m, int slot, hipStream_t st);
 hipError_t launch_ring_copy(const Dev &dv, const Src &src, int64_t src_t0, int64_t p0, int64_t p1,

@@ -210,7 +210,11 @@ def test_bf16_head_dim_64_generic_kernels():
 # ----------------------------------------------------------------------------- fold alone
 @pytest.mark.parametrize("io,d,C,m0,budget", [("f32", 64, 64, 64, 80), ("bf16", 128, 256, 300, 340),
                                                ("bf16", 128, 128, 128, 128), ("bf16", 64, 64, 100, 130),
-                                               ("bf16", 128, 1024, 700, 900), ("f32", 128, 576, 200, 200)])
+                                               ("bf16", 128, 1024, 700, 900), ("f32", 128, 576, 200, 200),
+                                               # a few new rows: selection, creation and the second
+                                               # scoring pass run in one launch
+                                               ("bf16", 128, 256, 300, 310), ("bf16", 64, 64, 100, 112),
+                                               ("f32", 128, 128, 200, 207), ("bf16", 128, 250, 300, 301)])
 def test_state_fold_entry_point(io, d, C, m0, budget):
     """kvm_state_fold on an imported state: partial append + re-score + merge in one call."""
     pkg, sy = kvm(), synth()
