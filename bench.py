@@ -162,14 +162,44 @@ def decode_leg(args, pkg, synth, dev):
     bytes_per_step = w.batch * w.n_q_heads * ((m + mean_w) * d * 2 * 2 + 2 * d * 2)
     avg_s = dec_ms / max(dec_n, 1) * 1e-3
     gbs = bytes_per_step / avg_s / 1e9 if dec_n else 0.0
+    ragged = ragged_decode(pkg, synth, dev, w, pre, qs, ks, vs, out, steps=200)
     return dict(us_per_token=dt / steps / w.batch * 1e6, us_per_step=dt / steps * 1e6, steps=steps,
-                folds=fold_n, fold_us=fold_ms / max(fold_n, 1) * 1e3,
+                folds=fold_n, fold_us=fold_ms / max(fold_n, 1) * 1e3, ragged=ragged,
                 config=dict(workload="decode", batch=w.batch, heads=w.n_q_heads, head_dim=d, state_rows=m,
                             window=L, chunk_len=C),
                 roofline=dict(bound="hbm", kernel="attn_rows_kernel", achieved=gbs, peak=HBM_PEAK_GBS,
                               unit="GB/s", frac=gbs / HBM_PEAK_GBS,
                               traffic=measured_traffic("attn_rows_kernel_decode_hbm_traffic.txt"),
                               avg_launch_us=avg_s * 1e6, bytes_per_launch=bytes_per_step))
+
+
+def ragged_decode(pkg, synth, dev, w, pre, qs, ks, vs, out, steps):
+    """The same decode workload as a ragged batch: one single-sequence state per sequence, each
+    standing at its own position (so their windows differ in length and they fold at different
+    steps), all advanced by one kvm_decode_step_multi launch per step."""
+    import torch
+    states = []
+    per_seq = ("sK", "sV", "rho", "w", "n", "win_k", "win_v", "win_g")
+    for b in range(w.batch):
+        wb = synth.shrink(w, batch=1)
+        stagger = (b * 37) % w.chunk_len
+        st = pkg.state_for(wb, device=dev, max_tokens=pre["tokens"] + stagger + 2 * steps + w.chunk_len)
+        one = {k: (pre[k][b:b + 1].contiguous() if k in per_seq else pre[k]) for k in pre}
+        one["tokens"] = pre["tokens"] + stagger
+        st.import_(one)
+        states.append(st)
+    n_in = len(qs)
+    for t in range(10):
+        pkg.binding.decode_multi(states, qs[t % n_in], ks[t % n_in], vs[t % n_in], out=out)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(steps):
+        pkg.binding.decode_multi(states, qs[t % n_in], ks[t % n_in], vs[t % n_in], out=out)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    folds = sum(st.folds for st in states)
+    return dict(us_per_token=dt / steps / w.batch * 1e6, us_per_step=dt / steps * 1e6, steps=steps,
+                states=len(states), folds=folds)
 
 
 def prep_leg(args, pkg, synth, dev):

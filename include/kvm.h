@@ -126,6 +126,24 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
 int kvm_decode_step(kvm_state *st, const void *q, const void *k, const void *v,
                     const float *gate, void *out, void *stream);
 
+/* One decode step over a ragged batch: the sequences of n_states states, each state at its own
+ * position and with its own number of state rows (the "growth" budget makes rows a function of
+ * the tokens seen; requests that joined at different times stand at different positions), in one
+ * attention launch.  Per state the effect is that of kvm_decode_step; a state whose token
+ * completes a chunk folds afterwards (its own launches).  All states must share one configuration
+ * apart from batch and capacity (heads, head_dim, dtype, chunk, window, sinks, LN_s parameters,
+ * temperatures: the first state's are used).
+ *   q, out: [sum of batches, H_q, d]; k, v: [sum, H_kv, d]; gate: [sum, H_kv] or NULL; rows in
+ *   the order of `states`, each state's sequences together.
+ *   workspace: device memory, 16-byte aligned, kvm_decode_multi_workspace_bytes(sum of batches)
+ *   bytes, owned by the caller; rewritten by every call (stream-ordered).
+ * KVM_ERR_CAPACITY (nothing enqueued) if any state's fold would exceed its buffer; KVM_ERR_ARG on
+ * mismatched configurations. */
+size_t kvm_decode_multi_workspace_bytes(int64_t n_sequences);
+int kvm_decode_step_multi(kvm_state *const *states, int32_t n_states, const void *q, const void *k,
+                          const void *v, const float *gate, void *out, void *workspace,
+                          size_t workspace_bytes, void *stream);
+
 /* Fold one overflow block into the state ("Append" and "Merge"): memory keys, similarity to
  * the normalised state, append of the n_append least similar tokens, winner-take-all merge of
  * the rest into rows >= S of the updated state, refresh of the normalised readout rows.

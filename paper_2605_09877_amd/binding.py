@@ -20,7 +20,8 @@ KVM_OK, KVM_ERR_ARG, KVM_ERR_CAPACITY, KVM_ERR_STATE, KVM_ERR_HIP, KVM_ERR_UNSUP
 
 EXPORTS = [
     "kvm_strerror", "kvm_last_hip_error", "kvm_state_rows_for", "kvm_state_bytes", "kvm_state_init",
-    "kvm_state_destroy", "kvm_prefill_chunked", "kvm_decode_step", "kvm_state_fold", "kvm_state_rows",
+    "kvm_state_destroy", "kvm_prefill_chunked", "kvm_decode_step", "kvm_decode_multi_workspace_bytes",
+    "kvm_decode_step_multi", "kvm_state_fold", "kvm_state_rows",
     "kvm_state_tokens", "kvm_state_capacity", "kvm_state_folds", "kvm_state_trace", "kvm_state_grow",
     "kvm_state_export", "kvm_state_import", "kvm_state_profile", "kvm_state_profile_read",
     "kvm_measure_mfma_bf16_peak", "kvm_measure_copy_peak", "kvm_prepare_scratch_bytes", "kvm_prepare_qkv",
@@ -86,6 +87,9 @@ def load_library() -> C.CDLL:
     lib.kvm_state_destroy.argtypes = [vp]
     lib.kvm_prefill_chunked.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, C.POINTER(kvm_strides), vp]
     lib.kvm_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+    lib.kvm_decode_multi_workspace_bytes.restype = C.c_size_t
+    lib.kvm_decode_multi_workspace_bytes.argtypes = [i64]
+    lib.kvm_decode_step_multi.argtypes = [C.POINTER(vp), i32, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
     lib.kvm_state_fold.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp, vp]
     for name in ("kvm_state_rows", "kvm_state_tokens", "kvm_state_capacity", "kvm_state_folds"):
         getattr(lib, name).argtypes = [vp, C.POINTER(i64)]
@@ -395,3 +399,34 @@ class KVMState:
         with torch.cuda.device(self.device):
             _check(self.lib.kvm_state_import(self.handle, *ptrs, m, int(o["tokens"]), int(o.get("folds", 0)),
                                              _stream()), "kvm_state_import")
+
+
+_multi_workspace: dict = {}
+
+
+def decode_multi(states, q, k, v, gate=None, out=None):
+    """kvm_decode_step_multi: one token for every sequence of every state in `states` (each state at
+    its own position and state size).  q [N,Hq,d], k/v [N,Hkv,d], gate [N,Hkv] fp32 or None, with
+    N = sum of the states' batches, rows in the order of `states`."""
+    first = states[0]
+    c = first.cfg
+    n = sum(st.cfg.batch for st in states)
+    first._chk(q, (n, c.n_q_heads, c.head_dim), first.dtype, "q")
+    first._chk(k, (n, c.n_kv_heads, c.head_dim), first.dtype, "k")
+    first._chk(v, (n, c.n_kv_heads, c.head_dim), first.dtype, "v")
+    if gate is not None:
+        first._chk(gate, (n, c.n_kv_heads), torch.float32, "gate")
+    if out is None:
+        out = torch.empty_like(q)
+    first._chk(out, q.shape, first.dtype, "out")
+    nbytes = first.lib.kvm_decode_multi_workspace_bytes(n)
+    ws = _multi_workspace.get((str(first.device), nbytes))
+    if ws is None:
+        ws = _multi_workspace[(str(first.device), nbytes)] = torch.empty(nbytes, dtype=torch.uint8, device=first.device)
+    handles = (C.c_void_p * len(states))(*[st.handle for st in states])
+    with torch.cuda.device(first.device):
+        _check(first.lib.kvm_decode_step_multi(handles, len(states), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                                               _ptr(gate), out.data_ptr(), ws.data_ptr(), nbytes, _stream()),
+               "kvm_decode_step_multi")
+    return out
+

@@ -16,36 +16,39 @@ namespace {
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
+// What one query needs, gathered by the two kernels below.
+template <typename T>
+struct RowQuery {
+  const T *q, *khat, *vhat, *ring_k, *ring_v, *in_k, *in_v;  // this query's row, this unit's arrays
+  T *out;
+  float *lse;        // this query's slot, or null
+  int64_t pos, t0;   // query position; window positions below t0 come from the ring
+  int64_t in_kt, in_vt;
+  int m, hq;
+};
+
 template <typename T, int D>
-__global__ __launch_bounds__(256) void attn_rows_kernel(Dev dv, AttnArgs a) {
+__device__ __forceinline__ void attn_row(const Dev &dv, const RowQuery<T> &rq) {
   constexpr int VEC = Vec16<T>::kN;
   constexpr int LPR = D / VEC;   // lanes per key row
   constexpr int RPW = 64 / LPR;  // key rows per wave step
   constexpr int KB = 4;          // rows in flight per lane group
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int sub = lane / LPR, cl = lane % LPR;
-  const int qi = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
-  const int hkv = hq / (dv.Hq / dv.Hkv);
-  const int u = b * dv.Hkv + hkv;
-  const int64_t pos = a.s + qi;
-  const int ci = (int)(pos / dv.C - a.s / dv.C);            // chunk of this query within the launch
+  const int64_t pos = rq.pos;
   const int64_t cs = pos / dv.C * dv.C;                      // its chunk starts here
   const int64_t wb = cs + dv.C - dv.L > 0 ? cs + dv.C - dv.L : 0;  // first window position
 
   float qf[VEC];
-  Vec16<T>::load((const T *)a.q + b * a.q_b + (int64_t)qi * a.q_t + hq * a.q_h + cl * VEC, qf);
+  Vec16<T>::load(rq.q + cl * VEC, qf);
   const float rs = kLog2e * rsqrtf((float)D);
-  const float c_state = (dv.tau_state ? dv.tau_state[hq] : 1.f) * rs;
-  const float c_bswa = (dv.tau_bswa ? dv.tau_bswa[hq] : 1.f) * rs;
+  const float c_state = (dv.tau_state ? dv.tau_state[rq.hq] : 1.f) * rs;
+  const float c_bswa = (dv.tau_bswa ? dv.tau_bswa[rq.hq] : 1.f) * rs;
 
-  const int m = a.m[ci];
+  const int m = rq.m;
   const int total = m + (int)(pos - wb + 1);
-  const T *khat = (const T *)dv.khat + a.slot[ci] * dv.slot_elems + (int64_t)u * dv.Mcap * D;
-  const T *vhat = (const T *)dv.vhat + a.slot[ci] * dv.slot_elems + (int64_t)u * dv.Mcap * D;
-  const T *ring_k = (const T *)dv.winK + (int64_t)u * dv.L * D;
-  const T *ring_v = (const T *)dv.winV + (int64_t)u * dv.L * D;
-  const T *in_k = (const T *)a.in.k + b * a.in.k_b + hkv * a.in.k_h;
-  const T *in_v = (const T *)a.in.v + b * a.in.v_b + hkv * a.in.v_h;
+  const T *khat = rq.khat, *vhat = rq.vhat, *ring_k = rq.ring_k, *ring_v = rq.ring_v;
+  const T *in_k = rq.in_k, *in_v = rq.in_v;
 
   float m_run = -INFINITY, l_run = 0.f;
   float acc[VEC];
@@ -64,9 +67,9 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(Dev dv, AttnArgs a) {
         vp = vhat + (int64_t)nc * D;
       } else {
         const int64_t p = wb + (nc - m);
-        if (p >= a.t0) {
-          kp = in_k + (p - a.t0) * a.in.k_t;
-          vp = in_v + (p - a.t0) * a.in.v_t;
+        if (p >= rq.t0) {
+          kp = in_k + (p - rq.t0) * rq.in_kt;
+          vp = in_v + (p - rq.t0) * rq.in_vt;
         } else {
           const int slot = (int)(p % dv.L);
           kp = ring_k + (int64_t)slot * D;
@@ -144,10 +147,78 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(Dev dv, AttnArgs a) {
     const float inv = 1.f / l;
 #pragma unroll
     for (int i = 0; i < VEC; ++i) o[i] *= inv;
-    Vec16<T>::store((T *)a.out + b * a.o_b + (int64_t)qi * a.o_t + hq * a.o_h + cl * VEC, o);
-    if (a.lse && cl == 0)
-      a.lse[b * a.lse_b + (int64_t)qi * a.lse_t + hq * a.lse_h] = (mm + log2f(l)) * kLn2;
+    Vec16<T>::store(rq.out + cl * VEC, o);
+    if (rq.lse && cl == 0) *rq.lse = (mm + log2f(l)) * kLn2;
   }
+}
+
+// One workgroup per (query, query head, sequence) of one state.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void attn_rows_kernel(Dev dv, AttnArgs a) {
+  const int qi = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
+  const int hkv = hq / (dv.Hq / dv.Hkv);
+  const int u = b * dv.Hkv + hkv;
+  RowQuery<T> rq;
+  rq.pos = a.s + qi;
+  const int ci = (int)(rq.pos / dv.C - a.s / dv.C);  // chunk of this query within the launch
+  rq.q = (const T *)a.q + b * a.q_b + (int64_t)qi * a.q_t + hq * a.q_h;
+  rq.out = (T *)a.out + b * a.o_b + (int64_t)qi * a.o_t + hq * a.o_h;
+  rq.lse = a.lse ? a.lse + b * a.lse_b + (int64_t)qi * a.lse_t + hq * a.lse_h : nullptr;
+  rq.m = a.m[ci];
+  rq.hq = hq;
+  rq.khat = (const T *)dv.khat + a.slot[ci] * dv.slot_elems + (int64_t)u * dv.Mcap * D;
+  rq.vhat = (const T *)dv.vhat + a.slot[ci] * dv.slot_elems + (int64_t)u * dv.Mcap * D;
+  rq.ring_k = (const T *)dv.winK + (int64_t)u * dv.L * D;
+  rq.ring_v = (const T *)dv.winV + (int64_t)u * dv.L * D;
+  rq.in_k = (const T *)a.in.k + b * a.in.k_b + hkv * a.in.k_h;
+  rq.in_v = (const T *)a.in.v + b * a.in.v_b + hkv * a.in.v_h;
+  rq.in_kt = a.in.k_t;
+  rq.in_vt = a.in.v_t;
+  rq.t0 = a.t0;
+  attn_row<T, D>(dv, rq);
+}
+
+// Decode over sequences that live in different states (each at its own position, with its own
+// number of state rows): one workgroup per (query head, sequence); sequence s reads seq[s].  dv is
+// the states' common configuration (heads, chunk, window, temperatures); every window token comes
+// from the sequence's ring, which already holds the new token.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void attn_rows_multi_kernel(Dev dv, const SeqDesc *seq, const void *q,
+                                                              void *out) {
+  const int hq = blockIdx.x, s = blockIdx.y;
+  const int hkv = hq / (dv.Hq / dv.Hkv);
+  const SeqDesc sd = seq[s];
+  RowQuery<T> rq;
+  rq.pos = sd.pos;
+  rq.q = (const T *)q + ((int64_t)s * dv.Hq + hq) * D;
+  rq.out = (T *)out + ((int64_t)s * dv.Hq + hq) * D;
+  rq.lse = nullptr;
+  rq.m = sd.m;
+  rq.hq = hq;
+  rq.khat = (const T *)sd.khat + (int64_t)hkv * sd.Mcap * D;
+  rq.vhat = (const T *)sd.vhat + (int64_t)hkv * sd.Mcap * D;
+  rq.ring_k = (const T *)sd.winK + (int64_t)hkv * dv.L * D;
+  rq.ring_v = (const T *)sd.winV + (int64_t)hkv * dv.L * D;
+  rq.in_k = rq.in_v = nullptr;
+  rq.in_kt = rq.in_vt = 0;
+  rq.t0 = INT64_MAX / 2;
+  attn_row<T, D>(dv, rq);
+}
+
+// The new token of every sequence into its ring slot (position pos of that sequence).
+template <typename T>
+__global__ __launch_bounds__(64) void ring_put_multi_kernel(Dev dv, const SeqDesc *seq, const void *k,
+                                                            const void *v, const float *gate) {
+  const int hkv = blockIdx.x, s = blockIdx.y;
+  const SeqDesc sd = seq[s];
+  const int slot = (int)(sd.pos % dv.L);
+  const int64_t src = ((int64_t)s * dv.Hkv + hkv) * dv.d;
+  const int64_t dst = ((int64_t)hkv * dv.L + slot) * dv.d;
+  for (int c = threadIdx.x; c < dv.d; c += 64) {
+    ((T *)sd.winK)[dst + c] = ((const T *)k)[src + c];
+    ((T *)sd.winV)[dst + c] = ((const T *)v)[src + c];
+  }
+  if (threadIdx.x == 0) sd.winG[(int64_t)hkv * dv.L + slot] = gate ? gate[(int64_t)s * dv.Hkv + hkv] : 1.f;
 }
 
 }  // namespace
@@ -163,6 +234,27 @@ hipError_t launch_attn_rows(const Dev &dv, const AttnArgs &a, hipStream_t st) {
     hipLaunchKernelGGL((attn_rows_kernel<bf16_t, 64>), grid, dim3(256), 0, st, dv, a);
   else if (dv.io == 1 && dv.d == 128)
     hipLaunchKernelGGL((attn_rows_kernel<bf16_t, 128>), grid, dim3(256), 0, st, dv, a);
+  else
+    return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+hipError_t launch_decode_multi(const Dev &dv, const SeqDesc *seq, int n_seq, const void *q, const void *k,
+                               const void *v, const float *gate, void *out, hipStream_t st) {
+  if (n_seq <= 0) return hipSuccess;
+  dim3 pgrid(dv.Hkv, n_seq), agrid(dv.Hq, n_seq);
+  if (dv.io == 0)
+    hipLaunchKernelGGL(ring_put_multi_kernel<float>, pgrid, dim3(64), 0, st, dv, seq, k, v, gate);
+  else
+    hipLaunchKernelGGL(ring_put_multi_kernel<bf16_t>, pgrid, dim3(64), 0, st, dv, seq, k, v, gate);
+  if (dv.io == 0 && dv.d == 64)
+    hipLaunchKernelGGL((attn_rows_multi_kernel<float, 64>), agrid, dim3(256), 0, st, dv, seq, q, out);
+  else if (dv.io == 0 && dv.d == 128)
+    hipLaunchKernelGGL((attn_rows_multi_kernel<float, 128>), agrid, dim3(256), 0, st, dv, seq, q, out);
+  else if (dv.io == 1 && dv.d == 64)
+    hipLaunchKernelGGL((attn_rows_multi_kernel<bf16_t, 64>), agrid, dim3(256), 0, st, dv, seq, q, out);
+  else if (dv.io == 1 && dv.d == 128)
+    hipLaunchKernelGGL((attn_rows_multi_kernel<bf16_t, 128>), agrid, dim3(256), 0, st, dv, seq, q, out);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();

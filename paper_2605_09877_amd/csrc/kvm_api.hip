@@ -660,6 +660,85 @@ int kvm_decode_step(kvm_state *st, const void *q, const void *k, const void *v,
   return KVM_OK;
 }
 
+size_t kvm_decode_multi_workspace_bytes(int64_t n_sequences) {
+  return n_sequences > 0 ? (size_t)n_sequences * sizeof(kvm::SeqDesc) : 0;
+}
+
+int kvm_decode_step_multi(kvm_state *const *states, int32_t n_states, const void *q, const void *k,
+                          const void *v, const float *gate, void *out, void *workspace,
+                          size_t workspace_bytes, void *stream_) {
+  if (!states || n_states <= 0 || !q || !k || !v || !out || !workspace) return KVM_ERR_ARG;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(workspace))
+    return KVM_ERR_ARG;
+  hipStream_t stream = (hipStream_t)stream_;
+  const kvm_state *first = states[0];
+  if (!first) return KVM_ERR_ARG;
+  const kvm_config &c0 = first->cfg;
+  int64_t n_seq = 0;
+  for (int i = 0; i < n_states; ++i) {
+    const kvm_state *st = states[i];
+    if (!st) return KVM_ERR_ARG;
+    for (int j = 0; j < i; ++j)
+      if (states[j] == st) return KVM_ERR_ARG;  // a state takes one token per step
+    const kvm_config &c = st->cfg;
+    if (c.n_q_heads != c0.n_q_heads || c.n_kv_heads != c0.n_kv_heads || c.head_dim != c0.head_dim ||
+        c.io_dtype != c0.io_dtype || c.chunk_len != c0.chunk_len || c.n_bswa_chunks != c0.n_bswa_chunks ||
+        c.n_sink != c0.n_sink || c.rope_dims != c0.rope_dims || c.tau_state != c0.tau_state ||
+        c.tau_bswa != c0.tau_bswa)
+      return KVM_ERR_ARG;
+    n_seq += st->dv.B;
+  }
+  if (workspace_bytes < kvm_decode_multi_workspace_bytes(n_seq)) return KVM_ERR_ARG;
+  const int64_t C = first->dv.C, L = first->dv.L, d = first->dv.d;
+  const size_t es = esize(c0.io_dtype);
+  // capacity of every fold this step triggers, before anything is enqueued
+  for (int i = 0; i < n_states; ++i) {
+    const kvm_state *st = states[i];
+    const int64_t u = st->tokens;
+    if ((u + 1) % C == 0 && u + 1 >= L && rows_after(st->cfg, st->table, st->m, u + 1) > st->dv.Mcap)
+      return KVM_ERR_CAPACITY;
+  }
+  std::vector<kvm::SeqDesc> desc((size_t)n_seq);
+  size_t s = 0;
+  for (int i = 0; i < n_states; ++i) {
+    const kvm_state *st = states[i];
+    const Dev &dv = st->dv;
+    const int64_t slot = slot_of(st, st->folds);
+    for (int b = 0; b < dv.B; ++b, ++s) {
+      const int64_t u0 = (int64_t)b * dv.Hkv;
+      kvm::SeqDesc &sd = desc[s];
+      sd.khat = (const char *)dv.khat + (slot * dv.slot_elems + u0 * dv.Mcap * d) * es;
+      sd.vhat = (const char *)dv.vhat + (slot * dv.slot_elems + u0 * dv.Mcap * d) * es;
+      sd.winK = (char *)dv.winK + u0 * L * d * es;
+      sd.winV = (char *)dv.winV + u0 * L * d * es;
+      sd.winG = dv.winG + u0 * L;
+      sd.pos = st->tokens;
+      sd.m = (int32_t)st->m;
+      sd.Mcap = dv.Mcap;
+    }
+  }
+  // pageable source: the copy is staged before the call returns, and ordered on the stream
+  HIP_TRY(hipMemcpyAsync(workspace, desc.data(), desc.size() * sizeof(kvm::SeqDesc), hipMemcpyHostToDevice,
+                         stream));
+  {
+    ProfileSpan span(states[0], 2, stream);
+    HIP_TRY(kvm::launch_decode_multi(first->dv, (const kvm::SeqDesc *)workspace, (int)n_seq, q, k, v, gate, out,
+                                     stream));
+  }
+  for (int i = 0; i < n_states; ++i) {
+    kvm_state *st = states[i];
+    const int64_t u = st->tokens;
+    st->tokens = u + 1;
+    if ((u + 1) % C == 0 && u + 1 >= L) {
+      const int64_t lo = u + 1 - L;
+      ProfileSpan span(st, 1, stream);
+      int rc = fold_block(st, advance(ring_src(st), lo % L, es), u + 1, nullptr, nullptr, stream, true);
+      if (rc != KVM_OK) return rc;
+    }
+  }
+  return KVM_OK;
+}
+
 int kvm_state_fold(kvm_state *st, const void *k_blk, const void *v_blk, const float *gate_blk,
                    int32_t n_tokens, int64_t e, int32_t *assign_out, float *score_out,
                    void *stream_) {

@@ -86,6 +86,17 @@ hipError_t launch_ring_copy(const Dev &dv, const Src &src, int64_t src_t0, int64
 hipError_t launch_score_mfma(const Dev &dv, int slot, int row0, int row1, bool first_pass, hipStream_t st);
 // attn_rows.hip
 hipError_t launch_attn_rows(const Dev &dv, const AttnArgs &a, hipStream_t st);
+// One decode step over sequences of several states (kvm_decode_step_multi): per sequence, where
+// its arrays start (its first KV head) and where it stands.
+struct SeqDesc {
+  const void *khat, *vhat;  // current readout version, this sequence's first unit
+  void *winK, *winV;        // window ring, this sequence's first unit
+  float *winG;
+  int64_t pos;              // position of the token being decoded
+  int32_t m, Mcap;          // state rows now, rows per unit in the buffer
+};
+hipError_t launch_decode_multi(const Dev &dv, const SeqDesc *seq, int n_seq, const void *q, const void *k,
+                               const void *v, const float *gate, void *out, hipStream_t st);
 // attn_mfma.hip (bf16, d = 128)
 hipError_t launch_attn_mfma(const Dev &dv, const AttnArgs &a, hipStream_t st);
 
