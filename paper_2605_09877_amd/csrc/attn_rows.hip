@@ -25,6 +25,12 @@ struct RowQuery {
   int64_t pos, t0;   // query position; window positions below t0 come from the ring
   int64_t in_kt, in_vt;
   int m, hq;
+  // decode: the workgroup of a KV head's first query head also stores the new token (k, v, gate
+  // at position pos, read from in_k / in_v like every key at or after t0) into its ring slot;
+  // nobody reads that slot in this launch
+  T *put_k, *put_v;  // ring rows of this unit, or null
+  float *put_g;
+  float gate;
 };
 
 template <typename T, int D>
@@ -39,6 +45,15 @@ __device__ __forceinline__ void attn_row(const Dev &dv, const RowQuery<T> &rq) {
   const int64_t cs = pos / dv.C * dv.C;                      // its chunk starts here
   const int64_t wb = cs + dv.C - dv.L > 0 ? cs + dv.C - dv.L : 0;  // first window position
 
+  if (rq.put_k && threadIdx.x < LPR) {
+    const int slot = (int)(pos % dv.L);
+    float x[VEC];
+    Vec16<T>::load(rq.in_k + (pos - rq.t0) * rq.in_kt + threadIdx.x * VEC, x);
+    Vec16<T>::store(rq.put_k + (int64_t)slot * D + threadIdx.x * VEC, x);
+    Vec16<T>::load(rq.in_v + (pos - rq.t0) * rq.in_vt + threadIdx.x * VEC, x);
+    Vec16<T>::store(rq.put_v + (int64_t)slot * D + threadIdx.x * VEC, x);
+    if (threadIdx.x == 0) rq.put_g[slot] = rq.gate;
+  }
   float qf[VEC];
   Vec16<T>::load(rq.q + cl * VEC, qf);
   const float rs = kLog2e * rsqrtf((float)D);
@@ -175,6 +190,15 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(Dev dv, AttnArgs a) {
   rq.in_kt = a.in.k_t;
   rq.in_vt = a.in.v_t;
   rq.t0 = a.t0;
+  rq.put_k = rq.put_v = nullptr;
+  rq.put_g = nullptr;
+  rq.gate = 1.f;
+  if (a.put_token && hq == hkv * (dv.Hq / dv.Hkv)) {
+    rq.put_k = (T *)dv.winK + (int64_t)u * dv.L * D;
+    rq.put_v = (T *)dv.winV + (int64_t)u * dv.L * D;
+    rq.put_g = dv.winG + (int64_t)u * dv.L;
+    rq.gate = a.in.g ? a.in.g[b * a.in.g_b + hkv * a.in.g_h + (rq.pos - a.t0) * a.in.g_t] : 1.f;
+  }
   attn_row<T, D>(dv, rq);
 }
 
@@ -184,6 +208,7 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(Dev dv, AttnArgs a) {
 // from the sequence's ring, which already holds the new token.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void attn_rows_multi_kernel(Dev dv, const SeqDesc *seq, const void *q,
+                                                              const void *k, const void *v, const float *gate,
                                                               void *out) {
   const int hq = blockIdx.x, s = blockIdx.y;
   const int hkv = hq / (dv.Hq / dv.Hkv);
@@ -199,26 +224,21 @@ __global__ __launch_bounds__(256) void attn_rows_multi_kernel(Dev dv, const SeqD
   rq.vhat = (const T *)sd.vhat + (int64_t)hkv * sd.Mcap * D;
   rq.ring_k = (const T *)sd.winK + (int64_t)hkv * dv.L * D;
   rq.ring_v = (const T *)sd.winV + (int64_t)hkv * dv.L * D;
-  rq.in_k = rq.in_v = nullptr;
+  // the new token is read from the call's k, v (position pos); everything older from the ring
+  rq.in_k = (const T *)k + ((int64_t)s * dv.Hkv + hkv) * D;
+  rq.in_v = (const T *)v + ((int64_t)s * dv.Hkv + hkv) * D;
   rq.in_kt = rq.in_vt = 0;
-  rq.t0 = INT64_MAX / 2;
-  attn_row<T, D>(dv, rq);
-}
-
-// The new token of every sequence into its ring slot (position pos of that sequence).
-template <typename T>
-__global__ __launch_bounds__(64) void ring_put_multi_kernel(Dev dv, const SeqDesc *seq, const void *k,
-                                                            const void *v, const float *gate) {
-  const int hkv = blockIdx.x, s = blockIdx.y;
-  const SeqDesc sd = seq[s];
-  const int slot = (int)(sd.pos % dv.L);
-  const int64_t src = ((int64_t)s * dv.Hkv + hkv) * dv.d;
-  const int64_t dst = ((int64_t)hkv * dv.L + slot) * dv.d;
-  for (int c = threadIdx.x; c < dv.d; c += 64) {
-    ((T *)sd.winK)[dst + c] = ((const T *)k)[src + c];
-    ((T *)sd.winV)[dst + c] = ((const T *)v)[src + c];
+  rq.t0 = sd.pos;
+  rq.put_k = rq.put_v = nullptr;
+  rq.put_g = nullptr;
+  rq.gate = 1.f;
+  if (hq == hkv * (dv.Hq / dv.Hkv)) {
+    rq.put_k = (T *)sd.winK + (int64_t)hkv * dv.L * D;
+    rq.put_v = (T *)sd.winV + (int64_t)hkv * dv.L * D;
+    rq.put_g = sd.winG + (int64_t)hkv * dv.L;
+    rq.gate = gate ? gate[(int64_t)s * dv.Hkv + hkv] : 1.f;
   }
-  if (threadIdx.x == 0) sd.winG[(int64_t)hkv * dv.L + slot] = gate ? gate[(int64_t)s * dv.Hkv + hkv] : 1.f;
+  attn_row<T, D>(dv, rq);
 }
 
 }  // namespace
@@ -242,19 +262,15 @@ hipError_t launch_attn_rows(const Dev &dv, const AttnArgs &a, hipStream_t st) {
 hipError_t launch_decode_multi(const Dev &dv, const SeqDesc *seq, int n_seq, const void *q, const void *k,
                                const void *v, const float *gate, void *out, hipStream_t st) {
   if (n_seq <= 0) return hipSuccess;
-  dim3 pgrid(dv.Hkv, n_seq), agrid(dv.Hq, n_seq);
-  if (dv.io == 0)
-    hipLaunchKernelGGL(ring_put_multi_kernel<float>, pgrid, dim3(64), 0, st, dv, seq, k, v, gate);
-  else
-    hipLaunchKernelGGL(ring_put_multi_kernel<bf16_t>, pgrid, dim3(64), 0, st, dv, seq, k, v, gate);
+  dim3 agrid(dv.Hq, n_seq);
   if (dv.io == 0 && dv.d == 64)
-    hipLaunchKernelGGL((attn_rows_multi_kernel<float, 64>), agrid, dim3(256), 0, st, dv, seq, q, out);
+    hipLaunchKernelGGL((attn_rows_multi_kernel<float, 64>), agrid, dim3(256), 0, st, dv, seq, q, k, v, gate, out);
   else if (dv.io == 0 && dv.d == 128)
-    hipLaunchKernelGGL((attn_rows_multi_kernel<float, 128>), agrid, dim3(256), 0, st, dv, seq, q, out);
+    hipLaunchKernelGGL((attn_rows_multi_kernel<float, 128>), agrid, dim3(256), 0, st, dv, seq, q, k, v, gate, out);
   else if (dv.io == 1 && dv.d == 64)
-    hipLaunchKernelGGL((attn_rows_multi_kernel<bf16_t, 64>), agrid, dim3(256), 0, st, dv, seq, q, out);
+    hipLaunchKernelGGL((attn_rows_multi_kernel<bf16_t, 64>), agrid, dim3(256), 0, st, dv, seq, q, k, v, gate, out);
   else if (dv.io == 1 && dv.d == 128)
-    hipLaunchKernelGGL((attn_rows_multi_kernel<bf16_t, 128>), agrid, dim3(256), 0, st, dv, seq, q, out);
+    hipLaunchKernelGGL((attn_rows_multi_kernel<bf16_t, 128>), agrid, dim3(256), 0, st, dv, seq, q, k, v, gate, out);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();

@@ -4,6 +4,7 @@
 
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -496,6 +497,61 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
       plan.push_back(ch);
     }
   }
+  // Two schedules.  The pipelined one below keeps a readout version per chunk, which costs a copy
+  // of every untouched row's readout per fold: U * m * d * 2 elements read and written.  When the
+  // state is large against the block (many units, thousands of rows, a few hundred tokens per
+  // fold) that copy outweighs what the pipeline gains, and the call runs chunk by chunk on the
+  // caller's stream instead: attention of a chunk, then its fold in place.
+  {
+    int64_t m_max = 0;
+    for (const Chunk &ch : plan) m_max = ch.m > m_max ? ch.m : m_max;
+    const double copy_us = (double)dv.U * (double)m_max * (double)d * (double)es * 4.0 / 4.0e6;  // at ~4 TB/s
+    static const int forced = [] {
+      const char *e = getenv("KVM_PREFILL_SERIAL");  // "0" / "1": for comparisons
+      return e ? (e[0] == '1' ? 1 : 0) : -1;
+    }();
+    // (and a call of a few chunks has nothing to pipeline: the events would cost more than they buy)
+    const bool serial = forced >= 0 ? forced == 1 : (copy_us > 60.0 || plan.size() <= 4);
+    if (serial) {
+      for (const Chunk &ch : plan) {
+        AttnArgs a;
+        a.put_token = 0;
+        a.q = (const char *)q + (ch.s - t0) * s.q_t * (int64_t)es;
+        a.out = (char *)out + (ch.s - t0) * s.o_t * (int64_t)es;
+        a.lse = lse ? lse + (ch.s - t0) * s.lse_t : nullptr;
+        a.q_b = s.q_b; a.q_t = s.q_t; a.q_h = s.q_h;
+        a.o_b = s.o_b; a.o_t = s.o_t; a.o_h = s.o_h;
+        a.lse_b = s.lse_b; a.lse_t = s.lse_t; a.lse_h = s.lse_h;
+        a.in = in;
+        a.t0 = t0;
+        a.s = ch.s;
+        a.n_chunks = 1;
+        a.nq_total = ch.nq;
+        for (int i = 0; i < kvm::kMaxGroup; ++i) {
+          a.m[i] = (int32_t)st->m;
+          a.slot[i] = (int32_t)slot_of(st, st->folds);
+        }
+        {
+          ProfileSpan span(st, 0, stream);
+          if (st->mfma)
+            HIP_TRY(kvm::launch_attn_mfma(dv, a, stream));
+          else
+            HIP_TRY(kvm::launch_attn_rows(dv, a, stream));
+        }
+        if (ch.folds) {
+          const int64_t ce = ch.s + C, lo = ce - L;
+          ProfileSpan span(st, 1, stream);
+          const int rc = lo >= t0 ? fold_block(st, advance(in, lo - t0, es), ce, nullptr, nullptr, stream, true)
+                                  : fold_block(st, advance(ring, lo % L, es), ce, nullptr, nullptr, stream, true);
+          if (rc != KVM_OK) return rc;
+        }
+      }
+      const int64_t p0 = t_end - L > t0 ? t_end - L : t0;
+      HIP_TRY(kvm::launch_ring_copy(dv, in, t0, p0, t_end, stream));
+      st->tokens = t_end;
+      return KVM_OK;
+    }
+  }
   // Folds depend only on k, v, g and the previous fold, so they run ahead on their own stream,
   // each writing a fresh readout version; attention follows on the caller's stream in groups
   // of chunks, each group waiting for the last version it reads.  A slot is rewritten only
@@ -574,6 +630,7 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
     if (rc != KVM_OK) return rc;
     if (last_fold_ev) HIP_TRY(hipStreamWaitEvent(stream, last_fold_ev, 0));
     AttnArgs a;
+    a.put_token = 0;  // a prefill copies its last L tokens into the ring once, at the end
     const int64_t cs = plan[g0].s;
     a.q = (const char *)q + (cs - t0) * s.q_t * (int64_t)es;
     a.out = (char *)out + (cs - t0) * s.o_t * (int64_t)es;
@@ -631,14 +688,14 @@ int kvm_decode_step(kvm_state *st, const void *q, const void *k, const void *v,
   tok.k = k; tok.v = v; tok.g = gate;
   tok.k_b = tok.v_b = dv.Hkv * d; tok.k_h = tok.v_h = d; tok.k_t = tok.v_t = 0;
   tok.g_b = dv.Hkv; tok.g_h = 1; tok.g_t = 0;
-  HIP_TRY(kvm::launch_ring_copy(dv, tok, u, u, u + 1, stream));
 
   AttnArgs a;
   a.q = q; a.out = out; a.lse = nullptr;
   a.q_b = a.o_b = dv.Hq * d; a.q_t = a.o_t = 0; a.q_h = a.o_h = d;
   a.lse_b = a.lse_t = a.lse_h = 0;
   a.in = tok;
-  a.t0 = INT64_MAX / 2;  // every window token comes from the ring
+  a.t0 = u;           // the new token is read from the call's k, v; older ones from the ring
+  a.put_token = 1;    // and stored into the ring by the same launch
   a.s = u;
   a.n_chunks = 1;
   a.nq_total = 1;

@@ -64,6 +64,7 @@ struct AttnArgs {
   int64_t s;         // position of the first query of the launch
   int32_t n_chunks;  // chunks covered
   int32_t nq_total;  // queries covered (all chunks but the last are full)
+  int32_t put_token = 0;  // decode (rows kernel): also store the token at position s into the ring
   int32_t m[kMaxGroup];     // state rows each chunk sees
   int32_t slot[kMaxGroup];  // readout slot of that state version
 };
