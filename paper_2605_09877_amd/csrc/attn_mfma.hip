@@ -19,6 +19,8 @@
 // but measured slower, both with one barrier per tile and with the two halves of the workgroup
 // running half a tile apart: the waves of one workgroup then move in step and their matrix and
 // softmax phases coincide instead of overlapping.
+#include <type_traits>
+
 #include "kvm_device.h"
 #include "kvm_internal.h"
 #include "kvm_mfma.h"
@@ -177,13 +179,13 @@ __device__ __forceinline__ void attn_body(const Dev &dv, const AttnArgs &a, uint
   // O^T += V^T . P^T for the tile whose P^T is in pb.  The first eight V^T fragments are asked
   // for ahead of the softmax (pv_fetch), so that their LDS latency is not waited for here.
   bf16x8 vf[8];
-  auto pv_fetch = [&](int tile) {
-    const uint16_t *Vt = Vs + (tile % kVBufs) * kTileElems;
+  auto pv_fetch = [&](auto parity) {
+    const uint16_t *Vt = Vs + decltype(parity)::value * kTileElems;
 #pragma unroll
     for (int i = 0; i < 8; ++i) vf[i] = vtile_frag(Vt, voff, i & 3, i >> 2);
   };
-  auto do_pv = [&](int tile) {
-    const uint16_t *Vt = Vs + (tile % kVBufs) * kTileElems;
+  auto do_pv = [&](auto parity) {
+    const uint16_t *Vt = Vs + decltype(parity)::value * kTileElems;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
@@ -195,7 +197,8 @@ __device__ __forceinline__ void attn_body(const Dev &dv, const AttnArgs &a, uint
   };
 
   // S^T = K . Q^T and the online softmax for the tile in the current K buffer; leaves P^T in pb.
-  auto do_qk_softmax = [&](bool is_state, int row0, int64_t p0, int tile) {
+  auto do_qk_softmax = [&](bool is_state, int row0, int64_t p0, auto parity) {
+    const uint16_t *Kt = Ks + decltype(parity)::value * kTileElems;
     const float scale = is_state ? c_state : c_bswa;
     const bool need_mask = is_state ? (m - row0 < kTileKeys) : (p0 + kTileKeys - 1 > cs + wq0);
     f32x16 sacc[2];
@@ -204,7 +207,7 @@ __device__ __forceinline__ void attn_body(const Dev &dv, const AttnArgs &a, uint
     {
       bf16x8 kf[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) kf[i] = ktile_frag(Ks, koff, i & 1, i >> 1);
+      for (int i = 0; i < 8; ++i) kf[i] = ktile_frag(Kt, koff, i & 1, i >> 1);
       const f32x16 zero = {0.f};
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
@@ -212,7 +215,7 @@ __device__ __forceinline__ void attn_body(const Dev &dv, const AttnArgs &a, uint
         for (int blk = 0; blk < 2; ++blk) {
           const int slot = (2 * ks + blk) & 7;
           sacc[blk] = mfma32(kf[slot], qreg[ks], ks == 0 ? zero : sacc[blk]);
-          if (ks + 4 < 8) kf[slot] = ktile_frag(Ks, koff, blk, ks + 4);
+          if (ks + 4 < 8) kf[slot] = ktile_frag(Kt, koff, blk, ks + 4);
         }
       }
       // pin that order: 8 LDS reads up front, then one read behind every matrix instruction
@@ -224,7 +227,7 @@ __device__ __forceinline__ void attn_body(const Dev &dv, const AttnArgs &a, uint
       }
       __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
     }
-    pv_fetch(tile);
+    pv_fetch(parity);
     if (need_mask) {
       // keys up to `lim` (tile-local) are visible to this lane's query
       const int lim = is_state ? (m - row0 - 1) : (int)(cs + myq - p0);
@@ -286,7 +289,9 @@ __device__ __forceinline__ void attn_body(const Dev &dv, const AttnArgs &a, uint
   // tile loads, would wait for "its" loads inside the loop and drain the tile loads with them
   __builtin_amdgcn_s_waitcnt(0);
   issue_tile(0);
-  for (int it = 0; it < n_tiles; ++it) {
+  // One tile; the buffer pair it lives in (tile number mod 2) is a compile-time constant, so
+  // that the buffer's offset folds into the LDS instructions instead of costing address updates.
+  auto tile_step = [&](int it, auto parity) {
     const bool is_state = it < n_st;
     if (((neg_bits & (is_state ? 1 : 2)) != 0) != q_negated) {
       asm volatile("" ::: "memory");  // stays a (rarely taken) branch
@@ -306,12 +311,13 @@ __device__ __forceinline__ void attn_body(const Dev &dv, const AttnArgs &a, uint
     const int64_t p0 = wb + (int64_t)(it - n_st) * kTileKeys;
     // skip tiles whose keys all lie after this wave's queries
     if (is_state || p0 <= cs + wq0 + 31) {
-      do_qk_softmax(is_state, it * kTileKeys, p0, it);
-      do_pv(it);
+      do_qk_softmax(is_state, it * kTileKeys, p0, parity);
+      do_pv(parity);
     }
-    // the next tile's K sits in the other buffer
-#pragma unroll
-    for (int i = 0; i < 8; ++i) koff[i] ^= (uint32_t)kTileElems;
+  };
+  for (int it = 0; it < n_tiles; it += 2) {
+    tile_step(it, std::integral_constant<int, 0>{});
+    if (it + 1 < n_tiles) tile_step(it + 1, std::integral_constant<int, 1>{});
   }
   const float l = xhalf_sum(l_part);
   if (myq < nq) {

@@ -463,6 +463,8 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
   const int64_t strides16[] = {s.q_b, s.q_t, s.q_h, s.k_b, s.k_t, s.k_h, s.v_b, s.v_t, s.v_h, s.o_b, s.o_t, s.o_h};
   for (int64_t x : strides16)
     if (x % vec) return KVM_ERR_ARG;
+  // rows of k and v are whole and apart (the tile loads count on at least d elements between tokens)
+  if (s.k_t < d || s.v_t < d || s.q_t < d || s.o_t < d) return KVM_ERR_ARG;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return KVM_ERR_ARG;
 
   const int64_t t0 = st->tokens, t_end = t0 + T;

@@ -134,6 +134,28 @@ __device__ __forceinline__ void dma16(const char *sbase, uint32_t voff, uint32_t
       : "v"(voff), "s"(sbase), "s"(lds_addr)
       : "memory", "m0");
 }
+// Four such loads from one scalar base into four consecutive 1-KiB pieces of LDS: M0 is written
+// once, load n carries the immediate 1024 * n, which the hardware adds to the LDS address and to
+// the global address alike.  One instruction sequence, so nothing can come between the write of
+// M0 and the loads that depend on it.
+__device__ __forceinline__ void dma16x4(const char *sbase, uint32_t v0, uint32_t v1, uint32_t v2, uint32_t v3,
+                                        uint32_t lds_addr) {
+  lds_addr = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_addr);
+  const uint64_t sb = (uint64_t)sbase;
+  const uint32_t sb_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)sb);
+  const uint32_t sb_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(sb >> 32));
+  sbase = (const char *)(((uint64_t)sb_hi << 32) | (uint64_t)sb_lo);
+  asm volatile(
+      "s_mov_b32 m0, %5\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %0, %4\n\t"
+      "global_load_lds_dwordx4 %1, %4 offset:1024\n\t"
+      "global_load_lds_dwordx4 %2, %4 offset:2048\n\t"
+      "global_load_lds_dwordx4 %3, %4 offset:3072"
+      :
+      : "v"(v0), "v"(v1), "v"(v2), "v"(v3), "s"(sbase), "s"(lds_addr)
+      : "memory", "m0");
+}
 __device__ __forceinline__ uint32_t lds_addr_of(const void *p) {
   return (uint32_t)(uintptr_t)KVM_LDS_VOID(p);
 }
@@ -149,14 +171,27 @@ __device__ __forceinline__ void tile_dma(const char *base, uint32_t stride, int 
   constexpr int kPer = 16 / kNW;
   if (rows_valid >= kTileKeys) {
     const uint32_t lane_row = dl.rl * stride;
+    if constexpr (kPer == 4) {
+      // the wave's four loads share one scalar base and one write of M0; the immediate that
+      // moves load n to its piece of LDS also moves its global address, so the per-lane offset
+      // takes that back out (a row is at least 256 bytes: 4 * n * stride >= 1024 * n)
+      const int bi0 = kPer * wave;
+      const uint32_t step = 4u * stride - 1024u;
+      const uint32_t v0 = lane_row + (kVSwz ? dl.vcol : dl.kcol[0]);
+      const uint32_t v1 = lane_row + (kVSwz ? dl.vcol : dl.kcol[1]) + step;
+      const uint32_t v2 = lane_row + (kVSwz ? dl.vcol : dl.kcol[2]) + 2u * step;
+      const uint32_t v3 = lane_row + (kVSwz ? dl.vcol : dl.kcol[3]) + 3u * step;
+      dma16x4(base + (uint32_t)(4 * bi0) * stride, v0, v1, v2, v3, lds_tile_addr + (uint32_t)bi0 * 1024u);
+    } else {
 #pragma unroll
-    for (int n = 0; n < kPer; ++n) {
-      const int bi = kPer * wave + n;
-      // the K chunk permutation depends on bi % 4, which is n for four waves and
-      // 2*(wave%2) + n for eight (a wave-uniform choice between two precomputed values)
-      const uint32_t kcol = kPer == 4 ? dl.kcol[n] : ((wave & 1) ? dl.kcol[2 + n] : dl.kcol[n]);
-      dma16(base + (uint32_t)(4 * bi) * stride, lane_row + (kVSwz ? dl.vcol : kcol),
-            lds_tile_addr + (uint32_t)bi * 1024u);
+      for (int n = 0; n < kPer; ++n) {
+        const int bi = kPer * wave + n;
+        // the K chunk permutation depends on bi % 4: 2*(wave%2) + n for eight waves (a
+        // wave-uniform choice between two precomputed values)
+        const uint32_t kcol = (wave & 1) ? dl.kcol[2 + n] : dl.kcol[n];
+        dma16(base + (uint32_t)(4 * bi) * stride, lane_row + (kVSwz ? dl.vcol : kcol),
+              lds_tile_addr + (uint32_t)bi * 1024u);
+      }
     }
   } else {
 #pragma unroll
