@@ -109,7 +109,7 @@ __global__ __launch_bounds__(256) void memkey_kernel(Dev dv, Src src, int n_bloc
     y[c] = Io<T>::round_from((x[c] - mean) * rden * ga + be);
   }
   if (j < n_tok) {
-    T *out = (T *)dv.kbar + ((int64_t)(j / dv.C) * dv.U * dv.C + (int64_t)u * dv.C + j % dv.C) * D;
+    T *out = (T *)dv.kbar + ((int64_t)(j / dv.C) * dv.Ufull * dv.C + (int64_t)u * dv.C + j % dv.C) * D;
     Vec16<T>::store(out + cl * VEC, y);
   }
 }

@@ -31,7 +31,8 @@ struct kvm_state {
   int group = 1;      // chunks per attention launch in prefill; the readout has 2 * group slots
   // prefill pipeline: folds run ahead on a library-owned stream, attention follows in groups
   int64_t inplace = 0;  // folds done in place so far: version v lives in slot (v - inplace) mod NS
-  hipStream_t fold_stream = nullptr;
+  static constexpr int kMaxChains = 2;
+  hipStream_t fold_streams[kMaxChains] = {nullptr, nullptr};
   std::vector<hipEvent_t> sync_events;  // untimed events, reused call after call
   size_t sync_used = 0;
   // optional kernel timing: (start, stop, class) event pairs, events reused across reads
@@ -199,6 +200,7 @@ void bind(Dev &dv, const kvm_config &c, void *buf, int64_t Mcap) {
   dv.Hq = c.n_q_heads;
   dv.Hkv = c.n_kv_heads;
   dv.U = c.batch * c.n_kv_heads;
+  dv.Ufull = dv.U;
   dv.d = c.head_dim;
   dv.r = c.rope_dims;
   dv.C = c.chunk_len;
@@ -247,21 +249,48 @@ int slot_of(const kvm_state *st, int64_t ver) {
 // rows copied over (prefill, where attention launches still read the older versions), or, in_place,
 // over the version it read (decode and the fold entry point: nothing else is in flight).
 // kbar_block >= 0: the block's memory keys were already computed into that slab of the scratch.
-int fold_block(kvm_state *st, const Src &src, int64_t e, int32_t *assign_out, float *score_out,
-               hipStream_t stream, bool in_place, int kbar_block = -1) {
+// The sequences [b0, b0 + nb) of a state as a state of their own: same strides, moved pointers.
+Dev batch_view(const Dev &full, int b0, int nb, size_t es) {
+  Dev v = full;
+  const int64_t u0 = (int64_t)b0 * full.Hkv, M = full.Mcap, d = full.d, L = full.L, C = full.C;
+  v.B = nb;
+  v.U = nb * full.Hkv;
+  v.sK += u0 * M * d;
+  v.sV += u0 * M * d;
+  v.rho += u0 * M;
+  v.w += u0 * M;
+  v.n += u0 * M;
+  v.khat = (char *)full.khat + u0 * M * d * es;  // the slot stride stays the whole state's
+  v.vhat = (char *)full.vhat + u0 * M * d * es;
+  v.winK = (char *)full.winK + u0 * L * d * es;
+  v.winV = (char *)full.winV + u0 * L * d * es;
+  v.winG += u0 * L;
+  v.kbar = (char *)full.kbar + u0 * C * d * es;  // the block stride stays Ufull * C * d
+  v.score += u0 * C;
+  v.pi += u0 * C;
+  v.app += u0 * C;
+  v.creator += u0 * C;
+  return v;
+}
+Src batch_view(const Src &s, int b0, size_t es) {
+  Src r = s;
+  r.k = (const char *)s.k + b0 * s.k_b * (int64_t)es;
+  r.v = (const char *)s.v + b0 * s.v_b * (int64_t)es;
+  if (s.g) r.g = s.g + b0 * s.g_b;
+  return r;
+}
+
+// The launches of one fold over the units of `dv` (the whole state or a view of part of its
+// batch), from m to m_after rows, reading readout slot so and writing slot sn.
+int fold_launches(const kvm_state *st, Dev dv, const Src &src, int64_t m, int64_t m_after, int so, int sn,
+                  bool in_place, int kbar_block, hipStream_t stream) {
   const kvm_config &c = st->cfg;
-  if (c.budget_kind == KVM_BUDGET_NONE) return KVM_OK;
-  const int64_t m = st->m;
-  const int64_t m_after = rows_after(c, st->table, m, e);
   const int n_app = (int)(m_after - m);
-  if (m_after > st->dv.Mcap) return KVM_ERR_CAPACITY;
-  Dev dv = st->dv;
   if (kbar_block < 0) {
     HIP_TRY(kvm::launch_memkey(dv, src, 1, stream));
   } else {
-    dv.kbar = (char *)dv.kbar + (size_t)kbar_block * dv.U * dv.C * dv.d * esize(c.io_dtype);
+    dv.kbar = (char *)dv.kbar + (size_t)kbar_block * dv.Ufull * dv.C * dv.d * esize(c.io_dtype);
   }
-  const int so = slot_of(st, st->folds), sn = in_place ? so : slot_of(st, st->folds + 1);
   const bool copy = !in_place;
   if (n_app == dv.C) {
     // room for the whole block (state creation included): no scores are needed
@@ -288,6 +317,32 @@ int fold_block(kvm_state *st, const Src &src, int64_t e, int32_t *assign_out, fl
     else
       HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, 0, false, true, true, n_app > 0, so, sn, stream));
   }
+  return KVM_OK;
+}
+
+// What a fold leaves for the parity tests: its assignments and scores, for the units of `dv`
+// (unit u0 on of the state), into the trace buffers at fold number `fold`.
+int fold_trace(const kvm_state *st, const Dev &dv, int64_t u0, int64_t fold, hipStream_t stream) {
+  const size_t ntok_all = (size_t)st->dv.U * dv.C, ntok = (size_t)dv.U * dv.C, off = (size_t)u0 * dv.C;
+  if (st->trace_assign && fold < st->trace_max)
+    HIP_TRY(hipMemcpyAsync(st->trace_assign + fold * ntok_all + off, dv.pi, ntok * 4, hipMemcpyDeviceToDevice, stream));
+  if (st->trace_score && fold < st->trace_max)
+    HIP_TRY(hipMemcpyAsync(st->trace_score + (fold * ntok_all + off) * 2, dv.score, ntok * 8, hipMemcpyDeviceToDevice,
+                           stream));
+  return KVM_OK;
+}
+
+int fold_block(kvm_state *st, const Src &src, int64_t e, int32_t *assign_out, float *score_out,
+               hipStream_t stream, bool in_place, int kbar_block = -1) {
+  const kvm_config &c = st->cfg;
+  if (c.budget_kind == KVM_BUDGET_NONE) return KVM_OK;
+  const int64_t m = st->m;
+  const int64_t m_after = rows_after(c, st->table, m, e);
+  if (m_after > st->dv.Mcap) return KVM_ERR_CAPACITY;
+  const Dev &dv = st->dv;
+  const int so = slot_of(st, st->folds), sn = in_place ? so : slot_of(st, st->folds + 1);
+  int rc = fold_launches(st, dv, src, m, m_after, so, sn, in_place, kbar_block, stream);
+  if (rc != KVM_OK) return rc;
   const size_t ntok = (size_t)dv.U * dv.C;
   if (assign_out)
     HIP_TRY(hipMemcpyAsync(assign_out, dv.pi, ntok * 4, hipMemcpyDeviceToDevice, stream));
@@ -326,7 +381,7 @@ struct ProfileSpan {
   hipEvent_t a = nullptr, b = nullptr;
   int kind, count;
   ProfileSpan(kvm_state *s, int k, hipStream_t str, int n = 1) : st(s), stream(str), kind(k), count(n) {
-    if (!st->profile) return;
+    if (!st || !st->profile) return;
     auto get = [&]() -> hipEvent_t {
       hipEvent_t e = nullptr;
       if (!st->free_events.empty()) {
@@ -406,7 +461,8 @@ int kvm_state_destroy(kvm_state *st) {
     }
     for (auto e : st->free_events) (void)hipEventDestroy(e);
     for (auto e : st->sync_events) (void)hipEventDestroy(e);
-    if (st->fold_stream) (void)hipStreamDestroy(st->fold_stream);
+    for (hipStream_t fs : st->fold_streams)
+      if (fs) (void)hipStreamDestroy(fs);
   }
   delete st;
   return KVM_OK;
@@ -558,21 +614,50 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
   // each writing a fresh readout version; attention follows on the caller's stream in groups
   // of chunks, each group waiting for the last version it reads.  A slot is rewritten only
   // after the attention launch that read its previous version has finished.
-  if (!st->fold_stream) HIP_TRY(hipStreamCreateWithFlags(&st->fold_stream, hipStreamNonBlocking));
-  hipStream_t fstream = st->fold_stream;
+  // The fold chain is a sequence of small dependent launches; when a fold moves little data the
+  // chain is bound by their latencies, not by bytes, and the batch is split into two halves
+  // whose chains run side by side on streams of their own (units are independent).  Two, not
+  // more: with four chains and the caller's stream the process has more streams than hardware
+  // queues (four), and the step was measured 40 % slower.
+  int n_chains = 1;
+  {
+    int64_t m_max = 0;
+    for (const Chunk &ch : plan) m_max = ch.m > m_max ? ch.m : m_max;
+    const double fold_mb = (double)dv.U * ((double)m_max * d * es * 5.0 + (double)C * d * es * 4.0) / 1.0e6;
+    if (fold_mb < 96.0 && dv.B % 2 == 0) n_chains = 2;
+    static const int forced = [] {
+      const char *e = getenv("KVM_FOLD_CHAINS");  // 1 or 2: for comparisons
+      return e ? atoi(e) : 0;
+    }();
+    if ((forced == 1 || forced == 2) && dv.B % forced == 0) n_chains = forced;
+  }
+  hipStream_t fstream[kvm_state::kMaxChains];
+  Dev cdv[kvm_state::kMaxChains];
+  const int cb = dv.B / n_chains;  // sequences per chain
+  for (int c2 = 0; c2 < n_chains; ++c2) {
+    if (!st->fold_streams[c2]) HIP_TRY(hipStreamCreateWithFlags(&st->fold_streams[c2], hipStreamNonBlocking));
+    fstream[c2] = st->fold_streams[c2];
+    cdv[c2] = n_chains == 1 ? dv : batch_view(dv, c2 * cb, cb, es);
+  }
   st->sync_used = 0;
   std::vector<hipEvent_t> slot_busy(dv.NS, nullptr);
   hipEvent_t ev;
   HIP_TRY(next_sync_event(st, &ev));
   HIP_TRY(hipEventRecord(ev, stream));
-  HIP_TRY(hipStreamWaitEvent(fstream, ev, 0));
+  for (int c2 = 0; c2 < n_chains; ++c2) HIP_TRY(hipStreamWaitEvent(fstream[c2], ev, 0));
   const int G = st->group;
   const int n_chunks = (int)plan.size();
   int next_fold = 0;                 // folds of chunks < next_fold are enqueued
-  hipEvent_t last_fold_ev = nullptr;
+  hipEvent_t last_fold_ev[kvm_state::kMaxChains] = {nullptr, nullptr};
   hipEvent_t last_att_ev = nullptr;
+  auto wait_for_folds = [&]() -> int {
+    for (int c2 = 0; c2 < n_chains; ++c2)
+      if (last_fold_ev[c2]) HIP_TRY(hipStreamWaitEvent(stream, last_fold_ev[c2], 0));
+    return KVM_OK;
+  };
   auto enqueue_folds_through = [&](int last_chunk) -> int {
-    if (st->isolate && last_att_ev) HIP_TRY(hipStreamWaitEvent(fstream, last_att_ev, 0));
+    if (st->isolate && last_att_ev)
+      for (int c2 = 0; c2 < n_chains; ++c2) HIP_TRY(hipStreamWaitEvent(fstream[c2], last_att_ev, 0));
     while (next_fold <= last_chunk && next_fold < n_chunks) {
       if (!plan[next_fold].folds) {
         ++next_fold;
@@ -587,40 +672,65 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
                plan[next_fold + run].folds)
           ++run;
       const bool batched = lo0 >= t0;
+      // Events cost microseconds each on the queue: one bracket and one ordering event per run
+      // of folds, not per fold.  The slots this run rewrites must have been read to the end:
+      // one wait per distinct attention launch (usually one), ahead of the run rather than
+      // between its folds.
       {
-        // Events cost microseconds each on the queue: one bracket and one ordering event per
-        // run of folds, not per fold.  The slots this run rewrites must have been read to the end: one wait per distinct
-        // attention launch (usually one), ahead of the run rather than between its folds
-        {
-          hipEvent_t waited[2 * kvm::kMaxGroup];
-          int n_waited = 0;
-          for (int i = 0; i < run; ++i) {
-            const int sn = slot_of(st, st->folds + 1 + i);
-            hipEvent_t e = slot_busy[sn];
-            slot_busy[sn] = nullptr;
-            bool seen = e == nullptr;
-            for (int k2 = 0; k2 < n_waited && !seen; ++k2) seen = waited[k2] == e;
-            if (!seen) {
-              HIP_TRY(hipStreamWaitEvent(fstream, e, 0));
-              waited[n_waited++] = e;
-            }
+        hipEvent_t waited[2 * kvm::kMaxGroup];
+        int n_waited = 0;
+        for (int i = 0; i < run; ++i) {
+          const int sn = slot_of(st, st->folds + 1 + i);
+          hipEvent_t e = slot_busy[sn];
+          slot_busy[sn] = nullptr;
+          bool seen = e == nullptr;
+          for (int k2 = 0; k2 < n_waited && !seen; ++k2) seen = waited[k2] == e;
+          if (!seen) {
+            for (int c2 = 0; c2 < n_chains; ++c2) HIP_TRY(hipStreamWaitEvent(fstream[c2], e, 0));
+            waited[n_waited++] = e;
           }
         }
-        ProfileSpan span(st, 1, fstream, run);
+      }
+      // rows and slots of the run's folds (integer arithmetic, the same for every chain)
+      struct Step {
+        int64_t m, m_after;
+        int so, sn;
+      };
+      Step steps[kvm::kMaxGroup];
+      {
+        int64_t m = st->m;
         for (int i = 0; i < run; ++i) {
-          const Chunk &ch = plan[next_fold + i];
-          const int64_t ce = ch.s + C, lo = ce - L;  // first token of the overflow block
-          int rc;
-          if (batched && i == 0) HIP_TRY(kvm::launch_memkey(dv, advance(in, lo0 - t0, es), run, fstream));
-          if (batched)
-            rc = fold_block(st, advance(in, lo - t0, es), ce, nullptr, nullptr, fstream, false, i);
-          else
-            rc = fold_block(st, advance(ring, lo % L, es), ce, nullptr, nullptr, fstream, false);
-          if (rc != KVM_OK) return rc;
+          const int64_t ce = plan[next_fold + i].s + C;
+          steps[i].m = m;
+          steps[i].m_after = rows_after(c, st->table, m, ce);
+          if (steps[i].m_after > dv.Mcap) return KVM_ERR_CAPACITY;
+          steps[i].so = slot_of(st, st->folds + i);
+          steps[i].sn = slot_of(st, st->folds + i + 1);
+          m = steps[i].m_after;
         }
       }
-      HIP_TRY(next_sync_event(st, &last_fold_ev));
-      HIP_TRY(hipEventRecord(last_fold_ev, fstream));
+      for (int c2 = 0; c2 < n_chains; ++c2) {
+        // the timing bracket goes on the first chain only (the chains run side by side)
+        ProfileSpan span(c2 == 0 ? st : nullptr, 1, fstream[c2], run);
+        const Src cin = batch_view(in, c2 * cb, es), cring = batch_view(ring, c2 * cb, es);
+        if (batched) HIP_TRY(kvm::launch_memkey(cdv[c2], advance(cin, lo0 - t0, es), run, fstream[c2]));
+        for (int i = 0; i < run; ++i) {
+          const int64_t lo = plan[next_fold + i].s + C - L;  // first token of the overflow block
+          const int rc = batched ? fold_launches(st, cdv[c2], advance(cin, lo - t0, es), steps[i].m, steps[i].m_after,
+                                                 steps[i].so, steps[i].sn, false, i, fstream[c2])
+                                 : fold_launches(st, cdv[c2], advance(cring, lo % L, es), steps[i].m,
+                                                 steps[i].m_after, steps[i].so, steps[i].sn, false, -1, fstream[c2]);
+          if (rc != KVM_OK) return rc;
+          const int rt = fold_trace(st, cdv[c2], (int64_t)c2 * cb * dv.Hkv, st->folds + i, fstream[c2]);
+          if (rt != KVM_OK) return rt;
+        }
+      }
+      st->m = steps[run - 1].m_after;
+      st->folds += run;
+      for (int c2 = 0; c2 < n_chains; ++c2) {
+        HIP_TRY(next_sync_event(st, &last_fold_ev[c2]));
+        HIP_TRY(hipEventRecord(last_fold_ev[c2], fstream[c2]));
+      }
       next_fold += run;
     }
     return KVM_OK;
@@ -630,7 +740,8 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
     // the last chunk of the group reads the version written by the fold after chunk g1 - 2
     int rc = enqueue_folds_through(g1 - 2);
     if (rc != KVM_OK) return rc;
-    if (last_fold_ev) HIP_TRY(hipStreamWaitEvent(stream, last_fold_ev, 0));
+    rc = wait_for_folds();
+    if (rc != KVM_OK) return rc;
     AttnArgs a;
     a.put_token = 0;  // a prefill copies its last L tokens into the ring once, at the end
     const int64_t cs = plan[g0].s;
@@ -664,7 +775,8 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
   {
     int rc = enqueue_folds_through(n_chunks - 1);
     if (rc != KVM_OK) return rc;
-    if (last_fold_ev) HIP_TRY(hipStreamWaitEvent(stream, last_fold_ev, 0));
+    rc = wait_for_folds();
+    if (rc != KVM_OK) return rc;
   }
   // keep the last L tokens for the calls that follow
   const int64_t p0 = t_end - L > t0 ? t_end - L : t0;

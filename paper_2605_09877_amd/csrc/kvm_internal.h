@@ -46,6 +46,7 @@ struct Dev {
   const float *gamma, *beta;          // [H_kv, d] or null
   const float *tau_state, *tau_bswa;  // [H_q] or null
   int32_t B, Hq, Hkv, U, d, r, C, L, S, Mcap;
+  int32_t Ufull;  // units of the whole state (a view of part of the batch keeps the state's strides)
   float ln_eps, norm_eps;
   int32_t io;  // KVM_F32 / KVM_BF16
 };
