@@ -137,7 +137,7 @@ __global__ __launch_bounds__(256) void prep_rows_kernel(RowArgs a, uint32_t n_ro
 // heads in blocks of eight; the per-lane partial dot products are summed across the wave at the
 // end.  kFull: the number of KV heads is a multiple of 8, so a row of eight gate weights is two
 // aligned 16-byte loads.
-constexpr int kGateTok = 4;
+constexpr int kGateTok = 8;
 template <typename T, bool kFull>
 __global__ __launch_bounds__(256) void gate_kernel(const T *x, const float *w, float *gate, int64_t n_tok,
                                                    int dm, int Hkv) {
