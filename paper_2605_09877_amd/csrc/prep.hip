@@ -5,7 +5,8 @@
 //   q, k <- RoPE_r(LN(q)), RoPE_r(LN(k))            LayerNorm with bias per head, rotary on r channels
 //   g  =  1 + ELU(x W_g)                            merge gate, one scalar per KV head
 // One row (token, head) is handled by d_h / kN adjacent lanes, 16 bytes of channels each, so a
-// wave takes several rows; statistics and the rotation partner come through lane exchanges.
+// wave takes several adjacent heads, and walks a run of consecutive tokens of them; statistics
+// and the rotation partner come through lane exchanges.
 // Arithmetic is fp32; the rotation angles are evaluated in fp64 once per position (a table),
 // because position * frequency loses its low bits in fp32 at 32k tokens.
 #include "../../include/kvm.h"
@@ -54,83 +55,116 @@ __device__ __forceinline__ void load_params(const float *p, float neutral, float
 }
 
 // kNorm: LayerNorm + rotation (q, k); kResidual: value residual (v).
+// A wave takes 64 / (D / kN) adjacent heads (one per lane group: together a contiguous piece of a
+// token) and walks kRun consecutive tokens of them, so that the token shift's "previous token" is
+// the row the lane group has just had in registers instead of a second read of it (one extra row
+// per run), and the per-head parameters are fetched once per run.  Tokens go in blocks of kAhead
+// whose loads are all requested before the first of them is worked on.
+constexpr int kRun = 16, kAhead = 4;
 template <typename T, int D, bool kNorm, bool kResidual>
-__global__ __launch_bounds__(256) void prep_rows_kernel(RowArgs a, uint32_t n_rows) {
+__global__ __launch_bounds__(256) void prep_rows_kernel(RowArgs a, uint32_t n_hg, uint32_t n_runs, uint32_t n_waves) {
   constexpr int VEC = Vec16<T>::kN;
   constexpr int LPT = D / VEC;   // lanes per row
-  constexpr int RPW = 64 / LPT;  // rows per wave
+  constexpr int RPW = 64 / LPT;  // heads per wave
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int sub = lane / LPT, cl = lane % LPT;
-  const uint32_t row_raw = (blockIdx.x * 4u + wave) * RPW + sub;
-  const bool live = row_raw < n_rows;
-  const uint32_t row = live ? row_raw : n_rows - 1;  // idle lane groups repeat the last row, store nothing
-  const uint32_t H = (uint32_t)a.H, bt = row / H, h = row - bt * H;
-  const uint32_t T_ = (uint32_t)a.T, b = bt / T_, t = bt - b * T_;
+  const uint32_t wg = blockIdx.x * 4u + wave;  // adjacent waves: adjacent head groups of one token run
+  if (wg >= n_waves) return;
+  const uint32_t hg = wg % n_hg, br = wg / n_hg, run = br % n_runs, b = br / n_runs;
+  const uint32_t H = (uint32_t)a.H, T_ = (uint32_t)a.T;
+  const uint32_t h_raw = hg * RPW + sub;
+  const bool live = h_raw < H;
+  const uint32_t h = live ? h_raw : H - 1;  // idle lane groups repeat the last head, store nothing
   const int c0 = cl * VEC;
-  const int64_t off = (int64_t)row * D + c0;
   const int pc = (int)h * D + c0;  // offset into the per-head parameter arrays
+  const uint32_t t_begin = run * kRun, t_end = t_begin + kRun < T_ ? t_begin + kRun : T_;
+  const int64_t row_stride = (int64_t)H * D;  // elements between tokens
+  const int64_t off0 = (((int64_t)b * T_ + t_begin) * H + h) * D + c0;
+  const bool resid = kResidual && a.first && a.lambda;
 
-  float y[VEC], p[VEC];
-  Vec16<T>::load((const T *)a.in + off, y);
-  const bool shift = a.alpha && (t > 0 || a.prev);
-  if (shift) {
-    if (t > 0)
-      Vec16<T>::load((const T *)a.in + off - (int64_t)H * D, p);
-    else
-      Vec16<T>::load((const T *)a.prev + (int64_t)(b * H + h) * D + c0, p);  // already residual-mixed
-  }
-  if (kResidual && a.first && a.lambda) {
-    float lm[VEC], f[VEC];
-    load_params<VEC>(a.lambda + pc, 0.f, lm);
-    Vec16<T>::load((const T *)a.first + off, f);
-#pragma unroll
-    for (int i = 0; i < VEC; ++i) y[i] = (1.f - lm[i]) * y[i] + lm[i] * f[i];
-    if (shift && t > 0) {
-      Vec16<T>::load((const T *)a.first + off - (int64_t)H * D, f);
-#pragma unroll
-      for (int i = 0; i < VEC; ++i) p[i] = (1.f - lm[i]) * p[i] + lm[i] * f[i];
-    }
-  }
-  if (shift) {
-    float al[VEC];
-    load_params<VEC>(a.alpha + pc, 0.f, al);
-#pragma unroll
-    for (int i = 0; i < VEC; ++i) y[i] += al[i] * (p[i] - y[i]);
-  }
+  float al[VEC], lm[VEC], ga[VEC], be[VEC];
+  load_params<VEC>(a.alpha ? a.alpha + pc : nullptr, 0.f, al);
+  load_params<VEC>(resid ? a.lambda + pc : nullptr, 0.f, lm);
   if (kNorm) {
-    float s = 0.f;
-#pragma unroll
-    for (int i = 0; i < VEC; ++i) s += y[i];
-    const float mean = group_sum<LPT>(s) * (1.f / (float)D);
-    float q = 0.f;
-#pragma unroll
-    for (int i = 0; i < VEC; ++i) {
-      y[i] -= mean;
-      q += y[i] * y[i];
-    }
-    const float rstd = rsqrtf(group_sum<LPT>(q) * (1.f / (float)D) + a.eps);
-    float ga[VEC], be[VEC];
     load_params<VEC>(a.gamma ? a.gamma + pc : nullptr, 1.f, ga);
     load_params<VEC>(a.beta ? a.beta + pc : nullptr, 0.f, be);
+  }
+  // the row before the run (already residual-mixed when it comes from the previous call)
+  float prev[VEC];
+  bool have_prev = false;
+  if (a.alpha) {
+    if (t_begin > 0) {
+      Vec16<T>::load((const T *)a.in + off0 - row_stride, prev);
+      if (resid) {
+        float f[VEC];
+        Vec16<T>::load((const T *)a.first + off0 - row_stride, f);
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) y[i] = y[i] * rstd * ga[i] + be[i];
-    if (a.r > 0) {
-      // channel c < r/2 pairs with c + r/2, which sits r/2/VEC lanes away (a power of two)
-      const int half = a.r / 2, hop = half / VEC;
-      float o[VEC];
-#pragma unroll
-      for (int i = 0; i < VEC; ++i) o[i] = __shfl_xor(y[i], hop, kWave);
-      if (c0 < a.r) {
-        const bool lower = c0 < half;
-        float cs[2 * VEC];  // (cos, sin) of this lane's channels
-        load_params<2 * VEC>((const float *)(a.tab + (int64_t)t * half + (lower ? c0 : c0 - half)), 0.f, cs);
-#pragma unroll
-        for (int i = 0; i < VEC; ++i)
-          y[i] = lower ? y[i] * cs[2 * i] - o[i] * cs[2 * i + 1] : y[i] * cs[2 * i] + o[i] * cs[2 * i + 1];
+        for (int i = 0; i < VEC; ++i) prev[i] = (1.f - lm[i]) * prev[i] + lm[i] * f[i];
       }
+      have_prev = true;
+    } else if (a.prev) {
+      Vec16<T>::load((const T *)a.prev + (int64_t)(b * H + h) * D + c0, prev);
+      have_prev = true;
     }
   }
-  if (live) Vec16<T>::store((T *)a.out + off, y);
+  for (uint32_t t0 = t_begin; t0 < t_end; t0 += kAhead) {
+    float y[kAhead][VEC], f[kAhead][VEC];
+#pragma unroll
+    for (int k = 0; k < kAhead; ++k) {
+      const uint32_t t = t0 + k < t_end ? t0 + k : t_end - 1;
+      const int64_t off = off0 + (int64_t)(t - t_begin) * row_stride;
+      Vec16<T>::load((const T *)a.in + off, y[k]);
+      if (resid) Vec16<T>::load((const T *)a.first + off, f[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < kAhead; ++k) {
+      const uint32_t t = t0 + k;
+      if (t >= t_end) break;
+      if (resid) {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) y[k][i] = (1.f - lm[i]) * y[k][i] + lm[i] * f[k][i];
+      }
+      float z[VEC];  // the row after the shift; y[k] stays the next token's "previous"
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) z[i] = have_prev ? y[k][i] + al[i] * (prev[i] - y[k][i]) : y[k][i];
+      if (a.alpha) {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) prev[i] = y[k][i];
+        have_prev = true;
+      }
+      if (kNorm) {
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) s += z[i];
+        const float mean = group_sum<LPT>(s) * (1.f / (float)D);
+        float q = 0.f;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+          z[i] -= mean;
+          q += z[i] * z[i];
+        }
+        const float rstd = rsqrtf(group_sum<LPT>(q) * (1.f / (float)D) + a.eps);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) z[i] = z[i] * rstd * ga[i] + be[i];
+        if (a.r > 0) {
+          // channel c < r/2 pairs with c + r/2, which sits r/2/VEC lanes away (a power of two)
+          const int half = a.r / 2, hop = half / VEC;
+          float o[VEC];
+#pragma unroll
+          for (int i = 0; i < VEC; ++i) o[i] = __shfl_xor(z[i], hop, kWave);
+          if (c0 < a.r) {
+            const bool lower = c0 < half;
+            float cs[2 * VEC];  // (cos, sin) of this lane's channels
+            load_params<2 * VEC>((const float *)(a.tab + (int64_t)t * half + (lower ? c0 : c0 - half)), 0.f, cs);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i)
+              z[i] = lower ? z[i] * cs[2 * i] - o[i] * cs[2 * i + 1] : z[i] * cs[2 * i] + o[i] * cs[2 * i + 1];
+          }
+        }
+      }
+      if (live) Vec16<T>::store((T *)a.out + off0 + (int64_t)(t - t_begin) * row_stride, z);
+    }
+  }
 }
 
 // Merge gate: a wave takes kGateTok tokens; lanes stride over the model width, 16 bytes of x each,
@@ -186,13 +220,19 @@ __global__ __launch_bounds__(256) void gate_kernel(const T *x, const float *w, f
 }
 
 template <typename T, bool kNorm, bool kResidual>
-hipError_t launch_rows(const RowArgs &a, int d, int64_t n_rows, hipStream_t st) {
-  const int rows_per_wg = 4 * 64 / (d / Vec16<T>::kN);
-  dim3 grid((unsigned)((n_rows + rows_per_wg - 1) / rows_per_wg));
+hipError_t launch_rows(const RowArgs &a, int d, int batch, hipStream_t st) {
+  const int heads_per_wave = 64 / (d / Vec16<T>::kN);
+  const uint32_t n_hg = (uint32_t)((a.H + heads_per_wave - 1) / heads_per_wave);
+  const uint32_t n_runs = (uint32_t)((a.T + kRun - 1) / kRun);
+  const int64_t n_waves = (int64_t)batch * n_runs * n_hg;
+  if (n_waves >= (1ll << 31)) return hipErrorInvalidValue;
+  dim3 grid((unsigned)((n_waves + 3) / 4));
   if (d == 64)
-    hipLaunchKernelGGL((prep_rows_kernel<T, 64, kNorm, kResidual>), grid, dim3(256), 0, st, a, (uint32_t)n_rows);
+    hipLaunchKernelGGL((prep_rows_kernel<T, 64, kNorm, kResidual>), grid, dim3(256), 0, st, a, n_hg, n_runs,
+                       (uint32_t)n_waves);
   else
-    hipLaunchKernelGGL((prep_rows_kernel<T, 128, kNorm, kResidual>), grid, dim3(256), 0, st, a, (uint32_t)n_rows);
+    hipLaunchKernelGGL((prep_rows_kernel<T, 128, kNorm, kResidual>), grid, dim3(256), 0, st, a, n_hg, n_runs,
+                       (uint32_t)n_waves);
   return hipGetLastError();
 }
 
@@ -262,10 +302,10 @@ extern "C" int kvm_prepare_qkv(const kvm_prep_params *p, const void *q_raw, cons
     if (n_rows >= (1ll << 31)) return KVM_ERR_ARG;  // rows are indexed with 32 bits
     hipError_t e;
     if (p->io_dtype == KVM_F32)
-      e = normalise ? launch_rows<float, true, false>(a, d, n_rows, st) : launch_rows<float, false, true>(a, d, n_rows, st);
+      e = normalise ? launch_rows<float, true, false>(a, d, p->batch, st) : launch_rows<float, false, true>(a, d, p->batch, st);
     else
-      e = normalise ? launch_rows<bf16_t, true, false>(a, d, n_rows, st)
-                    : launch_rows<bf16_t, false, true>(a, d, n_rows, st);
+      e = normalise ? launch_rows<bf16_t, true, false>(a, d, p->batch, st)
+                    : launch_rows<bf16_t, false, true>(a, d, p->batch, st);
     return e == hipSuccess ? KVM_OK : KVM_ERR_HIP;
   };
   int rc = rows(q_raw, nullptr, prev_q, q_out, p->alpha_q, nullptr, p->lnq_gamma, p->lnq_beta, p->n_q_heads, 1);
