@@ -224,7 +224,9 @@ typedef struct kvm_prep_params {
   const float *w_gate;                             /* [d_model, H_kv] */
 } kvm_prep_params;
 
-/* Bytes of device scratch kvm_prepare_qkv needs for T tokens (the rotation table); 0 on bad arguments. */
+/* Bytes of device scratch kvm_prepare_qkv needs for T tokens (the rotation table, and the merge
+ * gate's weights split into two bf16 halves when the gate runs on the matrix cores); 0 on bad
+ * arguments. */
 size_t kvm_prepare_scratch_bytes(const kvm_prep_params *p, int64_t T);
 
 /* Prepares T tokens at absolute positions pos0 .. pos0 + T - 1 for every sequence of the batch.

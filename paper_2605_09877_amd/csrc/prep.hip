@@ -11,6 +11,7 @@
 // because position * frequency loses its low bits in fp32 at 32k tokens.
 #include "../../include/kvm.h"
 #include "kvm_device.h"
+#include "kvm_mfma.h"
 
 namespace kvm {
 namespace {
@@ -219,6 +220,76 @@ __global__ __launch_bounds__(256) void gate_kernel(const T *x, const float *w, f
   }
 }
 
+// The merge gate on the matrix cores (bf16 x, at most 32 KV heads, d_model a multiple of 128).
+// W_g is fp32; it is split once per call into two bf16 halves, hi = bf16(w) and lo = bf16(w - hi),
+// transposed to [32 heads (zero rows beyond H_kv)][d_model], so that x W_g = x hi + x lo with the
+// products exact and the sums in fp32: the same 1e-6-relative arithmetic as the vector version.
+constexpr int kGateHeads = 32;
+__global__ __launch_bounds__(256) void gate_split_kernel(const float *w, uint16_t *hi, uint16_t *lo, int dm, int Hkv) {
+  const int i = blockIdx.x * 256 + threadIdx.x;  // over kGateHeads * dm
+  if (i >= kGateHeads * dm) return;
+  const int h = i / dm, c = i - h * dm;
+  const float x = h < Hkv ? w[(int64_t)c * Hkv + h] : 0.f;
+  const uint16_t a = float_to_bf16_bits(x);
+  hi[i] = a;
+  lo[i] = float_to_bf16_bits(x - bf16_bits_to_float(a));
+}
+
+// A wave takes 64 tokens (two blocks of 32 rows of the matrix instruction) and all heads; x goes
+// from global memory straight into the A operand (lane = token row, 16 bytes = its 8 channels of
+// the step), W's halves into the B operand (lane = head).  Per 128 channels: 16 loads of x in
+// flight per lane, 32 matrix instructions.
+__global__ __launch_bounds__(256) void gate_mfma_kernel(const uint16_t *x, const uint16_t *hi, const uint16_t *lo,
+                                                        float *gate, int64_t n_tok, int dm, int Hkv) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int l32 = lane & 31, g = lane >> 5;
+  const int64_t tok0 = ((int64_t)blockIdx.x * 4 + wave) * 64;
+  if (tok0 >= n_tok) return;
+  const uint16_t *xr[2];
+#pragma unroll
+  for (int tb = 0; tb < 2; ++tb) {
+    const int64_t t = tok0 + 32 * tb + l32;
+    xr[tb] = x + (t < n_tok ? t : n_tok - 1) * dm + 8 * g;
+  }
+  const bool head_lane = l32 < ((Hkv + 7) & ~7);  // lanes of the zero rows need not load them
+  const uint16_t *hr = hi + (int64_t)l32 * dm + 8 * g, *lr = lo + (int64_t)l32 * dm + 8 * g;
+  f32x16 acc[2];
+#pragma unroll
+  for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[tb][v] = 0.f;
+  for (int c0 = 0; c0 < dm; c0 += 128) {
+    Frag8 xa[2][8], wh[8], wl[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+#pragma unroll
+      for (int tb = 0; tb < 2; ++tb) xa[tb][ks].q = *reinterpret_cast<const uint4 *>(xr[tb] + c0 + 16 * ks);
+      wh[ks].q = wl[ks].q = make_uint4(0u, 0u, 0u, 0u);
+      if (head_lane) {
+        wh[ks].q = *reinterpret_cast<const uint4 *>(hr + c0 + 16 * ks);
+        wl[ks].q = *reinterpret_cast<const uint4 *>(lr + c0 + 16 * ks);
+      }
+    }
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+      for (int tb = 0; tb < 2; ++tb) {
+        acc[tb] = mfma32(xa[tb][ks].v, wh[ks].v, acc[tb]);
+        acc[tb] = mfma32(xa[tb][ks].v, wl[ks].v, acc[tb]);
+      }
+  }
+  if (l32 < Hkv) {
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int64_t t = tok0 + 32 * tb + mfma_row(v, g);
+        const float z = acc[tb][v];
+        if (t < n_tok) gate[t * Hkv + l32] = 1.f + (z > 0.f ? z : expm1f(z));
+      }
+  }
+}
+
 template <typename T, bool kNorm, bool kResidual>
 hipError_t launch_rows(const RowArgs &a, int d, int batch, hipStream_t st) {
   const int heads_per_wave = 64 / (d / Vec16<T>::kN);
@@ -237,6 +308,18 @@ hipError_t launch_rows(const RowArgs &a, int d, int batch, hipStream_t st) {
 }
 
 bool al16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+
+// Scratch layout: the rotation table, then (when the matrix-core gate applies) W_g's two bf16 halves.
+bool gate_on_mfma(const kvm_prep_params *p) {
+  return p->io_dtype == KVM_BF16 && p->d_model > 0 && p->d_model % 128 == 0 && p->n_kv_heads <= kGateHeads;
+}
+size_t rope_table_bytes(const kvm_prep_params *p, int64_t T) {
+  const size_t n = (size_t)T * (size_t)(p->rope_dims / 2) * sizeof(float2);
+  return ((n ? n : 16) + 255) & ~(size_t)255;
+}
+size_t gate_split_bytes(const kvm_prep_params *p) {
+  return gate_on_mfma(p) ? 2 * (size_t)kGateHeads * (size_t)p->d_model * 2 : 0;
+}
 
 bool valid(const kvm_prep_params *p) {
   if (!p || p->batch <= 0 || p->n_q_heads <= 0 || p->n_kv_heads <= 0) return false;
@@ -260,8 +343,7 @@ bool valid(const kvm_prep_params *p) {
 
 extern "C" size_t kvm_prepare_scratch_bytes(const kvm_prep_params *p, int64_t T) {
   if (!kvm::valid(p) || T <= 0) return 0;
-  const size_t n = (size_t)T * (size_t)(p->rope_dims / 2) * sizeof(float2);
-  return n ? n : 16;
+  return kvm::rope_table_bytes(p, T) + kvm::gate_split_bytes(p);
 }
 
 extern "C" int kvm_prepare_qkv(const kvm_prep_params *p, const void *q_raw, const void *k_raw,
@@ -320,7 +402,13 @@ extern "C" int kvm_prepare_qkv(const kvm_prep_params *p, const void *q_raw, cons
     const bool full = p->n_kv_heads % 8 == 0;
     const float *wg = p->w_gate;
     const int dm = p->d_model, hk = p->n_kv_heads;
-    if (p->io_dtype == KVM_F32) {
+    if (gate_on_mfma(p)) {
+      uint16_t *hi = (uint16_t *)((char *)scratch + rope_table_bytes(p, T)), *lo = hi + (size_t)kGateHeads * dm;
+      hipLaunchKernelGGL(gate_split_kernel, dim3((unsigned)((kGateHeads * dm + 255) / 256)), dim3(256), 0, st, wg, hi,
+                         lo, dm, hk);
+      hipLaunchKernelGGL(gate_mfma_kernel, dim3((unsigned)((n_tok + 255) / 256)), dim3(256), 0, st,
+                         (const uint16_t *)x, hi, lo, gate_out, n_tok, dm, hk);
+    } else if (p->io_dtype == KVM_F32) {
       if (full)
         hipLaunchKernelGGL((gate_kernel<float, true>), grid, dim3(256), 0, st, (const float *)x, wg, gate_out, n_tok, dm, hk);
       else
