@@ -525,12 +525,13 @@ __global__ __launch_bounds__(256) void accum_kernel(Dev dv, Src src, int m_befor
 // row: it adds every token with that target, in ascending position, and rewrites the row's
 // readout; the other waves leave at once.
 template <typename T, int D>
-__global__ __launch_bounds__(256) void merge_inplace_kernel(Dev dv, Src src, int check_app, int slot) {
+__device__ __forceinline__ void merge_token_wave(const Dev &dv, const Src &src, int check_app, int slot, int blk,
+                                                 int u) {
   constexpr int CPL = D / 64;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int u = blockIdx.y, b = u / dv.Hkv, h = u % dv.Hkv;
+  const int b = u / dv.Hkv, h = u % dv.Hkv;
   const int C = dv.C;
-  const int j = blockIdx.x * 4 + wave;
+  const int j = blk * 4 + wave;
   if (j >= C) return;
   const int64_t base = (int64_t)u * C;
   const int row = dv.pi[base + j];
@@ -609,6 +610,68 @@ __global__ __launch_bounds__(256) void merge_inplace_kernel(Dev dv, Src src, int
     dv.n[ro] = n;
   }
   write_readout<T, D>(dv, slot, u, h, row, sk, sv, rho, lane);
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void merge_inplace_kernel(Dev dv, Src src, int check_app, int slot) {
+  merge_token_wave<T, D>(dv, src, check_app, slot, blockIdx.x, blockIdx.y);
+}
+
+// The same merge for a prefill's small folds, where the new state version lives in another slot:
+// the token waves above write the touched rows' readout into slot_new, and further workgroups of
+// the same launch copy the readout of the rows no token goes to (a wave takes kCopyRows rows,
+// asks for their readout, scans the block's targets, stores the copies of the untouched ones).
+// Against accum_kernel, which walks rows and finds each row's tokens, a touched row here starts
+// from its token: one wave per touched row and a short chain of dependent loads, which is what
+// counts when the whole launch is a few thousand waves; accum_kernel moves the bytes of a large
+// state faster.
+constexpr int kCopyRows = 4;
+template <typename T, int D>
+__device__ __forceinline__ void copy_untouched_wave(const Dev &dv, int check_app, int slot_old, int slot_new,
+                                                    int m_before, int blk, int u) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int row_first = (blk * 4 + wave) * kCopyRows;
+  if (row_first >= m_before) return;
+  const int C = dv.C;
+  const int64_t base = (int64_t)u * C;
+  using Piece = typename PieceOf<2 * D * (int)sizeof(T) / 64>::type;
+  Piece piece[kCopyRows] = {};
+#pragma unroll
+  for (int rr = 0; rr < kCopyRows; ++rr) {
+    const int row = row_first + rr;
+    if (row < m_before) {
+      const int64_t eo = (slot_old * dv.slot_elems + ((int64_t)u * dv.Mcap + row) * D) * (int64_t)sizeof(T);
+      const char *from = (lane < 32 ? (const char *)dv.khat : (const char *)dv.vhat) + eo;
+      piece[rr] = reinterpret_cast<const Piece *>(from)[lane & 31];
+    }
+  }
+  bool touched[kCopyRows] = {};
+  for (int j0 = 0; j0 < C; j0 += 64) {
+    const int j = j0 + lane;
+    int tg = j < C ? dv.pi[base + j] : -1;
+    if (check_app && j < C && dv.app[base + j] >= 0) tg = -1;
+#pragma unroll
+    for (int rr = 0; rr < kCopyRows; ++rr)
+      touched[rr] = touched[rr] || __builtin_amdgcn_ballot_w64(tg == row_first + rr) != 0;
+  }
+#pragma unroll
+  for (int rr = 0; rr < kCopyRows; ++rr) {
+    const int row = row_first + rr;
+    if (row < m_before && (!touched[rr] || row < dv.S)) {  // sinks take no merges
+      const int64_t eo = (slot_new * dv.slot_elems + ((int64_t)u * dv.Mcap + row) * D) * (int64_t)sizeof(T);
+      char *to = (lane < 32 ? (char *)dv.khat : (char *)dv.vhat) + eo;
+      reinterpret_cast<Piece *>(to)[lane & 31] = piece[rr];
+    }
+  }
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void merge_copy_kernel(Dev dv, Src src, int check_app, int slot_old, int slot_new,
+                                                         int m_before, int n_tok_blocks) {
+  if ((int)blockIdx.x < n_tok_blocks)
+    merge_token_wave<T, D>(dv, src, check_app, slot_new, blockIdx.x, blockIdx.y);
+  else
+    copy_untouched_wave<T, D>(dv, check_app, slot_old, slot_new, m_before, blockIdx.x - n_tok_blocks, blockIdx.y);
 }
 
 // Recompute the normalised readout of rows [0, m) from the stored sums (after an import).
@@ -707,6 +770,15 @@ hipError_t launch_accum(const Dev &dv, const Src &src, int m_before, int m_after
 hipError_t launch_merge_inplace(const Dev &dv, const Src &src, bool check_app, int slot, hipStream_t st) {
   dim3 grid((dv.C + 3) / 4, dv.U);
   KVM_DISPATCH(dv, merge_inplace_kernel, grid, dim3(256), 0, st, dv, src, check_app ? 1 : 0, slot);
+  return hipGetLastError();
+}
+
+hipError_t launch_merge_copy(const Dev &dv, const Src &src, bool check_app, int slot_old, int slot_new,
+                             int m_before, hipStream_t st) {
+  const int n_tok_blocks = (dv.C + 3) / 4, n_row_blocks = (m_before + 4 * kCopyRows - 1) / (4 * kCopyRows);
+  dim3 grid(n_tok_blocks + n_row_blocks, dv.U);
+  KVM_DISPATCH(dv, merge_copy_kernel, grid, dim3(256), 0, st, dv, src, check_app ? 1 : 0, slot_old, slot_new,
+               m_before, n_tok_blocks);
   return hipGetLastError();
 }
 

@@ -312,8 +312,15 @@ int fold_launches(const kvm_state *st, Dev dv, const Src &src, int64_t m, int64_
       else
         HIP_TRY(kvm::launch_score(dv, sn, (int)m, (int)m_after, false, stream));
     }
+    static const int merge_copy_forced = [] {
+      const char *e = getenv("KVM_MERGE_COPY");  // "0" / "1": for comparisons
+      return e ? (e[0] == '1' ? 1 : 0) : -1;
+    }();
+    const bool small = merge_copy_forced >= 0 ? merge_copy_forced == 1 : (int64_t)dv.Ufull * m_after < 64 * 1024;
     if (in_place)
       HIP_TRY(kvm::launch_merge_inplace(dv, src, n_app > 0, sn, stream));
+    else if (small)
+      HIP_TRY(kvm::launch_merge_copy(dv, src, n_app > 0, so, sn, (int)m, stream));
     else
       HIP_TRY(kvm::launch_accum(dv, src, (int)m, (int)m_after, 0, false, true, true, n_app > 0, so, sn, stream));
   }

@@ -80,6 +80,9 @@ hipError_t launch_accum(const Dev &dv, const Src &src, int m_before, int m_after
 // selection + creation + second scoring pass of a small append, one launch
 bool append_fits(const Dev &dv, int n_app);
 hipError_t launch_append(const Dev &dv, const Src &src, int m, int n_app, int slot_new, hipStream_t st);
+// the merge of a small fold in a prefill: token-centred merge into slot_new + copies of untouched rows
+hipError_t launch_merge_copy(const Dev &dv, const Src &src, bool check_app, int slot_old, int slot_new,
+                             int m_before, hipStream_t st);
 hipError_t launch_merge_inplace(const Dev &dv, const Src &src, bool check_app, int slot, hipStream_t st);
 hipError_t launch_refresh(const Dev &dv, int m, int slot, hipStream_t st);
 hipError_t launch_ring_copy(const Dev &dv, const Src &src, int64_t src_t0, int64_t p0, int64_t p1,
