@@ -45,26 +45,34 @@ __device__ __forceinline__ void attn_body(const Dev &dv, const AttnArgs &a, uint
   // chunk x query heads of one KV group) are given to one XCD, whose L2 then serves all but the
   // first read of every tile: consecutive workgroup ids go round-robin over the 8 XCDs, so id % 8
   // picks the XCD and id / 8 walks that XCD's own sequence of (group, member) pairs.
-  const int tpc = (dv.C + kTileQ - 1) / kTileQ;
+  // The workgroup's 32 * NW query rows: with grouped queries (NW query heads or a multiple per KV
+  // head) the waves take the same 32 positions of NW different heads, so that all of them end at
+  // the same causal tile (no wave idles at the barriers while another finishes the diagonal, and
+  // the workgroup stops loading tiles a position block sooner); otherwise consecutive positions
+  // of one head.
   const int Gq = dv.Hq / dv.Hkv;
-  const int per_group = tpc * Gq;
+  const bool by_head = Gq % NW == 0;
+  const int span = by_head ? 32 : kTileQ;   // positions a workgroup covers
+  const int hpw = by_head ? NW : 1;         // heads a workgroup covers
+  const int tpc = (dv.C + span - 1) / span;
+  const int per_group = tpc * (Gq / hpw);
   const int n_groups = a.n_chunks * dv.Hkv * dv.B;
   const int xcd = blockIdx.x % kXcds, seq = blockIdx.x / kXcds;
   const int group = (seq / per_group) * kXcds + xcd;
   if (group >= n_groups) return;
   const int member = seq % per_group;
-  const int qt = member % tpc, gq = member / tpc;
+  const int qt = member % tpc, gq = (member / tpc) * hpw + (by_head ? wave : 0);
   const int ci = group % a.n_chunks;
   const int hkv = (group / a.n_chunks) % dv.Hkv;
   const int b = group / (a.n_chunks * dv.Hkv);
-  const int hq = hkv * Gq + gq;
+  const int hq = __builtin_amdgcn_readfirstlane(hkv * Gq + gq);
   const int u = b * dv.Hkv + hkv;
-  const int Q0 = (tpc - 1 - qt) * kTileQ;                                // longest causal part first
+  const int Q0 = (tpc - 1 - qt) * span;                                  // longest causal part first
   const int nq = ci == a.n_chunks - 1 ? a.nq_total - ci * dv.C : dv.C;  // queries of this chunk
   if (Q0 >= nq) return;
   const int64_t cs = a.s + (int64_t)ci * dv.C;                           // chunk start position
   const int64_t wb = cs + dv.C - dv.L > 0 ? cs + dv.C - dv.L : 0;        // first window position
-  const int wq0 = Q0 + 32 * wave;
+  const int wq0 = by_head ? Q0 : Q0 + 32 * wave;
   const int myq = wq0 + l32;
   const int m = a.m[ci];
 
@@ -93,7 +101,7 @@ __device__ __forceinline__ void attn_body(const Dev &dv, const AttnArgs &a, uint
   c_bswa = fabsf(c_bswa);
 
   const int n_st = __builtin_amdgcn_readfirstlane((m + kTileKeys - 1) / kTileKeys);
-  const int qend = (Q0 + kTileQ < nq) ? Q0 + kTileQ : nq;  // one past the last valid query here
+  const int qend = (Q0 + span < nq) ? Q0 + span : nq;  // one past the last valid query here
   const int n_win = (int)((cs + qend - wb + kTileKeys - 1) / kTileKeys);
   const int n_tiles = __builtin_amdgcn_readfirstlane(n_st + n_win);
 
@@ -347,8 +355,10 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel_q128(Dev dv, AttnArgs
 
 hipError_t launch_attn_mfma(const Dev &dv, const AttnArgs &a, hipStream_t st) {
   if (a.nq_total <= 0) return hipSuccess;
-  const int tile_q = 128;
-  const int per_group = ((dv.C + tile_q - 1) / tile_q) * (dv.Hq / dv.Hkv);
+  const int Gq = dv.Hq / dv.Hkv;
+  const bool by_head = Gq % 4 == 0;  // as in the kernel: four heads x 32 positions, or 128 positions of one head
+  const int span = by_head ? 32 : 128;
+  const int per_group = ((dv.C + span - 1) / span) * (by_head ? Gq / 4 : Gq);
   const int n_groups = a.n_chunks * dv.Hkv * dv.B;
   dim3 grid((unsigned)((n_groups + kXcds - 1) / kXcds * kXcds * per_group));
   hipLaunchKernelGGL(attn_mfma_kernel_q128, grid, dim3(256), 0, st, dv, a);
