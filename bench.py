@@ -163,14 +163,51 @@ def decode_leg(args, pkg, synth, dev):
     avg_s = dec_ms / max(dec_n, 1) * 1e-3
     gbs = bytes_per_step / avg_s / 1e9 if dec_n else 0.0
     ragged = ragged_decode(pkg, synth, dev, w, pre, qs, ks, vs, out, steps=200)
+    grouped = grouped_decode(pkg, synth, dev, w, steps=200)
     return dict(us_per_token=dt / steps / w.batch * 1e6, us_per_step=dt / steps * 1e6, steps=steps,
-                folds=fold_n, fold_us=fold_ms / max(fold_n, 1) * 1e3, ragged=ragged,
+                folds=fold_n, fold_us=fold_ms / max(fold_n, 1) * 1e3, ragged=ragged, grouped_query=grouped,
                 config=dict(workload="decode", batch=w.batch, heads=w.n_q_heads, head_dim=d, state_rows=m,
                             window=L, chunk_len=C),
                 roofline=dict(bound="hbm", kernel="attn_rows_kernel", achieved=gbs, peak=HBM_PEAK_GBS,
                               unit="GB/s", frac=gbs / HBM_PEAK_GBS,
                               traffic=measured_traffic("attn_rows_kernel_decode_hbm_traffic.txt"),
                               avg_launch_us=avg_s * 1e6, bytes_per_launch=bytes_per_step))
+
+
+def grouped_decode(pkg, synth, dev, w, steps):
+    """The decode workload with the headline workload's grouped queries (32 query heads on 8 KV
+    heads): a workgroup takes a KV head's four query heads together, so every key and value row is
+    fetched once for all of them; the rate is over the distinct K/V bytes of a step."""
+    import torch
+    wg = synth.shrink(w, n_kv_heads=8)
+    pre = synth.make_decode_state(wg, dev)
+    st = pkg.state_for(wg, device=dev, max_tokens=pre["tokens"] + 2 * steps)
+    st.import_(pre)
+    n_in = 16
+    q, k, v = synth.make_qkv(wg, dev, T=n_in, pos0=pre["tokens"])
+    qs = [q[:, t].contiguous() for t in range(n_in)]
+    ks = [k[:, t].contiguous() for t in range(n_in)]
+    vs = [v[:, t].contiguous() for t in range(n_in)]
+    out = torch.empty_like(qs[0])
+    for t in range(10):
+        st.decode(qs[t % n_in], ks[t % n_in], vs[t % n_in], out=out)
+    st.import_(pre)
+    torch.cuda.synchronize()
+    st.profile(True)
+    st.profile_read()
+    t0 = time.perf_counter()
+    for t in range(steps):
+        st.decode(qs[t % n_in], ks[t % n_in], vs[t % n_in], out=out)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    dec_ms, dec_n = st.profile_read()["decode"]
+    L, C, m, d = wg.chunk_len * wg.n_bswa_chunks, wg.chunk_len, wg.state_rows, wg.head_dim
+    mean_w = L - C + 1 + (steps - 1) / 2.0               # the window grows by one per step from L - C + 1
+    nbytes = wg.batch * (wg.n_kv_heads * (m + mean_w) * d * 2 * 2 + wg.n_q_heads * 2 * d * 2)
+    avg_s = dec_ms / max(dec_n, 1) * 1e-3
+    return dict(us_per_token=dt / steps / wg.batch * 1e6, us_per_step=dt / steps * 1e6, steps=steps,
+                n_q_heads=wg.n_q_heads, n_kv_heads=wg.n_kv_heads, kernel_us=avg_s * 1e6,
+                distinct_gbs=nbytes / avg_s / 1e9 if dec_n else 0.0)
 
 
 def ragged_decode(pkg, synth, dev, w, pre, qs, ks, vs, out, steps):

@@ -180,6 +180,15 @@ def test_split_prefill_then_decode_matches_oracle():
     run_prefill_case(w, plain=False, split=512, decode_tail=300 - 128 + 45, check_lse=True)
 
 
+@pytest.mark.parametrize("n_q,n_kv", [(8, 2), (8, 1), (4, 2), (6, 2)])
+def test_bf16_grouped_query_decode(n_q, n_kv):
+    """Decode steps with grouped queries: a workgroup takes four query heads of a KV head together
+    (groups of 4 and 8), two (group of 2), or one (group of 3)."""
+    w = synth().shrink(synth().WORKLOADS["prefill_fixed"], batch=2, n_q_heads=n_q, n_kv_heads=n_kv, seq=512 + 140,
+                       chunk_len=128, budget_fixed=256)
+    run_prefill_case(w, plain=False, decode_tail=140, check_lse=True)
+
+
 def test_f32_split_and_decode():
     w = synth().shrink(synth().WORKLOADS["tiny_f32"], seq=512 + 100)
     run_prefill_case(w, plain=False, split=192, decode_tail=100)
