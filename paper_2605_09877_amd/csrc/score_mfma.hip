@@ -49,16 +49,6 @@ __global__ __launch_bounds__(512, 2) void score_mfma_kernel(Dev dv, int slot, in
   const int n_tiles = (row1 - row0 + kTileKeys - 1) / kTileKeys;
   const int n_stages = (n_tiles + 1) / 2;
 
-  bf16x8 kreg[8];
-  if (wave_active) {
-    const uint16_t *krow = (const uint16_t *)dv.kbar + tj * D;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      Frag8 f;
-      f.q = *reinterpret_cast<const uint4 *>(krow + 16 * ks + 8 * g);
-      kreg[ks] = f.v;
-    }
-  }
   float best_all = -INFINITY, best = -INFINITY;
   int best_i = 0x7fffffff;
   uint32_t koff[8];
@@ -78,10 +68,19 @@ __global__ __launch_bounds__(512, 2) void score_mfma_kernel(Dev dv, int slot, in
       }
     }
   };
-  // the memory keys are in registers before the tile loads start, so that the waits below
-  // count tile loads only
-  __builtin_amdgcn_s_waitcnt(0);
+  // the first stage's tiles and the memory keys travel together; the wait at the top of the
+  // loop is for everything outstanding
   if (n_stages > 0) issue_stage(0);
+  bf16x8 kreg[8];
+  if (wave_active) {
+    const uint16_t *krow = (const uint16_t *)dv.kbar + tj * D;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      Frag8 f;
+      f.q = *reinterpret_cast<const uint4 *>(krow + 16 * ks + 8 * g);
+      kreg[ks] = f.v;
+    }
+  }
   for (int sg = 0; sg < n_stages; ++sg) {
     // stage sg has landed for every wave, and every wave is done reading stage sg - 1
     __builtin_amdgcn_s_waitcnt(0);
