@@ -71,7 +71,10 @@ def round_bf16(x: np.ndarray) -> np.ndarray:
 
 
 def round_io(x: np.ndarray, io: str) -> np.ndarray:
-    """Round to the I/O dtype ('f32' or 'bf16'); result is fp64."""
+    """Round to the I/O dtype ('f32' or 'bf16'); result is fp64.  'f64' rounds nothing (used
+    by the pins that differentiate the layer numerically)."""
+    if io == "f64":
+        return np.asarray(x, dtype=np.float64)
     if io == "bf16":
         return round_bf16(x)
     if io == "f32":
