@@ -157,6 +157,35 @@ int kvm_state_fold(kvm_state *st, const void *k_blk, const void *v_blk, const fl
                    int32_t n_tokens, int64_t e, int32_t *assign_out, float *score_out,
                    void *stream);
 
+/* Backward pass of a whole-sequence prefill (the paper's "Speed Benchmarks" time a backward pass;
+ * what it computes follows from the forward definition in "KVM Formulation" by the chain rule).
+ * `st` must be the state that ONE kvm_prefill_chunked call over exactly these T tokens, from an
+ * empty state, has left (KVM_ERR_STATE otherwise); it is read, not changed.  Given dout, the
+ * gradient of a scalar loss with respect to that call's out, the call writes the gradients with
+ * respect to its q, k, v and gate and to the layer's LN_s parameters and temperatures.
+ *   - Slot assignments are replayed as recorded: `assign` (int32 [folds, B, H_kv, C]) and `score`
+ *     (fp32 [folds, B, H_kv, C, 2]) are the records that kvm_state_trace collected during the
+ *     forward (the argmax is piecewise constant and gets no gradient; the append scores tell the
+ *     token that created a row from tokens that merged into it in the same fold).  The roundings of the memory keys and readout rows to the I/O dtype are passed
+ *     straight through.  A row's radius carries gradient to the value that created the row.
+ *   - q, out, dout, dq: [B, T, H_q, d]; k, v, dk, dv: [B, T, H_kv, d] (I/O dtype, dense);
+ *     gate (nullable: g = 1), dgate: [B, T, H_kv] fp32 (dgate is the gradient at g = 1 when gate is
+ *     NULL; 0 for tokens that were never folded); lse: [B, T, H_q] fp32 as the forward wrote it;
+ *     dgamma, dbeta: [H_kv, d] fp32; dtau_state, dtau_bswa: [H_q] fp32.  Every gradient is
+ *     overwritten (sums over the batch for the parameters).  All device pointers, the caller's.
+ *   - workspace: device, 256-byte aligned, kvm_backward_workspace_bytes(st, T) bytes; rewritten.
+ * Work is enqueued on `stream`; the host is not blocked.  Parameter gradients are summed with
+ * fp64 atomics (their last fp32 bit can differ from run to run). */
+typedef struct kvm_grads {
+  void *dq, *dk, *dv;
+  float *dgate, *dgamma, *dbeta, *dtau_state, *dtau_bswa;
+} kvm_grads;
+size_t kvm_backward_workspace_bytes(const kvm_state *st, int64_t T);
+int kvm_prefill_backward(kvm_state *st, const void *q, const void *k, const void *v, const float *gate,
+                         const void *out, const float *lse, const void *dout, const int32_t *assign,
+                         const float *score, const kvm_grads *grads, int64_t T, void *workspace,
+                         size_t workspace_bytes, void *stream);
+
 /* Introspection (host values, no device work). */
 int kvm_state_rows(const kvm_state *st, int64_t *m_out);          /* current m, same for all units */
 int kvm_state_tokens(const kvm_state *st, int64_t *tokens_seen);

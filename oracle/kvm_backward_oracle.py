@@ -15,6 +15,9 @@ Readings (the paper is silent on all of them):
   * The roundings of the materialised vectors (k-bar, s-hat^K, s-hat^V in the I/O dtype) are
     treated as the identity by the backward pass (straight through); the rounded values are
     the ones the forward used and are used here wherever the forward used them.
+  * The layer's output is a materialised vector too: the backward pass reads it as the forward
+    stored it, rounded to the I/O dtype (it enters through the softmax's own term, the row sums
+    of dy * y).
   * A new row's radius rho = ||v|| carries gradient to the value that created it.
   * The gradient of g is reported also when the forward ran without a gate (g = 1).
   * With grouped queries the gradients of the shared keys, values and state sum over the
@@ -107,8 +110,13 @@ def forward_backward_unit(cfg: ko.KVMConfig, q: np.ndarray, k: np.ndarray, v: np
                           gamma: Optional[np.ndarray] = None, beta: Optional[np.ndarray] = None,
                           tau_state: Optional[np.ndarray] = None, tau_bswa: Optional[np.ndarray] = None,
                           overrides: Optional[Dict[Tuple[int, int], int]] = None,
-                          append_overrides: Optional[Dict[int, Sequence[int]]] = None) -> dict:
+                          append_overrides: Optional[Dict[int, Sequence[int]]] = None,
+                          round_output: bool = True) -> dict:
     """Forward (from an empty state, position 0) and backward of one unit over T tokens.
+
+    round_output=False lets the backward read the unrounded output instead of the stored one:
+    the difference between the two results is how far the rounding of the output alone moves
+    each gradient, which tests use to size their bars.
 
     q, dy: [G, T, d]; k, v: [T, d]; g: [T] or None.  overrides / append_overrides as in
     kvm_oracle.KVMUnit (they let a test follow a run after a counted tie).
@@ -185,7 +193,8 @@ def forward_backward_unit(cfg: ko.KVMConfig, q: np.ndarray, k: np.ndarray, v: np
         b = max(0, (s // C) * C + C - L)
         pos_q, pos_w = np.arange(s, e), np.arange(b, e)
         a_dq, a_dkh, a_dvh, a_dkw, a_dvw, a_dts, a_dtb = attend_backward(
-            q[:, s:e], pos_q, khat, vhat, k[b:e], v[b:e], pos_w, ts, tb, lse[:, s:e], y[:, s:e], dy[:, s:e])
+            q[:, s:e], pos_q, khat, vhat, k[b:e], v[b:e], pos_w, ts, tb, lse[:, s:e],
+            ko.round_io(y[:, s:e], cfg.io) if round_output else y[:, s:e], dy[:, s:e])
         dq[:, s:e] += a_dq
         dk[b:e] += a_dkw
         dv[b:e] += a_dvw

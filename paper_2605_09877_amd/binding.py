@@ -25,6 +25,7 @@ EXPORTS = [
     "kvm_state_tokens", "kvm_state_capacity", "kvm_state_folds", "kvm_state_trace", "kvm_state_grow",
     "kvm_state_export", "kvm_state_import", "kvm_state_profile", "kvm_state_profile_read",
     "kvm_measure_mfma_bf16_peak", "kvm_measure_copy_peak", "kvm_prepare_scratch_bytes", "kvm_prepare_qkv",
+    "kvm_backward_workspace_bytes", "kvm_prefill_backward",
 ]
 
 
@@ -49,6 +50,10 @@ class kvm_prep_params(C.Structure):
         ("lnq_gamma", C.c_void_p), ("lnq_beta", C.c_void_p), ("lnk_gamma", C.c_void_p), ("lnk_beta", C.c_void_p),
         ("w_gate", C.c_void_p),
     ]
+
+
+class kvm_grads(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("dq", "dk", "dv", "dgate", "dgamma", "dbeta", "dtau_state", "dtau_bswa")]
 
 
 class kvm_strides(C.Structure):
@@ -102,6 +107,9 @@ def load_library() -> C.CDLL:
     lib.kvm_prepare_scratch_bytes.restype = C.c_size_t
     lib.kvm_prepare_scratch_bytes.argtypes = [C.POINTER(kvm_prep_params), i64]
     lib.kvm_prepare_qkv.argtypes = [C.POINTER(kvm_prep_params)] + [vp] * 13 + [i64, i64, vp]
+    lib.kvm_backward_workspace_bytes.restype = C.c_size_t
+    lib.kvm_backward_workspace_bytes.argtypes = [vp, i64]
+    lib.kvm_prefill_backward.argtypes = [vp] * 10 + [C.POINTER(kvm_grads), i64, vp, C.c_size_t, vp]
     lib.kvm_measure_mfma_bf16_peak.argtypes = [C.c_int, vp, C.POINTER(C.c_double), vp]
     lib.kvm_measure_copy_peak.argtypes = [vp, vp, C.c_size_t, C.POINTER(C.c_double), vp]
     _lib = lib
@@ -347,6 +355,45 @@ class KVMState:
         cnt = (C.c_int64 * 3)()
         _check(self.lib.kvm_state_profile_read(self.handle, ms, cnt), "kvm_state_profile_read")
         return {k: (ms[i], cnt[i]) for i, k in enumerate(("attn", "fold", "decode"))}
+
+    def backward(self, q, k, v, gate, out, lse, dout, assign, score, workspace=None) -> dict:
+        """kvm_prefill_backward for the prefill this state has just run (one call, from empty, over
+        exactly these tensors).  Returns the gradients as a dict of fresh tensors."""
+        c = self.cfg
+        T = q.shape[1]
+        self._chk(q, (c.batch, T, c.n_q_heads, c.head_dim), self.dtype, "q")
+        self._chk(k, (c.batch, T, c.n_kv_heads, c.head_dim), self.dtype, "k")
+        self._chk(v, (c.batch, T, c.n_kv_heads, c.head_dim), self.dtype, "v")
+        self._chk(out, q.shape, self.dtype, "out")
+        self._chk(dout, q.shape, self.dtype, "dout")
+        self._chk(lse, (c.batch, T, c.n_q_heads), torch.float32, "lse")
+        if gate is not None:
+            self._chk(gate, (c.batch, T, c.n_kv_heads), torch.float32, "gate")
+        if assign is not None:
+            if (assign.dtype != torch.int32 or not assign.is_contiguous() or assign.device != self.device
+                    or tuple(assign.shape[1:]) != (c.batch, c.n_kv_heads, c.chunk_len) or assign.shape[0] < self.folds):
+                raise ValueError("assign: want the contiguous int32 [folds, B, Hkv, C] record of kvm_state_trace")
+            if (score is None or score.dtype != torch.float32 or not score.is_contiguous()
+                    or tuple(score.shape) != tuple(assign.shape) + (2,)):
+                raise ValueError("score: want the fp32 [folds, B, Hkv, C, 2] record of kvm_state_trace")
+        f32 = dict(dtype=torch.float32, device=self.device)
+        g = dict(dq=torch.empty_like(q), dk=torch.empty_like(k), dv=torch.empty_like(v),
+                 dgate=torch.empty((c.batch, T, c.n_kv_heads), **f32),
+                 dgamma=torch.empty((c.n_kv_heads, c.head_dim), **f32),
+                 dbeta=torch.empty((c.n_kv_heads, c.head_dim), **f32),
+                 dtau_state=torch.empty((c.n_q_heads,), **f32), dtau_bswa=torch.empty((c.n_q_heads,), **f32))
+        nbytes = self.lib.kvm_backward_workspace_bytes(self.handle, T)
+        if workspace is None or workspace.numel() < nbytes:
+            workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        grads = kvm_grads(*[g[n].data_ptr() for n in ("dq", "dk", "dv", "dgate", "dgamma", "dbeta", "dtau_state",
+                                                        "dtau_bswa")])
+        with torch.cuda.device(self.device):
+            _check(self.lib.kvm_prefill_backward(self.handle, q.data_ptr(), k.data_ptr(), v.data_ptr(), _ptr(gate),
+                                                 out.data_ptr(), lse.data_ptr(), dout.data_ptr(), _ptr(assign), _ptr(score),
+                                                 C.byref(grads), T, workspace.data_ptr(), workspace.numel(),
+                                                 _stream()), "kvm_prefill_backward")
+        workspace.record_stream(torch.cuda.current_stream(self.device))
+        return g
 
     # ---- tracing, checkpoint
     def trace(self, max_folds: int):

@@ -1,0 +1,506 @@
+// Backward pass of a whole-sequence prefill (the paper's "Speed Benchmarks" time one; what it
+// computes follows from the forward definition in "KVM Formulation" by the chain rule).
+//
+// The walk goes over the chunks in reverse.  For a chunk: first the fold that followed it is
+// undone (its tokens receive the adjoint of the rows they went to -- gated for merged tokens,
+// ungated plus the radius term for the tokens that created a row -- and are subtracted from the
+// running sums again, which turns the sums back into the version the chunk saw); then the
+// chunk's attention is differentiated against that version's readout and its window; then the
+// readout's adjoint goes through LN_s and through the radius normalisation into the adjoint of
+// the sums.  Slot assignments are replayed from the forward's record (the argmax is piecewise
+// constant); the roundings of the materialised vectors are passed straight through.
+//
+// This file holds the kernels for every dtype and head size (vector ALU, fp32 accumulation, the
+// chunk's probabilities and logit adjoints written out once and read by the two contraction
+// kernels) and the walk itself.
+#include "kvm_device.h"
+#include "kvm_internal.h"
+
+namespace kvm {
+
+namespace {
+
+template <typename T, int D>
+__device__ __forceinline__ void load_row(const T *p, int lane, float (&f)[D / 64]) {
+#pragma unroll
+  for (int c = 0; c < D / 64; ++c) f[c] = Io<T>::load(p + lane * (D / 64) + c);
+}
+
+// delta[row] = sum over channels of dout * out ("Readout": the softmax's own term of the chain rule)
+template <typename T, int D>
+__global__ __launch_bounds__(256) void bwd_delta_kernel(const void *out_, const void *dout_, float *delta,
+                                                        int64_t rows) {
+  const T *out = (const T *)out_, *dout = (const T *)dout_;
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  float a[D / 64], b[D / 64];
+  load_row<T, D>(out + row * D, lane, a);
+  load_row<T, D>(dout + row * D, lane, b);
+  float s = 0.f;
+#pragma unroll
+  for (int c = 0; c < D / 64; ++c) s += a[c] * b[c];
+  s = wave_sum(s);
+  if (lane == 0) delta[row] = s;
+}
+
+// Undo fold number `fold` (block [lo, lo + C)): one wave per token.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void bwd_unfold_kernel(Bwd a, int fold, int64_t lo, int m_before) {
+  constexpr int CPL = D / 64;
+  const Dev &dv = a.dv;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int u = blockIdx.y, b = u / dv.Hkv, h = u % dv.Hkv;
+  const int j = blockIdx.x * 4 + wave;
+  if (j >= dv.C) return;
+  const int64_t t = lo + j;
+  const int64_t tok = ((int64_t)b * a.T + t) * dv.Hkv + h;
+  const int row = a.assign[((int64_t)fold * dv.U + u) * dv.C + j];
+  if (row < 0 || row >= dv.Mcap) return;  // not a recorded assignment: leave the token alone
+  // A token bound for a row of this fold's own making either created that row or merged into it
+  // afterwards.  The forward appends the tokens with the smallest (append score, position) keys,
+  // so among the tokens bound for one new row the creator is the one with the smallest key.
+  bool appended = row >= m_before;
+  if (appended) {
+    const int64_t base = ((int64_t)fold * dv.U + u) * dv.C;
+    const float sj = a.score[2 * (base + j)];
+    bool beaten = false;
+    for (int j2 = lane; j2 < dv.C; j2 += 64) {
+      if (j2 != j && a.assign[base + j2] == row) {
+        const float s2 = a.score[2 * (base + j2)];
+        beaten |= s2 < sj || (s2 == sj && j2 < j);
+      }
+    }
+    appended = __ballot(beaten) == 0;
+  }
+  const int64_t ro = ((int64_t)u * dv.Mcap + row) * D;
+  float kf[CPL], vf[CPL];
+  load_row<T, D>((const T *)a.k + tok * D, lane, kf);
+  load_row<T, D>((const T *)a.v + tok * D, lane, vf);
+  // memory key of the token as the forward made it: LN_s in fp64 over the key with its rotary
+  // channels zeroed, rounded to the I/O dtype
+  double x[CPL], s = 0.0;
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) {
+    x[c] = lane * CPL + c < dv.r ? 0.0 : (double)kf[c];
+    s += x[c];
+  }
+  const double mean = wave_sum(s) / (double)D;
+  double qq = 0.0;
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) qq += (x[c] - mean) * (x[c] - mean);
+  const double rden = 1.0 / sqrt(wave_sum(qq) / (double)D + (double)dv.ln_eps);
+  float xhat[CPL], kbar[CPL], ga[CPL];
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) {
+    const int ch = lane * CPL + c;
+    const double g_ = dv.gamma ? (double)dv.gamma[h * D + ch] : 1.0;
+    const double b_ = dv.beta ? (double)dv.beta[h * D + ch] : 0.0;
+    const double xh = (x[c] - mean) * rden;
+    xhat[c] = (float)xh;
+    ga[c] = (float)g_;
+    kbar[c] = Io<T>::round_from(xh * g_ + b_);
+  }
+  const float g = a.gate ? a.gate[tok] : 1.f;
+  float dsk[CPL], dsv[CPL], dkbar[CPL], dvt[CPL];
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) {
+    dsk[c] = a.dsK[ro + lane * CPL + c];
+    dsv[c] = a.dsV[ro + lane * CPL + c];
+  }
+  float dg = 0.f;
+  if (appended) {
+    // a new row is the ungated memory key and value; its radius is the value's length
+    float nn = 0.f;
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) nn += vf[c] * vf[c];
+    const float nv = sqrtf(wave_sum(nn));
+    const float dr = nv > 0.f ? a.drho[(int64_t)u * dv.Mcap + row] / nv : 0.f;
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) {
+      dkbar[c] = dsk[c];
+      dvt[c] = dsv[c] + dr * vf[c];
+    }
+  } else {
+    float dot = 0.f;
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) {
+      dkbar[c] = g * dsk[c];
+      dvt[c] = g * dsv[c];
+      dot += dsk[c] * kbar[c] + dsv[c] * vf[c];
+    }
+    dg = wave_sum(dot);
+    // back to the version before the fold: take the token out of its row's sums again
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) {
+      atomicAdd(a.wsK + ro + lane * CPL + c, -((double)g * (double)kbar[c]));
+      atomicAdd(a.wsV + ro + lane * CPL + c, -(g * vf[c]));
+    }
+  }
+  if (lane == 0) a.dgate[tok] = dg;
+  // through LN_s of the memory key
+  float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) {
+    s1 += dkbar[c] * ga[c];
+    s2 += dkbar[c] * ga[c] * xhat[c];
+  }
+  const float m1 = wave_sum(s1) / (float)D, m2 = wave_sum(s2) / (float)D;
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) {
+    const int ch = lane * CPL + c;
+    const float dkz = (dkbar[c] * ga[c] - m1 - xhat[c] * m2) * (float)rden;
+    if (ch >= dv.r) a.dk_acc[tok * D + ch] += dkz;
+    a.dv_acc[tok * D + ch] += dvt[c];
+    atomicAdd(a.par64 + h * D + ch, (double)(dkbar[c] * xhat[c]));
+    atomicAdd(a.par64 + (dv.Hkv + h) * D + ch, (double)dkbar[c]);
+  }
+}
+
+// Readout of the visited version: rows [0, m) of every unit, as the forward computes it.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void bwd_readout_kernel(Bwd a, int m) {
+  constexpr int CPL = D / 64;
+  const Dev &dv = a.dv;
+  const int lane = threadIdx.x & 63;
+  const int u = blockIdx.y, h = u % dv.Hkv;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= m) return;
+  const int64_t ro = ((int64_t)u * dv.Mcap + row) * D;
+  double sk[CPL], s = 0.0;
+  float sv[CPL], nn = 0.f;
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) {
+    sk[c] = a.wsK[ro + lane * CPL + c];
+    sv[c] = a.wsV[ro + lane * CPL + c];
+    s += sk[c];
+    nn += sv[c] * sv[c];
+  }
+  const double mean = wave_sum(s) / (double)D;
+  double qq = 0.0;
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) qq += (sk[c] - mean) * (sk[c] - mean);
+  const double rden = 1.0 / sqrt(wave_sum(qq) / (double)D + (double)dv.ln_eps);
+  const float vs = dv.rho[(int64_t)u * dv.Mcap + row] / fmaxf(sqrtf(wave_sum(nn)), dv.norm_eps);
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) {
+    const int ch = lane * CPL + c;
+    const double g_ = dv.gamma ? (double)dv.gamma[h * D + ch] : 1.0;
+    const double b_ = dv.beta ? (double)dv.beta[h * D + ch] : 0.0;
+    Io<T>::store((T *)a.khat + ro + ch, Io<T>::round_from((sk[c] - mean) * rden * g_ + b_));
+    Io<T>::store((T *)a.vhat + ro + ch, sv[c] * vs);
+  }
+}
+
+// Adjoint of the readout into the adjoint of the sums: rows [0, m).
+template <typename T, int D>
+__global__ __launch_bounds__(256) void bwd_readout_adjoint_kernel(Bwd a, int m) {
+  constexpr int CPL = D / 64;
+  const Dev &dv = a.dv;
+  const int lane = threadIdx.x & 63;
+  const int u = blockIdx.y, h = u % dv.Hkv;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= m) return;
+  const int64_t ro = ((int64_t)u * dv.Mcap + row) * D;
+  double sk[CPL], s = 0.0;
+  float sv[CPL], dkh[CPL], dvh[CPL], nn = 0.f;
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) {
+    sk[c] = a.wsK[ro + lane * CPL + c];
+    sv[c] = a.wsV[ro + lane * CPL + c];
+    dkh[c] = a.dkhat[ro + lane * CPL + c];
+    dvh[c] = a.dvhat[ro + lane * CPL + c];
+    s += sk[c];
+    nn += sv[c] * sv[c];
+  }
+  const double mean = wave_sum(s) / (double)D;
+  double qq = 0.0;
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) qq += (sk[c] - mean) * (sk[c] - mean);
+  const double rden = 1.0 / sqrt(wave_sum(qq) / (double)D + (double)dv.ln_eps);
+  float xhat[CPL], ga[CPL], s1 = 0.f, s2 = 0.f;
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) {
+    const int ch = lane * CPL + c;
+    xhat[c] = (float)((sk[c] - mean) * rden);
+    ga[c] = dv.gamma ? dv.gamma[h * D + ch] : 1.f;
+    s1 += dkh[c] * ga[c];
+    s2 += dkh[c] * ga[c] * xhat[c];
+  }
+  const float m1 = wave_sum(s1) / (float)D, m2 = wave_sum(s2) / (float)D;
+  // value readout: rho * sV / max(|sV|, eps)
+  const float nrm = sqrtf(wave_sum(nn));
+  const float den = fmaxf(nrm, dv.norm_eps);
+  const float rho = dv.rho[(int64_t)u * dv.Mcap + row];
+  float dot = 0.f;
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) dot += dvh[c] * sv[c];
+  dot = wave_sum(dot) / den;  // dvhat . unit vector
+  const float back = nrm > dv.norm_eps ? rho * dot / (den * den) : 0.f;
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) {
+    const int ch = lane * CPL + c;
+    a.dsK[ro + ch] += (dkh[c] * ga[c] - m1 - xhat[c] * m2) * (float)rden;
+    a.dsV[ro + ch] += rho / den * dvh[c] - back * sv[c];
+    atomicAdd(a.par64 + h * D + ch, (double)(dkh[c] * xhat[c]));
+    atomicAdd(a.par64 + (dv.Hkv + h) * D + ch, (double)dkh[c]);
+  }
+  if (lane == 0) a.drho[(int64_t)u * dv.Mcap + row] += dot;
+}
+
+// One chunk's keys: state rows [0, m) of the visited version, then window positions [wb, s + nq).
+struct ChunkArgs {
+  int64_t s, wb;
+  int32_t nq, m, nk, ld;  // nk = m + window keys; ld = row pitch of P and dS
+};
+
+template <typename T, int D>
+__device__ __forceinline__ void key_of(const Bwd &a, const ChunkArgs &c, int u, int b, int h, int j,
+                                       const T *&key, const T *&val, int64_t &pos) {
+  const Dev &dv = a.dv;
+  if (j < c.m) {
+    const int64_t ro = ((int64_t)u * dv.Mcap + j) * D;
+    key = (const T *)a.khat + ro;
+    val = (const T *)a.vhat + ro;
+    pos = -1;
+  } else {
+    pos = c.wb + (j - c.m);
+    const int64_t tok = ((int64_t)b * a.T + pos) * dv.Hkv + h;
+    key = (const T *)a.k + tok * D;
+    val = (const T *)a.v + tok * D;
+  }
+}
+
+// P and dS of one (query, head): a wave per key in turn.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void bwd_probs_kernel(Bwd a, ChunkArgs c) {
+  constexpr int CPL = D / 64;
+  const Dev &dv = a.dv;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int i = blockIdx.x, g = blockIdx.y, u = blockIdx.z;
+  const int G = dv.Hq / dv.Hkv, b = u / dv.Hkv, h = u % dv.Hkv, hq = h * G + g;
+  const int64_t t = c.s + i;
+  const int64_t qrow = ((int64_t)b * a.T + t) * dv.Hq + hq;
+  float qf[CPL], df[CPL];
+  load_row<T, D>((const T *)a.q + qrow * D, lane, qf);
+  load_row<T, D>((const T *)a.dout + qrow * D, lane, df);
+  const float lse = a.lse[qrow], delta = a.delta[qrow];
+  const float ts = dv.tau_state ? dv.tau_state[hq] : 1.f, tb = dv.tau_bswa ? dv.tau_bswa[hq] : 1.f;
+  const float scale = rsqrtf((float)D);
+  const int64_t prow = (((int64_t)u * G + g) * dv.C + i) * c.ld;
+  float acc_s = 0.f, acc_b = 0.f;
+  for (int j = wave; j < c.nk; j += 4) {
+    const T *key, *val;
+    int64_t pos;
+    key_of<T, D>(a, c, u, b, h, j, key, val, pos);
+    float kf[CPL], vf[CPL];
+    load_row<T, D>(key, lane, kf);
+    load_row<T, D>(val, lane, vf);
+    float d1 = 0.f, d2 = 0.f;
+#pragma unroll
+    for (int cc = 0; cc < CPL; ++cc) {
+      d1 += qf[cc] * kf[cc];
+      d2 += df[cc] * vf[cc];
+    }
+    const float raw = wave_sum(d1) * scale;
+    const float dp = wave_sum(d2);
+    const bool state = j < c.m;
+    const float p = (state || pos <= t) ? __expf((state ? ts : tb) * raw - lse) : 0.f;
+    const float ds = p * (dp - delta);
+    if (lane == 0) {
+      a.P[prow + j] = p;
+      a.dS[prow + j] = ds;
+    }
+    if (state) acc_s += ds * raw; else acc_b += ds * raw;
+  }
+  if (lane == 0) {
+    atomicAdd(a.par64 + 2 * dv.Hkv * D + hq, (double)acc_s);
+    atomicAdd(a.par64 + 2 * dv.Hkv * D + dv.Hq + hq, (double)acc_b);
+  }
+}
+
+// dq of one (query, head): sum over keys of dS * tau * scale * key.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void bwd_dq_kernel(Bwd a, ChunkArgs c) {
+  constexpr int CPL = D / 64;
+  __shared__ float red[4][D];
+  const Dev &dv = a.dv;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int i = blockIdx.x, g = blockIdx.y, u = blockIdx.z;
+  const int G = dv.Hq / dv.Hkv, b = u / dv.Hkv, h = u % dv.Hkv, hq = h * G + g;
+  const int64_t qrow = ((int64_t)b * a.T + c.s + i) * dv.Hq + hq;
+  const float ts = dv.tau_state ? dv.tau_state[hq] : 1.f, tb = dv.tau_bswa ? dv.tau_bswa[hq] : 1.f;
+  const int64_t prow = (((int64_t)u * G + g) * dv.C + i) * c.ld;
+  float acc[CPL] = {};
+  for (int j = wave; j < c.nk; j += 4) {
+    const T *key, *val;
+    int64_t pos;
+    key_of<T, D>(a, c, u, b, h, j, key, val, pos);
+    float kf[CPL];
+    load_row<T, D>(key, lane, kf);
+    const float coef = a.dS[prow + j] * (j < c.m ? ts : tb);
+#pragma unroll
+    for (int cc = 0; cc < CPL; ++cc) acc[cc] += coef * kf[cc];
+  }
+#pragma unroll
+  for (int cc = 0; cc < CPL; ++cc) red[wave][lane * CPL + cc] = acc[cc];
+  __syncthreads();
+  if (wave == 0) {
+    const float scale = rsqrtf((float)D);
+#pragma unroll
+    for (int cc = 0; cc < CPL; ++cc) {
+      const int ch = lane * CPL + cc;
+      Io<T>::store((T *)a.dq + qrow * D + ch, (red[0][ch] + red[1][ch] + red[2][ch] + red[3][ch]) * scale);
+    }
+  }
+}
+
+// Adjoint of one key and its value: sums over the chunk's queries and the group's heads.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void bwd_dkv_kernel(Bwd a, ChunkArgs c) {
+  constexpr int CPL = D / 64;
+  __shared__ float red[2][4][D];
+  const Dev &dv = a.dv;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int j = blockIdx.x, u = blockIdx.y;
+  const int G = dv.Hq / dv.Hkv, b = u / dv.Hkv, h = u % dv.Hkv;
+  const bool state = j < c.m;
+  float ak[CPL] = {}, av[CPL] = {};
+  for (int p = wave; p < G * c.nq; p += 4) {
+    const int g = p / c.nq, i = p % c.nq, hq = h * G + g;
+    const int64_t qrow = ((int64_t)b * a.T + c.s + i) * dv.Hq + hq;
+    const int64_t at = (((int64_t)u * G + g) * dv.C + i) * c.ld + j;
+    const float tau = state ? (dv.tau_state ? dv.tau_state[hq] : 1.f) : (dv.tau_bswa ? dv.tau_bswa[hq] : 1.f);
+    const float ds = a.dS[at] * tau, pr = a.P[at];
+    float qf[CPL], df[CPL];
+    load_row<T, D>((const T *)a.q + qrow * D, lane, qf);
+    load_row<T, D>((const T *)a.dout + qrow * D, lane, df);
+#pragma unroll
+    for (int cc = 0; cc < CPL; ++cc) {
+      ak[cc] += ds * qf[cc];
+      av[cc] += pr * df[cc];
+    }
+  }
+#pragma unroll
+  for (int cc = 0; cc < CPL; ++cc) {
+    red[0][wave][lane * CPL + cc] = ak[cc];
+    red[1][wave][lane * CPL + cc] = av[cc];
+  }
+  __syncthreads();
+  if (wave == 0) {
+    const float scale = rsqrtf((float)D);
+#pragma unroll
+    for (int cc = 0; cc < CPL; ++cc) {
+      const int ch = lane * CPL + cc;
+      const float dk = (red[0][0][ch] + red[0][1][ch] + red[0][2][ch] + red[0][3][ch]) * scale;
+      const float dvv = red[1][0][ch] + red[1][1][ch] + red[1][2][ch] + red[1][3][ch];
+      if (state) {
+        const int64_t ro = ((int64_t)u * dv.Mcap + j) * D;
+        a.dkhat[ro + ch] = dk;
+        a.dvhat[ro + ch] = dvv;
+      } else {
+        const int64_t tok = ((int64_t)b * a.T + c.wb + (j - c.m)) * dv.Hkv + h;
+        a.dk_acc[tok * D + ch] += dk;
+        a.dv_acc[tok * D + ch] += dvv;
+      }
+    }
+  }
+}
+
+// the parameter gradients leave their fp64 accumulators: [dgamma | dbeta | dtau_state | dtau_bswa]
+__global__ __launch_bounds__(256) void bwd_params_kernel(Bwd a) {
+  const int n_ln = a.dv.Hkv * a.dv.d, i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n_ln) {
+    a.dgamma[i] = (float)a.par64[i];
+    a.dbeta[i] = (float)a.par64[n_ln + i];
+  }
+  if (i < a.dv.Hq) {
+    a.dtau_state[i] = (float)a.par64[2 * n_ln + i];
+    a.dtau_bswa[i] = (float)a.par64[2 * n_ln + a.dv.Hq + i];
+  }
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void bwd_cast_kernel(const float *src, T *dst, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) Io<T>::store(dst + i, src[i]);
+}
+
+#define BWD_DISPATCH(dv, KERNEL, grid, block, st, ...)                                    \
+  do {                                                                                    \
+    if ((dv).io == 0 && (dv).d == 64)                                                     \
+      hipLaunchKernelGGL((KERNEL<float, 64>), grid, block, 0, st, __VA_ARGS__);           \
+    else if ((dv).io == 0 && (dv).d == 128)                                               \
+      hipLaunchKernelGGL((KERNEL<float, 128>), grid, block, 0, st, __VA_ARGS__);          \
+    else if ((dv).io == 1 && (dv).d == 64)                                                \
+      hipLaunchKernelGGL((KERNEL<bf16_t, 64>), grid, block, 0, st, __VA_ARGS__);          \
+    else if ((dv).io == 1 && (dv).d == 128)                                               \
+      hipLaunchKernelGGL((KERNEL<bf16_t, 128>), grid, block, 0, st, __VA_ARGS__);         \
+    else                                                                                  \
+      return hipErrorInvalidValue;                                                        \
+    if (hipError_t e_ = hipGetLastError(); e_ != hipSuccess) return e_;                   \
+  } while (0)
+
+#define BWD_TRY(expr)                        \
+  do {                                       \
+    if (hipError_t e_ = (expr); e_ != hipSuccess) return e_; \
+  } while (0)
+
+}  // namespace
+
+hipError_t run_backward(const Bwd &a, const BwdChunk *chunks, int n_chunks, hipStream_t st) {
+  const Dev &dv = a.dv;
+  const int G = dv.Hq / dv.Hkv, D = dv.d;
+  const int64_t state_elems = (int64_t)dv.U * dv.Mcap * D;
+  const int64_t kv_elems = (int64_t)dv.B * a.T * dv.Hkv * D;
+  const int64_t q_rows = (int64_t)dv.B * a.T * dv.Hq;
+  // everything that is accumulated starts at zero; the sums start as the forward left them
+  BWD_TRY(hipMemsetAsync(a.dsK, 0, state_elems * 4, st));
+  BWD_TRY(hipMemsetAsync(a.dsV, 0, state_elems * 4, st));
+  BWD_TRY(hipMemsetAsync(a.drho, 0, (int64_t)dv.U * dv.Mcap * 4, st));
+  BWD_TRY(hipMemsetAsync(a.dk_acc, 0, kv_elems * 4, st));
+  BWD_TRY(hipMemsetAsync(a.dv_acc, 0, kv_elems * 4, st));
+  BWD_TRY(hipMemsetAsync(a.dgate, 0, (int64_t)dv.B * a.T * dv.Hkv * 4, st));
+  BWD_TRY(hipMemsetAsync(a.par64, 0, (size_t)(2 * dv.Hkv * D + 2 * dv.Hq) * 8, st));
+  if (dv.sK) {
+    BWD_TRY(hipMemcpyAsync(a.wsK, dv.sK, state_elems * 8, hipMemcpyDeviceToDevice, st));
+    BWD_TRY(hipMemcpyAsync(a.wsV, dv.sV, state_elems * 4, hipMemcpyDeviceToDevice, st));
+  }
+  BWD_DISPATCH(dv, bwd_delta_kernel, dim3((unsigned)((q_rows + 3) / 4)), dim3(256), st, a.out, a.dout, a.delta, q_rows);
+
+  for (int ci = n_chunks - 1; ci >= 0; --ci) {
+    const BwdChunk &ch = chunks[ci];
+    if (ch.fold >= 0)
+      BWD_DISPATCH(dv, bwd_unfold_kernel, dim3((dv.C + 3) / 4, dv.U), dim3(256), st, a, ch.fold,
+                   ch.s + ch.nq - dv.L, ch.m);
+    const int64_t c0 = ch.s / dv.C * dv.C;
+    ChunkArgs c;
+    c.s = ch.s;
+    c.wb = c0 + dv.C - dv.L > 0 ? c0 + dv.C - dv.L : 0;
+    c.nq = ch.nq;
+    c.m = ch.m;
+    c.nk = ch.m + (int)(ch.s + ch.nq - c.wb);
+    c.ld = dv.Mcap + dv.L;
+    if (ch.m > 0) BWD_DISPATCH(dv, bwd_readout_kernel, dim3((ch.m + 3) / 4, dv.U), dim3(256), st, a, ch.m);
+    BWD_DISPATCH(dv, bwd_probs_kernel, dim3(ch.nq, G, dv.U), dim3(256), st, a, c);
+    BWD_DISPATCH(dv, bwd_dq_kernel, dim3(ch.nq, G, dv.U), dim3(256), st, a, c);
+    BWD_DISPATCH(dv, bwd_dkv_kernel, dim3(c.nk, dv.U), dim3(256), st, a, c);
+    if (ch.m > 0)
+      BWD_DISPATCH(dv, bwd_readout_adjoint_kernel, dim3((ch.m + 3) / 4, dv.U), dim3(256), st, a, ch.m);
+  }
+  {
+    const int n = dv.Hkv * D > dv.Hq ? dv.Hkv * D : dv.Hq;
+    hipLaunchKernelGGL(bwd_params_kernel, dim3((n + 255) / 256), dim3(256), 0, st, a);
+  }
+  const unsigned cast_blocks = (unsigned)((kv_elems + 255) / 256);
+  if (dv.io == 0) {
+    hipLaunchKernelGGL((bwd_cast_kernel<float, 64>), dim3(cast_blocks), dim3(256), 0, st, a.dk_acc, (float *)a.dk, kv_elems);
+    hipLaunchKernelGGL((bwd_cast_kernel<float, 64>), dim3(cast_blocks), dim3(256), 0, st, a.dv_acc, (float *)a.dv_out, kv_elems);
+  } else {
+    hipLaunchKernelGGL((bwd_cast_kernel<bf16_t, 64>), dim3(cast_blocks), dim3(256), 0, st, a.dk_acc, (bf16_t *)a.dk, kv_elems);
+    hipLaunchKernelGGL((bwd_cast_kernel<bf16_t, 64>), dim3(cast_blocks), dim3(256), 0, st, a.dv_acc, (bf16_t *)a.dv_out, kv_elems);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace kvm

@@ -379,6 +379,40 @@ hipError_t next_sync_event(kvm_state *st, hipEvent_t *out) {
   return hipSuccess;
 }
 
+// Work arrays of the backward pass, in the order of kvm::Bwd.
+struct BwdLayout {
+  size_t wsK, wsV, dsK, dsV, drho, khat, vhat, dkhat, dvhat, dk_acc, dv_acc, delta, P, dS, par64, total;
+};
+BwdLayout bwd_layout(const kvm_config &c, int64_t Mcap, int64_t T) {
+  const size_t U = (size_t)c.batch * c.n_kv_heads, d = c.head_dim, C = c.chunk_len;
+  const size_t L = C * c.n_bswa_chunks, es = esize(c.io_dtype), M = (size_t)Mcap;
+  const size_t G = c.n_q_heads / c.n_kv_heads, Tn = (size_t)T;
+  BwdLayout l;
+  size_t o = 0;
+  auto take = [&](size_t bytes) {
+    size_t at = o;
+    o += up256(bytes);
+    return at;
+  };
+  l.wsK = take(U * M * d * 8);
+  l.wsV = take(U * M * d * 4);
+  l.dsK = take(U * M * d * 4);
+  l.dsV = take(U * M * d * 4);
+  l.drho = take(U * M * 4);
+  l.khat = take(U * M * d * es);
+  l.vhat = take(U * M * d * es);
+  l.dkhat = take(U * M * d * 4);
+  l.dvhat = take(U * M * d * 4);
+  l.dk_acc = take(U * Tn * d * 4);
+  l.dv_acc = take(U * Tn * d * 4);
+  l.delta = take((size_t)c.batch * Tn * c.n_q_heads * 4);
+  l.P = take(U * G * C * (M + L) * 4);
+  l.dS = take(U * G * C * (M + L) * 4);
+  l.par64 = take((2 * (size_t)c.n_kv_heads * d + 2 * (size_t)c.n_q_heads) * 8);
+  l.total = o;
+  return l;
+}
+
 bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
 
 // RAII bracket: records a start event now and a stop event when it goes out of scope.
@@ -934,6 +968,65 @@ int kvm_state_fold(kvm_state *st, const void *k_blk, const void *v_blk, const fl
       rows_after(st->cfg, st->table, st->m, e) > dv.Mcap)
     return KVM_ERR_CAPACITY;
   return fold_block(st, src, e, assign_out, score_out, (hipStream_t)stream_, true);
+}
+
+size_t kvm_backward_workspace_bytes(const kvm_state *st, int64_t T) {
+  if (!st || T <= 0) return 0;
+  return bwd_layout(st->cfg, st->dv.Mcap, T).total;
+}
+
+int kvm_prefill_backward(kvm_state *st, const void *q, const void *k, const void *v, const float *gate,
+                         const void *out, const float *lse, const void *dout, const int32_t *assign,
+                         const float *score, const kvm_grads *grads, int64_t T, void *workspace,
+                         size_t workspace_bytes, void *stream) {
+  if (!st || !q || !k || !v || !out || !lse || !dout || !grads || !workspace || T <= 0) return KVM_ERR_ARG;
+  if (!grads->dq || !grads->dk || !grads->dv || !grads->dgate || !grads->dgamma || !grads->dbeta ||
+      !grads->dtau_state || !grads->dtau_bswa)
+    return KVM_ERR_ARG;
+  const kvm_config &c = st->cfg;
+  const int64_t C = c.chunk_len, L = C * c.n_bswa_chunks;
+  // the state must be the one a forward over exactly these T tokens, from empty, has left
+  std::vector<kvm::BwdChunk> chunks;
+  int64_t m = 0, folds = 0;
+  for (int64_t s = 0; s < T; s += C) {
+    const int64_t e = s + C < T ? s + C : T;
+    kvm::BwdChunk ch;
+    ch.s = s;
+    ch.nq = (int32_t)(e - s);
+    ch.m = (int32_t)m;
+    ch.fold = -1;
+    if (e == s + C && e >= L && c.budget_kind != KVM_BUDGET_NONE) {
+      ch.fold = (int32_t)folds++;
+      m = rows_after(c, st->table, m, e);
+    }
+    chunks.push_back(ch);
+  }
+  if (st->tokens != T || st->folds != folds || st->m != m) return KVM_ERR_STATE;
+  if (folds > 0 && (!assign || !score)) return KVM_ERR_ARG;
+  const BwdLayout l = bwd_layout(c, st->dv.Mcap, T);
+  if (workspace_bytes < l.total || ((uintptr_t)workspace & 255)) return KVM_ERR_ARG;
+  const void *ptrs[] = {q, k, v, out, dout, grads->dq, grads->dk, grads->dv};
+  for (const void *p : ptrs)
+    if (!aligned16(p)) return KVM_ERR_ARG;
+  kvm::Bwd a;
+  a.dv = st->dv;
+  a.T = T;
+  a.q = q; a.k = k; a.v = v; a.out = out; a.dout = dout;
+  a.gate = gate; a.lse = lse; a.assign = assign; a.score = score;
+  a.dq = grads->dq; a.dk = grads->dk; a.dv_out = grads->dv;
+  a.dgate = grads->dgate; a.dgamma = grads->dgamma; a.dbeta = grads->dbeta;
+  a.dtau_state = grads->dtau_state; a.dtau_bswa = grads->dtau_bswa;
+  char *w = (char *)workspace;
+  a.wsK = (double *)(w + l.wsK); a.wsV = (float *)(w + l.wsV);
+  a.dsK = (float *)(w + l.dsK); a.dsV = (float *)(w + l.dsV); a.drho = (float *)(w + l.drho);
+  a.khat = w + l.khat; a.vhat = w + l.vhat;
+  a.dkhat = (float *)(w + l.dkhat); a.dvhat = (float *)(w + l.dvhat);
+  a.dk_acc = (float *)(w + l.dk_acc); a.dv_acc = (float *)(w + l.dv_acc);
+  a.delta = (float *)(w + l.delta);
+  a.P = (float *)(w + l.P); a.dS = (float *)(w + l.dS);
+  a.par64 = (double *)(w + l.par64);
+  HIP_TRY(kvm::run_backward(a, chunks.data(), (int)chunks.size(), (hipStream_t)stream));
+  return KVM_OK;
 }
 
 int kvm_state_rows(const kvm_state *st, int64_t *m_out) {

@@ -105,4 +105,38 @@ hipError_t launch_decode_multi(const Dev &dv, const SeqDesc *seq, int n_seq, con
 // attn_mfma.hip (bf16, d = 128)
 hipError_t launch_attn_mfma(const Dev &dv, const AttnArgs &a, hipStream_t st);
 
+// backward.hip: the backward pass of a whole-sequence prefill that started from an empty state.
+// Dense operands: q, out, dout, dq [B, T, Hq, d]; k, v, dk, dv [B, T, Hkv, d]; gate, dgate
+// [B, T, Hkv]; lse [B, T, Hq]; assign [folds, U, C].  The work arrays have the state's row
+// capacity (Mcap rows per unit).
+struct Bwd {
+  Dev dv;  // dimensions, parameters and the final sums (sK, sV, rho) of the state after the forward
+  int64_t T;
+  const void *q, *k, *v, *out, *dout;
+  const float *gate, *lse;
+  const int32_t *assign;
+  const float *score;  // [folds, U, C, 2] the forward's record of (append score, merge score)
+  void *dq, *dk, *dv_out;
+  float *dgate, *dgamma, *dbeta, *dtau_state, *dtau_bswa;
+  // workspace
+  double *wsK;           // [U, Mcap, d] key sums of the version being visited
+  float *wsV;            // [U, Mcap, d]
+  float *dsK, *dsV;      // [U, Mcap, d] adjoints of the sums
+  float *drho;           // [U, Mcap]
+  void *khat, *vhat;     // [U, Mcap, d] I/O dtype: readout of the version being visited
+  float *dkhat, *dvhat;  // [U, Mcap, d] adjoint of that readout (one chunk's)
+  float *dk_acc, *dv_acc;  // [B, T, Hkv, d] fp32 accumulators of dk, dv
+  float *delta;          // [B, T, Hq] sum over channels of dout * out
+  float *P, *dS;         // [U, G, C, Mcap + L] probabilities and logit adjoints of one chunk
+  double *par64;         // [2 * Hkv * d + 2 * Hq] fp64 accumulators of dgamma, dbeta, dtau_state, dtau_bswa
+};
+// one chunk of the walk: its queries, the state rows it saw, and the fold that followed it
+struct BwdChunk {
+  int64_t s;       // first position
+  int32_t nq;      // queries
+  int32_t m;       // state rows the chunk saw ( = rows before the fold that follows)
+  int32_t fold;    // index of the fold that followed the chunk, or -1
+};
+hipError_t run_backward(const Bwd &a, const BwdChunk *chunks, int n_chunks, hipStream_t st);
+
 }  // namespace kvm

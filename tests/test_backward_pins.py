@@ -21,15 +21,20 @@ from oracle import kvm_backward_oracle as kb
 from oracle import kvm_oracle as ko
 
 
-def make_case(seed, T, C=8, n_bswa=2, d=16, r=4, G=2, budget=("fixed", 12), n_sink=1, gated=True):
+def make_case(seed, T, C=8, n_bswa=2, d=16, r=4, G=2, budget=("fixed", 12), n_sink=1, gated=True, twins=()):
     rng = np.random.default_rng(seed)
-    kind = {"fixed": ko.BUDGET_FIXED, "sqrt": ko.BUDGET_SQRT, "none": ko.BUDGET_NONE}[budget[0]]
+    kind = {"fixed": ko.BUDGET_FIXED, "sqrt": ko.BUDGET_SQRT, "none": ko.BUDGET_NONE,
+            "table": ko.BUDGET_TABLE}[budget[0]]
     cfg = ko.KVMConfig(head_dim=d, rope_dims=r, chunk_len=C, n_bswa_chunks=n_bswa, n_sink=n_sink, io="f64",
                        budget_kind=kind, budget_fixed=budget[1] if kind == ko.BUDGET_FIXED else 0,
-                       budget_scale=budget[1] if kind == ko.BUDGET_SQRT else 0.0)
+                       budget_scale=budget[1] if kind == ko.BUDGET_SQRT else 0.0,
+                       budget_table=budget[1] if kind == ko.BUDGET_TABLE else None)
     # clustered keys, so that merges have clear winners and a small step flips no assignment
     centres = rng.normal(size=(5, d)) * 1.5
     k = centres[rng.integers(0, 5, size=T)] + 0.3 * rng.normal(size=(T, d))
+    # twins: positions that share a centre of their own, unlike anything else
+    if twins:
+        k[list(twins)] = 2.0 * rng.normal(size=d) + 0.05 * rng.normal(size=(len(twins), d))
     x = dict(q=rng.normal(size=(G, T, d)), k=k, v=rng.normal(size=(T, d)),
              g=(1.0 + np.abs(rng.normal(size=T))) if gated else np.ones(T),
              gamma=rng.uniform(0.5, 1.5, size=d), beta=0.1 * rng.normal(size=d),
@@ -68,6 +73,8 @@ CASES = [
     dict(seed=2, T=61, budget=("sqrt", 2.0)),                 # growing state: partial appends; ragged tail
     dict(seed=3, T=72, budget=("fixed", 20), n_bswa=3, G=1),  # three-chunk window
     dict(seed=4, T=48, budget=("fixed", 8), n_sink=0, gated=False),
+    # one row per fold: of two twin outliers in a block one creates a row and the other joins it
+    dict(seed=5, T=48, budget=("table", [8, 8, 9, 10, 11, 12]), twins=(10, 13)),
 ]
 
 
@@ -117,6 +124,21 @@ def test_every_fold_kind_occurs_in_the_cases():
             else:
                 kinds.add("merge only")
     assert kinds == {"creation", "append all", "partial append", "merge only"}
+
+
+def test_some_token_merges_into_a_row_created_by_the_same_fold():
+    """That token is gated and gets a gate gradient although its row number is a new one -- the
+    case that separates "went to a new row" from "created a row"."""
+    hits = 0
+    for case in CASES:
+        cfg, x, dy, G = make_case(**case)
+        gr, out = grads(cfg, x, dy, G)
+        L = cfg.window
+        for f, log in enumerate(out["fold_logs"]):
+            late = (log["assign"] >= log["m_before"]) & ~log["appended"]
+            if log["m_before"] > 0 and late.any():
+                hits += int(late.sum())
+    assert hits > 0
 
 
 def test_without_state_equals_autodiff_of_block_sliding_window_attention():

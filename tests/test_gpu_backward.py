@@ -1,0 +1,167 @@
+"""Parity of kvm_prefill_backward (through the C ABI) with the backward oracle, unit by unit, on
+seeded inputs: every gradient, element by element.
+
+Bars.  fp32 I/O: max-abs error <= 1e-4 * max(1, max-abs of the reference tensor) (the gradients
+are fp32 sums of up to (m + L) * G * C products of O(1) numbers); 1e-3 for the temperature and
+LN_s gradients, which are sums over every row of the sequence of terms of both signs whose
+absolute values add up to some 1e2..1e3 times the result, so that fp32 rounding of the terms
+(and the order in which token sums are taken apart again) shows at the 1e-4 level.  bf16 I/O: max-abs error <= 2e-2 *
+max-abs of the reference tensor of the unit (of the whole tensor for the parameter gradients).  The
+bf16 bar is relative to the tensor, not to the row: the backward reads the forward's output in
+bf16, and an output within the forward's own bar of the oracle's (an ulp here and there) moves the
+softmax term D_i = sum_c dy_ic y_ic by up to 2^-8 sum_c |dy_ic y_ic|, which reaches dq_i and the
+dk_j of every visible key in absolute terms however small that row's own gradient is (measured on
+the bf16 case below: 1e-2 of the tensor's max-abs at worst, 1e-3 at the median).  Sums over all
+rows (the temperature and LN_s gradients) collect that term from every row; for them the bar adds
+twice the amount by which rounding the output to bf16 moves the oracle's own result (the oracle
+run with and without that rounding).  Slot assignments follow the forward's record under the tie
+protocol of kvm_testlib.
+"""
+import numpy as np
+import pytest
+import torch
+
+import kvm_testlib as tl
+from oracle import kvm_backward_oracle as kb
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def kvm():
+    import paper_2605_09877_amd as pkg
+    return pkg
+
+
+def synth():
+    from paper_2605_09877_amd import synth as s
+    return s
+
+
+def oracle_unit_following(w, params, u, dy, h, gpu_assign, max_rounds=50, **kw):
+    """forward_backward_unit with the library's counted ties overridden (see kvm_testlib)."""
+    G = w.n_q_heads // w.n_kv_heads
+    pick = lambda key, sl: None if params.get(key) is None else tl.f64(params[key][sl])
+    overrides, app_overrides = {}, {}
+    for _ in range(max_rounds):
+        res = kb.forward_backward_unit(
+            tl.oracle_cfg(w), u["q"], u["k"], u["v"], u["g"], dy, G, pick("ln_gamma", h), pick("ln_beta", h),
+            pick("tau_state", slice(h * G, (h + 1) * G)), pick("tau_bswa", slice(h * G, (h + 1) * G)),
+            overrides=overrides, append_overrides=app_overrides, **kw)
+        bad = None
+        for f, log in enumerate(res["fold_logs"]):
+            if not np.array_equal(log["assign"], gpu_assign[f]):
+                bad = (f, log, gpu_assign[f])
+                break
+        if bad is None:
+            return res
+        f, log, ga = bad
+        m0 = log["m_before"]
+        gpu_app = sorted(int(j) for j in np.nonzero(ga >= m0)[0]) if m0 > 0 else None
+        ora_app = sorted(int(j) for j in np.nonzero(log["appended"])[0]) if m0 > 0 else None
+        if m0 > 0 and gpu_app != ora_app:
+            app_overrides[f] = gpu_app
+        else:
+            j = int(np.nonzero(log["assign"] != ga)[0][0])
+            overrides[(f, j)] = int(ga[j])
+    raise AssertionError("tie protocol did not converge")
+
+
+def check(w, name, got, ref, slack=0.0, f32_bar=1e-4):
+    err = np.abs(got - ref)
+    top = float(np.abs(ref).max())
+    if w.io == "f32":
+        assert err.max() <= f32_bar * max(1.0, top), f"{name}: fp32 max-abs error {err.max():.3e} (reference max {top:.3e})"
+        return
+    worst = float(err.max() / (2e-2 * top + slack + 1e-6))
+    assert worst <= 1.0, f"{name}: bf16 error is {worst:.3f} x the 2e-2 bound"
+
+
+def run_backward_case(w, plain):
+    pkg, sy = kvm(), synth()
+    q, k, v = sy.make_qkv(w, DEV)
+    params = sy.make_params(w, DEV, plain=plain)
+    gate = params["gate"]
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(w.seed + 31337)
+    dout = torch.randn(q.shape, generator=gen, device=DEV, dtype=torch.float32).to(q.dtype)
+    st = pkg.state_for(w, device=DEV, **params)
+    assign, score = st.trace(w.seq // w.chunk_len + 1)
+    out, lse = st.prefill(q, k, v, gate, want_lse=True)
+    g = st.backward(q, k, v, gate, out, lse, dout, assign, score)
+    torch.cuda.synchronize()
+    ga_all = assign[:st.folds].cpu().numpy()
+    G = w.n_q_heads // w.n_kv_heads
+    d = w.head_dim
+    sums = dict(dgamma=np.zeros((w.n_kv_heads, d)), dbeta=np.zeros((w.n_kv_heads, d)),
+                dtau_state=np.zeros(w.n_q_heads), dtau_bswa=np.zeros(w.n_q_heads))
+    slack = {name: 0.0 for name in sums}
+    kinds = set()
+    for b in range(w.batch):
+        for h in range(w.n_kv_heads):
+            u = tl.unit_inputs(w, q, k, v, params, b, h)
+            dy = tl.f64(dout[b, :, h * G:(h + 1) * G]).transpose(1, 0, 2)
+            res = oracle_unit_following(w, params, u, dy, h, ga_all[:, b, h])
+            assert res["m"] == st.rows and len(res["fold_logs"]) == st.folds
+            for log in res["fold_logs"]:
+                kinds.add("creation" if log["m_before"] == 0 else "append all" if log["n_append"] == w.chunk_len
+                          else "partial append" if log["n_append"] > 0 else "merge only")
+            what = f"unit {(b, h)}"
+            check(w, f"dq {what}", tl.f64(g["dq"][b, :, h * G:(h + 1) * G]).transpose(1, 0, 2), res["dq"])
+            check(w, f"dk {what}", tl.f64(g["dk"][b, :, h]), res["dk"])
+            check(w, f"dv {what}", tl.f64(g["dv"][b, :, h]), res["dv"])
+            check(w, f"dgate {what}", tl.f64(g["dgate"][b, :, h]), res["dg"])
+            if w.io == "bf16":
+                exact = oracle_unit_following(w, params, u, dy, h, ga_all[:, b, h], round_output=False)
+                for name in slack:
+                    slack[name] += 2.0 * float(np.abs(res[name] - exact[name]).max())
+            sums["dgamma"][h] += res["dgamma"]
+            sums["dbeta"][h] += res["dbeta"]
+            sums["dtau_state"][h * G:(h + 1) * G] += res["dtau_state"]
+            sums["dtau_bswa"][h * G:(h + 1) * G] += res["dtau_bswa"]
+    for name, ref in sums.items():
+        check(w, name, tl.f64(g[name]), ref, slack[name], f32_bar=1e-3)
+    return kinds
+
+
+def test_f32_backward_fixed_budget_with_parameters():
+    w = synth().shrink(synth().WORKLOADS["tiny_f32"], batch=2, seq=64 * 9 + 17)
+    kinds = run_backward_case(w, plain=False)
+    assert {"creation", "merge only"} <= kinds
+
+
+def test_f32_backward_growing_state_grouped_queries():
+    w = synth().shrink(synth().WORKLOADS["tiny_f32"], n_q_heads=4, n_kv_heads=2, seq=64 * 12, budget_kind="sqrt",
+                       budget_scale=4.0, n_sink=2)
+    kinds = run_backward_case(w, plain=False)
+    assert "partial append" in kinds
+
+
+def test_f32_backward_plain_parameters_three_chunk_window():
+    w = synth().shrink(synth().WORKLOADS["tiny_f32"], seq=64 * 8, n_bswa_chunks=3, budget_fixed=160)
+    kinds = run_backward_case(w, plain=True)
+    assert "append all" in kinds or "partial append" in kinds
+
+
+def test_f32_backward_without_state():
+    w = synth().shrink(synth().WORKLOADS["tiny_f32"], seq=64 * 4 + 5, budget_kind="none")
+    run_backward_case(w, plain=False)
+
+
+def test_bf16_backward_d128():
+    w = synth().shrink(synth().WORKLOADS["prefill_fixed"], batch=1, n_q_heads=4, n_kv_heads=2, seq=128 * 7 + 64,
+                       chunk_len=128, budget_fixed=192)
+    run_backward_case(w, plain=False)
+
+
+def test_backward_rejects_a_state_that_did_not_run_this_prefill():
+    pkg, sy = kvm(), synth()
+    from paper_2605_09877_amd import binding
+    w = sy.shrink(sy.WORKLOADS["tiny_f32"], seq=256)
+    q, k, v = sy.make_qkv(w, DEV)
+    st = pkg.state_for(w, device=DEV)
+    assign, score = st.trace(8)
+    out, lse = st.prefill(q, k, v, None, want_lse=True)
+    with pytest.raises(binding.KVMError):
+        st.backward(q[:, :128].contiguous(), k[:, :128].contiguous(), v[:, :128].contiguous(), None,
+                    out[:, :128].contiguous(), lse[:, :128].contiguous(), out[:, :128].contiguous(), assign, score)
