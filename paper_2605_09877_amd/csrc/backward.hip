@@ -13,6 +13,8 @@
 // This file holds the kernels for every dtype and head size (vector ALU, fp32 accumulation, the
 // chunk's probabilities and logit adjoints written out once and read by the two contraction
 // kernels) and the walk itself.
+#include <stdlib.h>
+
 #include "kvm_device.h"
 #include "kvm_internal.h"
 
@@ -468,6 +470,11 @@ hipError_t run_backward(const Bwd &a, const BwdChunk *chunks, int n_chunks, hipS
   }
   BWD_DISPATCH(dv, bwd_delta_kernel, dim3((unsigned)((q_rows + 3) / 4)), dim3(256), st, a.out, a.dout, a.delta, q_rows);
 
+  static const bool no_mfma = [] {
+    const char *e = getenv("KVM_BACKWARD_GENERIC");  // "1": the vector-ALU kernels everywhere (comparisons)
+    return e && e[0] == '1';
+  }();
+  const bool on_mfma = backward_on_mfma(dv) && !no_mfma;
   for (int ci = n_chunks - 1; ci >= 0; --ci) {
     const BwdChunk &ch = chunks[ci];
     if (ch.fold >= 0)
@@ -482,9 +489,13 @@ hipError_t run_backward(const Bwd &a, const BwdChunk *chunks, int n_chunks, hipS
     c.nk = ch.m + (int)(ch.s + ch.nq - c.wb);
     c.ld = dv.Mcap + dv.L;
     if (ch.m > 0) BWD_DISPATCH(dv, bwd_readout_kernel, dim3((ch.m + 3) / 4, dv.U), dim3(256), st, a, ch.m);
-    BWD_DISPATCH(dv, bwd_probs_kernel, dim3(ch.nq, G, dv.U), dim3(256), st, a, c);
-    BWD_DISPATCH(dv, bwd_dq_kernel, dim3(ch.nq, G, dv.U), dim3(256), st, a, c);
-    BWD_DISPATCH(dv, bwd_dkv_kernel, dim3(c.nk, dv.U), dim3(256), st, a, c);
+    if (on_mfma) {
+      BWD_TRY(launch_backward_mfma(a, ch.s, ch.nq, ch.m, st));
+    } else {
+      BWD_DISPATCH(dv, bwd_probs_kernel, dim3(ch.nq, G, dv.U), dim3(256), st, a, c);
+      BWD_DISPATCH(dv, bwd_dq_kernel, dim3(ch.nq, G, dv.U), dim3(256), st, a, c);
+      BWD_DISPATCH(dv, bwd_dkv_kernel, dim3(c.nk, dv.U), dim3(256), st, a, c);
+    }
     if (ch.m > 0)
       BWD_DISPATCH(dv, bwd_readout_adjoint_kernel, dim3((ch.m + 3) / 4, dv.U), dim3(256), st, a, ch.m);
   }

@@ -1,0 +1,428 @@
+// Attention part of the backward pass for bf16, head_dim 128 on the gfx950 matrix cores.
+//
+// One kernel body in two roles.  Each wave keeps 32 "stationary" vectors in registers, as B
+// operands, and walks 64-row "streamed" tiles that come through LDS:
+//   role dQ : stationary = 32 queries (q and dout rows), streamed = keys (state rows of the
+//             visited version, then window tokens; K and V rows)           -> dq
+//   role dKV: stationary = 32 keys (K and V rows), streamed = the chunk's queries, head after
+//             head of the group (q and dout rows)                          -> dk, dv (or the
+//             adjoint of the state readout)
+// Per streamed tile and wave, with X the streamed "key-like" tile (K or q) and Y the streamed
+// "value-like" tile (V or dout):
+//   S^T  = X . staK^T           16 matrix instructions (32x32x16)    logits, transposed
+//   dP^T = Y . staV^T           16
+//   P^T  = exp(tau * scale * S^T - lse),  dS^T = P^T * (dP^T - D)   lse and D belong to the query:
+//          to the lane's own column in role dQ, to the row in role dKV (then they come from LDS)
+//   O1^T += X^T . (tau dS^T)    16      dq^T resp. dk^T
+//   O2^T += Y^T . P^T           16      role dKV only: dv^T
+// Both products that need a streamed tile transposed read it through the transposing LDS load
+// from the one swizzled image that the first two products read row by row.  Tiles are filled by
+// direct global -> LDS loads one tile ahead, one barrier per tile, like the forward kernel.
+#include <type_traits>
+
+#include "kvm_device.h"
+#include "kvm_internal.h"
+#include "kvm_mfma.h"
+
+namespace kvm {
+
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr int kXcds = 8;
+constexpr int kStaPerWg = 128;                                      // stationary vectors per workgroup (4 waves)
+constexpr int kBwdLdsBytes = 4 * kTileElems * 2 + 2 * 2 * 64 * 4;   // 2 stages x 2 images + row scalars
+
+// Transposed (A-operand) fragment of a K-swizzled row-major tile: lane gets channel
+// 32*dblk + lane%32 and rows 16*ks + 4*g + {0..3}, 16*ks + 8 + 4*g + {0..3}.  Lane j of a group
+// of 16 addresses row 4*g + j/4 (+ 8 for the second read) and the 8 bytes at channel
+// 32*dblk + 16*half + 4*(j%4); chunk q of row r sits in slot q ^ (r & 15).
+__device__ __forceinline__ void ttile_offsets(int lane, uint32_t (&off)[4][2]) {
+  const int j = lane & 15, t = j >> 2, c = j & 3;
+  const int g = lane >> 5, half = (lane >> 4) & 1;
+  const int x = 2 * half + (c >> 1);
+#pragma unroll
+  for (int dblk = 0; dblk < 4; ++dblk)
+#pragma unroll
+    for (int hi = 0; hi < 2; ++hi) {
+      const int r = 8 * hi + 4 * g + t;
+      const int slot = ((dblk ^ (2 * hi + g)) << 2) | (x ^ t);
+      off[dblk][hi] = (uint32_t)(r * kHeadDim + 8 * slot + 4 * (c & 1));
+    }
+}
+__device__ __forceinline__ bf16x8 ttile_frag(const uint16_t *tile, const uint32_t (&off)[4][2], int dblk, int ks) {
+  const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(KVM_LDS_V4(tile + off[dblk][0] + 16 * ks * kHeadDim));
+  const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(KVM_LDS_V4(tile + off[dblk][1] + 16 * ks * kHeadDim));
+  Frag8 f;
+  f.d[0] = __builtin_bit_cast(uint2, lo);
+  f.d[1] = __builtin_bit_cast(uint2, hi);
+  return f.v;
+}
+
+struct MfmaChunk {
+  int64_t cs, wb;  // chunk start, first window position
+  int32_t nq, m;   // queries of the chunk, state rows it saw
+};
+
+template <bool kKeysSta>
+__global__ __launch_bounds__(256, kKeysSta ? 1 : 2) void bwd_mfma_kernel(Bwd a, MfmaChunk c) {
+  extern __shared__ __attribute__((aligned(1024))) uint16_t lds[];
+  float *rowsc = reinterpret_cast<float *>(lds + 4 * kTileElems);  // [stage][lse * log2e | D][64]
+  constexpr int D = kHeadDim;
+  const Dev &dv = a.dv;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = lane >> 5, l32 = lane & 31;
+  const int G = dv.Hq / dv.Hkv;
+  const int n_keys_win = (int)(c.cs + c.nq - c.wb);
+  const int n_st_wg = (c.m + kStaPerWg - 1) / kStaPerWg;
+  const int tpc = (c.nq + kStaPerWg - 1) / kStaPerWg;
+  // consecutive workgroup ids go round-robin over the 8 XCDs: a unit's workgroups share one L2
+  const int per_group = kKeysSta ? n_st_wg + (n_keys_win + kStaPerWg - 1) / kStaPerWg : G * tpc;
+  const int xcd = blockIdx.x % kXcds, seq = blockIdx.x / kXcds;
+  const int u = (seq / per_group) * kXcds + xcd;
+  if (u >= dv.U) return;
+  const int member = seq % per_group;
+  const int b = u / dv.Hkv, h = u % dv.Hkv;
+  const float scale = rsqrtf((float)D);
+
+  // ---- stationary vectors
+  bool col_ok;
+  const uint16_t *sk_row, *sv_row;
+  int colq = 0;          // role dQ: the lane's query within the chunk
+  int64_t kpos = -1;     // role dKV, window keys: the lane's key position
+  int hq_sta = 0, st_row = 0;
+  bool sta_state = false;
+  int wg_first = 0;      // role dKV, window keys: first key position of the workgroup, relative to cs
+  if constexpr (!kKeysSta) {
+    const int qt = member % tpc, gq = member / tpc;
+    hq_sta = __builtin_amdgcn_readfirstlane(h * G + gq);
+    colq = kStaPerWg * qt + 32 * wave + l32;
+    col_ok = colq < c.nq;
+    const int qc = col_ok ? colq : c.nq - 1;
+    const int64_t qrow = ((int64_t)b * a.T + c.cs + qc) * dv.Hq + hq_sta;
+    sk_row = (const uint16_t *)a.q + qrow * D;
+    sv_row = (const uint16_t *)a.dout + qrow * D;
+  } else {
+    sta_state = member < n_st_wg;
+    if (sta_state) {
+      st_row = kStaPerWg * member + 32 * wave + l32;
+      col_ok = st_row < c.m;
+      const int64_t ro = ((int64_t)u * dv.Mcap + (col_ok ? st_row : c.m - 1)) * D;
+      sk_row = (const uint16_t *)a.khat + ro;
+      sv_row = (const uint16_t *)a.vhat + ro;
+    } else {
+      const int64_t first = c.wb + (int64_t)kStaPerWg * (member - n_st_wg);
+      wg_first = (int)(first - c.cs);
+      kpos = first + 32 * wave + l32;
+      col_ok = kpos < c.cs + c.nq;
+      const int64_t tok = ((int64_t)b * a.T + (col_ok ? kpos : c.cs + c.nq - 1)) * dv.Hkv + h;
+      sk_row = (const uint16_t *)a.k + tok * D;
+      sv_row = (const uint16_t *)a.v + tok * D;
+    }
+  }
+  bf16x8 sk[8], sv[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    Frag8 f;
+    f.q = *reinterpret_cast<const uint4 *>(sk_row + 16 * ks + 8 * g);
+    sk[ks] = f.v;
+    f.q = *reinterpret_cast<const uint4 *>(sv_row + 16 * ks + 8 * g);
+    sv[ks] = f.v;
+  }
+  float lse2_col = 0.f, d_col = 0.f;
+  if constexpr (!kKeysSta) {
+    const int qc = col_ok ? colq : c.nq - 1;
+    const int64_t qrow = ((int64_t)b * a.T + c.cs + qc) * dv.Hq + hq_sta;
+    lse2_col = a.lse[qrow] * kLog2e;
+    d_col = a.delta[qrow];
+  }
+
+  // ---- streamed tiles
+  int n_st = 0, n_tiles, qt0 = 0, per_head = 1;
+  if constexpr (!kKeysSta) {
+    n_st = (c.m + kTileKeys - 1) / kTileKeys;
+    const int qt = member % tpc;
+    const int qend = kStaPerWg * (qt + 1) < c.nq ? kStaPerWg * (qt + 1) : c.nq;
+    n_tiles = n_st + (int)((c.cs + qend - c.wb + kTileKeys - 1) / kTileKeys);
+  } else {
+    const int n_qt = (c.nq + kTileKeys - 1) / kTileKeys;
+    qt0 = (!sta_state && wg_first > 0) ? wg_first / kTileKeys : 0;
+    per_head = n_qt - qt0;
+    n_tiles = G * per_head;
+  }
+  n_tiles = __builtin_amdgcn_readfirstlane(n_tiles);
+
+  uint32_t koff[8], toff[4][2];
+  ktile_offsets(lane, koff);
+  ttile_offsets(lane, toff);
+  const DmaLane dl = dma_lane(lane);
+  const uint32_t lds_addr = lds_addr_of(lds);
+
+  auto issue_tile = [&](int it) {
+    const char *xb, *yb;
+    uint32_t stride;
+    int valid;
+    if constexpr (!kKeysSta) {
+      if (it < n_st) {
+        const int64_t ro = ((int64_t)u * dv.Mcap + (int64_t)it * kTileKeys) * D * 2;
+        xb = (const char *)a.khat + ro;
+        yb = (const char *)a.vhat + ro;
+        stride = D * 2;
+        valid = c.m - it * kTileKeys;
+      } else {
+        const int64_t p0 = c.wb + (int64_t)(it - n_st) * kTileKeys;
+        const int64_t tok = ((int64_t)b * a.T + p0) * dv.Hkv + h;
+        xb = (const char *)a.k + tok * D * 2;
+        yb = (const char *)a.v + tok * D * 2;
+        stride = (uint32_t)dv.Hkv * D * 2;
+        valid = (int)(c.cs + c.nq - p0);
+      }
+    } else {
+      const int gq = it / per_head, qtile = qt0 + it % per_head;
+      const int64_t qrow = ((int64_t)b * a.T + c.cs + (int64_t)qtile * kTileKeys) * dv.Hq + h * G + gq;
+      xb = (const char *)a.q + qrow * D * 2;
+      yb = (const char *)a.dout + qrow * D * 2;
+      stride = (uint32_t)dv.Hq * D * 2;
+      valid = c.nq - qtile * kTileKeys;
+    }
+    const uint32_t at = lds_addr + (uint32_t)(2 * (it & 1)) * (kTileElems * 2);
+    tile_dma<false, 4>(xb, stride, valid, at, wave, dl);
+    tile_dma<false, 4>(yb, stride, valid, at + kTileElems * 2, wave, dl);
+  };
+  // role dKV: lse and D of a tile's 64 query rows, fetched by the first wave a tile ahead and
+  // put into LDS just before the barrier that publishes the tile
+  float rs_lse = 0.f, rs_d = 0.f;
+  auto fetch_rowsc = [&](int it) {
+    if constexpr (kKeysSta) {
+      if (wave == 0) {
+        const int gq = it / per_head, qtile = qt0 + it % per_head;
+        int r = qtile * kTileKeys + lane;
+        r = r < c.nq ? r : c.nq - 1;
+        const int64_t qrow = ((int64_t)b * a.T + c.cs + r) * dv.Hq + h * G + gq;
+        rs_lse = a.lse[qrow] * kLog2e;
+        rs_d = a.delta[qrow];
+      }
+    }
+  };
+  auto store_rowsc = [&](int it) {
+    if constexpr (kKeysSta) {
+      if (wave == 0) {
+        rowsc[(it & 1) * 128 + lane] = rs_lse;
+        rowsc[(it & 1) * 128 + 64 + lane] = rs_d;
+      }
+    }
+  };
+
+  f32x16 o1[4], o2[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      o1[i][v] = 0.f;
+      o2[i][v] = 0.f;
+    }
+  float tau_sum_state = 0.f, tau_sum_bswa = 0.f;  // role dQ: sum of dS * S over state / window keys
+
+  auto tile_step = [&](int it, auto parity) {
+    store_rowsc(it);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    if (it + 1 < n_tiles) {
+      issue_tile(it + 1);
+      fetch_rowsc(it + 1);
+    }
+    const uint16_t *X = lds + (2 * decltype(parity)::value) * kTileElems;
+    const uint16_t *Y = X + kTileElems;
+    // what this tile is, and whether any of it is visible to this wave's columns
+    bool tile_state;   // logits of this tile use the state temperature
+    int lim_base;      // role dQ: tile rows <= lim_base + (lane's own term) are visible
+    int hq;
+    int row_pos0 = 0;  // role dKV: position of the tile's first query, relative to cs
+    if constexpr (!kKeysSta) {
+      hq = hq_sta;
+      tile_state = it < n_st;
+      if (tile_state) {
+        lim_base = c.m - it * kTileKeys - 1;
+      } else {
+        const int p0rel = (int)(c.wb - c.cs) + (it - n_st) * kTileKeys;
+        if (p0rel > kStaPerWg * (member % tpc) + 32 * wave + 31) return;  // all keys after the wave's queries
+        lim_base = -p0rel;  // visible rows: p0rel + r <= colq
+      }
+    } else {
+      const int gq = it / per_head, qtile = qt0 + it % per_head;
+      hq = __builtin_amdgcn_readfirstlane(h * G + gq);
+      tile_state = sta_state;
+      row_pos0 = qtile * kTileKeys;
+      lim_base = 0;
+      if (!sta_state && wg_first + 32 * wave > row_pos0 + kTileKeys - 1) return;  // all queries before the wave's keys
+    }
+    const float tau = tile_state ? (dv.tau_state ? dv.tau_state[hq] : 1.f) : (dv.tau_bswa ? dv.tau_bswa[hq] : 1.f);
+    const float cexp = tau * scale * kLog2e;
+
+    f32x16 sacc[2], dacc[2];
+    {
+      const f32x16 zero = {0.f};
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk) {
+          sacc[blk] = mfma32(ktile_frag(X, koff, blk, ks), sk[ks], ks == 0 ? zero : sacc[blk]);
+          dacc[blk] = mfma32(ktile_frag(Y, koff, blk, ks), sv[ks], ks == 0 ? zero : dacc[blk]);
+        }
+    }
+    Frag8 pP[4], pS[4];
+    float tsum = 0.f;
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk) {
+      float lse_r[16], d_r[16];
+      if constexpr (kKeysSta) {
+        const float *rl = rowsc + decltype(parity)::value * 128 + 32 * blk + 4 * g;
+#pragma unroll
+        for (int v4 = 0; v4 < 4; ++v4) {
+          const float4 x = *reinterpret_cast<const float4 *>(rl + 8 * v4);
+          const float4 y = *reinterpret_cast<const float4 *>(rl + 64 + 8 * v4);
+          lse_r[4 * v4] = x.x; lse_r[4 * v4 + 1] = x.y; lse_r[4 * v4 + 2] = x.z; lse_r[4 * v4 + 3] = x.w;
+          d_r[4 * v4] = y.x; d_r[4 * v4 + 1] = y.y; d_r[4 * v4 + 2] = y.z; d_r[4 * v4 + 3] = y.w;
+        }
+      }
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int r = 32 * blk + mfma_row(v, g);
+        bool vis;
+        float lse2, dd;
+        if constexpr (!kKeysSta) {
+          vis = tile_state ? r <= lim_base : r <= lim_base + colq;
+          lse2 = lse2_col;
+          dd = d_col;
+        } else {
+          const int qi = row_pos0 + r;  // query index within the chunk
+          vis = qi < c.nq && (sta_state || kpos <= c.cs + qi);
+          lse2 = lse_r[v];
+          dd = d_r[v];
+        }
+        const float s = sacc[blk][v];
+        const float p = vis ? __builtin_amdgcn_exp2f(fmaf(s, cexp, -lse2)) : 0.f;
+        const float ds = p * (dacc[blk][v] - dd);
+        tsum = fmaf(ds, s, tsum);
+        sacc[blk][v] = p;
+        dacc[blk][v] = ds * tau;
+      }
+    }
+    if constexpr (!kKeysSta) {
+      if (tile_state) tau_sum_state += tsum; else tau_sum_bswa += tsum;
+    }
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int v0 = (ks & 1) * 8 + 2 * e;
+        pP[ks].w[e] = pack_bf16(sacc[ks >> 1][v0], sacc[ks >> 1][v0 + 1]);
+        pS[ks].w[e] = pack_bf16(dacc[ks >> 1][v0], dacc[ks >> 1][v0 + 1]);
+      }
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+      for (int dblk = 0; dblk < 4; ++dblk) {
+        o1[dblk] = mfma32(ttile_frag(X, toff, dblk, ks), pS[ks].v, o1[dblk]);
+        if constexpr (kKeysSta) o2[dblk] = mfma32(ttile_frag(Y, toff, dblk, ks), pP[ks].v, o2[dblk]);
+      }
+  };
+
+  // the stationary vectors are in registers from here on (the compiler does not count the tile
+  // loads; said explicitly so that it does not wait for "its" loads inside the loop)
+  __builtin_amdgcn_s_waitcnt(0);
+  if (n_tiles > 0) {
+    issue_tile(0);
+    fetch_rowsc(0);
+  }
+  for (int it = 0; it < n_tiles; it += 2) {
+    tile_step(it, std::integral_constant<int, 0>{});
+    if (it + 1 < n_tiles) tile_step(it + 1, std::integral_constant<int, 1>{});
+  }
+
+  // ---- results
+  if constexpr (!kKeysSta) {
+    if (col_ok) {
+      const int64_t qrow = ((int64_t)b * a.T + c.cs + colq) * dv.Hq + hq_sta;
+      uint16_t *orow = (uint16_t *)a.dq + qrow * D;
+#pragma unroll
+      for (int dblk = 0; dblk < 4; ++dblk)
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) {
+          const uint32_t lo = pack_bf16(o1[dblk][4 * vq] * scale, o1[dblk][4 * vq + 1] * scale);
+          const uint32_t hi = pack_bf16(o1[dblk][4 * vq + 2] * scale, o1[dblk][4 * vq + 3] * scale);
+          *reinterpret_cast<uint2 *>(orow + 32 * dblk + 8 * vq + 4 * g) = make_uint2(lo, hi);
+        }
+    }
+    const float ts = wave_sum(col_ok ? tau_sum_state : 0.f) * scale;
+    const float tb = wave_sum(col_ok ? tau_sum_bswa : 0.f) * scale;
+    if (lane == 0) {
+      atomicAdd(a.par64 + 2 * dv.Hkv * D + hq_sta, (double)ts);
+      atomicAdd(a.par64 + 2 * dv.Hkv * D + dv.Hq + hq_sta, (double)tb);
+    }
+  } else {
+    if (col_ok) {
+      float *dk_row, *dv_row;
+      if (sta_state) {
+        const int64_t ro = ((int64_t)u * dv.Mcap + st_row) * D;
+        dk_row = a.dkhat + ro;
+        dv_row = a.dvhat + ro;
+      } else {
+        const int64_t tok = ((int64_t)b * a.T + kpos) * dv.Hkv + h;
+        dk_row = a.dk_acc + tok * D;
+        dv_row = a.dv_acc + tok * D;
+      }
+#pragma unroll
+      for (int dblk = 0; dblk < 4; ++dblk)
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) {
+          const int ch = 32 * dblk + 8 * vq + 4 * g;
+          float4 k4 = make_float4(o1[dblk][4 * vq] * scale, o1[dblk][4 * vq + 1] * scale, o1[dblk][4 * vq + 2] * scale,
+                                  o1[dblk][4 * vq + 3] * scale);
+          float4 v4 = make_float4(o2[dblk][4 * vq], o2[dblk][4 * vq + 1], o2[dblk][4 * vq + 2], o2[dblk][4 * vq + 3]);
+          if (!sta_state) {
+            const float4 k0 = *reinterpret_cast<const float4 *>(dk_row + ch);
+            const float4 v0 = *reinterpret_cast<const float4 *>(dv_row + ch);
+            k4.x += k0.x; k4.y += k0.y; k4.z += k0.z; k4.w += k0.w;
+            v4.x += v0.x; v4.y += v0.y; v4.z += v0.z; v4.w += v0.w;
+          }
+          *reinterpret_cast<float4 *>(dk_row + ch) = k4;
+          *reinterpret_cast<float4 *>(dv_row + ch) = v4;
+        }
+    }
+  }
+}
+
+}  // namespace
+
+bool backward_on_mfma(const Dev &dv) { return dv.io == 1 && dv.d == kHeadDim; }
+
+// The two launches of one chunk: dq (and the temperature sums), then dk, dv and the readout adjoint.
+hipError_t launch_backward_mfma(const Bwd &a, int64_t cs, int nq, int m, hipStream_t st) {
+  const Dev &dv = a.dv;
+  static bool allowed = false;  // more than 64 KiB of LDS per workgroup has to be asked for once
+  if (!allowed) {
+    hipError_t e = hipFuncSetAttribute((const void *)bwd_mfma_kernel<false>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kBwdLdsBytes);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute((const void *)bwd_mfma_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            kBwdLdsBytes);
+    if (e != hipSuccess) return e;
+    allowed = true;
+  }
+  MfmaChunk c;
+  c.cs = cs;
+  c.wb = cs + dv.C - dv.L > 0 ? cs + dv.C - dv.L : 0;
+  c.nq = nq;
+  c.m = m;
+  const int G = dv.Hq / dv.Hkv;
+  const unsigned groups = (unsigned)((dv.U + kXcds - 1) / kXcds * kXcds);
+  const int per_q = G * ((nq + kStaPerWg - 1) / kStaPerWg);
+  const int per_k = (m + kStaPerWg - 1) / kStaPerWg + ((int)(cs + nq - c.wb) + kStaPerWg - 1) / kStaPerWg;
+  hipLaunchKernelGGL((bwd_mfma_kernel<false>), dim3(groups * per_q), dim3(256), kBwdLdsBytes, st, a, c);
+  hipLaunchKernelGGL((bwd_mfma_kernel<true>), dim3(groups * per_k), dim3(256), kBwdLdsBytes, st, a, c);
+  return hipGetLastError();
+}
+
+}  // namespace kvm

@@ -406,8 +406,11 @@ BwdLayout bwd_layout(const kvm_config &c, int64_t Mcap, int64_t T) {
   l.dk_acc = take(U * Tn * d * 4);
   l.dv_acc = take(U * Tn * d * 4);
   l.delta = take((size_t)c.batch * Tn * c.n_q_heads * 4);
-  l.P = take(U * G * C * (M + L) * 4);
-  l.dS = take(U * G * C * (M + L) * 4);
+  // the chunk's probabilities and logit adjoints are written out only by the vector-ALU kernels
+  const char *env = getenv("KVM_BACKWARD_GENERIC");
+  const bool probs = !(c.io_dtype == KVM_BF16 && c.head_dim == 128) || (env && env[0] == '1');
+  l.P = take(probs ? U * G * C * (M + L) * 4 : 0);
+  l.dS = take(probs ? U * G * C * (M + L) * 4 : 0);
   l.par64 = take((2 * (size_t)c.n_kv_heads * d + 2 * (size_t)c.n_q_heads) * 8);
   l.total = o;
   return l;

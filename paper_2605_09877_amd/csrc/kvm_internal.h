@@ -138,5 +138,8 @@ struct BwdChunk {
   int32_t fold;    // index of the fold that followed the chunk, or -1
 };
 hipError_t run_backward(const Bwd &a, const BwdChunk *chunks, int n_chunks, hipStream_t st);
+// backward_mfma.hip (bf16, d = 128): one chunk's dq, dk, dv and readout adjoint on the matrix cores
+bool backward_on_mfma(const Dev &dv);
+hipError_t launch_backward_mfma(const Bwd &a, int64_t cs, int nq, int m, hipStream_t st);
 
 }  // namespace kvm

@@ -154,6 +154,19 @@ def test_bf16_backward_d128():
     run_backward_case(w, plain=False)
 
 
+def test_bf16_backward_grouped_queries_growing_state_ragged_tail():
+    w = synth().shrink(synth().WORKLOADS["prefill_sqrt"], batch=1, n_q_heads=8, n_kv_heads=2, seq=256 * 6 + 100,
+                       chunk_len=256, budget_scale=8.0)
+    kinds = run_backward_case(w, plain=True)
+    assert "partial append" in kinds
+
+
+def test_bf16_backward_short_chunks_three_chunk_window():
+    w = synth().shrink(synth().WORKLOADS["prefill_gqa_32k"], batch=2, n_q_heads=4, n_kv_heads=2, seq=64 * 11 + 7,
+                       chunk_len=64, n_bswa_chunks=3, budget_fixed=96, rope_dims=32)
+    run_backward_case(w, plain=False)
+
+
 def test_backward_rejects_a_state_that_did_not_run_this_prefill():
     pkg, sy = kvm(), synth()
     from paper_2605_09877_amd import binding
