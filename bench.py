@@ -129,6 +129,41 @@ def prefill_leg(args, pkg, synth, dev):
     return res, (q, k, v)
 
 
+def backward_leg(args, pkg, synth, dev, w):
+    """Backward pass of the same prefill (kvm_prefill_backward): its time alone, on resident
+    tensors, after one forward with the fold record switched on.  Algorithmic flops: five
+    contractions of 2*d flops per visible (query, key) pair -- the logits and dout . v^T once each,
+    dq, dk, dv -- against the forward's two."""
+    import torch
+    q, k, v = synth.make_qkv(w, dev)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(w.seed + 31337)
+    dout = torch.randn(q.shape, generator=gen, device=dev, dtype=torch.float32).to(q.dtype)
+    st = pkg.state_for(w, device=dev)
+    assign, score = st.trace(w.seq // w.chunk_len + 1)
+    out, lse = st.prefill(q, k, v, want_lse=True)
+    nbytes = st.lib.kvm_backward_workspace_bytes(st.handle, w.seq)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    reps = max(2, min(args.steps, 3))
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+    st.backward(q, k, v, None, out, lse, dout, assign, score, workspace=ws)   # warm-up
+    torch.cuda.synchronize()
+    for i in range(reps):
+        marks[i].record()
+        g = st.backward(q, k, v, None, out, lse, dout, assign, score, workspace=ws)
+        del g
+    marks[reps].record()
+    torch.cuda.synchronize()
+    ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(reps))
+    med = ms[len(ms) // 2]
+    flops = attention_flops(w, w.seq)[0] * 2.5
+    tf = flops / (med * 1e-3) / 1e12
+    return dict(ms_per_pass=med, ms_min=ms[0], ms_max=ms[-1], tokens_per_s=w.batch * w.seq / (med * 1e-3),
+                algorithmic_tflop=flops / 1e12, achieved_tflops=tf, frac_of_mfma_peak=tf / MFMA_BF16_PEAK_TFLOPS,
+                workspace_gb=nbytes / 1e9, note="whole pass: 64 chunks x (undo fold, readout, dq kernel, dk/dv kernel, "
+                "readout adjoint); the two matrix-core kernels compute the logits twice (7 contractions run)")
+
+
 def decode_leg(args, pkg, synth, dev):
     """Batched decode workload: successive steps against a pre-built state, folds included."""
     import torch
@@ -404,6 +439,7 @@ def main():
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the two other prefill workloads")
+    ap.add_argument("--no-backward", action="store_true", help="skip the backward pass of the prefill")
     ap.add_argument("--no-isolated", action="store_true",
                     help="skip the extra passes that time folds and attention apart")
     ap.add_argument("--sweep", action="store_true",
@@ -459,6 +495,12 @@ def main():
             del t2
             torch.cuda.empty_cache()
         tensors = None
+    if not args.no_backward:
+        tensors = None
+        torch.cuda.empty_cache()
+        line["backward"] = backward_leg(args, pkg, synth, dev, w)
+        line["backward"]["vs_forward_step"] = line["backward"]["ms_per_pass"] / res["ms_per_step"]
+        torch.cuda.empty_cache()
     if not args.no_others:
         line["prep"] = prep_leg(args, pkg, synth, dev)
         torch.cuda.empty_cache()

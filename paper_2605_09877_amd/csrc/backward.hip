@@ -46,19 +46,43 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(const void *out_, const 
   if (lane == 0) delta[row] = s;
 }
 
-// Undo fold number `fold` (block [lo, lo + C)): one wave per token.
+// The LN_s parameter gradients of a workgroup's rows: summed over its four waves in LDS, then one
+// fp64 atomic per channel (dgamma at par64[h * D + ch], dbeta behind all the dgammas).
+constexpr int kRowsPerWave = 16;
+template <int D>
+__device__ __forceinline__ void block_param_add(const Bwd &a, int h, const float (&dga)[D / 64],
+                                                const float (&dbe)[D / 64], float (*red)[4][D]) {
+  constexpr int CPL = D / 64;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) {
+    red[0][wave][lane * CPL + c] = dga[c];
+    red[1][wave][lane * CPL + c] = dbe[c];
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < 2 * D; i += 256) {
+    const int which = i / D, ch = i % D;
+    const float sum = red[which][0][ch] + red[which][1][ch] + red[which][2][ch] + red[which][3][ch];
+    atomicAdd(a.par64 + (which * a.dv.Hkv + h) * D + ch, (double)sum);
+  }
+}
+
+// Undo fold number `fold` (block [lo, lo + C)): a wave takes 16 tokens, one after the other.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void bwd_unfold_kernel(Bwd a, int fold, int64_t lo, int m_before) {
   constexpr int CPL = D / 64;
+  __shared__ float red[2][4][D];
   const Dev &dv = a.dv;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int u = blockIdx.y, b = u / dv.Hkv, h = u % dv.Hkv;
-  const int j = blockIdx.x * 4 + wave;
-  if (j >= dv.C) return;
+  float dga_sum[CPL] = {}, dbe_sum[CPL] = {};
+  for (int jj = 0; jj < kRowsPerWave; ++jj) {
+  const int j = (blockIdx.x * 4 + wave) * kRowsPerWave + jj;
+  if (j >= dv.C) break;
   const int64_t t = lo + j;
   const int64_t tok = ((int64_t)b * a.T + t) * dv.Hkv + h;
   const int row = a.assign[((int64_t)fold * dv.U + u) * dv.C + j];
-  if (row < 0 || row >= dv.Mcap) return;  // not a recorded assignment: leave the token alone
+  if (row < 0 || row >= dv.Mcap) continue;  // not a recorded assignment: leave the token alone
   // A token bound for a row of this fold's own making either created that row or merged into it
   // afterwards.  The forward appends the tokens with the smallest (append score, position) keys,
   // so among the tokens bound for one new row the creator is the one with the smallest key.
@@ -154,9 +178,11 @@ __global__ __launch_bounds__(256) void bwd_unfold_kernel(Bwd a, int fold, int64_
     const float dkz = (dkbar[c] * ga[c] - m1 - xhat[c] * m2) * (float)rden;
     if (ch >= dv.r) a.dk_acc[tok * D + ch] += dkz;
     a.dv_acc[tok * D + ch] += dvt[c];
-    atomicAdd(a.par64 + h * D + ch, (double)(dkbar[c] * xhat[c]));
-    atomicAdd(a.par64 + (dv.Hkv + h) * D + ch, (double)dkbar[c]);
+    dga_sum[c] += dkbar[c] * xhat[c];
+    dbe_sum[c] += dkbar[c];
   }
+  }
+  block_param_add<D>(a, h, dga_sum, dbe_sum, red);
 }
 
 // Readout of the visited version: rows [0, m) of every unit, as the forward computes it.
@@ -198,11 +224,14 @@ __global__ __launch_bounds__(256) void bwd_readout_kernel(Bwd a, int m) {
 template <typename T, int D>
 __global__ __launch_bounds__(256) void bwd_readout_adjoint_kernel(Bwd a, int m) {
   constexpr int CPL = D / 64;
+  __shared__ float red[2][4][D];
   const Dev &dv = a.dv;
   const int lane = threadIdx.x & 63;
   const int u = blockIdx.y, h = u % dv.Hkv;
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= m) return;
+  float dga_sum[CPL] = {}, dbe_sum[CPL] = {};
+  for (int jj = 0; jj < kRowsPerWave; ++jj) {
+  const int row = (blockIdx.x * 4 + (threadIdx.x >> 6)) * kRowsPerWave + jj;
+  if (row >= m) break;
   const int64_t ro = ((int64_t)u * dv.Mcap + row) * D;
   double sk[CPL], s = 0.0;
   float sv[CPL], dkh[CPL], dvh[CPL], nn = 0.f;
@@ -244,10 +273,12 @@ __global__ __launch_bounds__(256) void bwd_readout_adjoint_kernel(Bwd a, int m) 
     const int ch = lane * CPL + c;
     a.dsK[ro + ch] += (dkh[c] * ga[c] - m1 - xhat[c] * m2) * (float)rden;
     a.dsV[ro + ch] += rho / den * dvh[c] - back * sv[c];
-    atomicAdd(a.par64 + h * D + ch, (double)(dkh[c] * xhat[c]));
-    atomicAdd(a.par64 + (dv.Hkv + h) * D + ch, (double)dkh[c]);
+    dga_sum[c] += dkh[c] * xhat[c];
+    dbe_sum[c] += dkh[c];
   }
   if (lane == 0) a.drho[(int64_t)u * dv.Mcap + row] += dot;
+  }
+  block_param_add<D>(a, h, dga_sum, dbe_sum, red);
 }
 
 // One chunk's keys: state rows [0, m) of the visited version, then window positions [wb, s + nq).
@@ -478,7 +509,7 @@ hipError_t run_backward(const Bwd &a, const BwdChunk *chunks, int n_chunks, hipS
   for (int ci = n_chunks - 1; ci >= 0; --ci) {
     const BwdChunk &ch = chunks[ci];
     if (ch.fold >= 0)
-      BWD_DISPATCH(dv, bwd_unfold_kernel, dim3((dv.C + 3) / 4, dv.U), dim3(256), st, a, ch.fold,
+      BWD_DISPATCH(dv, bwd_unfold_kernel, dim3((dv.C + 4 * kRowsPerWave - 1) / (4 * kRowsPerWave), dv.U), dim3(256), st, a, ch.fold,
                    ch.s + ch.nq - dv.L, ch.m);
     const int64_t c0 = ch.s / dv.C * dv.C;
     ChunkArgs c;
@@ -497,7 +528,8 @@ hipError_t run_backward(const Bwd &a, const BwdChunk *chunks, int n_chunks, hipS
       BWD_DISPATCH(dv, bwd_dkv_kernel, dim3(c.nk, dv.U), dim3(256), st, a, c);
     }
     if (ch.m > 0)
-      BWD_DISPATCH(dv, bwd_readout_adjoint_kernel, dim3((ch.m + 3) / 4, dv.U), dim3(256), st, a, ch.m);
+      BWD_DISPATCH(dv, bwd_readout_adjoint_kernel, dim3((ch.m + 4 * kRowsPerWave - 1) / (4 * kRowsPerWave), dv.U),
+                   dim3(256), st, a, ch.m);
   }
   {
     const int n = dv.Hkv * D > dv.Hq ? dv.Hkv * D : dv.Hq;

@@ -1,20 +1,23 @@
 // Attention part of the backward pass for bf16, head_dim 128 on the gfx950 matrix cores.
 //
-// One kernel body in two roles.  Each wave keeps 32 "stationary" vectors in registers, as B
+// One kernel body in three roles.  Each wave keeps 32 "stationary" vectors in registers, as B
 // operands, and walks 64-row "streamed" tiles that come through LDS:
 //   role dQ : stationary = 32 queries (q and dout rows), streamed = keys (state rows of the
 //             visited version, then window tokens; K and V rows)           -> dq
-//   role dKV: stationary = 32 keys (K and V rows), streamed = the chunk's queries, head after
-//             head of the group (q and dout rows)                          -> dk, dv (or the
-//             adjoint of the state readout)
+//   roles dK, dV: stationary = 32 keys (K and V rows), streamed = the chunk's queries, head
+//             after head of the group (q and dout rows)                    -> dk resp. dv (or
+//             the adjoint of the state readout).  One kernel for both would hold two sets of
+//             result registers and run one wave per SIMD (measured: 550 us per chunk of the bench
+//             workload); apart they run two per SIMD, at the price of the logits computed once
+//             more.
 // Per streamed tile and wave, with X the streamed "key-like" tile (K or q) and Y the streamed
 // "value-like" tile (V or dout):
 //   S^T  = X . staK^T           16 matrix instructions (32x32x16)    logits, transposed
 //   dP^T = Y . staV^T           16
 //   P^T  = exp(tau * scale * S^T - lse),  dS^T = P^T * (dP^T - D)   lse and D belong to the query:
-//          to the lane's own column in role dQ, to the row in role dKV (then they come from LDS)
-//   O1^T += X^T . (tau dS^T)    16      dq^T resp. dk^T
-//   O2^T += Y^T . P^T           16      role dKV only: dv^T
+//          to the lane's own column in role dQ, to the row in roles dK, dV (then they come from LDS)
+//   O1^T += X^T . (tau dS^T)    16      dq^T resp. dk^T          (roles dQ, dK)
+//   O2^T += Y^T . P^T           16      dv^T                     (role dV, which skips dP^T and dS^T)
 // Both products that need a streamed tile transposed read it through the transposing LDS load
 // from the one swizzled image that the first two products read row by row.  Tiles are filled by
 // direct global -> LDS loads one tile ahead, one barrier per tile, like the forward kernel.
@@ -64,8 +67,12 @@ struct MfmaChunk {
   int32_t nq, m;   // queries of the chunk, state rows it saw
 };
 
-template <bool kKeysSta>
-__global__ __launch_bounds__(256, kKeysSta ? 1 : 2) void bwd_mfma_kernel(Bwd a, MfmaChunk c) {
+enum { kRoleDQ = 0, kRoleDK = 1, kRoleDV = 2 };
+
+template <int kRole>
+__global__ __launch_bounds__(256, 2) void bwd_mfma_kernel(Bwd a, MfmaChunk c) {
+  constexpr bool kKeysSta = kRole != kRoleDQ;
+  constexpr bool kWantDS = kRole != kRoleDV;  // dP^T, dS^T and the first result
   extern __shared__ __attribute__((aligned(1024))) uint16_t lds[];
   float *rowsc = reinterpret_cast<float *>(lds + 4 * kTileElems);  // [stage][lse * log2e | D][64]
   constexpr int D = kHeadDim;
@@ -90,10 +97,10 @@ __global__ __launch_bounds__(256, kKeysSta ? 1 : 2) void bwd_mfma_kernel(Bwd a, 
   bool col_ok;
   const uint16_t *sk_row, *sv_row;
   int colq = 0;          // role dQ: the lane's query within the chunk
-  int64_t kpos = -1;     // role dKV, window keys: the lane's key position
+  int64_t kpos = -1;     // roles dK, dV, window keys: the lane's key position
   int hq_sta = 0, st_row = 0;
   bool sta_state = false;
-  int wg_first = 0;      // role dKV, window keys: first key position of the workgroup, relative to cs
+  int wg_first = 0;      // roles dK, dV, window keys: first key position of the workgroup, relative to cs
   if constexpr (!kKeysSta) {
     const int qt = member % tpc, gq = member / tpc;
     hq_sta = __builtin_amdgcn_readfirstlane(h * G + gq);
@@ -127,8 +134,10 @@ __global__ __launch_bounds__(256, kKeysSta ? 1 : 2) void bwd_mfma_kernel(Bwd a, 
     Frag8 f;
     f.q = *reinterpret_cast<const uint4 *>(sk_row + 16 * ks + 8 * g);
     sk[ks] = f.v;
-    f.q = *reinterpret_cast<const uint4 *>(sv_row + 16 * ks + 8 * g);
-    sv[ks] = f.v;
+    if constexpr (kWantDS) {
+      f.q = *reinterpret_cast<const uint4 *>(sv_row + 16 * ks + 8 * g);
+      sv[ks] = f.v;
+    }
   }
   float lse2_col = 0.f, d_col = 0.f;
   if constexpr (!kKeysSta) {
@@ -190,7 +199,7 @@ __global__ __launch_bounds__(256, kKeysSta ? 1 : 2) void bwd_mfma_kernel(Bwd a, 
     tile_dma<false, 4>(xb, stride, valid, at, wave, dl);
     tile_dma<false, 4>(yb, stride, valid, at + kTileElems * 2, wave, dl);
   };
-  // role dKV: lse and D of a tile's 64 query rows, fetched by the first wave a tile ahead and
+  // roles dK, dV: lse and D of a tile's 64 query rows, fetched by the first wave a tile ahead and
   // put into LDS just before the barrier that publishes the tile
   float rs_lse = 0.f, rs_d = 0.f;
   auto fetch_rowsc = [&](int it) {
@@ -214,14 +223,11 @@ __global__ __launch_bounds__(256, kKeysSta ? 1 : 2) void bwd_mfma_kernel(Bwd a, 
     }
   };
 
-  f32x16 o1[4], o2[4];
+  f32x16 o1[4];  // the role's result, transposed: dq^T, dk^T or dv^T
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      o1[i][v] = 0.f;
-      o2[i][v] = 0.f;
-    }
+    for (int v = 0; v < 16; ++v) o1[i][v] = 0.f;
   float tau_sum_state = 0.f, tau_sum_bswa = 0.f;  // role dQ: sum of dS * S over state / window keys
 
   auto tile_step = [&](int it, auto parity) {
@@ -238,7 +244,7 @@ __global__ __launch_bounds__(256, kKeysSta ? 1 : 2) void bwd_mfma_kernel(Bwd a, 
     bool tile_state;   // logits of this tile use the state temperature
     int lim_base;      // role dQ: tile rows <= lim_base + (lane's own term) are visible
     int hq;
-    int row_pos0 = 0;  // role dKV: position of the tile's first query, relative to cs
+    int row_pos0 = 0;  // roles dK, dV: position of the tile's first query, relative to cs
     if constexpr (!kKeysSta) {
       hq = hq_sta;
       tile_state = it < n_st;
@@ -268,7 +274,7 @@ __global__ __launch_bounds__(256, kKeysSta ? 1 : 2) void bwd_mfma_kernel(Bwd a, 
 #pragma unroll
         for (int blk = 0; blk < 2; ++blk) {
           sacc[blk] = mfma32(ktile_frag(X, koff, blk, ks), sk[ks], ks == 0 ? zero : sacc[blk]);
-          dacc[blk] = mfma32(ktile_frag(Y, koff, blk, ks), sv[ks], ks == 0 ? zero : dacc[blk]);
+          if constexpr (kWantDS) dacc[blk] = mfma32(ktile_frag(Y, koff, blk, ks), sv[ks], ks == 0 ? zero : dacc[blk]);
         }
     }
     Frag8 pP[4], pS[4];
@@ -303,10 +309,12 @@ __global__ __launch_bounds__(256, kKeysSta ? 1 : 2) void bwd_mfma_kernel(Bwd a, 
         }
         const float s = sacc[blk][v];
         const float p = vis ? __builtin_amdgcn_exp2f(fmaf(s, cexp, -lse2)) : 0.f;
-        const float ds = p * (dacc[blk][v] - dd);
-        tsum = fmaf(ds, s, tsum);
         sacc[blk][v] = p;
-        dacc[blk][v] = ds * tau;
+        if constexpr (kWantDS) {
+          const float ds = p * (dacc[blk][v] - dd);
+          tsum = fmaf(ds, s, tsum);
+          dacc[blk][v] = ds * tau;
+        }
       }
     }
     if constexpr (!kKeysSta) {
@@ -317,15 +325,19 @@ __global__ __launch_bounds__(256, kKeysSta ? 1 : 2) void bwd_mfma_kernel(Bwd a, 
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const int v0 = (ks & 1) * 8 + 2 * e;
-        pP[ks].w[e] = pack_bf16(sacc[ks >> 1][v0], sacc[ks >> 1][v0 + 1]);
-        pS[ks].w[e] = pack_bf16(dacc[ks >> 1][v0], dacc[ks >> 1][v0 + 1]);
+        if constexpr (kWantDS)
+          pS[ks].w[e] = pack_bf16(dacc[ks >> 1][v0], dacc[ks >> 1][v0 + 1]);
+        else
+          pP[ks].w[e] = pack_bf16(sacc[ks >> 1][v0], sacc[ks >> 1][v0 + 1]);
       }
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
       for (int dblk = 0; dblk < 4; ++dblk) {
-        o1[dblk] = mfma32(ttile_frag(X, toff, dblk, ks), pS[ks].v, o1[dblk]);
-        if constexpr (kKeysSta) o2[dblk] = mfma32(ttile_frag(Y, toff, dblk, ks), pP[ks].v, o2[dblk]);
+        if constexpr (kWantDS)
+          o1[dblk] = mfma32(ttile_frag(X, toff, dblk, ks), pS[ks].v, o1[dblk]);
+        else
+          o1[dblk] = mfma32(ttile_frag(Y, toff, dblk, ks), pP[ks].v, o1[dblk]);
       }
   };
 
@@ -363,32 +375,27 @@ __global__ __launch_bounds__(256, kKeysSta ? 1 : 2) void bwd_mfma_kernel(Bwd a, 
     }
   } else {
     if (col_ok) {
-      float *dk_row, *dv_row;
+      // dk carries the logit scale; dv does not
+      const float os = kRole == kRoleDK ? scale : 1.f;
+      float *row;
       if (sta_state) {
-        const int64_t ro = ((int64_t)u * dv.Mcap + st_row) * D;
-        dk_row = a.dkhat + ro;
-        dv_row = a.dvhat + ro;
+        row = (kRole == kRoleDK ? a.dkhat : a.dvhat) + ((int64_t)u * dv.Mcap + st_row) * D;
       } else {
         const int64_t tok = ((int64_t)b * a.T + kpos) * dv.Hkv + h;
-        dk_row = a.dk_acc + tok * D;
-        dv_row = a.dv_acc + tok * D;
+        row = (kRole == kRoleDK ? a.dk_acc : a.dv_acc) + tok * D;
       }
 #pragma unroll
       for (int dblk = 0; dblk < 4; ++dblk)
 #pragma unroll
         for (int vq = 0; vq < 4; ++vq) {
           const int ch = 32 * dblk + 8 * vq + 4 * g;
-          float4 k4 = make_float4(o1[dblk][4 * vq] * scale, o1[dblk][4 * vq + 1] * scale, o1[dblk][4 * vq + 2] * scale,
-                                  o1[dblk][4 * vq + 3] * scale);
-          float4 v4 = make_float4(o2[dblk][4 * vq], o2[dblk][4 * vq + 1], o2[dblk][4 * vq + 2], o2[dblk][4 * vq + 3]);
-          if (!sta_state) {
-            const float4 k0 = *reinterpret_cast<const float4 *>(dk_row + ch);
-            const float4 v0 = *reinterpret_cast<const float4 *>(dv_row + ch);
-            k4.x += k0.x; k4.y += k0.y; k4.z += k0.z; k4.w += k0.w;
-            v4.x += v0.x; v4.y += v0.y; v4.z += v0.z; v4.w += v0.w;
+          float4 x4 = make_float4(o1[dblk][4 * vq] * os, o1[dblk][4 * vq + 1] * os, o1[dblk][4 * vq + 2] * os,
+                                  o1[dblk][4 * vq + 3] * os);
+          if (!sta_state) {  // a window token collects from every chunk that sees it
+            const float4 x0 = *reinterpret_cast<const float4 *>(row + ch);
+            x4.x += x0.x; x4.y += x0.y; x4.z += x0.z; x4.w += x0.w;
           }
-          *reinterpret_cast<float4 *>(dk_row + ch) = k4;
-          *reinterpret_cast<float4 *>(dv_row + ch) = v4;
+          *reinterpret_cast<float4 *>(row + ch) = x4;
         }
     }
   }
@@ -398,17 +405,17 @@ __global__ __launch_bounds__(256, kKeysSta ? 1 : 2) void bwd_mfma_kernel(Bwd a, 
 
 bool backward_on_mfma(const Dev &dv) { return dv.io == 1 && dv.d == kHeadDim; }
 
-// The two launches of one chunk: dq (and the temperature sums), then dk, dv and the readout adjoint.
+// The three launches of one chunk: dq (and the temperature sums), dk, dv (or the readout's adjoint).
 hipError_t launch_backward_mfma(const Bwd &a, int64_t cs, int nq, int m, hipStream_t st) {
   const Dev &dv = a.dv;
   static bool allowed = false;  // more than 64 KiB of LDS per workgroup has to be asked for once
   if (!allowed) {
-    hipError_t e = hipFuncSetAttribute((const void *)bwd_mfma_kernel<false>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kBwdLdsBytes);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void *)bwd_mfma_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            kBwdLdsBytes);
-    if (e != hipSuccess) return e;
+    const void *kernels[3] = {(const void *)bwd_mfma_kernel<kRoleDQ>, (const void *)bwd_mfma_kernel<kRoleDK>,
+                              (const void *)bwd_mfma_kernel<kRoleDV>};
+    for (const void *k : kernels) {
+      const hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kBwdLdsBytes);
+      if (e != hipSuccess) return e;
+    }
     allowed = true;
   }
   MfmaChunk c;
@@ -420,8 +427,9 @@ hipError_t launch_backward_mfma(const Bwd &a, int64_t cs, int nq, int m, hipStre
   const unsigned groups = (unsigned)((dv.U + kXcds - 1) / kXcds * kXcds);
   const int per_q = G * ((nq + kStaPerWg - 1) / kStaPerWg);
   const int per_k = (m + kStaPerWg - 1) / kStaPerWg + ((int)(cs + nq - c.wb) + kStaPerWg - 1) / kStaPerWg;
-  hipLaunchKernelGGL((bwd_mfma_kernel<false>), dim3(groups * per_q), dim3(256), kBwdLdsBytes, st, a, c);
-  hipLaunchKernelGGL((bwd_mfma_kernel<true>), dim3(groups * per_k), dim3(256), kBwdLdsBytes, st, a, c);
+  hipLaunchKernelGGL((bwd_mfma_kernel<kRoleDQ>), dim3(groups * per_q), dim3(256), kBwdLdsBytes, st, a, c);
+  hipLaunchKernelGGL((bwd_mfma_kernel<kRoleDK>), dim3(groups * per_k), dim3(256), kBwdLdsBytes, st, a, c);
+  hipLaunchKernelGGL((bwd_mfma_kernel<kRoleDV>), dim3(groups * per_k), dim3(256), kBwdLdsBytes, st, a, c);
   return hipGetLastError();
 }
 
