@@ -390,6 +390,22 @@ def sweep(args, pkg, synth, dev):
             F.scaled_dot_product_attention(qh, kh, vh, is_causal=True)
             row["sdpa_prefill_ms"] = timed(lambda: F.scaled_dot_product_attention(qh, kh, vh, is_causal=True),
                                            args.steps)[0]
+            # its backward pass alone (a fresh forward, untimed, before every repetition)
+            gen = torch.Generator(device=dev)
+            gen.manual_seed(w0.seed + 31337)
+            dout = torch.randn(q.shape, generator=gen, device=dev, dtype=torch.float32).to(q.dtype)
+            leaves = [x.detach().permute(0, 2, 1, 3).requires_grad_(True) for x in (q, k, v)]
+            bts = []
+            for _ in range(max(args.steps, 2)):
+                o = F.scaled_dot_product_attention(*leaves, is_causal=True)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                torch.autograd.grad(o, leaves, dout.permute(0, 2, 1, 3))
+                torch.cuda.synchronize()
+                bts.append((time.perf_counter() - t0) * 1e3)
+                del o
+            row["sdpa_backward_ms"] = statistics.median(bts[1:])
+            del leaves
             q1 = qh[:, :, -1:].contiguous()
             F.scaled_dot_product_attention(q1, kh, vh)
             row["sdpa_decode_us"] = timed(lambda: [F.scaled_dot_product_attention(q1, kh, vh) for _ in range(20)],
@@ -420,6 +436,18 @@ def sweep(args, pkg, synth, dev):
             dmed = timed(lambda: [st.decode(qs[t % 16], ks[t % 16], vs[t % 16], out=od) for t in range(n_dec)], 1)[0]
             row[name] = dict(prefill_ms=med, prefill_ms_min=lo, prefill_ms_max=hi, rows=rows_after_prefill(w, T),
                              tokens_per_s=w.batch * T / (med * 1e-3), decode_us_per_step=dmed * 1e3 / n_dec)
+            # backward of the same prefill (kvm_prefill_backward), alone
+            if "sdpa_backward_ms" in row:
+                st.reset()
+                assign, score = st.trace(T // w.chunk_len + 1)
+                o2, lse = st.prefill(q, k, v, want_lse=True)
+                ws = torch.empty(st.lib.kvm_backward_workspace_bytes(st.handle, T), dtype=torch.uint8, device=dev)
+                bwd = lambda: st.backward(q, k, v, None, o2, lse, dout, assign, score, workspace=ws)
+                bwd()
+                row[name]["backward_ms"] = timed(bwd, max(args.steps, 2))[0]
+                row[name]["backward_speedup_vs_sdpa"] = row["sdpa_backward_ms"] / row[name]["backward_ms"]
+                st.trace(0)
+                del ws, o2, lse, assign, score
             if "sdpa_prefill_ms" in row:
                 row[name]["prefill_speedup_vs_sdpa"] = row["sdpa_prefill_ms"] / med
                 row[name]["decode_speedup_vs_sdpa"] = row["sdpa_decode_us"] / (dmed * 1e3 / n_dec)

@@ -67,120 +67,171 @@ __device__ __forceinline__ void block_param_add(const Bwd &a, int h, const float
   }
 }
 
-// Undo fold number `fold` (block [lo, lo + C)): a wave takes 16 tokens, one after the other.
+// Undo fold number `fold` (block [lo, lo + C)).  A wave takes kUnfoldRows consecutive rows of the
+// state after the fold (one: the tokens of a row are a chain of dependent loads, and rows in
+// parallel hide it better than rows in turn): it scans the block's recorded targets (64 tokens
+// per ballot) and handles the tokens bound for its row -- they all read the row's adjoint, which
+// is loaded once, and the merged ones are taken out of the row's sums again in registers, so
+// that nothing needs an atomic.  A token bound for a row of this fold's own making either
+// created that row or merged into it afterwards: the forward appends the tokens with the
+// smallest (append score, position) keys, so among the tokens bound for one new row the creator
+// is the one with the smallest key.
+constexpr int kUnfoldRows = 1;
+
 template <typename T, int D>
-__global__ __launch_bounds__(256) void bwd_unfold_kernel(Bwd a, int fold, int64_t lo, int m_before) {
+__global__ __launch_bounds__(256) void bwd_unfold_kernel(Bwd a, int fold, int64_t lo, int m_before, int m_after) {
   constexpr int CPL = D / 64;
   __shared__ float red[2][4][D];
   const Dev &dv = a.dv;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int u = blockIdx.y, b = u / dv.Hkv, h = u % dv.Hkv;
+  const int C = dv.C;
+  const int row_first = (blockIdx.x * 4 + wave) * kUnfoldRows;
+  const int64_t base = ((int64_t)fold * dv.U + u) * C;
   float dga_sum[CPL] = {}, dbe_sum[CPL] = {};
-  for (int jj = 0; jj < kRowsPerWave; ++jj) {
-  const int j = (blockIdx.x * 4 + wave) * kRowsPerWave + jj;
-  if (j >= dv.C) break;
-  const int64_t t = lo + j;
-  const int64_t tok = ((int64_t)b * a.T + t) * dv.Hkv + h;
-  const int row = a.assign[((int64_t)fold * dv.U + u) * dv.C + j];
-  if (row < 0 || row >= dv.Mcap) continue;  // not a recorded assignment: leave the token alone
-  // A token bound for a row of this fold's own making either created that row or merged into it
-  // afterwards.  The forward appends the tokens with the smallest (append score, position) keys,
-  // so among the tokens bound for one new row the creator is the one with the smallest key.
-  bool appended = row >= m_before;
-  if (appended) {
-    const int64_t base = ((int64_t)fold * dv.U + u) * dv.C;
-    const float sj = a.score[2 * (base + j)];
-    bool beaten = false;
-    for (int j2 = lane; j2 < dv.C; j2 += 64) {
-      if (j2 != j && a.assign[base + j2] == row) {
-        const float s2 = a.score[2 * (base + j2)];
-        beaten |= s2 < sj || (s2 == sj && j2 < j);
+  float gam[CPL], bet[CPL];
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) {
+    gam[c] = dv.gamma ? dv.gamma[h * D + lane * CPL + c] : 1.f;
+    bet[c] = dv.beta ? dv.beta[h * D + lane * CPL + c] : 0.f;
+  }
+  int tg[8];
+  auto load_targets = [&](int j0) {
+#pragma unroll
+    for (int bk = 0; bk < 8; ++bk) {
+      const int j = j0 + 64 * bk + lane;
+      tg[bk] = j < C ? a.assign[base + j] : -1;
+    }
+  };
+  if (row_first < m_after) load_targets(0);
+  for (int rr = 0; rr < kUnfoldRows; ++rr) {
+    const int row = row_first + rr;
+    if (row >= m_after) break;
+    const bool fresh = row >= m_before;  // a row this fold created: it ends here
+    const int64_t ro = ((int64_t)u * dv.Mcap + row) * D;
+    int creator = -1;
+    if (fresh) {
+      float best = 0.f;
+      for (int j0 = 0; j0 < C; j0 += 512) {
+        if (C > 512) load_targets(j0);
+#pragma unroll
+        for (int bk = 0; bk < 8; ++bk) {
+          uint64_t hits = __builtin_amdgcn_ballot_w64(tg[bk] == row);
+          while (hits) {
+            const int j = j0 + 64 * bk + __builtin_ctzll(hits);
+            hits &= hits - 1;
+            const float sj = a.score[2 * (base + j)];
+            if (creator < 0 || sj < best) {  // positions ascend: equal scores keep the earlier token
+              best = sj;
+              creator = j;
+            }
+          }
+        }
       }
     }
-    appended = __ballot(beaten) == 0;
-  }
-  const int64_t ro = ((int64_t)u * dv.Mcap + row) * D;
-  float kf[CPL], vf[CPL];
-  load_row<T, D>((const T *)a.k + tok * D, lane, kf);
-  load_row<T, D>((const T *)a.v + tok * D, lane, vf);
-  // memory key of the token as the forward made it: LN_s in fp64 over the key with its rotary
-  // channels zeroed, rounded to the I/O dtype
-  double x[CPL], s = 0.0;
+    bool loaded = false;
+    float dsk[CPL], dsv[CPL], sv[CPL], dr = 0.f;
+    double sk[CPL];
+    for (int j0 = 0; j0 < C; j0 += 512) {
+      if (C > 512) load_targets(j0);
 #pragma unroll
-  for (int c = 0; c < CPL; ++c) {
-    x[c] = lane * CPL + c < dv.r ? 0.0 : (double)kf[c];
-    s += x[c];
-  }
-  const double mean = wave_sum(s) / (double)D;
-  double qq = 0.0;
+      for (int bk = 0; bk < 8; ++bk) {
+        uint64_t hits = __builtin_amdgcn_ballot_w64(tg[bk] == row);
+        while (hits) {
+          const int j = j0 + 64 * bk + __builtin_ctzll(hits);
+          hits &= hits - 1;
+          if (!loaded) {
 #pragma unroll
-  for (int c = 0; c < CPL; ++c) qq += (x[c] - mean) * (x[c] - mean);
-  const double rden = 1.0 / sqrt(wave_sum(qq) / (double)D + (double)dv.ln_eps);
-  float xhat[CPL], kbar[CPL], ga[CPL];
+            for (int c = 0; c < CPL; ++c) {
+              dsk[c] = a.dsK[ro + lane * CPL + c];
+              dsv[c] = a.dsV[ro + lane * CPL + c];
+              sk[c] = fresh ? 0.0 : a.wsK[ro + lane * CPL + c];
+              sv[c] = fresh ? 0.f : a.wsV[ro + lane * CPL + c];
+            }
+            dr = a.drho[(int64_t)u * dv.Mcap + row];
+            loaded = true;
+          }
+          const int64_t tok = ((int64_t)b * a.T + lo + j) * dv.Hkv + h;
+          float kf[CPL], vf[CPL];
+          load_row<T, D>((const T *)a.k + tok * D, lane, kf);
+          load_row<T, D>((const T *)a.v + tok * D, lane, vf);
+          const float g = a.gate ? a.gate[tok] : 1.f;
+          // memory key of the token as the forward made it: LN_s in fp64 over the key with its
+          // rotary channels zeroed, rounded to the I/O dtype
+          double x[CPL], s = 0.0;
 #pragma unroll
-  for (int c = 0; c < CPL; ++c) {
-    const int ch = lane * CPL + c;
-    const double g_ = dv.gamma ? (double)dv.gamma[h * D + ch] : 1.0;
-    const double b_ = dv.beta ? (double)dv.beta[h * D + ch] : 0.0;
-    const double xh = (x[c] - mean) * rden;
-    xhat[c] = (float)xh;
-    ga[c] = (float)g_;
-    kbar[c] = Io<T>::round_from(xh * g_ + b_);
-  }
-  const float g = a.gate ? a.gate[tok] : 1.f;
-  float dsk[CPL], dsv[CPL], dkbar[CPL], dvt[CPL];
+          for (int c = 0; c < CPL; ++c) {
+            x[c] = lane * CPL + c < dv.r ? 0.0 : (double)kf[c];
+            s += x[c];
+          }
+          const double mean = wave_sum(s) / (double)D;
+          double qq = 0.0;
 #pragma unroll
-  for (int c = 0; c < CPL; ++c) {
-    dsk[c] = a.dsK[ro + lane * CPL + c];
-    dsv[c] = a.dsV[ro + lane * CPL + c];
-  }
-  float dg = 0.f;
-  if (appended) {
-    // a new row is the ungated memory key and value; its radius is the value's length
-    float nn = 0.f;
+          for (int c = 0; c < CPL; ++c) qq += (x[c] - mean) * (x[c] - mean);
+          const double rden = 1.0 / sqrt(wave_sum(qq) / (double)D + (double)dv.ln_eps);
+          float xhat[CPL], kbar[CPL], dkbar[CPL], dvt[CPL];
 #pragma unroll
-    for (int c = 0; c < CPL; ++c) nn += vf[c] * vf[c];
-    const float nv = sqrtf(wave_sum(nn));
-    const float dr = nv > 0.f ? a.drho[(int64_t)u * dv.Mcap + row] / nv : 0.f;
+          for (int c = 0; c < CPL; ++c) {
+            const double xh = (x[c] - mean) * rden;
+            xhat[c] = (float)xh;
+            kbar[c] = Io<T>::round_from(xh * (double)gam[c] + (double)bet[c]);
+          }
+          float dg = 0.f;
+          if (j == creator) {
+            // a new row is the ungated memory key and value; its radius is the value's length
+            float nn = 0.f;
 #pragma unroll
-    for (int c = 0; c < CPL; ++c) {
-      dkbar[c] = dsk[c];
-      dvt[c] = dsv[c] + dr * vf[c];
+            for (int c = 0; c < CPL; ++c) nn += vf[c] * vf[c];
+            const float nv = sqrtf(wave_sum(nn));
+            const float drn = nv > 0.f ? dr / nv : 0.f;
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) {
+              dkbar[c] = dsk[c];
+              dvt[c] = dsv[c] + drn * vf[c];
+            }
+          } else {
+            float dot = 0.f;
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) {
+              dkbar[c] = g * dsk[c];
+              dvt[c] = g * dsv[c];
+              dot += dsk[c] * kbar[c] + dsv[c] * vf[c];
+              // back to the version before the fold: the token leaves its row's sums again
+              sk[c] -= (double)g * (double)kbar[c];
+              sv[c] -= g * vf[c];
+            }
+            dg = wave_sum(dot);
+          }
+          if (lane == 0) a.dgate[tok] = dg;
+          // through LN_s of the memory key
+          float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+          for (int c = 0; c < CPL; ++c) {
+            s1 += dkbar[c] * gam[c];
+            s2 += dkbar[c] * gam[c] * xhat[c];
+          }
+          const float m1 = wave_sum(s1) / (float)D, m2 = wave_sum(s2) / (float)D;
+#pragma unroll
+          for (int c = 0; c < CPL; ++c) {
+            const int ch = lane * CPL + c;
+            const float dkz = (dkbar[c] * gam[c] - m1 - xhat[c] * m2) * (float)rden;
+            // plain stores: walking backwards, a token's fold is undone before any chunk that had
+            // the token in its window is visited, so this is the first contribution it receives
+            a.dk_acc[tok * D + ch] = ch >= dv.r ? dkz : 0.f;
+            a.dv_acc[tok * D + ch] = dvt[c];
+            dga_sum[c] += dkbar[c] * xhat[c];
+            dbe_sum[c] += dkbar[c];
+          }
+        }
+      }
     }
-  } else {
-    float dot = 0.f;
+    if (loaded && !fresh) {
 #pragma unroll
-    for (int c = 0; c < CPL; ++c) {
-      dkbar[c] = g * dsk[c];
-      dvt[c] = g * dsv[c];
-      dot += dsk[c] * kbar[c] + dsv[c] * vf[c];
+      for (int c = 0; c < CPL; ++c) {
+        a.wsK[ro + lane * CPL + c] = sk[c];
+        a.wsV[ro + lane * CPL + c] = sv[c];
+      }
     }
-    dg = wave_sum(dot);
-    // back to the version before the fold: take the token out of its row's sums again
-#pragma unroll
-    for (int c = 0; c < CPL; ++c) {
-      atomicAdd(a.wsK + ro + lane * CPL + c, -((double)g * (double)kbar[c]));
-      atomicAdd(a.wsV + ro + lane * CPL + c, -(g * vf[c]));
-    }
-  }
-  if (lane == 0) a.dgate[tok] = dg;
-  // through LN_s of the memory key
-  float s1 = 0.f, s2 = 0.f;
-#pragma unroll
-  for (int c = 0; c < CPL; ++c) {
-    s1 += dkbar[c] * ga[c];
-    s2 += dkbar[c] * ga[c] * xhat[c];
-  }
-  const float m1 = wave_sum(s1) / (float)D, m2 = wave_sum(s2) / (float)D;
-#pragma unroll
-  for (int c = 0; c < CPL; ++c) {
-    const int ch = lane * CPL + c;
-    const float dkz = (dkbar[c] * ga[c] - m1 - xhat[c] * m2) * (float)rden;
-    if (ch >= dv.r) a.dk_acc[tok * D + ch] += dkz;
-    a.dv_acc[tok * D + ch] += dvt[c];
-    dga_sum[c] += dkbar[c] * xhat[c];
-    dbe_sum[c] += dkbar[c];
-  }
   }
   block_param_add<D>(a, h, dga_sum, dbe_sum, red);
 }
@@ -453,10 +504,19 @@ __global__ __launch_bounds__(256) void bwd_params_kernel(Bwd a) {
   }
 }
 
-template <typename T, int D>
+// fp32 accumulators to the I/O dtype, eight elements per thread (n is a multiple of 64)
+template <typename T>
 __global__ __launch_bounds__(256) void bwd_cast_kernel(const float *src, T *dst, int64_t n) {
-  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (i < n) Io<T>::store(dst + i, src[i]);
+  const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8;
+  if (i >= n) return;
+  const float4 x = *reinterpret_cast<const float4 *>(src + i), y = *reinterpret_cast<const float4 *>(src + i + 4);
+  if constexpr (sizeof(T) == 4) {
+    *reinterpret_cast<float4 *>((float *)dst + i) = x;
+    *reinterpret_cast<float4 *>((float *)dst + i + 4) = y;
+  } else {
+    *reinterpret_cast<uint4 *>((uint16_t *)dst + i) =
+        make_uint4(pack_bf16(x.x, x.y), pack_bf16(x.z, x.w), pack_bf16(y.x, y.y), pack_bf16(y.z, y.w));
+  }
 }
 
 #define BWD_DISPATCH(dv, KERNEL, grid, block, st, ...)                                    \
@@ -509,8 +569,8 @@ hipError_t run_backward(const Bwd &a, const BwdChunk *chunks, int n_chunks, hipS
   for (int ci = n_chunks - 1; ci >= 0; --ci) {
     const BwdChunk &ch = chunks[ci];
     if (ch.fold >= 0)
-      BWD_DISPATCH(dv, bwd_unfold_kernel, dim3((dv.C + 4 * kRowsPerWave - 1) / (4 * kRowsPerWave), dv.U), dim3(256), st, a, ch.fold,
-                   ch.s + ch.nq - dv.L, ch.m);
+      BWD_DISPATCH(dv, bwd_unfold_kernel, dim3((ch.m_after + 4 * kUnfoldRows - 1) / (4 * kUnfoldRows), dv.U),
+                   dim3(256), st, a, ch.fold, ch.s + ch.nq - dv.L, ch.m, ch.m_after);
     const int64_t c0 = ch.s / dv.C * dv.C;
     ChunkArgs c;
     c.s = ch.s;
@@ -535,13 +595,13 @@ hipError_t run_backward(const Bwd &a, const BwdChunk *chunks, int n_chunks, hipS
     const int n = dv.Hkv * D > dv.Hq ? dv.Hkv * D : dv.Hq;
     hipLaunchKernelGGL(bwd_params_kernel, dim3((n + 255) / 256), dim3(256), 0, st, a);
   }
-  const unsigned cast_blocks = (unsigned)((kv_elems + 255) / 256);
+  const unsigned cast_blocks = (unsigned)((kv_elems / 8 + 255) / 256);
   if (dv.io == 0) {
-    hipLaunchKernelGGL((bwd_cast_kernel<float, 64>), dim3(cast_blocks), dim3(256), 0, st, a.dk_acc, (float *)a.dk, kv_elems);
-    hipLaunchKernelGGL((bwd_cast_kernel<float, 64>), dim3(cast_blocks), dim3(256), 0, st, a.dv_acc, (float *)a.dv_out, kv_elems);
+    hipLaunchKernelGGL((bwd_cast_kernel<float>), dim3(cast_blocks), dim3(256), 0, st, a.dk_acc, (float *)a.dk, kv_elems);
+    hipLaunchKernelGGL((bwd_cast_kernel<float>), dim3(cast_blocks), dim3(256), 0, st, a.dv_acc, (float *)a.dv_out, kv_elems);
   } else {
-    hipLaunchKernelGGL((bwd_cast_kernel<bf16_t, 64>), dim3(cast_blocks), dim3(256), 0, st, a.dk_acc, (bf16_t *)a.dk, kv_elems);
-    hipLaunchKernelGGL((bwd_cast_kernel<bf16_t, 64>), dim3(cast_blocks), dim3(256), 0, st, a.dv_acc, (bf16_t *)a.dv_out, kv_elems);
+    hipLaunchKernelGGL((bwd_cast_kernel<bf16_t>), dim3(cast_blocks), dim3(256), 0, st, a.dk_acc, (bf16_t *)a.dk, kv_elems);
+    hipLaunchKernelGGL((bwd_cast_kernel<bf16_t>), dim3(cast_blocks), dim3(256), 0, st, a.dv_acc, (bf16_t *)a.dv_out, kv_elems);
   }
   return hipGetLastError();
 }

@@ -1002,6 +1002,7 @@ int kvm_prefill_backward(kvm_state *st, const void *q, const void *k, const void
       ch.fold = (int32_t)folds++;
       m = rows_after(c, st->table, m, e);
     }
+    ch.m_after = (int32_t)m;
     chunks.push_back(ch);
   }
   if (st->tokens != T || st->folds != folds || st->m != m) return KVM_ERR_STATE;

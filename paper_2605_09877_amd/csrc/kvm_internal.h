@@ -136,6 +136,7 @@ struct BwdChunk {
   int32_t nq;      // queries
   int32_t m;       // state rows the chunk saw ( = rows before the fold that follows)
   int32_t fold;    // index of the fold that followed the chunk, or -1
+  int32_t m_after; // state rows after that fold
 };
 hipError_t run_backward(const Bwd &a, const BwdChunk *chunks, int n_chunks, hipStream_t st);
 // backward_mfma.hip (bf16, d = 128): one chunk's dq, dk, dv and readout adjoint on the matrix cores
