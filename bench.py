@@ -160,8 +160,8 @@ def backward_leg(args, pkg, synth, dev, w):
     tf = flops / (med * 1e-3) / 1e12
     return dict(ms_per_pass=med, ms_min=ms[0], ms_max=ms[-1], tokens_per_s=w.batch * w.seq / (med * 1e-3),
                 algorithmic_tflop=flops / 1e12, achieved_tflops=tf, frac_of_mfma_peak=tf / MFMA_BF16_PEAK_TFLOPS,
-                workspace_gb=nbytes / 1e9, note="whole pass: 64 chunks x (undo fold, readout, dq kernel, dk/dv kernel, "
-                "readout adjoint); the two matrix-core kernels compute the logits twice (7 contractions run)")
+                workspace_gb=nbytes / 1e9, note="whole pass: per chunk undo fold, dq kernel, dk kernel, dv kernel, readout adjoint; the three "
+                "matrix-core kernels each compute the logits (8 contractions run for the 5 counted)")
 
 
 def decode_leg(args, pkg, synth, dev):

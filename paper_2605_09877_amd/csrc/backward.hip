@@ -226,10 +226,28 @@ __global__ __launch_bounds__(256) void bwd_unfold_kernel(Bwd a, int fold, int64_
       }
     }
     if (loaded && !fresh) {
+      // the row as the earlier version had it: its sums, and its readout as the forward made it
+      // (rows that the fold left alone keep the readout they have)
+      double sm = 0.0;
+      float nn = 0.f;
 #pragma unroll
       for (int c = 0; c < CPL; ++c) {
         a.wsK[ro + lane * CPL + c] = sk[c];
         a.wsV[ro + lane * CPL + c] = sv[c];
+        sm += sk[c];
+        nn += sv[c] * sv[c];
+      }
+      const double mean = wave_sum(sm) / (double)D;
+      double qq = 0.0;
+#pragma unroll
+      for (int c = 0; c < CPL; ++c) qq += (sk[c] - mean) * (sk[c] - mean);
+      const double rden = 1.0 / sqrt(wave_sum(qq) / (double)D + (double)dv.ln_eps);
+      const float vs = dv.rho[(int64_t)u * dv.Mcap + row] / fmaxf(sqrtf(wave_sum(nn)), dv.norm_eps);
+#pragma unroll
+      for (int c = 0; c < CPL; ++c) {
+        const int ch = lane * CPL + c;
+        Io<T>::store((T *)a.khat + ro + ch, Io<T>::round_from((sk[c] - mean) * rden * (double)gam[c] + (double)bet[c]));
+        Io<T>::store((T *)a.vhat + ro + ch, sv[c] * vs);
       }
     }
   }
@@ -561,6 +579,11 @@ hipError_t run_backward(const Bwd &a, const BwdChunk *chunks, int n_chunks, hipS
   }
   BWD_DISPATCH(dv, bwd_delta_kernel, dim3((unsigned)((q_rows + 3) / 4)), dim3(256), st, a.out, a.dout, a.delta, q_rows);
 
+  // the readout of the last version; undoing a fold then rewrites the rows it touched
+  if (n_chunks > 0 && chunks[n_chunks - 1].m_after > 0) {
+    const int m_end = chunks[n_chunks - 1].m_after;
+    BWD_DISPATCH(dv, bwd_readout_kernel, dim3((m_end + 3) / 4, dv.U), dim3(256), st, a, m_end);
+  }
   static const bool no_mfma = [] {
     const char *e = getenv("KVM_BACKWARD_GENERIC");  // "1": the vector-ALU kernels everywhere (comparisons)
     return e && e[0] == '1';
@@ -579,7 +602,6 @@ hipError_t run_backward(const Bwd &a, const BwdChunk *chunks, int n_chunks, hipS
     c.m = ch.m;
     c.nk = ch.m + (int)(ch.s + ch.nq - c.wb);
     c.ld = dv.Mcap + dv.L;
-    if (ch.m > 0) BWD_DISPATCH(dv, bwd_readout_kernel, dim3((ch.m + 3) / 4, dv.U), dim3(256), st, a, ch.m);
     if (on_mfma) {
       BWD_TRY(launch_backward_mfma(a, ch.s, ch.nq, ch.m, st));
     } else {
