@@ -609,7 +609,7 @@ hipError_t run_backward(const Bwd &a, const BwdChunk *chunks, int n_chunks, hipS
       BWD_DISPATCH(dv, bwd_dq_kernel, dim3(ch.nq, G, dv.U), dim3(256), st, a, c);
       BWD_DISPATCH(dv, bwd_dkv_kernel, dim3(c.nk, dv.U), dim3(256), st, a, c);
     }
-    if (ch.m > 0)
+    if (ch.m > 0 && !on_mfma)  // (the matrix-core kernels do this in their epilogues)
       BWD_DISPATCH(dv, bwd_readout_adjoint_kernel, dim3((ch.m + 4 * kRowsPerWave - 1) / (4 * kRowsPerWave), dv.U),
                    dim3(256), st, a, ch.m);
   }

@@ -34,7 +34,8 @@ namespace {
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kXcds = 8;
 constexpr int kStaPerWg = 128;                                      // stationary vectors per workgroup (4 waves)
-constexpr int kBwdLdsBytes = 4 * kTileElems * 2 + 2 * 2 * 64 * 4;   // 2 stages x 2 images + row scalars
+constexpr int kBwdTileBytes = 4 * kTileElems * 2 + 2 * 2 * 64 * 4;  // 2 stages x 2 images + row scalars
+constexpr int kBwdLdsBytes = kBwdTileBytes + 2 * 4 * kHeadDim * 4;  // + the LN_s parameter sums of the dK role
 
 // Transposed (A-operand) fragment of a K-swizzled row-major tile: lane gets channel
 // 32*dblk + lane%32 and rows 16*ks + 4*g + {0..3}, 16*ks + 8 + 4*g + {0..3}.  Lane j of a group
@@ -353,7 +354,9 @@ __global__ __launch_bounds__(256, 2) void bwd_mfma_kernel(Bwd a, MfmaChunk c) {
     if (it + 1 < n_tiles) tile_step(it + 1, std::integral_constant<int, 1>{});
   }
 
-  // ---- results
+  // ---- results (nothing of what follows is to be prepared, or kept in registers, during the loop)
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_sched_barrier(0);
   if constexpr (!kKeysSta) {
     if (col_ok) {
       const int64_t qrow = ((int64_t)b * a.T + c.cs + colq) * dv.Hq + hq_sta;
@@ -375,28 +378,145 @@ __global__ __launch_bounds__(256, 2) void bwd_mfma_kernel(Bwd a, MfmaChunk c) {
     }
   } else {
     if (col_ok) {
-      // dk carries the logit scale; dv does not
-      const float os = kRole == kRoleDK ? scale : 1.f;
-      float *row;
-      if (sta_state) {
-        row = (kRole == kRoleDK ? a.dkhat : a.dvhat) + ((int64_t)u * dv.Mcap + st_row) * D;
-      } else {
+      // window tokens: dk (which carries the logit scale) resp. dv collect from every chunk that
+      // sees the token
+      if (!sta_state) {
+        const float os = kRole == kRoleDK ? scale : 1.f;
         const int64_t tok = ((int64_t)b * a.T + kpos) * dv.Hkv + h;
-        row = (kRole == kRoleDK ? a.dk_acc : a.dv_acc) + tok * D;
-      }
+        float *row = (kRole == kRoleDK ? a.dk_acc : a.dv_acc) + tok * D;
 #pragma unroll
-      for (int dblk = 0; dblk < 4; ++dblk)
+        for (int dblk = 0; dblk < 4; ++dblk)
 #pragma unroll
-        for (int vq = 0; vq < 4; ++vq) {
-          const int ch = 32 * dblk + 8 * vq + 4 * g;
-          float4 x4 = make_float4(o1[dblk][4 * vq] * os, o1[dblk][4 * vq + 1] * os, o1[dblk][4 * vq + 2] * os,
-                                  o1[dblk][4 * vq + 3] * os);
-          if (!sta_state) {  // a window token collects from every chunk that sees it
-            const float4 x0 = *reinterpret_cast<const float4 *>(row + ch);
-            x4.x += x0.x; x4.y += x0.y; x4.z += x0.z; x4.w += x0.w;
+          for (int vq = 0; vq < 4; ++vq) {
+            const int ch = 32 * dblk + 8 * vq + 4 * g;
+            float4 x4 = *reinterpret_cast<const float4 *>(row + ch);
+            x4.x += o1[dblk][4 * vq] * os;
+            x4.y += o1[dblk][4 * vq + 1] * os;
+            x4.z += o1[dblk][4 * vq + 2] * os;
+            x4.w += o1[dblk][4 * vq + 3] * os;
+            *reinterpret_cast<float4 *>(row + ch) = x4;
           }
-          *reinterpret_cast<float4 *>(row + ch) = x4;
+      }
+    }
+    // State rows: the readout's adjoint goes straight on into the adjoint of the sums.  A lane
+    // holds half of its row's channels (four at a time: 32*dblk + 8*vq + 4*g ..), the lane 32
+    // away the other half, so a sum over the row is a sum over the lane's registers plus one
+    // exchange between the wave's halves.
+    if (sta_state) {
+      const int64_t ro = ((int64_t)u * dv.Mcap + (col_ok ? st_row : 0)) * D;
+      if constexpr (kRole == kRoleDK) {
+        // k-hat = LN_s(sK) * gamma + beta
+        double sum = 0.0, sq = 0.0;
+#pragma unroll
+        for (int dblk = 0; dblk < 4; ++dblk)
+#pragma unroll
+          for (int vq = 0; vq < 4; ++vq) {
+            const double *xp = a.wsK + ro + 32 * dblk + 8 * vq + 4 * g;
+            const double2 x0 = *reinterpret_cast<const double2 *>(xp), x1 = *reinterpret_cast<const double2 *>(xp + 2);
+            sum += (x0.x + x0.y) + (x1.x + x1.y);
+            sq += (x0.x * x0.x + x0.y * x0.y) + (x1.x * x1.x + x1.y * x1.y);
+          }
+        sum = swap_sum<true>(sum);
+        sq = swap_sum<true>(sq);
+        const double mean = sum / (double)D;
+        const double var = sq / (double)D - mean * mean;
+        const double rden = 1.0 / sqrt((var > 0.0 ? var : 0.0) + (double)dv.ln_eps);
+        float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+        for (int dblk = 0; dblk < 4; ++dblk)
+#pragma unroll
+          for (int vq = 0; vq < 4; ++vq) {
+            const int ch = 32 * dblk + 8 * vq + 4 * g;
+            const double *xp = a.wsK + ro + ch;
+            const double2 x0 = *reinterpret_cast<const double2 *>(xp), x1 = *reinterpret_cast<const double2 *>(xp + 2);
+            const double xs[4] = {x0.x, x0.y, x1.x, x1.y};
+            const float4 g4 = dv.gamma ? *reinterpret_cast<const float4 *>(dv.gamma + h * D + ch) : make_float4(1.f, 1.f, 1.f, 1.f);
+            const float gs[4] = {g4.x, g4.y, g4.z, g4.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float x = (float)((xs[e] - mean) * rden);
+              const float dk = o1[dblk][4 * vq + e] * scale * gs[e];  // dk-hat * gamma
+              o1[dblk][4 * vq + e] *= scale;
+              s1 += dk;
+              s2 += dk * x;
+            }
+          }
+        const float m1 = xhalf_sum(s1) / (float)D, m2 = xhalf_sum(s2) / (float)D;
+        float *red = reinterpret_cast<float *>(reinterpret_cast<char *>(lds) + kBwdTileBytes);  // [gamma | beta][wave][D]
+#pragma unroll
+        for (int dblk = 0; dblk < 4; ++dblk)
+#pragma unroll
+          for (int vq = 0; vq < 4; ++vq) {
+            const int ch = 32 * dblk + 8 * vq + 4 * g;
+            const float4 g4 = dv.gamma ? *reinterpret_cast<const float4 *>(dv.gamma + h * D + ch) : make_float4(1.f, 1.f, 1.f, 1.f);
+            const float gs[4] = {g4.x, g4.y, g4.z, g4.w};
+            const double *xp = a.wsK + ro + ch;
+            const double2 x0 = *reinterpret_cast<const double2 *>(xp), x1 = *reinterpret_cast<const double2 *>(xp + 2);
+            const double xs[4] = {x0.x, x0.y, x1.x, x1.y};
+            float add[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float dkh = o1[dblk][4 * vq + e], x = (float)((xs[e] - mean) * rden);
+              add[e] = (dkh * gs[e] - m1 - x * m2) * (float)rden;
+              // the LN_s parameter gradients are sums over rows: over the 32 lanes of this half
+              // of the wave here, over the waves below
+              const float pg = group_sum<32>(col_ok ? dkh * x : 0.f), pb = group_sum<32>(col_ok ? dkh : 0.f);
+              if (l32 == 0) {
+                red[wave * D + ch + e] = pg;
+                red[(4 + wave) * D + ch + e] = pb;
+              }
+            }
+            if (col_ok) {
+              float4 x4 = *reinterpret_cast<const float4 *>(a.dsK + ro + ch);
+              x4.x += add[0]; x4.y += add[1]; x4.z += add[2]; x4.w += add[3];
+              *reinterpret_cast<float4 *>(a.dsK + ro + ch) = x4;
+            }
+          }
+        __syncthreads();
+        {
+          const int which = tid / D, ch = tid % D;
+          const float sum4 = red[(4 * which) * D + ch] + red[(4 * which + 1) * D + ch] + red[(4 * which + 2) * D + ch] +
+                             red[(4 * which + 3) * D + ch];
+          atomicAdd(a.par64 + (which * dv.Hkv + h) * D + ch, (double)sum4);
         }
+      } else if constexpr (kRole == kRoleDV) {
+        // v-hat = rho * sV / max(|sV|, eps)
+        float svr[4][16];
+        float nn = 0.f, dot = 0.f;
+#pragma unroll
+        for (int dblk = 0; dblk < 4; ++dblk)
+#pragma unroll
+          for (int vq = 0; vq < 4; ++vq) {
+            const float4 x4 = *reinterpret_cast<const float4 *>(a.wsV + ro + 32 * dblk + 8 * vq + 4 * g);
+            const float xs[4] = {x4.x, x4.y, x4.z, x4.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              svr[dblk][4 * vq + e] = xs[e];
+              nn += xs[e] * xs[e];
+              dot += o1[dblk][4 * vq + e] * xs[e];
+            }
+          }
+        const float nrm = sqrtf(xhalf_sum(nn));
+        const float den = fmaxf(nrm, dv.norm_eps);
+        dot = xhalf_sum(dot) / den;  // dv-hat . unit vector
+        const float rho = dv.rho[(int64_t)u * dv.Mcap + (col_ok ? st_row : 0)];
+        const float back = nrm > dv.norm_eps ? rho * dot / (den * den) : 0.f;
+        if (col_ok) {
+#pragma unroll
+          for (int dblk = 0; dblk < 4; ++dblk)
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) {
+              const int ch = 32 * dblk + 8 * vq + 4 * g;
+              float4 x4 = *reinterpret_cast<const float4 *>(a.dsV + ro + ch);
+              x4.x += rho / den * o1[dblk][4 * vq] - back * svr[dblk][4 * vq];
+              x4.y += rho / den * o1[dblk][4 * vq + 1] - back * svr[dblk][4 * vq + 1];
+              x4.z += rho / den * o1[dblk][4 * vq + 2] - back * svr[dblk][4 * vq + 2];
+              x4.w += rho / den * o1[dblk][4 * vq + 3] - back * svr[dblk][4 * vq + 3];
+              *reinterpret_cast<float4 *>(a.dsV + ro + ch) = x4;
+            }
+          if (g == 0) a.drho[(int64_t)u * dv.Mcap + st_row] += dot;
+        }
+      }
     }
   }
 }
