@@ -243,103 +243,151 @@ __global__ __launch_bounds__(256, 2) void bwd_mfma_kernel(Bwd a, MfmaChunk c) {
     const uint16_t *Y = X + kTileElems;
     // what this tile is, and whether any of it is visible to this wave's columns
     bool tile_state;   // logits of this tile use the state temperature
-    int lim_base;      // role dQ: tile rows <= lim_base + (lane's own term) are visible
+    bool need_mask;    // wave-uniform: whether any pair of the tile is invisible to this wave
+    int lim_lane = 0;  // role dQ: tile rows <= lim_lane are visible to the lane's query
+    int lo_lane = 0, hi_row = 0;  // roles dK, dV: tile rows lo_lane .. hi_row are visible to the lane's key
     int hq;
-    int row_pos0 = 0;  // roles dK, dV: position of the tile's first query, relative to cs
     if constexpr (!kKeysSta) {
       hq = hq_sta;
       tile_state = it < n_st;
+      const int wave_q0 = kStaPerWg * (member % tpc) + 32 * wave;  // the wave's first query
       if (tile_state) {
-        lim_base = c.m - it * kTileKeys - 1;
+        lim_lane = c.m - it * kTileKeys - 1;
+        need_mask = lim_lane < kTileKeys - 1;
       } else {
         const int p0rel = (int)(c.wb - c.cs) + (it - n_st) * kTileKeys;
-        if (p0rel > kStaPerWg * (member % tpc) + 32 * wave + 31) return;  // all keys after the wave's queries
-        lim_base = -p0rel;  // visible rows: p0rel + r <= colq
+        if (p0rel > wave_q0 + 31) return;  // all keys after the wave's queries
+        lim_lane = colq - p0rel;           // visible rows: p0rel + r <= colq
+        need_mask = p0rel + kTileKeys - 1 > wave_q0;
       }
     } else {
       const int gq = it / per_head, qtile = qt0 + it % per_head;
       hq = __builtin_amdgcn_readfirstlane(h * G + gq);
       tile_state = sta_state;
-      row_pos0 = qtile * kTileKeys;
-      lim_base = 0;
-      if (!sta_state && wg_first + 32 * wave > row_pos0 + kTileKeys - 1) return;  // all queries before the wave's keys
+      const int row_pos0 = qtile * kTileKeys;  // the tile's first query, relative to the chunk start
+      hi_row = c.nq - 1 - row_pos0;            // rows beyond the chunk's last query are padding
+      need_mask = hi_row < kTileKeys - 1;
+      if (!sta_state) {
+        const int wave_k0 = wg_first + 32 * wave;  // the wave's first key, relative to the chunk start
+        if (wave_k0 > row_pos0 + kTileKeys - 1) return;  // all queries before the wave's keys
+        lo_lane = wave_k0 + l32 - row_pos0;              // visible rows: key position <= query position
+        need_mask = need_mask || wave_k0 + 31 > row_pos0;
+      }
     }
     const float tau = tile_state ? (dv.tau_state ? dv.tau_state[hq] : 1.f) : (dv.tau_bswa ? dv.tau_bswa[hq] : 1.f);
     const float cexp = tau * scale * kLog2e;
 
+    // Role dK takes the two 32-row halves of the tile one after the other -- logits and
+    // dout . v^T of the half, the elementwise step, then the half's share of the result -- so
+    // that half the logit registers are live; the other roles take them together.
     f32x16 sacc[2], dacc[2];
-    {
-      const f32x16 zero = {0.f};
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks)
-#pragma unroll
-        for (int blk = 0; blk < 2; ++blk) {
-          sacc[blk] = mfma32(ktile_frag(X, koff, blk, ks), sk[ks], ks == 0 ? zero : sacc[blk]);
-          if constexpr (kWantDS) dacc[blk] = mfma32(ktile_frag(Y, koff, blk, ks), sv[ks], ks == 0 ? zero : dacc[blk]);
-        }
-    }
     Frag8 pP[4], pS[4];
     float tsum = 0.f;
+    auto elementwise = [&](auto masked, auto blk_c) {
+      {
+        constexpr int blk = decltype(blk_c)::value;
+        float lse_r[16], d_r[16];
+        if constexpr (kKeysSta) {
+          const float *rl = rowsc + decltype(parity)::value * 128 + 32 * blk + 4 * g;
 #pragma unroll
-    for (int blk = 0; blk < 2; ++blk) {
-      float lse_r[16], d_r[16];
-      if constexpr (kKeysSta) {
-        const float *rl = rowsc + decltype(parity)::value * 128 + 32 * blk + 4 * g;
+          for (int v4 = 0; v4 < 4; ++v4) {
+            const float4 x = *reinterpret_cast<const float4 *>(rl + 8 * v4);
+            const float4 y = *reinterpret_cast<const float4 *>(rl + 64 + 8 * v4);
+            lse_r[4 * v4] = x.x; lse_r[4 * v4 + 1] = x.y; lse_r[4 * v4 + 2] = x.z; lse_r[4 * v4 + 3] = x.w;
+            d_r[4 * v4] = y.x; d_r[4 * v4 + 1] = y.y; d_r[4 * v4 + 2] = y.z; d_r[4 * v4 + 3] = y.w;
+          }
+        }
 #pragma unroll
-        for (int v4 = 0; v4 < 4; ++v4) {
-          const float4 x = *reinterpret_cast<const float4 *>(rl + 8 * v4);
-          const float4 y = *reinterpret_cast<const float4 *>(rl + 64 + 8 * v4);
-          lse_r[4 * v4] = x.x; lse_r[4 * v4 + 1] = x.y; lse_r[4 * v4 + 2] = x.z; lse_r[4 * v4 + 3] = x.w;
-          d_r[4 * v4] = y.x; d_r[4 * v4 + 1] = y.y; d_r[4 * v4 + 2] = y.z; d_r[4 * v4 + 3] = y.w;
+        for (int v = 0; v < 16; ++v) {
+          const int r = 32 * blk + mfma_row(v, g);
+          bool vis = true;
+          float lse2, dd;
+          if constexpr (!kKeysSta) {
+            if constexpr (decltype(masked)::value) vis = r <= lim_lane;
+            lse2 = lse2_col;
+            dd = d_col;
+          } else {
+            if constexpr (decltype(masked)::value) vis = r >= lo_lane && r <= hi_row;
+            lse2 = lse_r[v];
+            dd = d_r[v];
+          }
+          const float s = sacc[blk][v];
+          const float p = vis ? __builtin_amdgcn_exp2f(fmaf(s, cexp, -lse2)) : 0.f;
+          sacc[blk][v] = p;
+          if constexpr (kWantDS) {
+            const float ds = p * (dacc[blk][v] - dd);
+            tsum = fmaf(ds, s, tsum);
+            dacc[blk][v] = ds * tau;
+          }
         }
       }
+    };
+    auto first_products = [&](auto blk_c) {
+      constexpr int blk = decltype(blk_c)::value;
+      const f32x16 zero = {0.f};
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int r = 32 * blk + mfma_row(v, g);
-        bool vis;
-        float lse2, dd;
-        if constexpr (!kKeysSta) {
-          vis = tile_state ? r <= lim_base : r <= lim_base + colq;
-          lse2 = lse2_col;
-          dd = d_col;
-        } else {
-          const int qi = row_pos0 + r;  // query index within the chunk
-          vis = qi < c.nq && (sta_state || kpos <= c.cs + qi);
-          lse2 = lse_r[v];
-          dd = d_r[v];
+      for (int ks = 0; ks < 8; ++ks) {
+        sacc[blk] = mfma32(ktile_frag(X, koff, blk, ks), sk[ks], ks == 0 ? zero : sacc[blk]);
+        if constexpr (kWantDS) dacc[blk] = mfma32(ktile_frag(Y, koff, blk, ks), sv[ks], ks == 0 ? zero : dacc[blk]);
+      }
+    };
+    auto second_product = [&](auto blk_c) {
+      constexpr int blk = decltype(blk_c)::value;
+#pragma unroll
+      for (int ks = 2 * blk; ks < 2 * blk + 2; ++ks) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int v0 = (ks & 1) * 8 + 2 * e;
+          if constexpr (kWantDS)
+            pS[ks].w[e] = pack_bf16(dacc[blk][v0], dacc[blk][v0 + 1]);
+          else
+            pP[ks].w[e] = pack_bf16(sacc[blk][v0], sacc[blk][v0 + 1]);
         }
-        const float s = sacc[blk][v];
-        const float p = vis ? __builtin_amdgcn_exp2f(fmaf(s, cexp, -lse2)) : 0.f;
-        sacc[blk][v] = p;
-        if constexpr (kWantDS) {
-          const float ds = p * (dacc[blk][v] - dd);
-          tsum = fmaf(ds, s, tsum);
-          dacc[blk][v] = ds * tau;
+#pragma unroll
+        for (int dblk = 0; dblk < 4; ++dblk) {
+          if constexpr (kWantDS)
+            o1[dblk] = mfma32(ttile_frag(X, toff, dblk, ks), pS[ks].v, o1[dblk]);
+          else
+            o1[dblk] = mfma32(ttile_frag(Y, toff, dblk, ks), pP[ks].v, o1[dblk]);
         }
       }
+    };
+    using B0 = std::integral_constant<int, 0>;
+    using B1 = std::integral_constant<int, 1>;
+    using Masked = std::integral_constant<bool, true>;
+    using Plain = std::integral_constant<bool, false>;
+    if constexpr (kRole == kRoleDK) {
+      first_products(B0{});
+      if (need_mask) elementwise(Masked{}, B0{}); else elementwise(Plain{}, B0{});
+      second_product(B0{});
+      first_products(B1{});
+      if (need_mask) elementwise(Masked{}, B1{}); else elementwise(Plain{}, B1{});
+      second_product(B1{});
+    } else if constexpr (kRole == kRoleDV) {
+      first_products(B0{});
+      first_products(B1{});
+      if (need_mask) {
+        elementwise(Masked{}, B0{});
+        elementwise(Masked{}, B1{});
+      } else {
+        elementwise(Plain{}, B0{});
+        elementwise(Plain{}, B1{});
+      }
+      second_product(B0{});
+      second_product(B1{});
+    } else {
+      // role dQ has no registers for two variants of the elementwise step: it always compares
+      (void)need_mask;
+      first_products(B0{});
+      first_products(B1{});
+      elementwise(Masked{}, B0{});
+      elementwise(Masked{}, B1{});
+      second_product(B0{});
+      second_product(B1{});
     }
     if constexpr (!kKeysSta) {
       if (tile_state) tau_sum_state += tsum; else tau_sum_bswa += tsum;
     }
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int v0 = (ks & 1) * 8 + 2 * e;
-        if constexpr (kWantDS)
-          pS[ks].w[e] = pack_bf16(dacc[ks >> 1][v0], dacc[ks >> 1][v0 + 1]);
-        else
-          pP[ks].w[e] = pack_bf16(sacc[ks >> 1][v0], sacc[ks >> 1][v0 + 1]);
-      }
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-      for (int dblk = 0; dblk < 4; ++dblk) {
-        if constexpr (kWantDS)
-          o1[dblk] = mfma32(ttile_frag(X, toff, dblk, ks), pS[ks].v, o1[dblk]);
-        else
-          o1[dblk] = mfma32(ttile_frag(Y, toff, dblk, ks), pP[ks].v, o1[dblk]);
-      }
   };
 
   // the stationary vectors are in registers from here on (the compiler does not count the tile
