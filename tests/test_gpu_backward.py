@@ -77,7 +77,9 @@ def check(w, name, got, ref, slack=0.0, f32_bar=1e-4):
     assert worst <= 1.0, f"{name}: bf16 error is {worst:.3f} x the 2e-2 bound"
 
 
-def run_backward_case(w, plain):
+def run_backward_case(w, plain, units=None):
+    """Forward with the fold record on, backward, and the oracle on every unit (or on the sampled
+    `units`: then the gradients summed over all units -- LN_s, temperatures -- are not checked)."""
     pkg, sy = kvm(), synth()
     q, k, v = sy.make_qkv(w, DEV)
     params = sy.make_params(w, DEV, plain=plain)
@@ -97,30 +99,33 @@ def run_backward_case(w, plain):
                 dtau_state=np.zeros(w.n_q_heads), dtau_bswa=np.zeros(w.n_q_heads))
     slack = {name: 0.0 for name in sums}
     kinds = set()
-    for b in range(w.batch):
-        for h in range(w.n_kv_heads):
-            u = tl.unit_inputs(w, q, k, v, params, b, h)
-            dy = tl.f64(dout[b, :, h * G:(h + 1) * G]).transpose(1, 0, 2)
-            res = oracle_unit_following(w, params, u, dy, h, ga_all[:, b, h])
-            assert res["m"] == st.rows and len(res["fold_logs"]) == st.folds
-            for log in res["fold_logs"]:
-                kinds.add("creation" if log["m_before"] == 0 else "append all" if log["n_append"] == w.chunk_len
-                          else "partial append" if log["n_append"] > 0 else "merge only")
-            what = f"unit {(b, h)}"
-            check(w, f"dq {what}", tl.f64(g["dq"][b, :, h * G:(h + 1) * G]).transpose(1, 0, 2), res["dq"])
-            check(w, f"dk {what}", tl.f64(g["dk"][b, :, h]), res["dk"])
-            check(w, f"dv {what}", tl.f64(g["dv"][b, :, h]), res["dv"])
-            check(w, f"dgate {what}", tl.f64(g["dgate"][b, :, h]), res["dg"])
-            if w.io == "bf16":
-                exact = oracle_unit_following(w, params, u, dy, h, ga_all[:, b, h], round_output=False)
-                for name in slack:
-                    slack[name] += 2.0 * float(np.abs(res[name] - exact[name]).max())
-            sums["dgamma"][h] += res["dgamma"]
-            sums["dbeta"][h] += res["dbeta"]
-            sums["dtau_state"][h * G:(h + 1) * G] += res["dtau_state"]
-            sums["dtau_bswa"][h * G:(h + 1) * G] += res["dtau_bswa"]
-    for name, ref in sums.items():
-        check(w, name, tl.f64(g[name]), ref, slack[name], f32_bar=1e-3)
+    all_units = [(b, h) for b in range(w.batch) for h in range(w.n_kv_heads)]
+    for key in ("dq", "dk", "dv", "dgate", "dgamma", "dbeta", "dtau_state", "dtau_bswa"):
+        assert bool(torch.isfinite(g[key].float()).all()), f"{key} has non-finite entries"
+    for (b, h) in (all_units if units is None else units):
+        u = tl.unit_inputs(w, q, k, v, params, b, h)
+        dy = tl.f64(dout[b, :, h * G:(h + 1) * G]).transpose(1, 0, 2)
+        res = oracle_unit_following(w, params, u, dy, h, ga_all[:, b, h])
+        assert res["m"] == st.rows and len(res["fold_logs"]) == st.folds
+        for log in res["fold_logs"]:
+            kinds.add("creation" if log["m_before"] == 0 else "append all" if log["n_append"] == w.chunk_len
+                      else "partial append" if log["n_append"] > 0 else "merge only")
+        what = f"unit {(b, h)}"
+        check(w, f"dq {what}", tl.f64(g["dq"][b, :, h * G:(h + 1) * G]).transpose(1, 0, 2), res["dq"])
+        check(w, f"dk {what}", tl.f64(g["dk"][b, :, h]), res["dk"])
+        check(w, f"dv {what}", tl.f64(g["dv"][b, :, h]), res["dv"])
+        check(w, f"dgate {what}", tl.f64(g["dgate"][b, :, h]), res["dg"])
+        if w.io == "bf16" and units is None:
+            exact = oracle_unit_following(w, params, u, dy, h, ga_all[:, b, h], round_output=False)
+            for name in slack:
+                slack[name] += 2.0 * float(np.abs(res[name] - exact[name]).max())
+        sums["dgamma"][h] += res["dgamma"]
+        sums["dbeta"][h] += res["dbeta"]
+        sums["dtau_state"][h * G:(h + 1) * G] += res["dtau_state"]
+        sums["dtau_bswa"][h * G:(h + 1) * G] += res["dtau_bswa"]
+    if units is None:
+        for name, ref in sums.items():
+            check(w, name, tl.f64(g[name]), ref, slack[name], f32_bar=1e-3)
     return kinds
 
 
@@ -165,6 +170,14 @@ def test_bf16_backward_short_chunks_three_chunk_window():
     w = synth().shrink(synth().WORKLOADS["prefill_gqa_32k"], batch=2, n_q_heads=4, n_kv_heads=2, seq=64 * 11 + 7,
                        chunk_len=64, n_bswa_chunks=3, budget_fixed=96, rope_dims=32)
     run_backward_case(w, plain=False)
+
+
+def test_full_size_backward_sampled_units():
+    """The benchmark workload at full size, in the configuration bench.py times (plain parameters,
+    no gate): the library runs the whole backward pass, the oracle replays the first and the last
+    (batch, KV head) unit over all chunks and folds."""
+    w = synth().WORKLOADS["prefill_gqa_32k"]
+    run_backward_case(w, plain=True, units=[(0, 0), (w.batch - 1, w.n_kv_heads - 1)])
 
 
 def test_backward_rejects_a_state_that_did_not_run_this_prefill():
