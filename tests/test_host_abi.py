@@ -114,6 +114,33 @@ def test_argument_and_capacity_errors_before_any_launch():
     assert lib.kvm_state_destroy(h) == 0
 
 
+def test_backward_argument_and_state_errors_before_any_launch():
+    lib = kb.load_library()
+    c = cfg()
+    h = C.c_void_p()
+    assert lib.kvm_state_init(C.byref(h), C.byref(c), FAKE_DEV_PTR, lib.kvm_state_bytes(C.byref(c), 4096), 4096) == 0
+    p = FAKE_DEV_PTR
+    grads = kb.kvm_grads(*([p] * 8))
+    assert lib.kvm_backward_workspace_bytes(None, 1024) == 0
+    assert lib.kvm_backward_workspace_bytes(h, 0) == 0
+    nbytes = lib.kvm_backward_workspace_bytes(h, 1024)
+    # the work arrays hold at least the fp32 accumulators of dk and dv and the sums' copies
+    U, d, T, M = 4, 128, 1024, 512
+    assert nbytes >= 2 * U * T * d * 4 + U * M * d * (8 + 4 + 4 + 4)
+    args = lambda **kw: [kw.get("st", h), kw.get("q", p), p, p, None, p, kw.get("lse", p), p, p, p,
+                         kw.get("grads", C.byref(grads)), kw.get("T", 1024), kw.get("ws", p), kw.get("n", nbytes), None]
+    # the state is empty: it has not run a prefill of 1024 tokens
+    assert lib.kvm_prefill_backward(*args()) == kb.KVM_ERR_STATE
+    assert lib.kvm_prefill_backward(*args(q=None)) == kb.KVM_ERR_ARG
+    assert lib.kvm_prefill_backward(*args(lse=None)) == kb.KVM_ERR_ARG
+    assert lib.kvm_prefill_backward(*args(grads=None)) == kb.KVM_ERR_ARG
+    assert lib.kvm_prefill_backward(*args(T=0)) == kb.KVM_ERR_ARG
+    assert lib.kvm_prefill_backward(*args(st=None)) == kb.KVM_ERR_ARG
+    missing = kb.kvm_grads(p, p, p, p, None, p, p, p)
+    assert lib.kvm_prefill_backward(*args(grads=C.byref(missing))) == kb.KVM_ERR_ARG
+    assert lib.kvm_state_destroy(h) == 0
+
+
 def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(kb, "_lib", None)
     monkeypatch.setattr(kb, "LIB_PATH", str(tmp_path / "libkvm.so"))
