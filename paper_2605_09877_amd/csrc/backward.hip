@@ -49,9 +49,9 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(const void *out_, const 
 // The LN_s parameter gradients of a workgroup's rows: summed over its four waves in LDS, then one
 // fp64 atomic per channel (dgamma at par64[h * D + ch], dbeta behind all the dgammas).
 constexpr int kRowsPerWave = 16;
-template <int D>
+template <int D, int kWaves>
 __device__ __forceinline__ void block_param_add(const Bwd &a, int h, const float (&dga)[D / 64],
-                                                const float (&dbe)[D / 64], float (*red)[4][D]) {
+                                                const float (&dbe)[D / 64], float (*red)[kWaves][D]) {
   constexpr int CPL = D / 64;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
@@ -60,10 +60,12 @@ __device__ __forceinline__ void block_param_add(const Bwd &a, int h, const float
     red[1][wave][lane * CPL + c] = dbe[c];
   }
   __syncthreads();
-  for (int i = threadIdx.x; i < 2 * D; i += 256) {
+  for (int i = threadIdx.x; i < 2 * D; i += 64 * kWaves) {
     const int which = i / D, ch = i % D;
-    const float sum = red[which][0][ch] + red[which][1][ch] + red[which][2][ch] + red[which][3][ch];
-    atomicAdd(a.par64 + (which * a.dv.Hkv + h) * D + ch, (double)sum);
+    float sum = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) sum += red[which][w][ch];
+    if (sum != 0.f) atomicAdd(a.par64 + (which * a.dv.Hkv + h) * D + ch, (double)sum);
   }
 }
 
@@ -77,16 +79,18 @@ __device__ __forceinline__ void block_param_add(const Bwd &a, int h, const float
 // smallest (append score, position) keys, so among the tokens bound for one new row the creator
 // is the one with the smallest key.
 constexpr int kUnfoldRows = 1;
+constexpr int kUnfoldWaves = 4;  // waves per workgroup (16 measured slower: the workgroup waits for its slowest row)
 
 template <typename T, int D>
-__global__ __launch_bounds__(256) void bwd_unfold_kernel(Bwd a, int fold, int64_t lo, int m_before, int m_after) {
+__global__ __launch_bounds__(64 * kUnfoldWaves) void bwd_unfold_kernel(Bwd a, int fold, int64_t lo, int m_before,
+                                                                     int m_after) {
   constexpr int CPL = D / 64;
-  __shared__ float red[2][4][D];
+  __shared__ float red[2][kUnfoldWaves][D];
   const Dev &dv = a.dv;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int u = blockIdx.y, b = u / dv.Hkv, h = u % dv.Hkv;
   const int C = dv.C;
-  const int row_first = (blockIdx.x * 4 + wave) * kUnfoldRows;
+  const int row_first = (blockIdx.x * kUnfoldWaves + wave) * kUnfoldRows;
   const int64_t base = ((int64_t)fold * dv.U + u) * C;
   float dga_sum[CPL] = {}, dbe_sum[CPL] = {};
   float gam[CPL], bet[CPL];
@@ -251,7 +255,7 @@ __global__ __launch_bounds__(256) void bwd_unfold_kernel(Bwd a, int fold, int64_
       }
     }
   }
-  block_param_add<D>(a, h, dga_sum, dbe_sum, red);
+  block_param_add<D, kUnfoldWaves>(a, h, dga_sum, dbe_sum, red);
 }
 
 // Readout of the visited version: rows [0, m) of every unit, as the forward computes it.
@@ -347,7 +351,7 @@ __global__ __launch_bounds__(256) void bwd_readout_adjoint_kernel(Bwd a, int m) 
   }
   if (lane == 0) a.drho[(int64_t)u * dv.Mcap + row] += dot;
   }
-  block_param_add<D>(a, h, dga_sum, dbe_sum, red);
+  block_param_add<D, 4>(a, h, dga_sum, dbe_sum, red);
 }
 
 // One chunk's keys: state rows [0, m) of the visited version, then window positions [wb, s + nq).
@@ -577,7 +581,6 @@ hipError_t run_backward(const Bwd &a, const BwdChunk *chunks, int n_chunks, hipS
     BWD_TRY(hipMemcpyAsync(a.wsK, dv.sK, state_elems * 8, hipMemcpyDeviceToDevice, st));
     BWD_TRY(hipMemcpyAsync(a.wsV, dv.sV, state_elems * 4, hipMemcpyDeviceToDevice, st));
   }
-  BWD_DISPATCH(dv, bwd_delta_kernel, dim3((unsigned)((q_rows + 3) / 4)), dim3(256), st, a.out, a.dout, a.delta, q_rows);
 
   // the readout of the last version; undoing a fold then rewrites the rows it touched
   if (n_chunks > 0 && chunks[n_chunks - 1].m_after > 0) {
@@ -589,11 +592,15 @@ hipError_t run_backward(const Bwd &a, const BwdChunk *chunks, int n_chunks, hipS
     return e && e[0] == '1';
   }();
   const bool on_mfma = backward_on_mfma(dv) && !no_mfma;
+  // D = dout . out per query (the matrix-core dq kernel computes it for its own queries)
+  if (!on_mfma)
+    BWD_DISPATCH(dv, bwd_delta_kernel, dim3((unsigned)((q_rows + 3) / 4)), dim3(256), st, a.out, a.dout, a.delta, q_rows);
   for (int ci = n_chunks - 1; ci >= 0; --ci) {
     const BwdChunk &ch = chunks[ci];
     if (ch.fold >= 0)
-      BWD_DISPATCH(dv, bwd_unfold_kernel, dim3((ch.m_after + 4 * kUnfoldRows - 1) / (4 * kUnfoldRows), dv.U),
-                   dim3(256), st, a, ch.fold, ch.s + ch.nq - dv.L, ch.m, ch.m_after);
+      BWD_DISPATCH(dv, bwd_unfold_kernel,
+                   dim3((ch.m_after + kUnfoldWaves * kUnfoldRows - 1) / (kUnfoldWaves * kUnfoldRows), dv.U),
+                   dim3(64 * kUnfoldWaves), st, a, ch.fold, ch.s + ch.nq - dv.L, ch.m, ch.m_after);
     const int64_t c0 = ch.s / dv.C * dv.C;
     ChunkArgs c;
     c.s = ch.s;

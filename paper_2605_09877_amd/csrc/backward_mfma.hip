@@ -145,7 +145,23 @@ __global__ __launch_bounds__(256, 2) void bwd_mfma_kernel(Bwd a, MfmaChunk c) {
     const int qc = col_ok ? colq : c.nq - 1;
     const int64_t qrow = ((int64_t)b * a.T + c.cs + qc) * dv.Hq + hq_sta;
     lse2_col = a.lse[qrow] * kLog2e;
-    d_col = a.delta[qrow];
+    // D = dout . out of the lane's query: the lane has half of the dout row already; the other
+    // roles, which run after this one, read D from memory
+    const uint16_t *o_row = (const uint16_t *)a.out + qrow * D;
+    float part = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      const uint4 ov = *reinterpret_cast<const uint4 *>(o_row + 16 * ks + 8 * g);
+      Frag8 f;
+      f.v = sv[ks];
+      float of[8], df[8];
+      unpack16<bf16_t>(ov, of);
+      unpack16<bf16_t>(f.q, df);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) part = fmaf(of[e], df[e], part);
+    }
+    d_col = xhalf_sum(part);
+    if (col_ok && g == 0) a.delta[qrow] = d_col;
   }
 
   // ---- streamed tiles
