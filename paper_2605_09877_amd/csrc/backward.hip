@@ -78,19 +78,19 @@ __device__ __forceinline__ void block_param_add(const Bwd &a, int h, const float
 // created that row or merged into it afterwards: the forward appends the tokens with the
 // smallest (append score, position) keys, so among the tokens bound for one new row the creator
 // is the one with the smallest key.
-constexpr int kUnfoldRows = 1;
+constexpr int kUnfoldRows = 4;  // at most
 constexpr int kUnfoldWaves = 4;  // waves per workgroup (16 measured slower: the workgroup waits for its slowest row)
 
 template <typename T, int D>
 __global__ __launch_bounds__(64 * kUnfoldWaves) void bwd_unfold_kernel(Bwd a, int fold, int64_t lo, int m_before,
-                                                                     int m_after) {
+                                                                     int m_after, int rows_per_wave) {
   constexpr int CPL = D / 64;
   __shared__ float red[2][kUnfoldWaves][D];
   const Dev &dv = a.dv;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int u = blockIdx.y, b = u / dv.Hkv, h = u % dv.Hkv;
   const int C = dv.C;
-  const int row_first = (blockIdx.x * kUnfoldWaves + wave) * kUnfoldRows;
+  const int row_first = (blockIdx.x * kUnfoldWaves + wave) * rows_per_wave;
   const int64_t base = ((int64_t)fold * dv.U + u) * C;
   float dga_sum[CPL] = {}, dbe_sum[CPL] = {};
   float gam[CPL], bet[CPL];
@@ -108,7 +108,7 @@ __global__ __launch_bounds__(64 * kUnfoldWaves) void bwd_unfold_kernel(Bwd a, in
     }
   };
   if (row_first < m_after) load_targets(0);
-  for (int rr = 0; rr < kUnfoldRows; ++rr) {
+  for (int rr = 0; rr < rows_per_wave; ++rr) {
     const int row = row_first + rr;
     if (row >= m_after) break;
     const bool fresh = row >= m_before;  // a row this fold created: it ends here
@@ -597,10 +597,14 @@ hipError_t run_backward(const Bwd &a, const BwdChunk *chunks, int n_chunks, hipS
     BWD_DISPATCH(dv, bwd_delta_kernel, dim3((unsigned)((q_rows + 3) / 4)), dim3(256), st, a.out, a.dout, a.delta, q_rows);
   for (int ci = n_chunks - 1; ci >= 0; --ci) {
     const BwdChunk &ch = chunks[ci];
-    if (ch.fold >= 0)
-      BWD_DISPATCH(dv, bwd_unfold_kernel,
-                   dim3((ch.m_after + kUnfoldWaves * kUnfoldRows - 1) / (kUnfoldWaves * kUnfoldRows), dv.U),
-                   dim3(64 * kUnfoldWaves), st, a, ch.fold, ch.s + ch.nq - dv.L, ch.m, ch.m_after);
+    if (ch.fold >= 0) {
+      // rows per wave: about one block token per wave's rows, so that the scan of the targets is
+      // shared where rows are many and hot rows run in parallel where they are few
+      int rpw = ch.m_after / dv.C;
+      rpw = rpw < 1 ? 1 : (rpw > kUnfoldRows ? kUnfoldRows : rpw);
+      BWD_DISPATCH(dv, bwd_unfold_kernel, dim3((ch.m_after + kUnfoldWaves * rpw - 1) / (kUnfoldWaves * rpw), dv.U),
+                   dim3(64 * kUnfoldWaves), st, a, ch.fold, ch.s + ch.nq - dv.L, ch.m, ch.m_after, rpw);
+    }
     const int64_t c0 = ch.s / dv.C * dv.C;
     ChunkArgs c;
     c.s = ch.s;
