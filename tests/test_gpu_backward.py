@@ -172,6 +172,19 @@ def test_bf16_backward_short_chunks_three_chunk_window():
     run_backward_case(w, plain=False)
 
 
+@pytest.mark.parametrize("seq", [64 + 5, 128, 64 * 3])
+def test_f32_backward_of_short_sequences(seq):
+    """No fold at all (shorter than the window), exactly one window (one fold, after the last
+    chunk, that no query sees), and one chunk more."""
+    w = synth().shrink(synth().WORKLOADS["tiny_f32"], seq=seq)
+    run_backward_case(w, plain=False)
+
+
+def test_bf16_backward_of_one_window():
+    w = synth().shrink(synth().WORKLOADS["prefill_fixed"], batch=1, n_q_heads=2, n_kv_heads=2, seq=512, chunk_len=256)
+    run_backward_case(w, plain=False)
+
+
 def test_full_size_backward_sampled_units():
     """The benchmark workload at full size, in the configuration bench.py times (plain parameters,
     no gate): the library runs the whole backward pass, the oracle replays the first and the last
