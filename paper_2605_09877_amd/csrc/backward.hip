@@ -541,6 +541,27 @@ __global__ __launch_bounds__(256) void bwd_cast_kernel(const float *src, T *dst,
   }
 }
 
+template <typename T, int D>
+__global__ __launch_bounds__(256) void bwd_zero_floats_kernel(float *p, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0.f;
+}
+
+// Zero fill with a kernel of the library's own (a caller may capture the call in a graph, where
+// memset nodes are best avoided): n4 pieces of 16 bytes.
+__global__ __launch_bounds__(256) void bwd_zero_kernel(uint4 *p, int64_t n4) {
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) p[i] = make_uint4(0u, 0u, 0u, 0u);
+}
+hipError_t zero_fill(void *p, size_t bytes, hipStream_t st) {
+  const int64_t n4 = (int64_t)((bytes + 15) / 16);  // the work arrays are padded to 256 bytes
+  if (n4 == 0) return hipSuccess;
+  const int64_t want = (n4 + 255) / 256;
+  const unsigned blocks = (unsigned)(want < 8192 ? want : 8192);
+  hipLaunchKernelGGL(bwd_zero_kernel, dim3(blocks), dim3(256), 0, st, (uint4 *)p, n4);
+  return hipGetLastError();
+}
+
 #define BWD_DISPATCH(dv, KERNEL, grid, block, st, ...)                                    \
   do {                                                                                    \
     if ((dv).io == 0 && (dv).d == 64)                                                     \
@@ -570,13 +591,15 @@ hipError_t run_backward(const Bwd &a, const BwdChunk *chunks, int n_chunks, hipS
   const int64_t kv_elems = (int64_t)dv.B * a.T * dv.Hkv * D;
   const int64_t q_rows = (int64_t)dv.B * a.T * dv.Hq;
   // everything that is accumulated starts at zero; the sums start as the forward left them
-  BWD_TRY(hipMemsetAsync(a.dsK, 0, state_elems * 4, st));
-  BWD_TRY(hipMemsetAsync(a.dsV, 0, state_elems * 4, st));
-  BWD_TRY(hipMemsetAsync(a.drho, 0, (int64_t)dv.U * dv.Mcap * 4, st));
-  BWD_TRY(hipMemsetAsync(a.dk_acc, 0, kv_elems * 4, st));
-  BWD_TRY(hipMemsetAsync(a.dv_acc, 0, kv_elems * 4, st));
-  BWD_TRY(hipMemsetAsync(a.dgate, 0, (int64_t)dv.B * a.T * dv.Hkv * 4, st));
-  BWD_TRY(hipMemsetAsync(a.par64, 0, (size_t)(2 * dv.Hkv * D + 2 * dv.Hq) * 8, st));
+  BWD_TRY(zero_fill(a.dsK, state_elems * 4, st));
+  BWD_TRY(zero_fill(a.dsV, state_elems * 4, st));
+  BWD_TRY(zero_fill(a.drho, (size_t)dv.U * dv.Mcap * 4, st));
+  BWD_TRY(zero_fill(a.dk_acc, kv_elems * 4, st));
+  BWD_TRY(zero_fill(a.dv_acc, kv_elems * 4, st));
+  BWD_TRY(zero_fill(a.par64, (size_t)(2 * dv.Hkv * D + 2 * dv.Hq) * 8, st));
+  // dgate is the caller's tensor: its size need not be a multiple of 16 bytes
+  BWD_DISPATCH(dv, bwd_zero_floats_kernel, dim3((unsigned)(((int64_t)dv.B * a.T * dv.Hkv + 255) / 256)), dim3(256), st,
+               a.dgate, (int64_t)dv.B * a.T * dv.Hkv);
   if (dv.sK) {
     BWD_TRY(hipMemcpyAsync(a.wsK, dv.sK, state_elems * 8, hipMemcpyDeviceToDevice, st));
     BWD_TRY(hipMemcpyAsync(a.wsV, dv.sV, state_elems * 4, hipMemcpyDeviceToDevice, st));
