@@ -180,6 +180,19 @@ def test_f32_backward_of_short_sequences(seq):
     run_backward_case(w, plain=False)
 
 
+def test_f32_backward_head_dim_128_table_budget_no_sinks():
+    w = synth().shrink(synth().WORKLOADS["tiny_f32"], head_dim=128, rope_dims=32, seq=64 * 7 + 9, n_sink=0,
+                       budget_kind="table", budget_table=(0, 64, 70, 70, 100, 101))
+    kinds = run_backward_case(w, plain=False)
+    assert "partial append" in kinds
+
+
+def test_bf16_backward_head_dim_64_on_the_vector_kernels():
+    w = synth().shrink(synth().WORKLOADS["prefill_fixed"], batch=1, n_q_heads=4, n_kv_heads=2, head_dim=64, rope_dims=16,
+                       seq=64 * 6 + 30, chunk_len=64, budget_fixed=96)
+    run_backward_case(w, plain=False)
+
+
 def test_bf16_backward_of_one_window():
     w = synth().shrink(synth().WORKLOADS["prefill_fixed"], batch=1, n_q_heads=2, n_kv_heads=2, seq=512, chunk_len=256)
     run_backward_case(w, plain=False)
