@@ -252,7 +252,9 @@ __global__ __launch_bounds__(64 * kUnfoldWaves) void bwd_unfold_kernel(Bwd a, in
         const int ch = lane * CPL + c;
         Io<T>::store((T *)a.khat + ro + ch, Io<T>::round_from((sk[c] - mean) * rden * (double)gam[c] + (double)bet[c]));
         Io<T>::store((T *)a.vhat + ro + ch, sv[c] * vs);
+        a.xhat[ro + ch] = (float)((sk[c] - mean) * rden);
       }
+      if (lane == 0) a.rden[(int64_t)u * dv.Mcap + row] = (float)rden;
     }
   }
   block_param_add<D, kUnfoldWaves>(a, h, dga_sum, dbe_sum, red);
@@ -290,7 +292,9 @@ __global__ __launch_bounds__(256) void bwd_readout_kernel(Bwd a, int m) {
     const double b_ = dv.beta ? (double)dv.beta[h * D + ch] : 0.0;
     Io<T>::store((T *)a.khat + ro + ch, Io<T>::round_from((sk[c] - mean) * rden * g_ + b_));
     Io<T>::store((T *)a.vhat + ro + ch, sv[c] * vs);
+    a.xhat[ro + ch] = (float)((sk[c] - mean) * rden);
   }
+  if (lane == 0) a.rden[(int64_t)u * dv.Mcap + row] = (float)rden;
 }
 
 // Adjoint of the readout into the adjoint of the sums: rows [0, m).

@@ -469,66 +469,46 @@ __global__ __launch_bounds__(256, 2) void bwd_mfma_kernel(Bwd a, MfmaChunk c) {
     if (sta_state) {
       const int64_t ro = ((int64_t)u * dv.Mcap + (col_ok ? st_row : 0)) * D;
       if constexpr (kRole == kRoleDK) {
-        // k-hat = LN_s(sK) * gamma + beta
-        double sum = 0.0, sq = 0.0;
-#pragma unroll
-        for (int dblk = 0; dblk < 4; ++dblk)
-#pragma unroll
-          for (int vq = 0; vq < 4; ++vq) {
-            const double *xp = a.wsK + ro + 32 * dblk + 8 * vq + 4 * g;
-            const double2 x0 = *reinterpret_cast<const double2 *>(xp), x1 = *reinterpret_cast<const double2 *>(xp + 2);
-            sum += (x0.x + x0.y) + (x1.x + x1.y);
-            sq += (x0.x * x0.x + x0.y * x0.y) + (x1.x * x1.x + x1.y * x1.y);
-          }
-        sum = swap_sum<true>(sum);
-        sq = swap_sum<true>(sq);
-        const double mean = sum / (double)D;
-        const double var = sq / (double)D - mean * mean;
-        const double rden = 1.0 / sqrt((var > 0.0 ? var : 0.0) + (double)dv.ln_eps);
+        // k-hat = LN_s(sK) * gamma + beta.  The standardised sums x-hat and 1 / sqrt(var + eps) of
+        // the visited version are kept beside its readout, so everything the row needs is asked
+        // for at once: one memory round trip, not a chain of them.
+        const float rden = a.rden[(int64_t)u * dv.Mcap + (col_ok ? st_row : 0)];
+        float xh[4][16], pg[4][16], pb[4][16];
         float s1 = 0.f, s2 = 0.f;
 #pragma unroll
         for (int dblk = 0; dblk < 4; ++dblk)
 #pragma unroll
           for (int vq = 0; vq < 4; ++vq) {
             const int ch = 32 * dblk + 8 * vq + 4 * g;
-            const double *xp = a.wsK + ro + ch;
-            const double2 x0 = *reinterpret_cast<const double2 *>(xp), x1 = *reinterpret_cast<const double2 *>(xp + 2);
-            const double xs[4] = {x0.x, x0.y, x1.x, x1.y};
+            const float4 x4 = *reinterpret_cast<const float4 *>(a.xhat + ro + ch);
             const float4 g4 = dv.gamma ? *reinterpret_cast<const float4 *>(dv.gamma + h * D + ch) : make_float4(1.f, 1.f, 1.f, 1.f);
-            const float gs[4] = {g4.x, g4.y, g4.z, g4.w};
+            const float xs[4] = {x4.x, x4.y, x4.z, x4.w}, gs[4] = {g4.x, g4.y, g4.z, g4.w};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-              const float x = (float)((xs[e] - mean) * rden);
-              const float dk = o1[dblk][4 * vq + e] * scale * gs[e];  // dk-hat * gamma
-              o1[dblk][4 * vq + e] *= scale;
-              s1 += dk;
-              s2 += dk * x;
+              const float dkh = o1[dblk][4 * vq + e] * scale;
+              xh[dblk][4 * vq + e] = xs[e];
+              pb[dblk][4 * vq + e] = dkh * gs[e];  // dk-hat * gamma for now
+              pg[dblk][4 * vq + e] = dkh;
+              s1 += dkh * gs[e];
+              s2 += dkh * gs[e] * xs[e];
             }
           }
         const float m1 = xhalf_sum(s1) / (float)D, m2 = xhalf_sum(s2) / (float)D;
         float *red = reinterpret_cast<float *>(reinterpret_cast<char *>(lds) + kBwdTileBytes);  // [gamma | beta][wave][D]
+        // the adjoint of the sums; what the parameter gradients sum over the rows is kept:
+        // pg = dk-hat * x-hat (dgamma), pb = dk-hat (dbeta), zero for rows beyond the state
 #pragma unroll
         for (int dblk = 0; dblk < 4; ++dblk)
 #pragma unroll
           for (int vq = 0; vq < 4; ++vq) {
             const int ch = 32 * dblk + 8 * vq + 4 * g;
-            const float4 g4 = dv.gamma ? *reinterpret_cast<const float4 *>(dv.gamma + h * D + ch) : make_float4(1.f, 1.f, 1.f, 1.f);
-            const float gs[4] = {g4.x, g4.y, g4.z, g4.w};
-            const double *xp = a.wsK + ro + ch;
-            const double2 x0 = *reinterpret_cast<const double2 *>(xp), x1 = *reinterpret_cast<const double2 *>(xp + 2);
-            const double xs[4] = {x0.x, x0.y, x1.x, x1.y};
             float add[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-              const float dkh = o1[dblk][4 * vq + e], x = (float)((xs[e] - mean) * rden);
-              add[e] = (dkh * gs[e] - m1 - x * m2) * (float)rden;
-              // the LN_s parameter gradients are sums over rows: over the 32 lanes of this half
-              // of the wave here, over the waves below
-              const float pg = group_sum<32>(col_ok ? dkh * x : 0.f), pb = group_sum<32>(col_ok ? dkh : 0.f);
-              if (l32 == 0) {
-                red[wave * D + ch + e] = pg;
-                red[(4 + wave) * D + ch + e] = pb;
-              }
+              const float dkh = pg[dblk][4 * vq + e], x = xh[dblk][4 * vq + e];
+              add[e] = (pb[dblk][4 * vq + e] - m1 - x * m2) * rden;
+              pg[dblk][4 * vq + e] = col_ok ? dkh * x : 0.f;
+              pb[dblk][4 * vq + e] = col_ok ? dkh : 0.f;
             }
             if (col_ok) {
               float4 x4 = *reinterpret_cast<const float4 *>(a.dsK + ro + ch);
@@ -536,12 +516,54 @@ __global__ __launch_bounds__(256, 2) void bwd_mfma_kernel(Bwd a, MfmaChunk c) {
               *reinterpret_cast<float4 *>(a.dsK + ro + ch) = x4;
             }
           }
+        // Sums over the 32 rows (lanes) of this half of the wave, for 64 channels at once: a
+        // butterfly in which every exchange also halves the number of channels a lane carries --
+        // the lane whose bit is set keeps the upper half of its channels and hands the lower half
+        // to its partner, and the other way round -- so that 62 exchanges do the work of 64 x 5.
+        // Register i stands for channel 32*(i/16) + 8*((i%16)/4) + 4*g + i%4; after the five
+        // steps a lane holds the sums of registers base, base + 1, base = 32*b0 + 16*b1 + 8*b2 +
+        // 4*b3 + 2*b4 (b_k = bit k of its lane number).
+        auto rows_sum = [&](float (&v)[4][16], int which) {
+          float *f = &v[0][0];
+#define KVM_BFLY(N, BIT, XCHG)                                  \
+  {                                                             \
+    const bool up = (lane & BIT) != 0;                          \
+    _Pragma("unroll") for (int i = 0; i < N / 2; ++i) {         \
+      const float send = up ? f[i] : f[i + N / 2];              \
+      const float keep = up ? f[i + N / 2] : f[i];              \
+      f[i] = keep + XCHG(send);                                 \
+    }                                                           \
+  }
+#define KVM_X1(x) dpp_get<0xB1>(x)
+#define KVM_X2(x) dpp_get<0x4E>(x)
+#define KVM_X4(x) __uint_as_float(__builtin_amdgcn_ds_swizzle(__float_as_uint(x), 0x101F))
+#define KVM_X8(x) __uint_as_float(__builtin_amdgcn_ds_swizzle(__float_as_uint(x), 0x201F))
+#define KVM_X16(x) __uint_as_float(__builtin_amdgcn_ds_swizzle(__float_as_uint(x), 0x401F))
+          KVM_BFLY(64, 1, KVM_X1)
+          KVM_BFLY(32, 2, KVM_X2)
+          KVM_BFLY(16, 4, KVM_X4)
+          KVM_BFLY(8, 8, KVM_X8)
+          KVM_BFLY(4, 16, KVM_X16)
+#undef KVM_BFLY
+#undef KVM_X1
+#undef KVM_X2
+#undef KVM_X4
+#undef KVM_X8
+#undef KVM_X16
+          const int i0 = 32 * (lane & 1) + 16 * ((lane >> 1) & 1) + 8 * ((lane >> 2) & 1) + 4 * ((lane >> 3) & 1) +
+                         2 * ((lane >> 4) & 1);
+          const int ch0 = 32 * (i0 >> 4) + 8 * ((i0 & 15) >> 2) + 4 * g + (i0 & 3);
+          red[(4 * which + wave) * D + ch0] = f[0];
+          red[(4 * which + wave) * D + ch0 + 1] = f[1];
+        };
+        rows_sum(pg, 0);
+        rows_sum(pb, 1);
         __syncthreads();
         {
           const int which = tid / D, ch = tid % D;
           const float sum4 = red[(4 * which) * D + ch] + red[(4 * which + 1) * D + ch] + red[(4 * which + 2) * D + ch] +
                              red[(4 * which + 3) * D + ch];
-          atomicAdd(a.par64 + (which * dv.Hkv + h) * D + ch, (double)sum4);
+          if (sum4 != 0.f) atomicAdd(a.par64 + (which * dv.Hkv + h) * D + ch, (double)sum4);
         }
       } else if constexpr (kRole == kRoleDV) {
         // v-hat = rho * sV / max(|sV|, eps)

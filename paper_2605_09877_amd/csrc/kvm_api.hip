@@ -381,7 +381,7 @@ hipError_t next_sync_event(kvm_state *st, hipEvent_t *out) {
 
 // Work arrays of the backward pass, in the order of kvm::Bwd.
 struct BwdLayout {
-  size_t wsK, wsV, dsK, dsV, drho, khat, vhat, dkhat, dvhat, dk_acc, dv_acc, delta, P, dS, par64, total;
+  size_t wsK, wsV, dsK, dsV, drho, khat, vhat, xhat, rden, dkhat, dvhat, dk_acc, dv_acc, delta, P, dS, par64, total;
 };
 BwdLayout bwd_layout(const kvm_config &c, int64_t Mcap, int64_t T) {
   const size_t U = (size_t)c.batch * c.n_kv_heads, d = c.head_dim, C = c.chunk_len;
@@ -401,6 +401,8 @@ BwdLayout bwd_layout(const kvm_config &c, int64_t Mcap, int64_t T) {
   l.drho = take(U * M * 4);
   l.khat = take(U * M * d * es);
   l.vhat = take(U * M * d * es);
+  l.xhat = take(U * M * d * 4);
+  l.rden = take(U * M * 4);
   l.dkhat = take(U * M * d * 4);
   l.dvhat = take(U * M * d * 4);
   l.dk_acc = take(U * Tn * d * 4);
@@ -1024,6 +1026,7 @@ int kvm_prefill_backward(kvm_state *st, const void *q, const void *k, const void
   a.wsK = (double *)(w + l.wsK); a.wsV = (float *)(w + l.wsV);
   a.dsK = (float *)(w + l.dsK); a.dsV = (float *)(w + l.dsV); a.drho = (float *)(w + l.drho);
   a.khat = w + l.khat; a.vhat = w + l.vhat;
+  a.xhat = (float *)(w + l.xhat); a.rden = (float *)(w + l.rden);
   a.dkhat = (float *)(w + l.dkhat); a.dvhat = (float *)(w + l.dvhat);
   a.dk_acc = (float *)(w + l.dk_acc); a.dv_acc = (float *)(w + l.dv_acc);
   a.delta = (float *)(w + l.delta);

@@ -124,6 +124,8 @@ struct Bwd {
   float *dsK, *dsV;      // [U, Mcap, d] adjoints of the sums
   float *drho;           // [U, Mcap]
   void *khat, *vhat;     // [U, Mcap, d] I/O dtype: readout of the version being visited
+  float *xhat;           // [U, Mcap, d] the key sums of that version, standardised (before gamma, beta)
+  float *rden;           // [U, Mcap]    1 / sqrt(var + eps) of those rows
   float *dkhat, *dvhat;  // [U, Mcap, d] adjoint of that readout (one chunk's)
   float *dk_acc, *dv_acc;  // [B, T, Hkv, d] fp32 accumulators of dk, dv
   float *delta;          // [B, T, Hq] sum over channels of dout * out
