@@ -130,39 +130,7 @@ __global__ __launch_bounds__(256, 2) void bwd_mfma_kernel(Bwd a, MfmaChunk c) {
     }
   }
   bf16x8 sk[8], sv[8];
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) {
-    Frag8 f;
-    f.q = *reinterpret_cast<const uint4 *>(sk_row + 16 * ks + 8 * g);
-    sk[ks] = f.v;
-    if constexpr (kWantDS) {
-      f.q = *reinterpret_cast<const uint4 *>(sv_row + 16 * ks + 8 * g);
-      sv[ks] = f.v;
-    }
-  }
   float lse2_col = 0.f, d_col = 0.f;
-  if constexpr (!kKeysSta) {
-    const int qc = col_ok ? colq : c.nq - 1;
-    const int64_t qrow = ((int64_t)b * a.T + c.cs + qc) * dv.Hq + hq_sta;
-    lse2_col = a.lse[qrow] * kLog2e;
-    // D = dout . out of the lane's query: the lane has half of the dout row already; the other
-    // roles, which run after this one, read D from memory
-    const uint16_t *o_row = (const uint16_t *)a.out + qrow * D;
-    float part = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      const uint4 ov = *reinterpret_cast<const uint4 *>(o_row + 16 * ks + 8 * g);
-      Frag8 f;
-      f.v = sv[ks];
-      float of[8], df[8];
-      unpack16<bf16_t>(ov, of);
-      unpack16<bf16_t>(f.q, df);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) part = fmaf(of[e], df[e], part);
-    }
-    d_col = xhalf_sum(part);
-    if (col_ok && g == 0) a.delta[qrow] = d_col;
-  }
 
   // ---- streamed tiles
   int n_st = 0, n_tiles, qt0 = 0, per_head = 1;
@@ -406,13 +374,48 @@ __global__ __launch_bounds__(256, 2) void bwd_mfma_kernel(Bwd a, MfmaChunk c) {
     }
   };
 
-  // the stationary vectors are in registers from here on (the compiler does not count the tile
-  // loads; said explicitly so that it does not wait for "its" loads inside the loop)
-  __builtin_amdgcn_s_waitcnt(0);
+  // The first tile is asked for ahead of the stationary vectors, so that the two travel together
+  // (short loops -- few streamed tiles per workgroup -- feel every round trip of the prologue).
   if (n_tiles > 0) {
     issue_tile(0);
     fetch_rowsc(0);
   }
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    Frag8 f;
+    f.q = *reinterpret_cast<const uint4 *>(sk_row + 16 * ks + 8 * g);
+    sk[ks] = f.v;
+    if constexpr (kWantDS) {
+      f.q = *reinterpret_cast<const uint4 *>(sv_row + 16 * ks + 8 * g);
+      sv[ks] = f.v;
+    }
+  }
+  if constexpr (!kKeysSta) {
+    const int qc = col_ok ? colq : c.nq - 1;
+    const int64_t qrow = ((int64_t)b * a.T + c.cs + qc) * dv.Hq + hq_sta;
+    lse2_col = a.lse[qrow] * kLog2e;
+    // D = dout . out of the lane's query: the lane has half of the dout row already; the other
+    // roles, which run after this one, read D from memory
+    const uint16_t *o_row = (const uint16_t *)a.out + qrow * D;
+    float part = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      const uint4 ov = *reinterpret_cast<const uint4 *>(o_row + 16 * ks + 8 * g);
+      Frag8 f;
+      f.v = sv[ks];
+      float of[8], df[8];
+      unpack16<bf16_t>(ov, of);
+      unpack16<bf16_t>(f.q, df);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) part = fmaf(of[e], df[e], part);
+    }
+    d_col = xhalf_sum(part);
+    if (col_ok && g == 0) a.delta[qrow] = d_col;
+  }
+
+  // the stationary vectors are in registers from here on (the compiler does not count the tile
+  // loads; said explicitly so that it does not wait for "its" loads inside the loop)
+  __builtin_amdgcn_s_waitcnt(0);
   for (int it = 0; it < n_tiles; it += 2) {
     tile_step(it, std::integral_constant<int, 0>{});
     if (it + 1 < n_tiles) tile_step(it + 1, std::integral_constant<int, 1>{});
