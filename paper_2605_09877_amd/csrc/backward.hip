@@ -78,7 +78,7 @@ __device__ __forceinline__ void block_param_add(const Bwd &a, int h, const float
 // created that row or merged into it afterwards: the forward appends the tokens with the
 // smallest (append score, position) keys, so among the tokens bound for one new row the creator
 // is the one with the smallest key.
-constexpr int kUnfoldRows = 4;  // at most
+constexpr int kUnfoldRows = 16;  // at most
 constexpr int kUnfoldWaves = 4;  // waves per workgroup (16 measured slower: the workgroup waits for its slowest row)
 
 template <typename T, int D>
