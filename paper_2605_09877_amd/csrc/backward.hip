@@ -156,6 +156,9 @@ __global__ __launch_bounds__(64 * kUnfoldWaves) void bwd_unfold_kernel(Bwd a, in
             loaded = true;
           }
           const int64_t tok = ((int64_t)b * a.T + lo + j) * dv.Hkv + h;
+          // where the token's share goes: its row of the full accumulators, or of the ring
+          const int64_t acc_row =
+              a.ring_rows ? (int64_t)u * a.ring_rows + (int)((lo / C) % (dv.L / C)) * C + j : tok;
           float kf[CPL], vf[CPL];
           load_row<T, D>((const T *)a.k + tok * D, lane, kf);
           load_row<T, D>((const T *)a.v + tok * D, lane, vf);
@@ -221,8 +224,8 @@ __global__ __launch_bounds__(64 * kUnfoldWaves) void bwd_unfold_kernel(Bwd a, in
             const float dkz = (dkbar[c] * gam[c] - m1 - xhat[c] * m2) * (float)rden;
             // plain stores: walking backwards, a token's fold is undone before any chunk that had
             // the token in its window is visited, so this is the first contribution it receives
-            a.dk_acc[tok * D + ch] = ch >= dv.r ? dkz : 0.f;
-            a.dv_acc[tok * D + ch] = dvt[c];
+            a.dk_acc[acc_row * D + ch] = ch >= dv.r ? dkz : 0.f;
+            a.dv_acc[acc_row * D + ch] = dvt[c];
             dga_sum[c] += dkbar[c] * xhat[c];
             dbe_sum[c] += dkbar[c];
           }
@@ -588,9 +591,19 @@ hipError_t zero_fill(void *p, size_t bytes, hipStream_t st) {
 
 }  // namespace
 
-hipError_t run_backward(const Bwd &a, const BwdChunk *chunks, int n_chunks, hipStream_t st) {
-  const Dev &dv = a.dv;
+hipError_t run_backward(const Bwd &a_in, const BwdChunk *chunks, int n_chunks, hipStream_t st) {
+  const Dev &dv = a_in.dv;
   const int G = dv.Hq / dv.Hkv, D = dv.d;
+  static const bool no_mfma = [] {
+    const char *e = getenv("KVM_BACKWARD_GENERIC");  // "1": the vector-ALU kernels everywhere (comparisons)
+    return e && e[0] == '1';
+  }();
+  const bool on_mfma = backward_on_mfma(dv) && !no_mfma;
+  Bwd a = a_in;
+  // On the matrix-core path a token's dk, dv are finished when its block has been the window keys
+  // of a launch; until then only what the token got when its fold was undone is kept, for the
+  // blocks of one window.  Elsewhere dk, dv are summed in full-size fp32 accumulators.
+  a.ring_rows = on_mfma ? dv.L : 0;
   const int64_t state_elems = (int64_t)dv.U * dv.Mcap * D;
   const int64_t kv_elems = (int64_t)dv.B * a.T * dv.Hkv * D;
   const int64_t q_rows = (int64_t)dv.B * a.T * dv.Hq;
@@ -598,8 +611,10 @@ hipError_t run_backward(const Bwd &a, const BwdChunk *chunks, int n_chunks, hipS
   BWD_TRY(zero_fill(a.dsK, state_elems * 4, st));
   BWD_TRY(zero_fill(a.dsV, state_elems * 4, st));
   BWD_TRY(zero_fill(a.drho, (size_t)dv.U * dv.Mcap * 4, st));
-  BWD_TRY(zero_fill(a.dk_acc, kv_elems * 4, st));
-  BWD_TRY(zero_fill(a.dv_acc, kv_elems * 4, st));
+  if (!on_mfma) {
+    BWD_TRY(zero_fill(a.dk_acc, kv_elems * 4, st));
+    BWD_TRY(zero_fill(a.dv_acc, kv_elems * 4, st));
+  }
   BWD_TRY(zero_fill(a.par64, (size_t)(2 * dv.Hkv * D + 2 * dv.Hq) * 8, st));
   // dgate is the caller's tensor: its size need not be a multiple of 16 bytes
   BWD_DISPATCH(dv, bwd_zero_floats_kernel, dim3((unsigned)(((int64_t)dv.B * a.T * dv.Hkv + 255) / 256)), dim3(256), st,
@@ -614,11 +629,6 @@ hipError_t run_backward(const Bwd &a, const BwdChunk *chunks, int n_chunks, hipS
     const int m_end = chunks[n_chunks - 1].m_after;
     BWD_DISPATCH(dv, bwd_readout_kernel, dim3((m_end + 3) / 4, dv.U), dim3(256), st, a, m_end);
   }
-  static const bool no_mfma = [] {
-    const char *e = getenv("KVM_BACKWARD_GENERIC");  // "1": the vector-ALU kernels everywhere (comparisons)
-    return e && e[0] == '1';
-  }();
-  const bool on_mfma = backward_on_mfma(dv) && !no_mfma;
   // D = dout . out per query (the matrix-core dq kernel computes it for its own queries)
   if (!on_mfma)
     BWD_DISPATCH(dv, bwd_delta_kernel, dim3((unsigned)((q_rows + 3) / 4)), dim3(256), st, a.out, a.dout, a.delta, q_rows);
@@ -641,7 +651,10 @@ hipError_t run_backward(const Bwd &a, const BwdChunk *chunks, int n_chunks, hipS
     c.nk = ch.m + (int)(ch.s + ch.nq - c.wb);
     c.ld = dv.Mcap + dv.L;
     if (on_mfma) {
-      BWD_TRY(launch_backward_mfma(a, ch.s, ch.nq, ch.m, st));
+      // the chunk's own block was folded after the last chunk that had it in its window
+      const int cj = ci + dv.L / dv.C - 1;
+      const bool folded = cj < n_chunks && chunks[cj].fold >= 0;
+      BWD_TRY(launch_backward_mfma(a, ch.s, ch.nq, ch.m, folded, st));
     } else {
       BWD_DISPATCH(dv, bwd_probs_kernel, dim3(ch.nq, G, dv.U), dim3(256), st, a, c);
       BWD_DISPATCH(dv, bwd_dq_kernel, dim3(ch.nq, G, dv.U), dim3(256), st, a, c);
@@ -655,6 +668,7 @@ hipError_t run_backward(const Bwd &a, const BwdChunk *chunks, int n_chunks, hipS
     const int n = dv.Hkv * D > dv.Hq ? dv.Hkv * D : dv.Hq;
     hipLaunchKernelGGL(bwd_params_kernel, dim3((n + 255) / 256), dim3(256), 0, st, a);
   }
+  if (on_mfma) return hipGetLastError();  // dk, dv went out finished
   const unsigned cast_blocks = (unsigned)((kv_elems / 8 + 255) / 256);
   if (dv.io == 0) {
     hipLaunchKernelGGL((bwd_cast_kernel<float>), dim3(cast_blocks), dim3(256), 0, st, a.dk_acc, (float *)a.dk, kv_elems);

@@ -64,8 +64,11 @@ __device__ __forceinline__ bf16x8 ttile_frag(const uint16_t *tile, const uint32_
 }
 
 struct MfmaChunk {
-  int64_t cs, wb;  // chunk start, first window position
-  int32_t nq, m;   // queries of the chunk, state rows it saw
+  int64_t cs, wb;   // chunk start, first window position
+  int32_t nq, m;    // queries of the chunk, state rows it saw
+  int32_t nq_ext;   // queries from the chunk start on that see the chunk's own tokens as window keys
+  int32_t folded;   // the chunk's tokens were folded later on: their first gradient share is in the ring
+  int32_t ring_row0;  // where in the ring ([U, ring rows, d]) the chunk's tokens have that share
 };
 
 enum { kRoleDQ = 0, kRoleDK = 1, kRoleDV = 2 };
@@ -82,12 +85,24 @@ __global__ __launch_bounds__(256, 2) void bwd_mfma_kernel(Bwd a, MfmaChunk c) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 5, l32 = lane & 31;
   const int G = dv.Hq / dv.Hkv;
-  const int n_keys_win = (int)(c.cs + c.nq - c.wb);
+  const int n_keys_win = c.nq;  // roles dK, dV: the window keys of a launch are the chunk's own tokens
   const int n_st_wg = (c.m + kStaPerWg - 1) / kStaPerWg;
   const int tpc = (c.nq + kStaPerWg - 1) / kStaPerWg;
-  // consecutive workgroup ids go round-robin over the 8 XCDs: a unit's workgroups share one L2
-  const int per_group = kKeysSta ? n_st_wg + (n_keys_win + kStaPerWg - 1) / kStaPerWg : G * tpc;
-  const int xcd = blockIdx.x % kXcds, seq = blockIdx.x / kXcds;
+  // Consecutive workgroup ids go round-robin over the 8 XCDs: a unit's workgroups share one L2.
+  // Roles dK, dV: the grid has two sections, the window-key workgroups of all units first and the
+  // state-row workgroups after them.  The former stream a whole window of queries and the latter
+  // one chunk: started first, the long ones are done when the short ones have had two rounds
+  // (interleaved unit by unit, the last long ones would start after the first round of short ones).
+  const int n_win_wg = (n_keys_win + kStaPerWg - 1) / kStaPerWg;
+  const int groups8 = (dv.U + kXcds - 1) / kXcds * kXcds;
+  int wg = blockIdx.x, per_group = G * tpc;
+  bool section_state = false;
+  if constexpr (kKeysSta) {
+    section_state = wg >= groups8 * n_win_wg;
+    per_group = section_state ? n_st_wg : n_win_wg;
+    if (section_state) wg -= groups8 * n_win_wg;
+  }
+  const int xcd = wg % kXcds, seq = wg / kXcds;
   const int u = (seq / per_group) * kXcds + xcd;
   if (u >= dv.U) return;
   const int member = seq % per_group;
@@ -112,7 +127,7 @@ __global__ __launch_bounds__(256, 2) void bwd_mfma_kernel(Bwd a, MfmaChunk c) {
     sk_row = (const uint16_t *)a.q + qrow * D;
     sv_row = (const uint16_t *)a.dout + qrow * D;
   } else {
-    sta_state = member < n_st_wg;
+    sta_state = section_state;
     if (sta_state) {
       st_row = kStaPerWg * member + 32 * wave + l32;
       col_ok = st_row < c.m;
@@ -120,7 +135,7 @@ __global__ __launch_bounds__(256, 2) void bwd_mfma_kernel(Bwd a, MfmaChunk c) {
       sk_row = (const uint16_t *)a.khat + ro;
       sv_row = (const uint16_t *)a.vhat + ro;
     } else {
-      const int64_t first = c.wb + (int64_t)kStaPerWg * (member - n_st_wg);
+      const int64_t first = c.cs + (int64_t)kStaPerWg * member;
       wg_first = (int)(first - c.cs);
       kpos = first + 32 * wave + l32;
       col_ok = kpos < c.cs + c.nq;
@@ -134,13 +149,15 @@ __global__ __launch_bounds__(256, 2) void bwd_mfma_kernel(Bwd a, MfmaChunk c) {
 
   // ---- streamed tiles
   int n_st = 0, n_tiles, qt0 = 0, per_head = 1;
+  int nq_str = c.nq;  // roles dK, dV: queries streamed, from the chunk start on
   if constexpr (!kKeysSta) {
     n_st = (c.m + kTileKeys - 1) / kTileKeys;
     const int qt = member % tpc;
     const int qend = kStaPerWg * (qt + 1) < c.nq ? kStaPerWg * (qt + 1) : c.nq;
     n_tiles = n_st + (int)((c.cs + qend - c.wb + kTileKeys - 1) / kTileKeys);
   } else {
-    const int n_qt = (c.nq + kTileKeys - 1) / kTileKeys;
+    nq_str = sta_state ? c.nq : c.nq_ext;
+    const int n_qt = (nq_str + kTileKeys - 1) / kTileKeys;
     qt0 = (!sta_state && wg_first > 0) ? wg_first / kTileKeys : 0;
     per_head = n_qt - qt0;
     n_tiles = G * per_head;
@@ -178,7 +195,7 @@ __global__ __launch_bounds__(256, 2) void bwd_mfma_kernel(Bwd a, MfmaChunk c) {
       xb = (const char *)a.q + qrow * D * 2;
       yb = (const char *)a.dout + qrow * D * 2;
       stride = (uint32_t)dv.Hq * D * 2;
-      valid = c.nq - qtile * kTileKeys;
+      valid = nq_str - qtile * kTileKeys;
     }
     const uint32_t at = lds_addr + (uint32_t)(2 * (it & 1)) * (kTileElems * 2);
     tile_dma<false, 4>(xb, stride, valid, at, wave, dl);
@@ -192,7 +209,7 @@ __global__ __launch_bounds__(256, 2) void bwd_mfma_kernel(Bwd a, MfmaChunk c) {
       if (wave == 0) {
         const int gq = it / per_head, qtile = qt0 + it % per_head;
         int r = qtile * kTileKeys + lane;
-        r = r < c.nq ? r : c.nq - 1;
+        r = r < nq_str ? r : nq_str - 1;
         const int64_t qrow = ((int64_t)b * a.T + c.cs + r) * dv.Hq + h * G + gq;
         rs_lse = a.lse[qrow] * kLog2e;
         rs_d = a.delta[qrow];
@@ -249,7 +266,7 @@ __global__ __launch_bounds__(256, 2) void bwd_mfma_kernel(Bwd a, MfmaChunk c) {
       hq = __builtin_amdgcn_readfirstlane(h * G + gq);
       tile_state = sta_state;
       const int row_pos0 = qtile * kTileKeys;  // the tile's first query, relative to the chunk start
-      hi_row = c.nq - 1 - row_pos0;            // rows beyond the chunk's last query are padding
+      hi_row = nq_str - 1 - row_pos0;          // rows beyond the last query are padding
       need_mask = hi_row < kTileKeys - 1;
       if (!sta_state) {
         const int wave_k0 = wg_first + 32 * wave;  // the wave's first key, relative to the chunk start
@@ -445,23 +462,27 @@ __global__ __launch_bounds__(256, 2) void bwd_mfma_kernel(Bwd a, MfmaChunk c) {
     }
   } else {
     if (col_ok) {
-      // window tokens: dk (which carries the logit scale) resp. dv collect from every chunk that
-      // sees the token
+      // The chunk's own tokens as window keys: this launch has streamed every query that sees
+      // them, so dk (which carries the logit scale) resp. dv is complete once the share the
+      // token got when its fold was undone (kept in fp32 in a ring of the last window's blocks)
+      // is added, and goes out in the I/O dtype.
       if (!sta_state) {
         const float os = kRole == kRoleDK ? scale : 1.f;
         const int64_t tok = ((int64_t)b * a.T + kpos) * dv.Hkv + h;
-        float *row = (kRole == kRoleDK ? a.dk_acc : a.dv_acc) + tok * D;
+        uint16_t *orow = (uint16_t *)(kRole == kRoleDK ? a.dk : a.dv_out) + tok * D;
+        const float *ring = (kRole == kRoleDK ? a.dk_acc : a.dv_acc) +
+                            ((int64_t)u * a.ring_rows + c.ring_row0 + (int)(kpos - c.cs)) * D;
 #pragma unroll
         for (int dblk = 0; dblk < 4; ++dblk)
 #pragma unroll
           for (int vq = 0; vq < 4; ++vq) {
             const int ch = 32 * dblk + 8 * vq + 4 * g;
-            float4 x4 = *reinterpret_cast<const float4 *>(row + ch);
+            float4 x4 = c.folded ? *reinterpret_cast<const float4 *>(ring + ch) : make_float4(0.f, 0.f, 0.f, 0.f);
             x4.x += o1[dblk][4 * vq] * os;
             x4.y += o1[dblk][4 * vq + 1] * os;
             x4.z += o1[dblk][4 * vq + 2] * os;
             x4.w += o1[dblk][4 * vq + 3] * os;
-            *reinterpret_cast<float4 *>(row + ch) = x4;
+            *reinterpret_cast<uint2 *>(orow + ch) = make_uint2(pack_bf16(x4.x, x4.y), pack_bf16(x4.z, x4.w));
           }
       }
     }
@@ -615,7 +636,7 @@ __global__ __launch_bounds__(256, 2) void bwd_mfma_kernel(Bwd a, MfmaChunk c) {
 bool backward_on_mfma(const Dev &dv) { return dv.io == 1 && dv.d == kHeadDim; }
 
 // The three launches of one chunk: dq (and the temperature sums), dk, dv (or the readout's adjoint).
-hipError_t launch_backward_mfma(const Bwd &a, int64_t cs, int nq, int m, hipStream_t st) {
+hipError_t launch_backward_mfma(const Bwd &a, int64_t cs, int nq, int m, bool folded, hipStream_t st) {
   const Dev &dv = a.dv;
   static bool allowed = false;  // more than 64 KiB of LDS per workgroup has to be asked for once
   if (!allowed) {
@@ -632,10 +653,15 @@ hipError_t launch_backward_mfma(const Bwd &a, int64_t cs, int nq, int m, hipStre
   c.wb = cs + dv.C - dv.L > 0 ? cs + dv.C - dv.L : 0;
   c.nq = nq;
   c.m = m;
+  // the chunk's tokens are window keys for the queries of one window from the chunk start on
+  const int64_t ext = a.T - cs < dv.L ? a.T - cs : dv.L;
+  c.nq_ext = (int)ext;
+  c.folded = folded ? 1 : 0;
+  c.ring_row0 = (int)((cs / dv.C) % (dv.L / dv.C)) * dv.C;
   const int G = dv.Hq / dv.Hkv;
   const unsigned groups = (unsigned)((dv.U + kXcds - 1) / kXcds * kXcds);
   const int per_q = G * ((nq + kStaPerWg - 1) / kStaPerWg);
-  const int per_k = (m + kStaPerWg - 1) / kStaPerWg + ((int)(cs + nq - c.wb) + kStaPerWg - 1) / kStaPerWg;
+  const int per_k = (m + kStaPerWg - 1) / kStaPerWg + (nq + kStaPerWg - 1) / kStaPerWg;
   hipLaunchKernelGGL((bwd_mfma_kernel<kRoleDQ>), dim3(groups * per_q), dim3(256), kBwdLdsBytes, st, a, c);
   hipLaunchKernelGGL((bwd_mfma_kernel<kRoleDK>), dim3(groups * per_k), dim3(256), kBwdLdsBytes, st, a, c);
   hipLaunchKernelGGL((bwd_mfma_kernel<kRoleDV>), dim3(groups * per_k), dim3(256), kBwdLdsBytes, st, a, c);

@@ -405,8 +405,12 @@ BwdLayout bwd_layout(const kvm_config &c, int64_t Mcap, int64_t T) {
   l.rden = take(U * M * 4);
   l.dkhat = take(U * M * d * 4);
   l.dvhat = take(U * M * d * 4);
-  l.dk_acc = take(U * Tn * d * 4);
-  l.dv_acc = take(U * Tn * d * 4);
+  // full-size accumulators of dk, dv on the vector-ALU path; on the matrix-core path a ring of
+  // one window's blocks (see kvm::Bwd)
+  const char *env_g = getenv("KVM_BACKWARD_GENERIC");
+  const bool mfma_path = c.io_dtype == KVM_BF16 && c.head_dim == 128 && !(env_g && env_g[0] == '1');
+  l.dk_acc = take(U * (mfma_path ? L : Tn) * d * 4);
+  l.dv_acc = take(U * (mfma_path ? L : Tn) * d * 4);
   l.delta = take((size_t)c.batch * Tn * c.n_q_heads * 4);
   // the chunk's probabilities and logit adjoints are written out only by the vector-ALU kernels
   const char *env = getenv("KVM_BACKWARD_GENERIC");
@@ -1030,6 +1034,7 @@ int kvm_prefill_backward(kvm_state *st, const void *q, const void *k, const void
   a.dkhat = (float *)(w + l.dkhat); a.dvhat = (float *)(w + l.dvhat);
   a.dk_acc = (float *)(w + l.dk_acc); a.dv_acc = (float *)(w + l.dv_acc);
   a.delta = (float *)(w + l.delta);
+  a.ring_rows = 0;
   a.P = (float *)(w + l.P); a.dS = (float *)(w + l.dS);
   a.par64 = (double *)(w + l.par64);
   HIP_TRY(kvm::run_backward(a, chunks.data(), (int)chunks.size(), (hipStream_t)stream));

@@ -127,7 +127,11 @@ struct Bwd {
   float *xhat;           // [U, Mcap, d] the key sums of that version, standardised (before gamma, beta)
   float *rden;           // [U, Mcap]    1 / sqrt(var + eps) of those rows
   float *dkhat, *dvhat;  // [U, Mcap, d] adjoint of that readout (one chunk's)
-  float *dk_acc, *dv_acc;  // [B, T, Hkv, d] fp32 accumulators of dk, dv
+  // fp32 accumulators of dk, dv: [B, T, Hkv, d] (ring_rows = 0), or, on the matrix-core path, only
+  // the share a token gets when its fold is undone, kept until the token's block is finished as
+  // window keys: [U, ring_rows, d] with ring_rows = L, block number mod n_bswa
+  float *dk_acc, *dv_acc;
+  int32_t ring_rows;
   float *delta;          // [B, T, Hq] sum over channels of dout * out
   float *P, *dS;         // [U, G, C, Mcap + L] probabilities and logit adjoints of one chunk
   double *par64;         // [2 * Hkv * d + 2 * Hq] fp64 accumulators of dgamma, dbeta, dtau_state, dtau_bswa
@@ -143,6 +147,6 @@ struct BwdChunk {
 hipError_t run_backward(const Bwd &a, const BwdChunk *chunks, int n_chunks, hipStream_t st);
 // backward_mfma.hip (bf16, d = 128): one chunk's dq, dk, dv and readout adjoint on the matrix cores
 bool backward_on_mfma(const Dev &dv);
-hipError_t launch_backward_mfma(const Bwd &a, int64_t cs, int nq, int m, hipStream_t st);
+hipError_t launch_backward_mfma(const Bwd &a, int64_t cs, int nq, int m, bool folded, hipStream_t st);
 
 }  // namespace kvm
