@@ -522,6 +522,11 @@ def main():
                             budget=w2.budget_kind))
             del t2
             torch.cuda.empty_cache()
+            if not args.no_backward:
+                b2 = backward_leg(a2, pkg, synth, dev, w2)
+                line["other_workloads"][name]["backward_ms_per_pass"] = b2["ms_per_pass"]
+                line["other_workloads"][name]["backward_tflops"] = b2["achieved_tflops"]
+                torch.cuda.empty_cache()
         tensors = None
     if not args.no_backward:
         tensors = None
