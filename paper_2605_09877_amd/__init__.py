@@ -3,6 +3,7 @@ and a thin ctypes binding.  Entry points carry the names of include/kvm.h."""
 from .binding import (KVM_BF16, KVM_BUDGET_FIXED, KVM_BUDGET_NONE, KVM_BUDGET_SQRT, KVM_BUDGET_TABLE,
                       KVM_ERR_ARG, KVM_ERR_CAPACITY, KVM_ERR_HIP, KVM_ERR_STATE, KVM_ERR_UNSUPPORTED, KVM_F32,
                       KVM_OK, EXPORTS, KVMError, KVMState, kvm_config, kvm_strides, load_library)
+from .autograd import kvm_attention
 
 
 def kvm_state_init(**kw) -> KVMState:

@@ -206,6 +206,35 @@ def test_full_size_backward_sampled_units():
     run_backward_case(w, plain=True, units=[(0, 0), (w.batch - 1, w.n_kv_heads - 1)])
 
 
+def test_autograd_front_end_returns_the_library_gradients():
+    """kvm_attention(...).backward() hands torch the tensors kvm_prefill_backward wrote."""
+    pkg, sy = kvm(), synth()
+    w = sy.shrink(sy.WORKLOADS["tiny_f32"], seq=64 * 5 + 11)
+    q, k, v = sy.make_qkv(w, DEV)
+    params = sy.make_params(w, DEV, plain=False)
+    leaves = dict(q=q, k=k, v=v, gate=params["gate"], ln_gamma=params["ln_gamma"], ln_beta=params["ln_beta"],
+                  tau_state=params["tau_state"], tau_bswa=params["tau_bswa"])
+    leaves = {n: t.clone().requires_grad_(True) for n, t in leaves.items()}
+    out = pkg.kvm_attention(leaves["q"], leaves["k"], leaves["v"], leaves["gate"], chunk_len=w.chunk_len,
+                            rope_dims=w.rope_dims, n_bswa_chunks=w.n_bswa_chunks, n_sink=w.n_sink,
+                            budget_fixed=w.budget_fixed, ln_gamma=leaves["ln_gamma"], ln_beta=leaves["ln_beta"],
+                            tau_state=leaves["tau_state"], tau_bswa=leaves["tau_bswa"])
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(5)
+    dout = torch.randn(out.shape, generator=gen, device=DEV)
+    out.backward(dout)
+    st = pkg.state_for(w, device=DEV, **params)
+    assign, score = st.trace(w.seq // w.chunk_len + 1)
+    o2, lse = st.prefill(q, k, v, params["gate"], want_lse=True)
+    g = st.backward(q, k, v, params["gate"], o2, lse, dout, assign, score)
+    torch.testing.assert_close(out.detach(), o2, rtol=0, atol=0)
+    for name, key in (("q", "dq"), ("k", "dk"), ("v", "dv"), ("gate", "dgate")):
+        torch.testing.assert_close(leaves[name].grad, g[key], rtol=0, atol=0)
+    # parameter gradients are summed with atomics: equal to the last bits only
+    for name, key in (("ln_gamma", "dgamma"), ("ln_beta", "dbeta"), ("tau_state", "dtau_state"), ("tau_bswa", "dtau_bswa")):
+        torch.testing.assert_close(leaves[name].grad, g[key], rtol=1e-5, atol=1e-6)
+
+
 def test_backward_rejects_a_state_that_did_not_run_this_prefill():
     pkg, sy = kvm(), synth()
     from paper_2605_09877_amd import binding
