@@ -30,6 +30,9 @@ called, not repeated.
 Pinned by tests/test_backward_pins.py: central finite differences of the forward oracle (run
 without rounding) for every input and parameter, and the special case without a state, which
 is textbook masked softmax attention differentiated by a library's automatic differentiation.
+The straight-through treatment of the roundings (bf16 / fp32 I/O) is a reading that changes no
+formula, only the values the formulas are evaluated at, and no numerical pin can check it:
+parity unpinned for that reading.
 """
 from __future__ import annotations
 
