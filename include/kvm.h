@@ -159,8 +159,10 @@ int kvm_state_fold(kvm_state *st, const void *k_blk, const void *v_blk, const fl
 
 /* Backward pass of a whole-sequence prefill (the paper's "Speed Benchmarks" time a backward pass;
  * what it computes follows from the forward definition in "KVM Formulation" by the chain rule).
- * `st` must be the state that ONE kvm_prefill_chunked call over exactly these T tokens, from an
- * empty state, has left (KVM_ERR_STATE otherwise); it is read, not changed.  Given dout, the
+ * `st` must be the state that a kvm_prefill_chunked over exactly these T tokens, from an empty
+ * state, has left -- in one call, or in several that each started on a chunk boundary, their
+ * operands concatenated here (KVM_ERR_STATE when the token, fold or row counts disagree); it is
+ * read, not changed.  Given dout, the
  * gradient of a scalar loss with respect to that call's out, the call writes the gradients with
  * respect to its q, k, v and gate and to the layer's LN_s parameters and temperatures.
  *   - Slot assignments are replayed as recorded: `assign` (int32 [folds, B, H_kv, C]) and `score`

@@ -77,7 +77,7 @@ def check(w, name, got, ref, slack=0.0, f32_bar=1e-4):
     assert worst <= 1.0, f"{name}: bf16 error is {worst:.3f} x the 2e-2 bound"
 
 
-def run_backward_case(w, plain, units=None):
+def run_backward_case(w, plain, units=None, split=None):
     """Forward with the fold record on, backward, and the oracle on every unit (or on the sampled
     `units`: then the gradients summed over all units -- LN_s, temperatures -- are not checked)."""
     pkg, sy = kvm(), synth()
@@ -89,7 +89,14 @@ def run_backward_case(w, plain, units=None):
     dout = torch.randn(q.shape, generator=gen, device=DEV, dtype=torch.float32).to(q.dtype)
     st = pkg.state_for(w, device=DEV, **params)
     assign, score = st.trace(w.seq // w.chunk_len + 1)
-    out, lse = st.prefill(q, k, v, gate, want_lse=True)
+    if split is None:
+        out, lse = st.prefill(q, k, v, gate, want_lse=True)
+    else:  # the forward in two calls (the second starts on a chunk boundary); one backward over all of it
+        parts = [st.prefill(q[:, lo:hi].contiguous(), k[:, lo:hi].contiguous(), v[:, lo:hi].contiguous(),
+                            None if gate is None else gate[:, lo:hi].contiguous(), want_lse=True)
+                 for lo, hi in ((0, split), (split, w.seq))]
+        out = torch.cat([p[0] for p in parts], dim=1).contiguous()
+        lse = torch.cat([p[1] for p in parts], dim=1).contiguous()
     g = st.backward(q, k, v, gate, out, lse, dout, assign, score)
     torch.cuda.synchronize()
     ga_all = assign[:st.folds].cpu().numpy()
@@ -204,6 +211,12 @@ def test_full_size_backward_sampled_units():
     (batch, KV head) unit over all chunks and folds."""
     w = synth().WORKLOADS["prefill_gqa_32k"]
     run_backward_case(w, plain=True, units=[(0, 0), (w.batch - 1, w.n_kv_heads - 1)])
+
+
+def test_backward_after_a_forward_in_two_calls():
+    w = synth().shrink(synth().WORKLOADS["prefill_fixed"], batch=1, n_q_heads=4, n_kv_heads=2, seq=128 * 6 + 50,
+                       chunk_len=128, budget_fixed=200)
+    run_backward_case(w, plain=False, split=128 * 3)
 
 
 def test_autograd_front_end_returns_the_library_gradients():
