@@ -205,12 +205,14 @@ def test_bf16_backward_of_one_window():
     run_backward_case(w, plain=False)
 
 
-def test_full_size_backward_sampled_units():
-    """The benchmark workload at full size, in the configuration bench.py times (plain parameters,
-    no gate): the library runs the whole backward pass, the oracle replays the first and the last
-    (batch, KV head) unit over all chunks and folds."""
-    w = synth().WORKLOADS["prefill_gqa_32k"]
-    run_backward_case(w, plain=True, units=[(0, 0), (w.batch - 1, w.n_kv_heads - 1)])
+@pytest.mark.parametrize("name,n_units", [("prefill_gqa_32k", 2), ("prefill_fixed", 2), ("prefill_sqrt", 1)])
+def test_full_size_backward_sampled_units(name, n_units):
+    """The prefill workloads at full size, in the configuration bench.py times (plain parameters,
+    no gate): the library runs the whole backward pass, the oracle replays the last (and the
+    first) (batch, KV head) unit over all chunks and folds."""
+    w = synth().WORKLOADS[name]
+    units = [(w.batch - 1, w.n_kv_heads - 1), (0, 0)][:n_units]
+    run_backward_case(w, plain=True, units=units)
 
 
 def test_backward_after_a_forward_in_two_calls():
