@@ -161,6 +161,12 @@ __global__ __launch_bounds__(256, 2) void bwd_mfma_kernel(Bwd a, MfmaChunk c) {
     qt0 = (!sta_state && wg_first > 0) ? wg_first / kTileKeys : 0;
     per_head = n_qt - qt0;
     n_tiles = G * per_head;
+    // Order of the streamed tiles: the last query tile first, and for each query tile the heads
+    // of the group one after the other.  The workgroups of a unit that share a stream differ in
+    // where their first visible tile lies, not in where the last one does: walking backwards
+    // they all start on the same tile and stay in step, so that one of them brings a tile into
+    // the XCD's L2 and the others find it there (ascending, head by head, they ran up to six
+    // tiles apart and the stream was fetched more than twice over).
   }
   n_tiles = __builtin_amdgcn_readfirstlane(n_tiles);
 
@@ -190,7 +196,7 @@ __global__ __launch_bounds__(256, 2) void bwd_mfma_kernel(Bwd a, MfmaChunk c) {
         valid = (int)(c.cs + c.nq - p0);
       }
     } else {
-      const int gq = it / per_head, qtile = qt0 + it % per_head;
+      const int gq = it % G, qtile = qt0 + per_head - 1 - it / G;
       const int64_t qrow = ((int64_t)b * a.T + c.cs + (int64_t)qtile * kTileKeys) * dv.Hq + h * G + gq;
       xb = (const char *)a.q + qrow * D * 2;
       yb = (const char *)a.dout + qrow * D * 2;
@@ -207,7 +213,7 @@ __global__ __launch_bounds__(256, 2) void bwd_mfma_kernel(Bwd a, MfmaChunk c) {
   auto fetch_rowsc = [&](int it) {
     if constexpr (kKeysSta) {
       if (wave == 0) {
-        const int gq = it / per_head, qtile = qt0 + it % per_head;
+        const int gq = it % G, qtile = qt0 + per_head - 1 - it / G;
         int r = qtile * kTileKeys + lane;
         r = r < nq_str ? r : nq_str - 1;
         const int64_t qrow = ((int64_t)b * a.T + c.cs + r) * dv.Hq + h * G + gq;
@@ -262,7 +268,7 @@ __global__ __launch_bounds__(256, 2) void bwd_mfma_kernel(Bwd a, MfmaChunk c) {
         need_mask = p0rel + kTileKeys - 1 > wave_q0;
       }
     } else {
-      const int gq = it / per_head, qtile = qt0 + it % per_head;
+      const int gq = it % G, qtile = qt0 + per_head - 1 - it / G;
       hq = __builtin_amdgcn_readfirstlane(h * G + gq);
       tile_state = sta_state;
       const int row_pos0 = qtile * kTileKeys;  // the tile's first query, relative to the chunk start
