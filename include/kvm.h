@@ -168,16 +168,19 @@ int kvm_state_fold(kvm_state *st, const void *k_blk, const void *v_blk, const fl
  *   - Slot assignments are replayed as recorded: `assign` (int32 [folds, B, H_kv, C]) and `score`
  *     (fp32 [folds, B, H_kv, C, 2]) are the records that kvm_state_trace collected during the
  *     forward (the argmax is piecewise constant and gets no gradient; the append scores tell the
- *     token that created a row from tokens that merged into it in the same fold).  The roundings of the memory keys and readout rows to the I/O dtype are passed
- *     straight through.  A row's radius carries gradient to the value that created the row.
+ *     token that created a row from tokens that merged into it in the same fold).  The roundings
+ *     of the memory keys and readout rows to the I/O dtype are passed straight through.  A row's radius carries gradient to the value that created the row.
  *   - q, out, dout, dq: [B, T, H_q, d]; k, v, dk, dv: [B, T, H_kv, d] (I/O dtype, dense);
  *     gate (nullable: g = 1), dgate: [B, T, H_kv] fp32 (dgate is the gradient at g = 1 when gate is
  *     NULL; 0 for tokens that were never folded); lse: [B, T, H_q] fp32 as the forward wrote it;
  *     dgamma, dbeta: [H_kv, d] fp32; dtau_state, dtau_bswa: [H_q] fp32.  Every gradient is
  *     overwritten (sums over the batch for the parameters).  All device pointers, the caller's.
  *   - workspace: device, 256-byte aligned, kvm_backward_workspace_bytes(st, T) bytes; rewritten.
- * Work is enqueued on `stream`; the host is not blocked.  Parameter gradients are summed with
- * fp64 atomics (their last fp32 bit can differ from run to run). */
+ * Work is enqueued on `stream`; the host is not blocked (with bf16 and head_dim 128 part of each
+ * chunk's work runs on the state's own second stream, the one a prefill's folds use, forked from
+ * and joined to `stream` by events inside the call: later work on `stream` sees all of it).
+ * Parameter gradients are summed with fp64 atomics (their last fp32 bit can differ from run to
+ * run). */
 typedef struct kvm_grads {
   void *dq, *dk, *dv;
   float *dgate, *dgamma, *dbeta, *dtau_state, *dtau_bswa;

@@ -591,7 +591,7 @@ hipError_t zero_fill(void *p, size_t bytes, hipStream_t st) {
 
 }  // namespace
 
-hipError_t run_backward(const Bwd &a_in, const BwdChunk *chunks, int n_chunks, hipStream_t st) {
+hipError_t run_backward(const Bwd &a_in, const BwdChunk *chunks, int n_chunks, hipStream_t st, const BwdStreams &x) {
   const Dev &dv = a_in.dv;
   const int G = dv.Hq / dv.Hkv, D = dv.d;
   static const bool no_mfma = [] {
@@ -632,8 +632,14 @@ hipError_t run_backward(const Bwd &a_in, const BwdChunk *chunks, int n_chunks, h
   // D = dout . out per query (the matrix-core dq kernel computes it for its own queries)
   if (!on_mfma)
     BWD_DISPATCH(dv, bwd_delta_kernel, dim3((unsigned)((q_rows + 3) / 4)), dim3(256), st, a.out, a.dout, a.delta, q_rows);
+  const bool use_side = on_mfma && x.side && x.fork && x.join;
+  bool side_busy = false;
   for (int ci = n_chunks - 1; ci >= 0; --ci) {
     const BwdChunk &ch = chunks[ci];
+    if (side_busy) {  // the fold about to be undone reads the value adjoints the dv role adds to
+      BWD_TRY(hipStreamWaitEvent(st, x.join, 0));
+      side_busy = false;
+    }
     if (ch.fold >= 0) {
       // rows per wave: about one block token per wave's rows, so that the scan of the targets is
       // shared where rows are many and hot rows run in parallel where they are few
@@ -654,7 +660,15 @@ hipError_t run_backward(const Bwd &a_in, const BwdChunk *chunks, int n_chunks, h
       // the chunk's own block was folded after the last chunk that had it in its window
       const int cj = ci + dv.L / dv.C - 1;
       const bool folded = cj < n_chunks && chunks[cj].fold >= 0;
-      BWD_TRY(launch_backward_mfma(a, ch.s, ch.nq, ch.m, folded, st));
+      if (use_side) {
+        BWD_TRY(hipEventRecord(x.fork, st));
+        BWD_TRY(hipStreamWaitEvent(x.side, x.fork, 0));
+      }
+      BWD_TRY(launch_backward_mfma(a, ch.s, ch.nq, ch.m, folded, st, use_side ? x.side : st));
+      if (use_side) {
+        BWD_TRY(hipEventRecord(x.join, x.side));
+        side_busy = true;
+      }
     } else {
       BWD_DISPATCH(dv, bwd_probs_kernel, dim3(ch.nq, G, dv.U), dim3(256), st, a, c);
       BWD_DISPATCH(dv, bwd_dq_kernel, dim3(ch.nq, G, dv.U), dim3(256), st, a, c);
@@ -664,6 +678,7 @@ hipError_t run_backward(const Bwd &a_in, const BwdChunk *chunks, int n_chunks, h
       BWD_DISPATCH(dv, bwd_readout_adjoint_kernel, dim3((ch.m + 4 * kRowsPerWave - 1) / (4 * kRowsPerWave), dv.U),
                    dim3(256), st, a, ch.m);
   }
+  if (side_busy) BWD_TRY(hipStreamWaitEvent(st, x.join, 0));
   {
     const int n = dv.Hkv * D > dv.Hq ? dv.Hkv * D : dv.Hq;
     hipLaunchKernelGGL(bwd_params_kernel, dim3((n + 255) / 256), dim3(256), 0, st, a);

@@ -642,7 +642,7 @@ __global__ __launch_bounds__(256, 2) void bwd_mfma_kernel(Bwd a, MfmaChunk c) {
 bool backward_on_mfma(const Dev &dv) { return dv.io == 1 && dv.d == kHeadDim; }
 
 // The three launches of one chunk: dq (and the temperature sums), dk, dv (or the readout's adjoint).
-hipError_t launch_backward_mfma(const Bwd &a, int64_t cs, int nq, int m, bool folded, hipStream_t st) {
+hipError_t launch_backward_mfma(const Bwd &a, int64_t cs, int nq, int m, bool folded, hipStream_t st, hipStream_t st_dv) {
   const Dev &dv = a.dv;
   static bool allowed = false;  // more than 64 KiB of LDS per workgroup has to be asked for once
   if (!allowed) {
@@ -670,7 +670,7 @@ hipError_t launch_backward_mfma(const Bwd &a, int64_t cs, int nq, int m, bool fo
   const int per_k = (m + kStaPerWg - 1) / kStaPerWg + (nq + kStaPerWg - 1) / kStaPerWg;
   hipLaunchKernelGGL((bwd_mfma_kernel<kRoleDQ>), dim3(groups * per_q), dim3(256), kBwdLdsBytes, st, a, c);
   hipLaunchKernelGGL((bwd_mfma_kernel<kRoleDK>), dim3(groups * per_k), dim3(256), kBwdLdsBytes, st, a, c);
-  hipLaunchKernelGGL((bwd_mfma_kernel<kRoleDV>), dim3(groups * per_k), dim3(256), kBwdLdsBytes, st, a, c);
+  hipLaunchKernelGGL((bwd_mfma_kernel<kRoleDV>), dim3(groups * per_k), dim3(256), kBwdLdsBytes, st_dv, a, c);
   return hipGetLastError();
 }
 

@@ -1037,7 +1037,15 @@ int kvm_prefill_backward(kvm_state *st, const void *q, const void *k, const void
   a.ring_rows = 0;
   a.P = (float *)(w + l.P); a.dS = (float *)(w + l.dS);
   a.par64 = (double *)(w + l.par64);
-  HIP_TRY(kvm::run_backward(a, chunks.data(), (int)chunks.size(), (hipStream_t)stream));
+  kvm::BwdStreams x;
+  if (kvm::backward_on_mfma(st->dv)) {
+    if (!st->fold_streams[0]) HIP_TRY(hipStreamCreateWithFlags(&st->fold_streams[0], hipStreamNonBlocking));
+    x.side = st->fold_streams[0];
+    st->sync_used = 0;
+    HIP_TRY(next_sync_event(st, &x.fork));
+    HIP_TRY(next_sync_event(st, &x.join));
+  }
+  HIP_TRY(kvm::run_backward(a, chunks.data(), (int)chunks.size(), (hipStream_t)stream, x));
   return KVM_OK;
 }
 

@@ -144,9 +144,15 @@ struct BwdChunk {
   int32_t fold;    // index of the fold that followed the chunk, or -1
   int32_t m_after; // state rows after that fold
 };
-hipError_t run_backward(const Bwd &a, const BwdChunk *chunks, int n_chunks, hipStream_t st);
+// A second stream and two untimed events, owned by the caller: the dv role of a chunk runs beside its
+// dq and dk roles (it needs neither D nor anything they write) and fills the ends of their grids.
+struct BwdStreams {
+  hipStream_t side = nullptr;  // null: everything on the one stream
+  hipEvent_t fork = nullptr, join = nullptr;
+};
+hipError_t run_backward(const Bwd &a, const BwdChunk *chunks, int n_chunks, hipStream_t st, const BwdStreams &x);
 // backward_mfma.hip (bf16, d = 128): one chunk's dq, dk, dv and readout adjoint on the matrix cores
 bool backward_on_mfma(const Dev &dv);
-hipError_t launch_backward_mfma(const Bwd &a, int64_t cs, int nq, int m, bool folded, hipStream_t st);
+hipError_t launch_backward_mfma(const Bwd &a, int64_t cs, int nq, int m, bool folded, hipStream_t st, hipStream_t st_dv);
 
 }  // namespace kvm
