@@ -250,6 +250,40 @@ def test_autograd_front_end_returns_the_library_gradients():
         torch.testing.assert_close(leaves[name].grad, g[key], rtol=1e-5, atol=1e-6)
 
 
+def test_backward_on_a_stream_of_the_callers_choice():
+    """Forward and backward enqueued on a stream other than the default one, with the caller's own
+    work before and after them on that stream and no host synchronisation in between: the
+    library's second stream is forked from and joined to the caller's stream, so the results are
+    those of the default stream (to the bit, where no atomics are involved)."""
+    pkg, sy = kvm(), synth()
+    w = sy.shrink(sy.WORKLOADS["prefill_gqa_32k"], batch=1, n_q_heads=8, n_kv_heads=2, seq=128 * 9 + 70, chunk_len=128,
+                  budget_fixed=256)
+    q, k, v = sy.make_qkv(w, DEV)
+    params = sy.make_params(w, DEV, plain=False)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(11)
+    dout0 = torch.randn(q.shape, generator=gen, device=DEV, dtype=torch.float32)
+
+    def both(stream):
+        with torch.cuda.stream(stream):
+            dout = (dout0 * 0.5).to(q.dtype)  # the caller's own kernel ahead of the library's
+            st = pkg.state_for(w, device=DEV, **params)
+            assign, score = st.trace(w.seq // w.chunk_len + 1)
+            out, lse = st.prefill(q, k, v, params["gate"], want_lse=True)
+            g = st.backward(q, k, v, params["gate"], out, lse, dout, assign, score)
+            after = {n: t.float() * 2.0 for n, t in g.items()}  # and one behind them
+        stream.synchronize()
+        return after
+
+    torch.cuda.synchronize()
+    ref = both(torch.cuda.current_stream())
+    got = both(torch.cuda.Stream())
+    for name in ("dq", "dk", "dv", "dgate"):
+        torch.testing.assert_close(got[name], ref[name], rtol=0, atol=0)
+    for name in ("dgamma", "dbeta", "dtau_state", "dtau_bswa"):
+        torch.testing.assert_close(got[name], ref[name], rtol=1e-5, atol=1e-5)
+
+
 def test_backward_rejects_a_state_that_did_not_run_this_prefill():
     pkg, sy = kvm(), synth()
     from paper_2605_09877_amd import binding
