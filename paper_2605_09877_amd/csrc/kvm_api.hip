@@ -785,8 +785,16 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
     }
     return KVM_OK;
   };
-  for (int g0 = 0; g0 < n_chunks; g0 += G) {
-    const int g1 = g0 + G < n_chunks ? g0 + G : n_chunks;
+  // Groups grow: the first holds the chunks that see the state as the call found it (they wait for
+  // no fold), the next ones two and four chunks, so that attention starts at once and has work
+  // while the first folds of the chain run; from then on G chunks per launch.
+  int first = 0;
+  while (first < n_chunks && first < G && plan[first].ver == plan[0].ver) ++first;
+  int gsz = first;
+  for (int g0 = 0, g1 = 0; g0 < n_chunks; g0 = g1) {
+    g1 = g0 + gsz < n_chunks ? g0 + gsz : n_chunks;
+    gsz = g0 == 0 ? 2 : 2 * gsz;
+    gsz = gsz > G ? G : gsz;
     // the last chunk of the group reads the version written by the fold after chunk g1 - 2
     int rc = enqueue_folds_through(g1 - 2);
     if (rc != KVM_OK) return rc;
