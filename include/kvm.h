@@ -177,7 +177,7 @@ int kvm_state_fold(kvm_state *st, const void *k_blk, const void *v_blk, const fl
  *     overwritten (sums over the batch for the parameters).  All device pointers, the caller's.
  *   - workspace: device, 256-byte aligned, kvm_backward_workspace_bytes(st, T) bytes; rewritten.
  * Work is enqueued on `stream`; the host is not blocked (with bf16 and head_dim 128 part of each
- * chunk's work runs on the state's own second stream, the one a prefill's folds use, forked from
+ * chunk's work runs on the state's own two streams, the ones a prefill's folds use, forked from
  * and joined to `stream` by events inside the call: later work on `stream` sees all of it).
  * Parameter gradients are summed with fp64 atomics (their last fp32 bit can differ from run to
  * run). */

@@ -158,7 +158,7 @@ __global__ __launch_bounds__(64 * kUnfoldWaves) void bwd_unfold_kernel(Bwd a, in
           const int64_t tok = ((int64_t)b * a.T + lo + j) * dv.Hkv + h;
           // where the token's share goes: its row of the full accumulators, or of the ring
           const int64_t acc_row =
-              a.ring_rows ? (int64_t)u * a.ring_rows + (int)((lo / C) % (dv.L / C)) * C + j : tok;
+              a.ring_rows ? (int64_t)u * a.ring_rows + (int)((lo / C) % (a.ring_rows / C)) * C + j : tok;
           float kf[CPL], vf[CPL];
           load_row<T, D>((const T *)a.k + tok * D, lane, kf);
           load_row<T, D>((const T *)a.v + tok * D, lane, vf);
@@ -603,7 +603,7 @@ hipError_t run_backward(const Bwd &a_in, const BwdChunk *chunks, int n_chunks, h
   // On the matrix-core path a token's dk, dv are finished when its block has been the window keys
   // of a launch; until then only what the token got when its fold was undone is kept, for the
   // blocks of one window.  Elsewhere dk, dv are summed in full-size fp32 accumulators.
-  a.ring_rows = on_mfma ? dv.L : 0;
+  a.ring_rows = on_mfma ? dv.L + dv.C : 0;
   const int64_t state_elems = (int64_t)dv.U * dv.Mcap * D;
   const int64_t kv_elems = (int64_t)dv.B * a.T * dv.Hkv * D;
   const int64_t q_rows = (int64_t)dv.B * a.T * dv.Hq;
@@ -632,13 +632,25 @@ hipError_t run_backward(const Bwd &a_in, const BwdChunk *chunks, int n_chunks, h
   // D = dout . out per query (the matrix-core dq kernel computes it for its own queries)
   if (!on_mfma)
     BWD_DISPATCH(dv, bwd_delta_kernel, dim3((unsigned)((q_rows + 3) / 4)), dim3(256), st, a.out, a.dout, a.delta, q_rows);
-  const bool use_side = on_mfma && x.side && x.fork && x.join;
-  bool side_busy = false;
+  // Matrix-core path, three streams.  The caller's carries the chain that the state imposes:
+  // undo the fold, dq (which also forms D), dk of the state rows.  dv of the state rows needs the
+  // undone fold only and runs on `side`.  dk and dv of the chunk's own tokens (window keys) need D
+  // and nothing of the state: they run on `side2` and may still be running while the next chunk
+  // of the walk is on the other two, which is what fills the chip while a fold is undone.  The
+  // ring holds one block more than a window so that the fold undone then writes another slot than
+  // they read; they must be done before the fold after that.
+  const bool use_side = on_mfma && x.side && x.side2 && x.fork && x.dq_done && x.join_state && x.join_window[0] &&
+                        x.join_window[1];
+  bool state_busy = false, window_busy[2] = {false, false};
   for (int ci = n_chunks - 1; ci >= 0; --ci) {
     const BwdChunk &ch = chunks[ci];
-    if (side_busy) {  // the fold about to be undone reads the value adjoints the dv role adds to
-      BWD_TRY(hipStreamWaitEvent(st, x.join, 0));
-      side_busy = false;
+    if (state_busy) {  // the fold about to be undone reads the value adjoints the dv role adds to
+      BWD_TRY(hipStreamWaitEvent(st, x.join_state, 0));
+      state_busy = false;
+    }
+    if (window_busy[ci & 1]) {  // ... and writes the ring slot that the window keys of chunk ci + 2 read
+      BWD_TRY(hipStreamWaitEvent(st, x.join_window[ci & 1], 0));
+      window_busy[ci & 1] = false;
     }
     if (ch.fold >= 0) {
       // rows per wave: about one block token per wave's rows, so that the scan of the targets is
@@ -663,11 +675,22 @@ hipError_t run_backward(const Bwd &a_in, const BwdChunk *chunks, int n_chunks, h
       if (use_side) {
         BWD_TRY(hipEventRecord(x.fork, st));
         BWD_TRY(hipStreamWaitEvent(x.side, x.fork, 0));
-      }
-      BWD_TRY(launch_backward_mfma(a, ch.s, ch.nq, ch.m, folded, st, use_side ? x.side : st));
-      if (use_side) {
-        BWD_TRY(hipEventRecord(x.join, x.side));
-        side_busy = true;
+        BWD_TRY(launch_backward_mfma(a, ch.s, ch.nq, ch.m, folded, kRoleDV, kSecState, x.side));
+        BWD_TRY(hipEventRecord(x.join_state, x.side));
+        state_busy = true;
+        // (behind it on the same stream, so that the wait for the next chunk's join_state, one
+        // fold before the ring slot is rewritten, also covers it)
+        BWD_TRY(launch_backward_mfma(a, ch.s, ch.nq, ch.m, folded, kRoleDV, kSecWindow, x.side));
+        BWD_TRY(launch_backward_mfma(a, ch.s, ch.nq, ch.m, folded, kRoleDQ, kSecBoth, st));
+        BWD_TRY(hipEventRecord(x.dq_done, st));
+        BWD_TRY(hipStreamWaitEvent(x.side2, x.dq_done, 0));
+        BWD_TRY(launch_backward_mfma(a, ch.s, ch.nq, ch.m, folded, kRoleDK, kSecWindow, x.side2));
+        BWD_TRY(hipEventRecord(x.join_window[ci & 1], x.side2));
+        window_busy[ci & 1] = true;
+        BWD_TRY(launch_backward_mfma(a, ch.s, ch.nq, ch.m, folded, kRoleDK, kSecState, st));
+      } else {
+        for (int role : {kRoleDQ, kRoleDK, kRoleDV})
+          BWD_TRY(launch_backward_mfma(a, ch.s, ch.nq, ch.m, folded, role, kSecBoth, st));
       }
     } else {
       BWD_DISPATCH(dv, bwd_probs_kernel, dim3(ch.nq, G, dv.U), dim3(256), st, a, c);
@@ -678,7 +701,12 @@ hipError_t run_backward(const Bwd &a_in, const BwdChunk *chunks, int n_chunks, h
       BWD_DISPATCH(dv, bwd_readout_adjoint_kernel, dim3((ch.m + 4 * kRowsPerWave - 1) / (4 * kRowsPerWave), dv.U),
                    dim3(256), st, a, ch.m);
   }
-  if (side_busy) BWD_TRY(hipStreamWaitEvent(st, x.join, 0));
+  if (state_busy) {  // the last launch on that stream is a dv role of window keys
+    BWD_TRY(hipEventRecord(x.join_state, x.side));
+    BWD_TRY(hipStreamWaitEvent(st, x.join_state, 0));
+  }
+  for (int i = 0; i < 2; ++i)
+    if (window_busy[i]) BWD_TRY(hipStreamWaitEvent(st, x.join_window[i], 0));
   {
     const int n = dv.Hkv * D > dv.Hq ? dv.Hkv * D : dv.Hq;
     hipLaunchKernelGGL(bwd_params_kernel, dim3((n + 255) / 256), dim3(256), 0, st, a);

@@ -69,9 +69,9 @@ struct MfmaChunk {
   int32_t nq_ext;   // queries from the chunk start on that see the chunk's own tokens as window keys
   int32_t folded;   // the chunk's tokens were folded later on: their first gradient share is in the ring
   int32_t ring_row0;  // where in the ring ([U, ring rows, d]) the chunk's tokens have that share
+  int32_t section;    // roles dK, dV: kSecBoth, or only the window-key / only the state-row workgroups
 };
 
-enum { kRoleDQ = 0, kRoleDK = 1, kRoleDV = 2 };
 
 template <int kRole>
 __global__ __launch_bounds__(256, 2) void bwd_mfma_kernel(Bwd a, MfmaChunk c) {
@@ -98,9 +98,9 @@ __global__ __launch_bounds__(256, 2) void bwd_mfma_kernel(Bwd a, MfmaChunk c) {
   int wg = blockIdx.x, per_group = G * tpc;
   bool section_state = false;
   if constexpr (kKeysSta) {
-    section_state = wg >= groups8 * n_win_wg;
+    section_state = c.section == kSecState || (c.section == kSecBoth && wg >= groups8 * n_win_wg);
     per_group = section_state ? n_st_wg : n_win_wg;
-    if (section_state) wg -= groups8 * n_win_wg;
+    if (section_state && c.section == kSecBoth) wg -= groups8 * n_win_wg;
   }
   const int xcd = wg % kXcds, seq = wg / kXcds;
   const int u = (seq / per_group) * kXcds + xcd;
@@ -470,7 +470,7 @@ __global__ __launch_bounds__(256, 2) void bwd_mfma_kernel(Bwd a, MfmaChunk c) {
     if (col_ok) {
       // The chunk's own tokens as window keys: this launch has streamed every query that sees
       // them, so dk (which carries the logit scale) resp. dv is complete once the share the
-      // token got when its fold was undone (kept in fp32 in a ring of the last window's blocks)
+      // token got when its fold was undone (kept in fp32 in a ring of the last window's blocks and one more)
       // is added, and goes out in the I/O dtype.
       if (!sta_state) {
         const float os = kRole == kRoleDK ? scale : 1.f;
@@ -642,7 +642,8 @@ __global__ __launch_bounds__(256, 2) void bwd_mfma_kernel(Bwd a, MfmaChunk c) {
 bool backward_on_mfma(const Dev &dv) { return dv.io == 1 && dv.d == kHeadDim; }
 
 // The three launches of one chunk: dq (and the temperature sums), dk, dv (or the readout's adjoint).
-hipError_t launch_backward_mfma(const Bwd &a, int64_t cs, int nq, int m, bool folded, hipStream_t st, hipStream_t st_dv) {
+hipError_t launch_backward_mfma(const Bwd &a, int64_t cs, int nq, int m, bool folded, int role, int section,
+                                hipStream_t st) {
   const Dev &dv = a.dv;
   static bool allowed = false;  // more than 64 KiB of LDS per workgroup has to be asked for once
   if (!allowed) {
@@ -663,14 +664,21 @@ hipError_t launch_backward_mfma(const Bwd &a, int64_t cs, int nq, int m, bool fo
   const int64_t ext = a.T - cs < dv.L ? a.T - cs : dv.L;
   c.nq_ext = (int)ext;
   c.folded = folded ? 1 : 0;
-  c.ring_row0 = (int)((cs / dv.C) % (dv.L / dv.C)) * dv.C;
+  c.ring_row0 = (int)((cs / dv.C) % (a.ring_rows / dv.C)) * dv.C;
+  c.section = section;
   const int G = dv.Hq / dv.Hkv;
   const unsigned groups = (unsigned)((dv.U + kXcds - 1) / kXcds * kXcds);
-  const int per_q = G * ((nq + kStaPerWg - 1) / kStaPerWg);
-  const int per_k = (m + kStaPerWg - 1) / kStaPerWg + (nq + kStaPerWg - 1) / kStaPerWg;
-  hipLaunchKernelGGL((bwd_mfma_kernel<kRoleDQ>), dim3(groups * per_q), dim3(256), kBwdLdsBytes, st, a, c);
-  hipLaunchKernelGGL((bwd_mfma_kernel<kRoleDK>), dim3(groups * per_k), dim3(256), kBwdLdsBytes, st, a, c);
-  hipLaunchKernelGGL((bwd_mfma_kernel<kRoleDV>), dim3(groups * per_k), dim3(256), kBwdLdsBytes, st_dv, a, c);
+  const int n_win_wg = (nq + kStaPerWg - 1) / kStaPerWg, n_st_wg = (m + kStaPerWg - 1) / kStaPerWg;
+  if (role == kRoleDQ) {
+    hipLaunchKernelGGL((bwd_mfma_kernel<kRoleDQ>), dim3(groups * G * n_win_wg), dim3(256), kBwdLdsBytes, st, a, c);
+    return hipGetLastError();
+  }
+  const int per_k = section == kSecBoth ? n_st_wg + n_win_wg : section == kSecState ? n_st_wg : n_win_wg;
+  if (per_k == 0) return hipSuccess;
+  if (role == kRoleDK)
+    hipLaunchKernelGGL((bwd_mfma_kernel<kRoleDK>), dim3(groups * per_k), dim3(256), kBwdLdsBytes, st, a, c);
+  else
+    hipLaunchKernelGGL((bwd_mfma_kernel<kRoleDV>), dim3(groups * per_k), dim3(256), kBwdLdsBytes, st, a, c);
   return hipGetLastError();
 }
 

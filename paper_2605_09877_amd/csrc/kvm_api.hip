@@ -406,11 +406,11 @@ BwdLayout bwd_layout(const kvm_config &c, int64_t Mcap, int64_t T) {
   l.dkhat = take(U * M * d * 4);
   l.dvhat = take(U * M * d * 4);
   // full-size accumulators of dk, dv on the vector-ALU path; on the matrix-core path a ring of
-  // one window's blocks (see kvm::Bwd)
+  // one window's blocks and one more (see kvm::Bwd)
   const char *env_g = getenv("KVM_BACKWARD_GENERIC");
   const bool mfma_path = c.io_dtype == KVM_BF16 && c.head_dim == 128 && !(env_g && env_g[0] == '1');
-  l.dk_acc = take(U * (mfma_path ? L : Tn) * d * 4);
-  l.dv_acc = take(U * (mfma_path ? L : Tn) * d * 4);
+  l.dk_acc = take(U * (mfma_path ? L + C : Tn) * d * 4);
+  l.dv_acc = take(U * (mfma_path ? L + C : Tn) * d * 4);
   l.delta = take((size_t)c.batch * Tn * c.n_q_heads * 4);
   // the chunk's probabilities and logit adjoints are written out only by the vector-ALU kernels
   const char *env = getenv("KVM_BACKWARD_GENERIC");
@@ -1047,11 +1047,13 @@ int kvm_prefill_backward(kvm_state *st, const void *q, const void *k, const void
   a.par64 = (double *)(w + l.par64);
   kvm::BwdStreams x;
   if (kvm::backward_on_mfma(st->dv)) {
-    if (!st->fold_streams[0]) HIP_TRY(hipStreamCreateWithFlags(&st->fold_streams[0], hipStreamNonBlocking));
+    for (hipStream_t &fs : st->fold_streams)
+      if (!fs) HIP_TRY(hipStreamCreateWithFlags(&fs, hipStreamNonBlocking));
     x.side = st->fold_streams[0];
+    x.side2 = st->fold_streams[1];
     st->sync_used = 0;
-    HIP_TRY(next_sync_event(st, &x.fork));
-    HIP_TRY(next_sync_event(st, &x.join));
+    for (hipEvent_t *e : {&x.fork, &x.dq_done, &x.join_state, &x.join_window[0], &x.join_window[1]})
+      HIP_TRY(next_sync_event(st, e));
   }
   HIP_TRY(kvm::run_backward(a, chunks.data(), (int)chunks.size(), (hipStream_t)stream, x));
   return KVM_OK;

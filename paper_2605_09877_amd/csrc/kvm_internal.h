@@ -129,7 +129,7 @@ struct Bwd {
   float *dkhat, *dvhat;  // [U, Mcap, d] adjoint of that readout (one chunk's)
   // fp32 accumulators of dk, dv: [B, T, Hkv, d] (ring_rows = 0), or, on the matrix-core path, only
   // the share a token gets when its fold is undone, kept until the token's block is finished as
-  // window keys: [U, ring_rows, d] with ring_rows = L, block number mod n_bswa
+  // window keys: [U, ring_rows, d] with ring_rows = L + C, block number mod (n_bswa + 1)
   float *dk_acc, *dv_acc;
   int32_t ring_rows;
   float *delta;          // [B, T, Hq] sum over channels of dout * out
@@ -144,15 +144,21 @@ struct BwdChunk {
   int32_t fold;    // index of the fold that followed the chunk, or -1
   int32_t m_after; // state rows after that fold
 };
-// A second stream and two untimed events, owned by the caller: the dv role of a chunk runs beside its
-// dq and dk roles (it needs neither D nor anything they write) and fills the ends of their grids.
+// Two more streams and a few untimed events, owned by the caller, for the matrix-core path: what
+// does not depend on the dq role's D, or on the state at all, runs beside the chain undo-fold ->
+// dq -> dk of the state rows (see run_backward).
 struct BwdStreams {
-  hipStream_t side = nullptr;  // null: everything on the one stream
-  hipEvent_t fork = nullptr, join = nullptr;
+  hipStream_t side = nullptr, side2 = nullptr;  // null: everything on the one stream
+  hipEvent_t fork = nullptr, dq_done = nullptr, join_state = nullptr, join_window[2] = {nullptr, nullptr};
 };
 hipError_t run_backward(const Bwd &a, const BwdChunk *chunks, int n_chunks, hipStream_t st, const BwdStreams &x);
 // backward_mfma.hip (bf16, d = 128): one chunk's dq, dk, dv and readout adjoint on the matrix cores
 bool backward_on_mfma(const Dev &dv);
-hipError_t launch_backward_mfma(const Bwd &a, int64_t cs, int nq, int m, bool folded, hipStream_t st, hipStream_t st_dv);
+enum { kRoleDQ = 0, kRoleDK = 1, kRoleDV = 2 };
+enum { kSecBoth = 0, kSecWindow = 1, kSecState = 2 };
+// one role of the matrix-core tile kernel over one chunk; roles dK, dV: all key workgroups, or only
+// those of the chunk's own tokens (window keys), or only those of the state rows
+hipError_t launch_backward_mfma(const Bwd &a, int64_t cs, int nq, int m, bool folded, int role, int section,
+                                hipStream_t st);
 
 }  // namespace kvm
