@@ -272,7 +272,10 @@ def test_backward_on_a_stream_of_the_callers_choice():
             out, lse = st.prefill(q, k, v, params["gate"], want_lse=True)
             g = st.backward(q, k, v, params["gate"], out, lse, dout, assign, score)
             after = {n: t.float() * 2.0 for n, t in g.items()}  # and one behind them
+            again = st.backward(q, k, v, params["gate"], out, lse, dout, assign, score)  # the state is only read
         stream.synchronize()
+        for name in ("dq", "dk", "dv", "dgate"):
+            torch.testing.assert_close(again[name], g[name], rtol=0, atol=0)
         return after
 
     torch.cuda.synchronize()
