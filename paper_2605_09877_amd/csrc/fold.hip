@@ -71,46 +71,57 @@ __device__ __forceinline__ void write_readout(const Dev &dv, int slot, int u, in
 // Covers n_blocks consecutive C-token blocks of `src`; block i goes to the i-th [U, C, d] slab
 // after dv.kbar (memory keys depend on k alone, so a prefill computes them a group at a time).
 // A token takes D / kN adjacent lanes, 16 bytes of channels each, so a wave handles several tokens.
+constexpr int kMemkeyTok = 4;  // tokens per lane group, their loads in flight together
 template <typename T, int D>
 __global__ __launch_bounds__(256) void memkey_kernel(Dev dv, Src src, int n_blocks) {
   constexpr int VEC = Vec16<T>::kN;
   constexpr int LPT = D / VEC;   // lanes per token
-  constexpr int TPW = 64 / LPT;  // tokens per wave
+  constexpr int TPW = 64 / LPT;  // tokens per wave and round
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int sub = lane / LPT, cl = lane % LPT;
   const int u = blockIdx.y, b = u / dv.Hkv, h = u % dv.Hkv;
   const int n_tok = dv.C * n_blocks;
-  const int j = (blockIdx.x * 4 + wave) * TPW + sub;
-  const int jc = j < n_tok ? j : n_tok - 1;  // lanes past the end repeat the last token, store nothing
-  const T *krow = (const T *)src.k + b * src.k_b + h * src.k_h + (int64_t)jc * src.k_t;
-  float raw[VEC];
-  Vec16<T>::load(krow + cl * VEC, raw);
-  double x[VEC];
-  double s = 0.0;
+  const int j0 = (blockIdx.x * 4 + wave) * TPW * kMemkeyTok + sub;
+  float raw[kMemkeyTok][VEC];
 #pragma unroll
-  for (int c = 0; c < VEC; ++c) {
-    x[c] = cl * VEC + c < dv.r ? 0.0 : (double)raw[c];
-    s += x[c];
+  for (int t = 0; t < kMemkeyTok; ++t) {
+    const int j = j0 + t * TPW;
+    const int jc = j < n_tok ? j : n_tok - 1;  // lanes past the end repeat the last token, store nothing
+    const T *krow = (const T *)src.k + b * src.k_b + h * src.k_h + (int64_t)jc * src.k_t;
+    Vec16<T>::load(krow + cl * VEC, raw[t]);
   }
-  const double mean = group_sum<LPT>(s) / (double)D;
-  double q = 0.0;
-#pragma unroll
-  for (int c = 0; c < VEC; ++c) {
-    const double dl = x[c] - mean;
-    q += dl * dl;
-  }
-  const double rden = 1.0 / sqrt(group_sum<LPT>(q) / (double)D + (double)dv.ln_eps);
-  float y[VEC];
+  double ga[VEC], be[VEC];
 #pragma unroll
   for (int c = 0; c < VEC; ++c) {
     const int ch = cl * VEC + c;
-    const double ga = dv.gamma ? (double)dv.gamma[h * D + ch] : 1.0;
-    const double be = dv.beta ? (double)dv.beta[h * D + ch] : 0.0;
-    y[c] = Io<T>::round_from((x[c] - mean) * rden * ga + be);
+    ga[c] = dv.gamma ? (double)dv.gamma[h * D + ch] : 1.0;
+    be[c] = dv.beta ? (double)dv.beta[h * D + ch] : 0.0;
   }
-  if (j < n_tok) {
-    T *out = (T *)dv.kbar + ((int64_t)(j / dv.C) * dv.Ufull * dv.C + (int64_t)u * dv.C + j % dv.C) * D;
-    Vec16<T>::store(out + cl * VEC, y);
+#pragma unroll
+  for (int t = 0; t < kMemkeyTok; ++t) {
+    const int j = j0 + t * TPW;
+    double x[VEC];
+    double s = 0.0;
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) {
+      x[c] = cl * VEC + c < dv.r ? 0.0 : (double)raw[t][c];
+      s += x[c];
+    }
+    const double mean = group_sum<LPT>(s) / (double)D;
+    double q = 0.0;
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) {
+      const double dl = x[c] - mean;
+      q += dl * dl;
+    }
+    const double rden = 1.0 / sqrt(group_sum<LPT>(q) / (double)D + (double)dv.ln_eps);
+    float y[VEC];
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) y[c] = Io<T>::round_from((x[c] - mean) * rden * ga[c] + be[c]);
+    if (j < n_tok) {
+      T *out = (T *)dv.kbar + ((int64_t)(j / dv.C) * dv.Ufull * dv.C + (int64_t)u * dv.C + j % dv.C) * D;
+      Vec16<T>::store(out + cl * VEC, y);
+    }
   }
 }
 
@@ -729,7 +740,7 @@ __global__ __launch_bounds__(64) void ring_copy_kernel(Dev dv, Src src, int64_t 
 }  // namespace
 
 hipError_t launch_memkey(const Dev &dv, const Src &src, int n_blocks, hipStream_t st) {
-  const int per_wg = 4 * 64 / (dv.d * (dv.io == 0 ? 4 : 2) / 16);  // tokens per workgroup
+  const int per_wg = kMemkeyTok * 4 * 64 / (dv.d * (dv.io == 0 ? 4 : 2) / 16);  // tokens per workgroup
   dim3 grid((dv.C * n_blocks + per_wg - 1) / per_wg, dv.U);
   KVM_DISPATCH(dv, memkey_kernel, grid, dim3(256), 0, st, dv, src, n_blocks);
   return hipGetLastError();
