@@ -619,7 +619,7 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
       return e ? (e[0] == '1' ? 1 : 0) : -1;
     }();
     // (and a call of a few chunks has nothing to pipeline: the events would cost more than they buy)
-    const bool serial = forced >= 0 ? forced == 1 : (copy_us > 60.0 || plan.size() <= 4);
+    const bool serial = forced >= 0 ? forced == 1 : (copy_us > 45.0 || plan.size() <= 4);
     if (serial) {
       for (const Chunk &ch : plan) {
         AttnArgs a;
