@@ -653,9 +653,10 @@ hipError_t run_backward(const Bwd &a_in, const BwdChunk *chunks, int n_chunks, h
       window_busy[ci & 1] = false;
     }
     if (ch.fold >= 0) {
-      // rows per wave: about one block token per wave's rows, so that the scan of the targets is
-      // shared where rows are many and hot rows run in parallel where they are few
-      int rpw = ch.m_after / dv.C;
+      // rows per wave: so many that the launch is about one resident round of waves (8 per SIMD,
+      // 8192 on the chip) -- a wave's rows share one scan of the block's targets, and more waves
+      // than fit at once only queue up behind the scan of the first
+      int rpw = (int)((int64_t)dv.U * ch.m_after / 8192);
       rpw = rpw < 1 ? 1 : (rpw > kUnfoldRows ? kUnfoldRows : rpw);
       BWD_DISPATCH(dv, bwd_unfold_kernel, dim3((ch.m_after + kUnfoldWaves * rpw - 1) / (kUnfoldWaves * rpw), dv.U),
                    dim3(64 * kUnfoldWaves), st, a, ch.fold, ch.s + ch.nq - dv.L, ch.m, ch.m_after, rpw);
