@@ -422,7 +422,10 @@ def test_state_size_follows_the_growth_budget():
 def test_run_state_sizes_match_integer_replay():
     T, C = 96, 4
     for kind, kw in [(ko.BUDGET_FIXED, dict(budget_fixed=10)), (ko.BUDGET_SQRT, dict(budget_scale=2.0)),
-                     (ko.BUDGET_TABLE, dict(budget_table=[0, 4, 5, 5, 9, 30, 31, 31]))]:
+                     (ko.BUDGET_TABLE, dict(budget_table=[0, 4, 5, 5, 9, 30, 31, 31])),
+                     # budgets below the rows the state already has: it neither grows nor shrinks
+                     (ko.BUDGET_FIXED, dict(budget_fixed=2)),
+                     (ko.BUDGET_TABLE, dict(budget_table=[0, 4, 7, 3, 3, 9, 1]))]:
         cfg = ko.KVMConfig(head_dim=8, rope_dims=2, chunk_len=C, io="f32", budget_kind=kind, **kw)
         unit, q, k, v, _ = make_unit(cfg, seed=50, T=T)
         unit.prefill(q, k, v)
@@ -433,7 +436,7 @@ def test_run_state_sizes_match_integer_replay():
                 m = C
             else:
                 if kind == ko.BUDGET_FIXED:
-                    B = 10
+                    B = kw["budget_fixed"]
                 elif kind == ko.BUDGET_SQRT:
                     B = int(2.0 * math.ceil(math.sqrt(e)))
                 else:
@@ -443,6 +446,8 @@ def test_run_state_sizes_match_integer_replay():
             want.append(m)
         assert got == want
         assert all(lg["m_after"] - lg["m_before"] == lg["n_append"] for lg in unit.fold_logs)
+        assert all(int(lg["appended"].sum()) == lg["n_append"] >= 0 for lg in unit.fold_logs)
+        assert unit.state.m == want[-1] == len(unit.state.rho)
 
 
 # ----------------------------------------------------------------------------- P4 softmax
@@ -545,3 +550,135 @@ def test_override_is_refused_outside_the_tie_margin():
     other = 1 if log["assign"][j] != 1 else 2
     with pytest.raises(ValueError):
         ko.fold(st2, k1, v1, None, 3 * cfg.chunk_len, cfg, gamma, beta, overrides={j: other})
+
+
+def _append_boundary_case():
+    """Five rows, nine tokens, room for three new rows; token b is token a scaled by 1 + 1e-7,
+    so their memory keys (LN_s is scale invariant) and append scores agree to ~1e-7 while the
+    other scores lie far apart.  a and b are placed on the selection boundary by brute force."""
+    d, r_, n_rows, n_tok = 8, 2, 5, 9
+    cfg = ko.KVMConfig(head_dim=d, rope_dims=r_, chunk_len=n_tok, io="f32",
+                       budget_kind=ko.BUDGET_FIXED, budget_fixed=n_rows + 3)
+    gamma, beta = np.ones(d), np.zeros(d)
+    for seed in range(200, 260):
+        r = rng(seed)
+        st = ko.UnitState(d)
+        k0, v0 = r.normal(size=(n_rows, d)), r.normal(size=(n_rows, d))
+        st.append_rows(ko.memory_key(k0, cfg, gamma, beta), v0, list(range(n_rows)))
+        k1, v1 = r.normal(size=(n_tok, d)), r.normal(size=(n_tok, d))
+        # brute-force append scores (scalar loops, equation for s_j)
+        def scores(kblk):
+            out = []
+            for j in range(n_tok):
+                kz = [0.0] * r_ + list(kblk[j, r_:])
+                kb = brute_ln(kz, gamma, beta, cfg.ln_eps).astype(np.float32).astype(np.float64)
+                best = -1e300
+                for i in range(n_rows):
+                    kh = brute_ln(list(st.sK[i]), gamma, beta, cfg.ln_eps).astype(np.float32).astype(np.float64)
+                    best = max(best, sum(kb[c] * kh[c] for c in range(d)))
+                out.append(best)
+            return np.array(out)
+        s = scores(k1)
+        order = sorted(range(n_tok), key=lambda j: (s[j], j))
+        a = order[2]                       # the last token taken
+        b = order[3]                       # the first token left out: make it a's near twin
+        k1[b] = k1[a] * (1.0 + 1e-7)
+        s = scores(k1)
+        order = sorted(range(n_tok), key=lambda j: (s[j], j))
+        gaps_ok = all(abs(s[j] - s[a]) > 1e-2 for j in range(n_tok) if j not in (a, b))
+        if set(order[2:4]) == {a, b} and abs(s[a] - s[b]) < 1e-5 and gaps_ok:
+            return cfg, st, k1, v1, gamma, beta, s, order
+    raise AssertionError("no seed gave a clean boundary pair")
+
+
+def test_append_override_is_honoured_only_inside_the_tie_margin():
+    """"Append": A_e is the n_append tokens with the smallest s_j.  The oracle lets a test swap
+    tokens in and out of A_e only when their scores lie within 1e-4 of the boundary score (the
+    n_append-th smallest); the accepted set is then what gets appended, in ascending position."""
+    import copy
+    cfg, st, k1, v1, gamma, beta, s, order = _append_boundary_case()
+    n_rows, n_tok, e = st.m, k1.shape[0], 3 * k1.shape[0]
+    own = sorted(order[:3])
+    log = ko.fold(copy.deepcopy(st), k1, v1, None, e, cfg, gamma, beta)
+    assert sorted(np.nonzero(log["appended"])[0].tolist()) == own
+    # inside the margin: the boundary pair swapped
+    taken, left = order[2], order[3]
+    alt = sorted(set(own) - {taken} | {left})
+    st_alt = copy.deepcopy(st)
+    log_alt = ko.fold(st_alt, k1, v1, None, e, cfg, gamma, beta, append_override=alt)
+    assert sorted(np.nonzero(log_alt["appended"])[0].tolist()) == alt
+    assert [int(log_alt["assign"][j]) for j in alt] == [n_rows, n_rows + 1, n_rows + 2]
+    for a_, j in enumerate(alt):           # the new rows were created from the override's tokens
+        assert abs(st_alt.rho[n_rows + a_] - np.linalg.norm(v1[j])) < 1e-13
+    assert not log_alt["appended"][taken] and log_alt["assign"][taken] >= cfg.n_sink
+    # the same set as the oracle's own choice is a no-op
+    log_same = ko.fold(copy.deepcopy(st), k1, v1, None, e, cfg, gamma, beta, append_override=list(reversed(own)))
+    np.testing.assert_array_equal(log_same["assign"], log["assign"])
+    # outside the margin: any swap that involves a token far from the boundary
+    far_out = order[-1]
+    far_in = order[0]
+    for bad in (sorted(set(own) - {taken} | {far_out}), sorted(set(own) - {far_in} | {left}),
+                sorted(set(own) - {far_in} | {far_out})):
+        with pytest.raises(ValueError, match="tie margin"):
+            ko.fold(copy.deepcopy(st), k1, v1, None, e, cfg, gamma, beta, append_override=bad)
+    # wrong sizes, repeated tokens
+    for bad in (own[:2], own + [left], [own[0], own[0], own[1]]):
+        with pytest.raises(ValueError, match="wrong size"):
+            ko.fold(copy.deepcopy(st), k1, v1, None, e, cfg, gamma, beta, append_override=bad)
+
+
+def test_append_override_margin_is_measured_from_the_boundary_score():
+    """A token 5e-5 above the boundary may be swapped in; one 2e-4 above may not (margin 1e-4)."""
+    import copy
+    cfg, st, k1, v1, gamma, beta, s, order = _append_boundary_case()
+    e = 3 * k1.shape[0]
+    own = sorted(order[:3])
+    taken, left = order[2], order[3]
+
+    # the left-out token's append score is moved by a chosen amount: its raw key is pushed along
+    # the state key it scores highest against
+    khat, _ = ko.readout(st, cfg, gamma, beta)
+    kb = ko.memory_key(k1, cfg, gamma, beta)
+    sim = kb @ khat.T
+    i_star = int(np.argmax(sim[left]))
+    for delta, ok in ((5e-5, True), (2e-4, False)):
+        # find a scale of the raw key's component along khat[i*] that lifts s_left by ~delta
+        k_mod = k1.copy()
+        lo, hi = 0.0, 1.0
+        for _ in range(60):
+            mid = 0.5 * (lo + hi)
+            k_try = k1.copy()
+            k_try[left, cfg.rope_dims:] += mid * khat[i_star, cfg.rope_dims:]
+            s_try = (ko.memory_key(k_try, cfg, gamma, beta) @ khat.T).max(axis=1)
+            if s_try[left] - s[taken] < delta:
+                lo = mid
+            else:
+                hi = mid
+        k_mod[left, cfg.rope_dims:] += hi * khat[i_star, cfg.rope_dims:]
+        s_mod = (ko.memory_key(k_mod, cfg, gamma, beta) @ khat.T).max(axis=1)
+        gap = s_mod[left] - s_mod[taken]
+        assert abs(gap - delta) < 2e-5, gap
+        alt = sorted(set(own) - {taken} | {left})
+        if ok:
+            log = ko.fold(copy.deepcopy(st), k_mod, v1, None, e, cfg, gamma, beta, append_override=alt)
+            assert sorted(np.nonzero(log["appended"])[0].tolist()) == alt
+        else:
+            with pytest.raises(ValueError, match="tie margin"):
+                ko.fold(copy.deepcopy(st), k_mod, v1, None, e, cfg, gamma, beta, append_override=alt)
+
+
+def test_merge_override_is_honoured_inside_the_tie_margin():
+    """Two state rows with the same key sums score alike; the lowest row wins by default and an
+    override to its twin is accepted (margin 0 <= 1e-4), then that row receives the token."""
+    import copy
+    cfg, st, k0, v0, k1, v1, g, gamma, beta = run_fold_case(96, gated=False)
+    st.sK[4] = st.sK[2]
+    base = copy.deepcopy(st)
+    log = ko.fold(copy.deepcopy(base), k1, v1, None, 3 * cfg.chunk_len, cfg, gamma, beta)
+    js = [j for j in range(k1.shape[0]) if log["assign"][j] == 2]
+    assert js and not (log["assign"] == 4).any()
+    j = js[0]
+    st2 = copy.deepcopy(base)
+    log2 = ko.fold(st2, k1, v1, None, 3 * cfg.chunk_len, cfg, gamma, beta, overrides={j: 4})
+    assert log2["assign"][j] == 4 and st2.n[4] == 2
+    np.testing.assert_allclose(st2.sV[4], base.sV[4] + v1[j], atol=1e-13)
