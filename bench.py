@@ -485,8 +485,8 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
-    if not os.path.exists(pkg.binding.LIB_PATH):
-        from paper_2605_09877_amd import build
+    from paper_2605_09877_amd import build
+    if build.is_stale():      # missing, or built from other sources than the tree holds
         build.build()
     dev = "cuda:0"
     if args.sweep:

@@ -114,8 +114,12 @@ def forward_backward_unit(cfg: ko.KVMConfig, q: np.ndarray, k: np.ndarray, v: np
                           tau_state: Optional[np.ndarray] = None, tau_bswa: Optional[np.ndarray] = None,
                           overrides: Optional[Dict[Tuple[int, int], int]] = None,
                           append_overrides: Optional[Dict[int, Sequence[int]]] = None,
-                          round_output: bool = True) -> dict:
+                          round_output: bool = True, stored_output: Optional[np.ndarray] = None) -> dict:
     """Forward (from an empty state, position 0) and backward of one unit over T tokens.
+
+    stored_output [G, T, d]: the layer's output as the caller stored it.  A backward call is
+    handed that tensor, not the exact output, and the softmax term D_i = sum_c dy_ic * y_ic is taken
+    over it; when given it replaces this function's own (rounded) output in that one place.
 
     round_output=False lets the backward read the unrounded output instead of the stored one:
     the difference between the two results is how far the rounding of the output alone moves
@@ -197,7 +201,8 @@ def forward_backward_unit(cfg: ko.KVMConfig, q: np.ndarray, k: np.ndarray, v: np
         pos_q, pos_w = np.arange(s, e), np.arange(b, e)
         a_dq, a_dkh, a_dvh, a_dkw, a_dvw, a_dts, a_dtb = attend_backward(
             q[:, s:e], pos_q, khat, vhat, k[b:e], v[b:e], pos_w, ts, tb, lse[:, s:e],
-            ko.round_io(y[:, s:e], cfg.io) if round_output else y[:, s:e], dy[:, s:e])
+            np.asarray(stored_output, np.float64)[:, s:e] if stored_output is not None
+            else ko.round_io(y[:, s:e], cfg.io) if round_output else y[:, s:e], dy[:, s:e])
         dq[:, s:e] += a_dq
         dk[b:e] += a_dkw
         dv[b:e] += a_dvw

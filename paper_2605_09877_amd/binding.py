@@ -288,25 +288,37 @@ class KVMState:
                              f"got {t.dtype} {tuple(t.shape)} on {t.device}")
         return t
 
+    def _chk_view(self, t: torch.Tensor, shape, dtype, name: str) -> torch.Tensor:
+        """Like _chk, but any strides are allowed as long as the last axis is contiguous."""
+        if t.device != self.device or t.dtype != dtype or tuple(t.shape) != tuple(shape) or \
+                (t.dim() > 3 and t.stride(-1) != 1):
+            raise ValueError(f"{name}: want {dtype} {tuple(shape)} on {self.device} with a contiguous last axis, "
+                             f"got {t.dtype} {tuple(t.shape)} strides {t.stride()} on {t.device}")
+        return t
+
     def prefill(self, q, k, v, gate=None, out=None, lse=None, want_lse=False):
-        """kvm_prefill_chunked.  q [B,T,Hq,d], k/v [B,T,Hkv,d], gate [B,T,Hkv] fp32 or None."""
+        """kvm_prefill_chunked.  q [B,T,Hq,d], k/v [B,T,Hkv,d], gate [B,T,Hkv] fp32 or None.  The
+        tensors may be views of wider buffers (say slices of one fused projection output): their
+        element strides go to the library as kvm_strides; head_dim must be contiguous."""
         c = self.cfg
         T = q.shape[1]
-        self._chk(q, (c.batch, T, c.n_q_heads, c.head_dim), self.dtype, "q")
-        self._chk(k, (c.batch, T, c.n_kv_heads, c.head_dim), self.dtype, "k")
-        self._chk(v, (c.batch, T, c.n_kv_heads, c.head_dim), self.dtype, "v")
+        self._chk_view(q, (c.batch, T, c.n_q_heads, c.head_dim), self.dtype, "q")
+        self._chk_view(k, (c.batch, T, c.n_kv_heads, c.head_dim), self.dtype, "k")
+        self._chk_view(v, (c.batch, T, c.n_kv_heads, c.head_dim), self.dtype, "v")
         if gate is not None:
-            self._chk(gate, (c.batch, T, c.n_kv_heads), torch.float32, "gate")
+            self._chk_view(gate, (c.batch, T, c.n_kv_heads), torch.float32, "gate")
         if out is None:
-            out = torch.empty_like(q)
-        self._chk(out, q.shape, self.dtype, "out")
+            out = torch.empty((c.batch, T, c.n_q_heads, c.head_dim), dtype=self.dtype, device=self.device)
+        self._chk_view(out, q.shape, self.dtype, "out")
         if lse is None and want_lse:
             lse = torch.empty((c.batch, T, c.n_q_heads), dtype=torch.float32, device=self.device)
         if lse is not None:
-            self._chk(lse, (c.batch, T, c.n_q_heads), torch.float32, "lse")
+            self._chk_view(lse, (c.batch, T, c.n_q_heads), torch.float32, "lse")
+        bth = lambda t, n: (0, 0, 0) if t is None else (t.stride(0), t.stride(1), t.stride(2))
+        strides = kvm_strides(*bth(q, 4), *bth(k, 4), *bth(v, 4), *bth(out, 4), *bth(gate, 3), *bth(lse, 3))
         with torch.cuda.device(self.device):
             _check(self.lib.kvm_prefill_chunked(self.handle, q.data_ptr(), k.data_ptr(), v.data_ptr(), _ptr(gate),
-                                                out.data_ptr(), _ptr(lse), T, None, _stream()),
+                                                out.data_ptr(), _ptr(lse), T, C.byref(strides), _stream()),
                    "kvm_prefill_chunked")
         return (out, lse) if (want_lse or lse is not None) else out
 

@@ -17,6 +17,32 @@ FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17",
          "-Wno-unused-command-line-argument"]
 
 
+STAMP = LIB + ".srchash"
+
+
+def source_hash() -> str:
+    """Digest of everything the library is built from: sources, headers, flags."""
+    import hashlib
+    h = hashlib.sha256(" ".join(FLAGS + SOURCES).encode())
+    files = sorted(os.listdir(CSRC))
+    paths = [os.path.join(CSRC, f) for f in files if f.endswith((".hip", ".h"))]
+    paths.append(os.path.join(os.path.dirname(HERE), "include", "kvm.h"))
+    for p in paths:
+        with open(p, "rb") as f:
+            h.update(p[len(os.path.dirname(HERE)):].encode())
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def is_stale() -> bool:
+    """True when libkvm.so is missing or was built from other sources than the tree holds now
+    (compared by content, so that copying the tree to another machine changes nothing)."""
+    if not os.path.exists(LIB) or not os.path.exists(STAMP):
+        return True
+    with open(STAMP) as f:
+        return f.read().strip() != source_hash()
+
+
 def _hipcc() -> str:
     for cand in (os.environ.get("HIPCC"), "/opt/rocm/bin/hipcc", "hipcc"):
         if cand and (os.path.isabs(cand) and os.path.exists(cand) or not os.path.isabs(cand)):
@@ -41,6 +67,8 @@ def build(verbose: bool = True) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
+    with open(STAMP, "w") as f:
+        f.write(source_hash() + "\n")
     if verbose:
         print(f"built {LIB}", file=sys.stderr)
     return LIB

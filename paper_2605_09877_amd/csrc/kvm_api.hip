@@ -571,6 +571,15 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
     if (x % vec) return KVM_ERR_ARG;
   // rows of k and v are whole and apart (the tile loads count on at least d elements between tokens)
   if (s.k_t < d || s.v_t < d || s.q_t < d || s.o_t < d) return KVM_ERR_ARG;
+  if (s.q_h < d || s.k_h < d || s.v_h < d || s.o_h < d) return KVM_ERR_ARG;
+  // the tile loads keep a token's byte offset inside a tile in 32 bits (64 rows of a tile times
+  // the stride): a token stride of up to 16 MiB is far beyond any fused-projection layout
+  if (s.k_t * (int64_t)es > (int64_t)1 << 24 || s.v_t * (int64_t)es > (int64_t)1 << 24) return KVM_ERR_ARG;
+  for (int64_t x : strides16)
+    if (x < 0) return KVM_ERR_ARG;
+  if (gate && (s.g_b < 0 || s.g_t < 0 || s.g_h < 0)) return KVM_ERR_ARG;
+  // lse is written: its three strides must address B * T * H_q distinct floats
+  if (lse && (s.lse_h <= 0 || s.lse_t <= 0 || s.lse_b <= 0)) return KVM_ERR_ARG;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return KVM_ERR_ARG;
 
   const int64_t t0 = st->tokens, t_end = t0 + T;

@@ -47,15 +47,60 @@ def make_oracle_unit(w, params, h) -> ko.KVMUnit:
                       pick("tau_state", slice(h * G, (h + 1) * G)), pick("tau_bswa", slice(h * G, (h + 1) * G)))
 
 
-def run_oracle_following(w, params, h, drive, gpu_assign, max_rounds=50):
+class Ties:
+    """Counted ties of one run: disagreements with the oracle that the oracle's own scores put
+    inside the 1e-4 margin (merge: the library's row scores within 1e-4 of the best row; append:
+    the swapped tokens' scores within 1e-4 of the selection boundary)."""
+
+    def __init__(self, merge=0, append=0):
+        self.merge, self.append = merge, append
+
+    @property
+    def total(self):
+        return self.merge + self.append
+
+    def __iadd__(self, other):
+        self.merge += other.merge
+        self.append += other.append
+        return self
+
+    def __repr__(self):
+        return f"Ties(merge={self.merge}, append={self.append})"
+
+
+# Ceiling on counted ties per (batch, KV head) unit and fold.  fp32 I/O: both sides sum the same
+# fp32 operands in fp64, so none.  bf16 I/O: the library's scores are fp32 sums of exact products
+# on the matrix cores (error up to ~d * 2^-24 * |score| ~ 1e-5 on scores of size 10), the oracle's
+# are fp64 sums: two rows (or two tokens at the append boundary) closer than that can swap.  With
+# C tokens per fold and continuous random data such near-ties are rare: at most one in four folds
+# of a unit is allowed, and never more than one per fold.
+def tie_ceiling(w, n_folds):
+    return 0 if w.io == "f32" else (n_folds + 3) // 4
+
+
+# What the parity tests of a session saw, one record per test case: written to
+# gpurun_out/parity_stats.json by tests/conftest.py when the session ends.
+PARITY_LOG = []
+
+
+def record_parity(case, units, ties, max_err, io):
+    PARITY_LOG.append(dict(case=case, io=io, units=int(units), ties_merge=int(ties.merge),
+                           ties_append=int(ties.append), max_err=float(max_err)))
+
+
+def run_oracle_following(w, params, h, drive, gpu_assign, n_folds=None):
     """Run `drive(unit)` (which feeds tokens and returns outputs) and compare the fold logs with
     gpu_assign [F, C] (the library's trace for this unit).  Ties are overridden and the run is
-    repeated.  Returns (outputs of drive, unit, number of counted ties)."""
-    overrides, app_overrides, ties = {}, {}, 0
-    for _ in range(max_rounds):
+    repeated; more of them than tie_ceiling allows fail.  n_folds: folds the run must have (the
+    rows of gpu_assign by default).  Returns (outputs of drive, unit, Ties)."""
+    overrides, app_overrides, ties = {}, {}, Ties()
+    n_folds = gpu_assign.shape[0] if n_folds is None else n_folds
+    ceiling = tie_ceiling(w, n_folds)
+    while True:
         unit = make_oracle_unit(w, params, h)
         unit.overrides, unit.append_overrides = dict(overrides), dict(app_overrides)
         out = drive(unit)
+        assert len(unit.fold_logs) == n_folds, (len(unit.fold_logs), n_folds)
         bad = None
         for f, log in enumerate(unit.fold_logs):
             ga = gpu_assign[f]
@@ -63,19 +108,21 @@ def run_oracle_following(w, params, h, drive, gpu_assign, max_rounds=50):
                 bad = (f, log, ga)
                 break
         if bad is None:
-            assert len(unit.fold_logs) == gpu_assign.shape[0] or len(unit.fold_logs) <= gpu_assign.shape[0]
             return out, unit, ties
         f, log, ga = bad
         m0 = log["m_before"]
         gpu_app = sorted(int(j) for j in np.nonzero(ga >= m0)[0]) if m0 > 0 else None
         ora_app = sorted(int(j) for j in np.nonzero(log["appended"])[0]) if m0 > 0 else None
-        ties += 1
         if m0 > 0 and gpu_app != ora_app:
+            assert f not in app_overrides, f"fold {f}: the append override did not settle the selection"
+            ties.append += 1
             app_overrides[f] = gpu_app        # the oracle raises unless it is a boundary tie
         else:
             j = int(np.nonzero(log["assign"] != ga)[0][0])
+            assert (f, j) not in overrides, f"fold {f} token {j}: the override did not settle the row"
+            ties.merge += 1
             overrides[(f, j)] = int(ga[j])    # the oracle raises unless within the margin
-    raise AssertionError("tie protocol did not converge")
+        assert ties.total <= ceiling, f"{ties} over {n_folds} folds of one unit: more than the {ceiling} allowed"
 
 
 def check_outputs(w, y_gpu: np.ndarray, y_ref: np.ndarray, what=""):
@@ -106,8 +153,10 @@ def check_state(w, exp: dict, unit: ko.KVMUnit, b: int, h: int):
     np.testing.assert_array_equal(exp["n"][b, h].cpu().numpy(), st.n)
     khat, vhat = ko.readout(st, unit.cfg, unit.gamma, unit.beta)
     kh_gpu, vh_gpu = f64(exp["khat"][b, h]), f64(exp["vhat"][b, h])
+    # LN_s is done in fp64 on both sides from bit-equal sums; the last bits of the two fp64
+    # evaluations may differ (a reciprocal against a division), so an element flips only when its
+    # exact value lies within ~1e-15 of a rounding boundary of the I/O dtype: none is expected
     n_diff = int((kh_gpu != khat).sum())
-    # LN_s is done in fp64 on both sides; a rounding flip needs a value within ~1e-15 of a tie
-    assert n_diff <= max(1, khat.size // 100000), f"{n_diff} of {khat.size} key readout elements differ"
+    assert n_diff == 0, f"{n_diff} of {khat.size} key readout elements differ"
     tol = 2.0 ** -7 if w.io == "bf16" else 1e-5
     np.testing.assert_allclose(vh_gpu, vhat, rtol=tol, atol=tol * 1e-2)

@@ -6,15 +6,14 @@ are fp32 sums of up to (m + L) * G * C products of O(1) numbers); 1e-3 for the t
 LN_s gradients, which are sums over every row of the sequence of terms of both signs whose
 absolute values add up to some 1e2..1e3 times the result, so that fp32 rounding of the terms
 (and the order in which token sums are taken apart again) shows at the 1e-4 level.  bf16 I/O: max-abs error <= 2e-2 *
-max-abs of the reference tensor of the unit (of the whole tensor for the parameter gradients).  The
-bf16 bar is relative to the tensor, not to the row: the backward reads the forward's output in
-bf16, and an output within the forward's own bar of the oracle's (an ulp here and there) moves the
-softmax term D_i = sum_c dy_ic y_ic by up to 2^-8 sum_c |dy_ic y_ic|, which reaches dq_i and the
-dk_j of every visible key in absolute terms however small that row's own gradient is (measured on
-the bf16 case below: 1e-2 of the tensor's max-abs at worst, 1e-3 at the median).  Sums over all
-rows (the temperature and LN_s gradients) collect that term from every row; for them the bar adds
-twice the amount by which rounding the output to bf16 moves the oracle's own result (the oracle
-run with and without that rounding).  Slot assignments follow the forward's record under the tie
+max-abs of the reference tensor of the unit (of the whole tensor for the parameter gradients).
+The backward call is handed the forward's output as the library stored it (bf16); the oracle is
+handed that very tensor for the softmax term D_i = sum_c dy_ic y_ic (`stored_output`), so both
+sides differentiate from the same stored values and the bar covers only what the bf16 kernels
+themselves round: P^T and dS^T as bf16 operands of the second products (2^-9 relative per term)
+and the bf16 store of dq, dk, dv (2^-9 of the element).  The bar is relative to the tensor, not
+to the row, because a row's gradient is a sum of terms of both signs whose rounding errors scale
+with the terms, not with the sum.  Slot assignments follow the forward's record under the tie
 protocol of kvm_testlib.
 """
 import numpy as np
@@ -38,42 +37,50 @@ def synth():
     return s
 
 
-def oracle_unit_following(w, params, u, dy, h, gpu_assign, max_rounds=50, **kw):
-    """forward_backward_unit with the library's counted ties overridden (see kvm_testlib)."""
+def oracle_unit_following(w, params, u, dy, h, gpu_assign, **kw):
+    """forward_backward_unit with the library's counted ties overridden, under the same ceiling on
+    their number as the forward tests (see kvm_testlib)."""
     G = w.n_q_heads // w.n_kv_heads
     pick = lambda key, sl: None if params.get(key) is None else tl.f64(params[key][sl])
-    overrides, app_overrides = {}, {}
-    for _ in range(max_rounds):
+    overrides, app_overrides, ties = {}, {}, tl.Ties()
+    ceiling = tl.tie_ceiling(w, gpu_assign.shape[0])
+    while True:
         res = kb.forward_backward_unit(
             tl.oracle_cfg(w), u["q"], u["k"], u["v"], u["g"], dy, G, pick("ln_gamma", h), pick("ln_beta", h),
             pick("tau_state", slice(h * G, (h + 1) * G)), pick("tau_bswa", slice(h * G, (h + 1) * G)),
             overrides=overrides, append_overrides=app_overrides, **kw)
+        assert len(res["fold_logs"]) == gpu_assign.shape[0]
         bad = None
         for f, log in enumerate(res["fold_logs"]):
             if not np.array_equal(log["assign"], gpu_assign[f]):
                 bad = (f, log, gpu_assign[f])
                 break
         if bad is None:
+            res["ties"] = ties
             return res
         f, log, ga = bad
         m0 = log["m_before"]
         gpu_app = sorted(int(j) for j in np.nonzero(ga >= m0)[0]) if m0 > 0 else None
         ora_app = sorted(int(j) for j in np.nonzero(log["appended"])[0]) if m0 > 0 else None
         if m0 > 0 and gpu_app != ora_app:
+            assert f not in app_overrides
+            ties.append += 1
             app_overrides[f] = gpu_app
         else:
             j = int(np.nonzero(log["assign"] != ga)[0][0])
+            assert (f, j) not in overrides
+            ties.merge += 1
             overrides[(f, j)] = int(ga[j])
-    raise AssertionError("tie protocol did not converge")
+        assert ties.total <= ceiling, f"{ties}: more than the {ceiling} allowed"
 
 
-def check(w, name, got, ref, slack=0.0, f32_bar=1e-4):
+def check(w, name, got, ref, f32_bar=1e-4):
     err = np.abs(got - ref)
     top = float(np.abs(ref).max())
     if w.io == "f32":
         assert err.max() <= f32_bar * max(1.0, top), f"{name}: fp32 max-abs error {err.max():.3e} (reference max {top:.3e})"
         return
-    worst = float(err.max() / (2e-2 * top + slack + 1e-6))
+    worst = float(err.max() / (2e-2 * top + 1e-6))
     assert worst <= 1.0, f"{name}: bf16 error is {worst:.3f} x the 2e-2 bound"
 
 
@@ -104,7 +111,6 @@ def run_backward_case(w, plain, units=None, split=None):
     d = w.head_dim
     sums = dict(dgamma=np.zeros((w.n_kv_heads, d)), dbeta=np.zeros((w.n_kv_heads, d)),
                 dtau_state=np.zeros(w.n_q_heads), dtau_bswa=np.zeros(w.n_q_heads))
-    slack = {name: 0.0 for name in sums}
     kinds = set()
     all_units = [(b, h) for b in range(w.batch) for h in range(w.n_kv_heads)]
     for key in ("dq", "dk", "dv", "dgate", "dgamma", "dbeta", "dtau_state", "dtau_bswa"):
@@ -112,7 +118,8 @@ def run_backward_case(w, plain, units=None, split=None):
     for (b, h) in (all_units if units is None else units):
         u = tl.unit_inputs(w, q, k, v, params, b, h)
         dy = tl.f64(dout[b, :, h * G:(h + 1) * G]).transpose(1, 0, 2)
-        res = oracle_unit_following(w, params, u, dy, h, ga_all[:, b, h])
+        y_stored = tl.f64(out[b, :, h * G:(h + 1) * G]).transpose(1, 0, 2)
+        res = oracle_unit_following(w, params, u, dy, h, ga_all[:, b, h], stored_output=y_stored)
         assert res["m"] == st.rows and len(res["fold_logs"]) == st.folds
         for log in res["fold_logs"]:
             kinds.add("creation" if log["m_before"] == 0 else "append all" if log["n_append"] == w.chunk_len
@@ -122,17 +129,13 @@ def run_backward_case(w, plain, units=None, split=None):
         check(w, f"dk {what}", tl.f64(g["dk"][b, :, h]), res["dk"])
         check(w, f"dv {what}", tl.f64(g["dv"][b, :, h]), res["dv"])
         check(w, f"dgate {what}", tl.f64(g["dgate"][b, :, h]), res["dg"])
-        if w.io == "bf16" and units is None:
-            exact = oracle_unit_following(w, params, u, dy, h, ga_all[:, b, h], round_output=False)
-            for name in slack:
-                slack[name] += 2.0 * float(np.abs(res[name] - exact[name]).max())
         sums["dgamma"][h] += res["dgamma"]
         sums["dbeta"][h] += res["dbeta"]
         sums["dtau_state"][h * G:(h + 1) * G] += res["dtau_state"]
         sums["dtau_bswa"][h * G:(h + 1) * G] += res["dtau_bswa"]
     if units is None:
         for name, ref in sums.items():
-            check(w, name, tl.f64(g[name]), ref, slack[name], f32_bar=1e-3)
+            check(w, name, tl.f64(g[name]), ref, f32_bar=1e-3)
     return kinds
 
 

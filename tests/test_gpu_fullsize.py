@@ -32,22 +32,24 @@ def test_full_size_prefill_sampled_units(name, rows):
 
 
 def test_full_size_decode_sampled_units():
-    """Batched decode workload at full size: 64 x 32 heads, 2048 rows + 256-token window, 260
-    successive steps (two folds); sampled units replayed by the oracle."""
+    """Batched decode workload at full size: 64 x 32 heads, 2048 rows + 256-token window, all of
+    its 1000 successive steps (seven folds); sampled units replayed by the oracle."""
     pkg, sy = kvm(), synth()
-    w = sy.shrink(sy.WORKLOADS["decode"], seq=260)
+    w = sy.WORKLOADS["decode"]
+    assert w.seq == 1000
     pre = sy.make_decode_state(w, "cuda:0")
     st = pkg.state_for(w, device="cuda:0", max_tokens=pre["tokens"] + 2 * w.seq)
-    assign, _ = st.trace(4)
+    assign, _ = st.trace(8)
     st.import_(dict(pre, folds=0))
     q, k, v = sy.make_qkv(w, "cuda:0", T=w.seq, pos0=pre["tokens"])
     outs = [st.decode(q[:, t].contiguous(), k[:, t].contiguous(), v[:, t].contiguous()) for t in range(w.seq)]
     torch.cuda.synchronize()
     y_gpu = torch.stack(outs, dim=1)
-    assert st.folds == 2 and st.rows == 2048
-    ga = assign[:2].cpu().numpy()
+    assert st.folds == 7 and st.rows == 2048
+    ga = assign[:7].cpu().numpy()
     L, t0 = w.chunk_len * w.n_bswa_chunks, pre["tokens"]
-    for (b, h) in sample_units(w):
+    all_ties, worst, units = tl.Ties(), 0.0, sample_units(w)
+    for (b, h) in units:
         def drive(unit):
             s0 = unit.state
             s0.sK = pre["sK"][b, h].cpu().numpy().copy()
@@ -67,4 +69,7 @@ def test_full_size_decode_sampled_units():
             return np.stack(ys, axis=1)
 
         y_ref, unit, ties = tl.run_oracle_following(w, {}, h, drive, ga[:, b, h])
-        tl.check_outputs(w, tl.f64(y_gpu[b, :, h:h + 1]).transpose(1, 0, 2), y_ref, f"decode unit {(b, h)}")
+        all_ties += ties
+        worst = max(worst, tl.check_outputs(w, tl.f64(y_gpu[b, :, h:h + 1]).transpose(1, 0, 2), y_ref,
+                                            f"decode unit {(b, h)}"))
+    tl.record_parity("full_size_decode[1000 steps]", len(units), all_ties, worst, w.io)

@@ -57,6 +57,7 @@ def run_ragged(base, batches, prompts, n_dec, plain):
             s += B
         rows_seen.add(tuple(st.rows for st in states))
     torch.cuda.synchronize()
+    all_ties, worst, n_units = tl.Ties(), 0.0, 0
     for d, st in zip(data, states):
         w, Tp = d["w"], d["Tp"]
         assert st.tokens == w.seq
@@ -79,8 +80,11 @@ def run_ragged(base, batches, prompts, n_dec, plain):
                 y_ref, unit, ties = tl.run_oracle_following(w, d["params"], h, drive, ga_all[:, b, h])
                 assert len(unit.fold_logs) == st.folds and unit.state.m == st.rows
                 yg = tl.f64(y_gpu[b, :, h * G:(h + 1) * G]).transpose(1, 0, 2)
-                tl.check_outputs(w, yg, y_ref, f"state with prompt {Tp}, unit {(b, h)}")
+                worst = max(worst, tl.check_outputs(w, yg, y_ref, f"state with prompt {Tp}, unit {(b, h)}"))
+                all_ties += ties
+                n_units += 1
                 tl.check_state(w, exp, unit, b, h)
+    tl.record_parity(f"ragged_decode[{base.name},{base.io}]", n_units, all_ties, worst, base.io)
     return states, rows_seen
 
 
