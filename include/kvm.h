@@ -44,7 +44,8 @@ typedef enum kvm_status {
   KVM_ERR_CAPACITY = -2,    /* the bound buffer cannot hold the rows the budget asks for */
   KVM_ERR_STATE = -3,       /* call not valid in the state's current position            */
   KVM_ERR_HIP = -4,         /* a HIP runtime call failed (see kvm_last_hip_error)        */
-  KVM_ERR_UNSUPPORTED = -5  /* shape/dtype combination has no kernel                     */
+  KVM_ERR_UNSUPPORTED = -5, /* shape/dtype combination has no kernel                     */
+  KVM_ERR_LIMIT = -6        /* beyond the fixed maximum of an allocation-free entry point */
 } kvm_status;
 
 enum { KVM_F32 = 0, KVM_BF16 = 1 };
@@ -143,6 +144,21 @@ size_t kvm_decode_multi_workspace_bytes(int64_t n_sequences);
 int kvm_decode_step_multi(kvm_state *const *states, int32_t n_states, const void *q, const void *k,
                           const void *v, const float *gate, void *out, void *workspace,
                           size_t workspace_bytes, void *stream);
+
+/* kvm_decode_step_multi for callers that cannot allocate or bring a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments minus the
+ * workspace, same effect, same results to the bit (the same attention and fold kernels run).  The
+ * per-sequence descriptor table lives in a device array inside the library, fixed at
+ * KVM_STATIC_MAX_SEQUENCES sequences per call (about 224 KiB on every GPU the library runs on,
+ * held until the process ends); it is filled by a small kernel from values passed as kernel
+ * arguments, so the call makes no hipMalloc / hipFree, no host-to-device copy and no host heap
+ * allocation (with kvm_state_profile off).  More sequences than the maximum: KVM_ERR_LIMIT,
+ * nothing enqueued (kvm_last_hip_error() says how many were asked for).  The table is rewritten
+ * by every call: calls on one GPU must be ordered (one stream, or events); calls that overlap on
+ * one GPU race on it. */
+#define KVM_STATIC_MAX_SEQUENCES 4096
+int kvm_decode_step_multi_static(kvm_state *const *states, int32_t n_states, const void *q, const void *k,
+                                 const void *v, const float *gate, void *out, void *stream);
 
 /* Fold one overflow block into the state ("Append" and "Merge"): memory keys, similarity to
  * the normalised state, append of the n_append least similar tokens, winner-take-all merge of

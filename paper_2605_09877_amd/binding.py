@@ -17,11 +17,13 @@ LIB_PATH = os.path.join(_HERE, "libkvm.so")
 KVM_F32, KVM_BF16 = 0, 1
 KVM_BUDGET_NONE, KVM_BUDGET_FIXED, KVM_BUDGET_SQRT, KVM_BUDGET_TABLE = 0, 1, 2, 3
 KVM_OK, KVM_ERR_ARG, KVM_ERR_CAPACITY, KVM_ERR_STATE, KVM_ERR_HIP, KVM_ERR_UNSUPPORTED = 0, -1, -2, -3, -4, -5
+KVM_ERR_LIMIT = -6
+KVM_STATIC_MAX_SEQUENCES = 4096
 
 EXPORTS = [
     "kvm_strerror", "kvm_last_hip_error", "kvm_state_rows_for", "kvm_state_bytes", "kvm_state_init",
     "kvm_state_destroy", "kvm_prefill_chunked", "kvm_decode_step", "kvm_decode_multi_workspace_bytes",
-    "kvm_decode_step_multi", "kvm_state_fold", "kvm_state_rows",
+    "kvm_decode_step_multi", "kvm_decode_step_multi_static", "kvm_state_fold", "kvm_state_rows",
     "kvm_state_tokens", "kvm_state_capacity", "kvm_state_folds", "kvm_state_trace", "kvm_state_grow",
     "kvm_state_export", "kvm_state_import", "kvm_state_profile", "kvm_state_profile_read",
     "kvm_measure_mfma_bf16_peak", "kvm_measure_copy_peak", "kvm_prepare_scratch_bytes", "kvm_prepare_qkv",
@@ -95,6 +97,7 @@ def load_library() -> C.CDLL:
     lib.kvm_decode_multi_workspace_bytes.restype = C.c_size_t
     lib.kvm_decode_multi_workspace_bytes.argtypes = [i64]
     lib.kvm_decode_step_multi.argtypes = [C.POINTER(vp), i32, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+    lib.kvm_decode_step_multi_static.argtypes = [C.POINTER(vp), i32, vp, vp, vp, vp, vp, vp]
     lib.kvm_state_fold.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp, vp]
     for name in ("kvm_state_rows", "kvm_state_tokens", "kvm_state_capacity", "kvm_state_folds"):
         getattr(lib, name).argtypes = [vp, C.POINTER(i64)]
@@ -120,7 +123,7 @@ def _check(status: int, what: str) -> None:
     if status != KVM_OK:
         lib = load_library()
         msg = lib.kvm_strerror(status).decode()
-        if status == KVM_ERR_HIP:
+        if status in (KVM_ERR_HIP, KVM_ERR_LIMIT):
             msg += " (" + lib.kvm_last_hip_error().decode() + ")"
         raise KVMError(status, f"{what}: {msg}")
 
@@ -489,3 +492,23 @@ def decode_multi(states, q, k, v, gate=None, out=None):
                "kvm_decode_step_multi")
     return out
 
+
+
+def decode_multi_static(states, q, k, v, gate=None, *, out):
+    """kvm_decode_step_multi_static: decode_multi without a workspace and without any allocation
+    (here neither: the caller passes `out`)."""
+    first = states[0]
+    c = first.cfg
+    n = sum(st.cfg.batch for st in states)
+    first._chk(q, (n, c.n_q_heads, c.head_dim), first.dtype, "q")
+    first._chk(k, (n, c.n_kv_heads, c.head_dim), first.dtype, "k")
+    first._chk(v, (n, c.n_kv_heads, c.head_dim), first.dtype, "v")
+    if gate is not None:
+        first._chk(gate, (n, c.n_kv_heads), torch.float32, "gate")
+    first._chk(out, q.shape, first.dtype, "out")
+    handles = (C.c_void_p * len(states))(*[st.handle for st in states])
+    with torch.cuda.device(first.device):
+        _check(first.lib.kvm_decode_step_multi_static(handles, len(states), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                                                      _ptr(gate), out.data_ptr(), _stream()),
+               "kvm_decode_step_multi_static")
+    return out

@@ -6,6 +6,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -454,6 +455,72 @@ struct ProfileSpan {
   }
 };
 
+// ---------------------------------------------------------------------------------------------
+// Allocation-free ragged decode (kvm_decode_step_multi_static): the per-sequence descriptor table
+// that kvm_decode_step_multi keeps in a caller workspace lives in this file-scope device array
+// instead, one copy per GPU, held until the process ends.  Host code never uses the array's name
+// as an address: scratch_on_device() asks the runtime for the array's address on the current
+// device once and keeps it.
+constexpr int kStaticMaxSeq = 4096;   // sequences per call
+constexpr int kStaticMaxDev = 64;     // devices a process can hold
+static __device__ __align__(256) unsigned char scratch[kStaticMaxSeq * sizeof(kvm::SeqDesc)];
+
+struct ScratchPtrs {
+  void *ptr[kStaticMaxDev] = {};
+  bool known[kStaticMaxDev] = {};
+};
+ScratchPtrs g_scratch;
+std::mutex g_scratch_mutex;
+
+// Address of `scratch` on the device that is current for the calling thread.
+int scratch_on_device(void **out) {
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kStaticMaxDev) return KVM_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch.known[dev]) {
+    void *p = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return KVM_ERR_HIP;
+    g_scratch.ptr[dev] = p;
+    g_scratch.known[dev] = true;
+  }
+  *out = g_scratch.ptr[dev];
+  return KVM_OK;
+}
+
+// Up to kPackStates states' worth of descriptors per launch, handed over as a kernel argument
+// (no host-to-device copy, no host buffer): per state where its arrays start and where it stands;
+// thread i of the launch writes the descriptor of sequence pack.seq0[0] + i.
+constexpr int kPackStates = 32;
+struct StatePack {
+  const void *khat[kPackStates], *vhat[kPackStates];  // current readout version, first unit
+  void *winK[kPackStates], *winV[kPackStates];
+  float *winG[kPackStates];
+  int64_t pos[kPackStates];
+  int32_t m[kPackStates], Mcap[kPackStates];
+  int32_t seq0[kPackStates + 1];  // first sequence of each state; [n] = one past the last
+  int32_t n;
+};
+__global__ __launch_bounds__(256) void seqdesc_fill_kernel(StatePack pk, kvm::SeqDesc *table, int Hkv, int L, int d,
+                                                           int es) {
+  const int s = pk.seq0[0] + blockIdx.x * blockDim.x + threadIdx.x;
+  if (s >= pk.seq0[pk.n]) return;
+  int i = 0;
+  while (i + 1 < pk.n && s >= pk.seq0[i + 1]) ++i;
+  const int64_t u0 = (int64_t)(s - pk.seq0[i]) * Hkv;  // the sequence's first unit within its state
+  kvm::SeqDesc sd;
+  sd.khat = (const char *)pk.khat[i] + u0 * pk.Mcap[i] * d * es;
+  sd.vhat = (const char *)pk.vhat[i] + u0 * pk.Mcap[i] * d * es;
+  sd.winK = (char *)pk.winK[i] + u0 * L * d * es;
+  sd.winV = (char *)pk.winV[i] + u0 * L * d * es;
+  sd.winG = pk.winG[i] + u0 * L;
+  sd.pos = pk.pos[i];
+  sd.m = pk.m[i];
+  sd.Mcap = pk.Mcap[i];
+  table[s] = sd;
+}
+
 }  // namespace
 
 extern "C" {
@@ -466,6 +533,7 @@ const char *kvm_strerror(int status) {
     case KVM_ERR_STATE: return "call not valid at the state's current position";
     case KVM_ERR_HIP: return "HIP runtime error";
     case KVM_ERR_UNSUPPORTED: return "unsupported shape or dtype";
+    case KVM_ERR_LIMIT: return "beyond the fixed size of an allocation-free entry point's static buffer";
     default: return "unknown status";
   }
 }
@@ -962,6 +1030,92 @@ int kvm_decode_step_multi(kvm_state *const *states, int32_t n_states, const void
     ProfileSpan span(states[0], 2, stream);
     HIP_TRY(kvm::launch_decode_multi(first->dv, (const kvm::SeqDesc *)workspace, (int)n_seq, q, k, v, gate, out,
                                      stream));
+  }
+  for (int i = 0; i < n_states; ++i) {
+    kvm_state *st = states[i];
+    const int64_t u = st->tokens;
+    st->tokens = u + 1;
+    if ((u + 1) % C == 0 && u + 1 >= L) {
+      const int64_t lo = u + 1 - L;
+      ProfileSpan span(st, 1, stream);
+      int rc = fold_block(st, advance(ring_src(st), lo % L, es), u + 1, nullptr, nullptr, stream, true);
+      if (rc != KVM_OK) return rc;
+    }
+  }
+  return KVM_OK;
+}
+
+int kvm_decode_step_multi_static(kvm_state *const *states, int32_t n_states, const void *q, const void *k,
+                                 const void *v, const float *gate, void *out, void *stream_) {
+  if (!states || n_states <= 0 || !q || !k || !v || !out) return KVM_ERR_ARG;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return KVM_ERR_ARG;
+  hipStream_t stream = (hipStream_t)stream_;
+  const kvm_state *first = states[0];
+  if (!first) return KVM_ERR_ARG;
+  const kvm_config &c0 = first->cfg;
+  int64_t n_seq = 0;
+  for (int i = 0; i < n_states; ++i) {
+    const kvm_state *st = states[i];
+    if (!st) return KVM_ERR_ARG;
+    for (int j = 0; j < i; ++j)
+      if (states[j] == st) return KVM_ERR_ARG;  // a state takes one token per step
+    const kvm_config &c = st->cfg;
+    if (c.n_q_heads != c0.n_q_heads || c.n_kv_heads != c0.n_kv_heads || c.head_dim != c0.head_dim ||
+        c.io_dtype != c0.io_dtype || c.chunk_len != c0.chunk_len || c.n_bswa_chunks != c0.n_bswa_chunks ||
+        c.n_sink != c0.n_sink || c.rope_dims != c0.rope_dims || c.tau_state != c0.tau_state ||
+        c.tau_bswa != c0.tau_bswa)
+      return KVM_ERR_ARG;
+    n_seq += st->dv.B;
+  }
+  if (n_seq > kStaticMaxSeq) {
+    g_hip_error = "kvm_decode_step_multi_static: " + std::to_string(n_seq) + " sequences, the static table holds " +
+                  std::to_string(kStaticMaxSeq);
+    return KVM_ERR_LIMIT;
+  }
+  const int64_t C = first->dv.C, L = first->dv.L, d = first->dv.d;
+  const size_t es = esize(c0.io_dtype);
+  for (int i = 0; i < n_states; ++i) {
+    const kvm_state *st = states[i];
+    const int64_t u = st->tokens;
+    if ((u + 1) % C == 0 && u + 1 >= L && rows_after(st->cfg, st->table, st->m, u + 1) > st->dv.Mcap)
+      return KVM_ERR_CAPACITY;
+  }
+  void *table = nullptr;
+  {
+    const int rc = scratch_on_device(&table);
+    if (rc != KVM_OK) return rc;
+  }
+  // the descriptor table, kPackStates states per launch
+  for (int i0 = 0, seq0 = 0; i0 < n_states; i0 += kPackStates) {
+    StatePack pk;
+    pk.n = n_states - i0 < kPackStates ? n_states - i0 : kPackStates;
+    int sq = seq0;
+    for (int i = 0; i < pk.n; ++i) {
+      const kvm_state *st = states[i0 + i];
+      const Dev &dv = st->dv;
+      const int64_t slot = slot_of(st, st->folds);
+      pk.khat[i] = (const char *)dv.khat + slot * dv.slot_elems * (int64_t)es;
+      pk.vhat[i] = (const char *)dv.vhat + slot * dv.slot_elems * (int64_t)es;
+      pk.winK[i] = dv.winK;
+      pk.winV[i] = dv.winV;
+      pk.winG[i] = dv.winG;
+      pk.pos[i] = st->tokens;
+      pk.m[i] = (int32_t)st->m;
+      pk.Mcap[i] = dv.Mcap;
+      pk.seq0[i] = sq;
+      sq += dv.B;
+    }
+    pk.seq0[pk.n] = sq;
+    for (int i = pk.n + 1; i <= kPackStates; ++i) pk.seq0[i] = sq;
+    const int n_here = sq - seq0;
+    hipLaunchKernelGGL(seqdesc_fill_kernel, dim3((n_here + 255) / 256), dim3(256), 0, stream, pk,
+                       (kvm::SeqDesc *)table, (int)first->dv.Hkv, (int)L, (int)d, (int)es);
+    HIP_TRY(hipGetLastError());
+    seq0 = sq;
+  }
+  {
+    ProfileSpan span(states[0], 2, stream);
+    HIP_TRY(kvm::launch_decode_multi(first->dv, (const kvm::SeqDesc *)table, (int)n_seq, q, k, v, gate, out, stream));
   }
   for (int i = 0; i < n_states; ++i) {
     kvm_state *st = states[i];
