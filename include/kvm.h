@@ -71,8 +71,8 @@ typedef struct kvm_config {
   int64_t budget_table_len;
   float ln_eps;            /* LN_s epsilon; 0 selects 1e-5 */
   float norm_eps;          /* eps_norm of the value readout; 0 selects 1e-12 */
-  const float *ln_gamma;   /* device [H_kv, d] or NULL => 1 */
-  const float *ln_beta;    /* device [H_kv, d] or NULL => 0 */
+  const float *ln_gamma;   /* device [H_kv, d], 16-byte aligned, or NULL => 1 */
+  const float *ln_beta;    /* device [H_kv, d], 16-byte aligned, or NULL => 0 */
   const float *tau_state;  /* device [H_q] or NULL => 1 ("Readout": per-head inverse temperatures) */
   const float *tau_bswa;   /* device [H_q] or NULL => 1 */
 } kvm_config;
@@ -236,6 +236,21 @@ int kvm_state_import(kvm_state *st, const double *sK, const float *sV, const flo
                      const float *w, const int32_t *n, const void *win_k, const void *win_v,
                      const float *win_g, int64_t m, int64_t tokens_seen, int64_t folds,
                      void *stream);
+
+/* Choices the library normally makes by itself, forced for tests and comparisons (no passage of
+ * the paper).  value 0 gives the choice back to the library.  Takes effect from the next call on.
+ *   KVM_DEBUG_FOLD_PATH         1: a run of folds is one launch, one workgroup per unit (bf16,
+ *                               head_dim 128; the default there), 2: one kernel per fold step
+ *   KVM_DEBUG_FOLD_WAVES        8 or 16: wavefronts of a fold workgroup on the one-launch path
+ *   KVM_DEBUG_PREFILL_SCHEDULE  1: chunk by chunk on the caller's stream, folds in place,
+ *                               2: folds ahead on the library's stream, attention in groups
+ *   KVM_DEBUG_FOLD_CHAINS       1 or 2: fold chains side by side (kernel-per-step path)
+ *   KVM_DEBUG_MERGE_COPY        1 / 2: token-centred merge with row copies on / off (same path)
+ *   KVM_DEBUG_BACKWARD_PATH     1: attention adjoints on the vector ALU on every shape (it also
+ *                               sizes kvm_backward_workspace_bytes: set it before asking) */
+enum { KVM_DEBUG_FOLD_PATH = 0, KVM_DEBUG_FOLD_WAVES = 1, KVM_DEBUG_PREFILL_SCHEDULE = 2, KVM_DEBUG_FOLD_CHAINS = 3,
+       KVM_DEBUG_MERGE_COPY = 4, KVM_DEBUG_BACKWARD_PATH = 5, KVM_DEBUG_KNOBS = 8 };
+int kvm_debug_set(kvm_state *st, int knob, int value);
 
 /* Kernel timing for benchmarks (no passage of the paper: a measurement aid).  While enabled,
  * every attention launch and every fold of this state is bracketed by HIP events recorded on

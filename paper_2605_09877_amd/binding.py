@@ -27,8 +27,10 @@ EXPORTS = [
     "kvm_state_tokens", "kvm_state_capacity", "kvm_state_folds", "kvm_state_trace", "kvm_state_grow",
     "kvm_state_export", "kvm_state_import", "kvm_state_profile", "kvm_state_profile_read",
     "kvm_measure_mfma_bf16_peak", "kvm_measure_copy_peak", "kvm_prepare_scratch_bytes", "kvm_prepare_qkv",
-    "kvm_backward_workspace_bytes", "kvm_prefill_backward",
+    "kvm_backward_workspace_bytes", "kvm_prefill_backward", "kvm_debug_set",
 ]
+(KVM_DEBUG_FOLD_PATH, KVM_DEBUG_FOLD_WAVES, KVM_DEBUG_PREFILL_SCHEDULE, KVM_DEBUG_FOLD_CHAINS, KVM_DEBUG_MERGE_COPY,
+ KVM_DEBUG_BACKWARD_PATH) = range(6)
 
 
 class kvm_config(C.Structure):
@@ -105,6 +107,7 @@ def load_library() -> C.CDLL:
     lib.kvm_state_grow.argtypes = [vp, vp, C.c_size_t, i64, vp]
     lib.kvm_state_export.argtypes = [vp] * 12
     lib.kvm_state_import.argtypes = [vp] * 9 + [i64, i64, i64, vp]
+    lib.kvm_debug_set.argtypes = [vp, C.c_int, C.c_int]
     lib.kvm_state_profile.argtypes = [vp, C.c_int]
     lib.kvm_state_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
     lib.kvm_prepare_scratch_bytes.restype = C.c_size_t
@@ -359,6 +362,10 @@ class KVMState:
     def reset(self) -> None:
         """Back to the empty state (m = 0, no tokens seen) in the same buffer; no device work."""
         _check(self.lib.kvm_state_import(self.handle, *([None] * 8), 0, 0, 0, None), "kvm_state_import")
+
+    def debug_set(self, knob: int, value: int) -> None:
+        """kvm_debug_set: force one of the library's own choices (0 gives it back)."""
+        _check(self.lib.kvm_debug_set(self.handle, knob, value), "kvm_debug_set")
 
     def profile(self, enable) -> None:
         """kvm_state_profile: False/0 off, True/1 on, 2 on with folds and attention kept apart."""

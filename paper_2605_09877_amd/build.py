@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libkvm.so")
-SOURCES = ["kvm_api.hip", "fold.hip", "score_mfma.hip", "attn_rows.hip", "attn_mfma.hip", "peaks.hip", "prep.hip", "backward.hip", "backward_mfma.hip"]
+SOURCES = ["kvm_api.hip", "fold.hip", "fold_fused.hip", "score_mfma.hip", "attn_rows.hip", "attn_mfma.hip", "peaks.hip", "prep.hip", "backward.hip", "backward_mfma.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17",
          # packed fp32 VALU forms are kept out of the generated code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

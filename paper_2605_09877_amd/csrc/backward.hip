@@ -594,11 +594,7 @@ hipError_t zero_fill(void *p, size_t bytes, hipStream_t st) {
 hipError_t run_backward(const Bwd &a_in, const BwdChunk *chunks, int n_chunks, hipStream_t st, const BwdStreams &x) {
   const Dev &dv = a_in.dv;
   const int G = dv.Hq / dv.Hkv, D = dv.d;
-  static const bool no_mfma = [] {
-    const char *e = getenv("KVM_BACKWARD_GENERIC");  // "1": the vector-ALU kernels everywhere (comparisons)
-    return e && e[0] == '1';
-  }();
-  const bool on_mfma = backward_on_mfma(dv) && !no_mfma;
+  const bool on_mfma = a_in.on_mfma;  // decided once by the caller, who sized the workspace by it
   Bwd a = a_in;
   // On the matrix-core path a token's dk, dv are finished when its block has been the window keys
   // of a launch; until then only what the token got when its fold was undone is kept, for the

@@ -639,7 +639,7 @@ __global__ __launch_bounds__(256, 2) void bwd_mfma_kernel(Bwd a, MfmaChunk c) {
 
 }  // namespace
 
-bool backward_on_mfma(const Dev &dv) { return dv.io == 1 && dv.d == kHeadDim; }
+bool backward_on_mfma(const Dev &dv) { return dv.io == 1 && dv.d == kHeadDim && dv.C % 64 == 0; }
 
 // The three launches of one chunk: dq (and the temperature sums), dk, dv (or the readout's adjoint).
 hipError_t launch_backward_mfma(const Bwd &a, int64_t cs, int nq, int m, bool folded, int role, int section,

@@ -29,6 +29,9 @@ struct kvm_state {
   float *trace_score = nullptr;
   int64_t trace_max = 0;
   bool mfma = false;  // bf16, d = 128, C % 64 == 0: matrix-core kernels
+  bool fused = false; // folds run as one launch per run of folds (fold_fused.hip)
+  // kvm_debug_set knobs (0 = the library's own choice)
+  int dbg[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   int group = 1;      // chunks per attention launch in prefill; the readout has 2 * group slots
   // prefill pipeline: folds run ahead on a library-owned stream, attention follows in groups
   int64_t inplace = 0;  // folds done in place so far: version v lives in slot (v - inplace) mod NS
@@ -313,11 +316,8 @@ int fold_launches(const kvm_state *st, Dev dv, const Src &src, int64_t m, int64_
       else
         HIP_TRY(kvm::launch_score(dv, sn, (int)m, (int)m_after, false, stream));
     }
-    static const int merge_copy_forced = [] {
-      const char *e = getenv("KVM_MERGE_COPY");  // "0" / "1": for comparisons
-      return e ? (e[0] == '1' ? 1 : 0) : -1;
-    }();
-    const bool small = merge_copy_forced >= 0 ? merge_copy_forced == 1 : (int64_t)dv.Ufull * m_after < 64 * 1024;
+    const int mc = st->dbg[KVM_DEBUG_MERGE_COPY];  // 1 / 2 force it on / off: for comparisons
+    const bool small = mc ? mc == 1 : (int64_t)dv.Ufull * m_after < 64 * 1024;
     if (in_place)
       HIP_TRY(kvm::launch_merge_inplace(dv, src, n_app > 0, sn, stream));
     else if (small)
@@ -340,6 +340,20 @@ int fold_trace(const kvm_state *st, const Dev &dv, int64_t u0, int64_t fold, hip
   return KVM_OK;
 }
 
+// The fused path: one launch per run of folds (bf16, d = 128 states whose tables fit LDS), unless
+// kvm_debug_set asked for the kernel-per-step path.
+bool use_fused(const kvm_state *st) { return st->fused && st->dbg[KVM_DEBUG_FOLD_PATH] != 2; }
+int fused_waves(const kvm_state *st) { return st->dbg[KVM_DEBUG_FOLD_WAVES] == 16 ? 16 : 8; }
+kvm::FoldRunArgs fused_run(const kvm_state *st, bool in_place) {
+  kvm::FoldRunArgs run;
+  run.n = 0;
+  run.in_place = in_place ? 1 : 0;
+  run.trace_assign = st->trace_assign;
+  run.trace_score = st->trace_score;
+  run.trace_stride = (int64_t)st->dv.U * st->dv.C;
+  return run;
+}
+
 int fold_block(kvm_state *st, const Src &src, int64_t e, int32_t *assign_out, float *score_out,
                hipStream_t stream, bool in_place, int kbar_block = -1) {
   const kvm_config &c = st->cfg;
@@ -349,19 +363,26 @@ int fold_block(kvm_state *st, const Src &src, int64_t e, int32_t *assign_out, fl
   if (m_after > st->dv.Mcap) return KVM_ERR_CAPACITY;
   const Dev &dv = st->dv;
   const int so = slot_of(st, st->folds), sn = in_place ? so : slot_of(st, st->folds + 1);
-  int rc = fold_launches(st, dv, src, m, m_after, so, sn, in_place, kbar_block, stream);
-  if (rc != KVM_OK) return rc;
   const size_t ntok = (size_t)dv.U * dv.C;
+  if (use_fused(st)) {
+    kvm::FoldRunArgs run = fused_run(st, in_place);
+    run.n = 1;
+    run.s[0] = {(int32_t)m, (int32_t)m_after, so, sn, 0, st->folds < st->trace_max ? st->folds : -1};
+    HIP_TRY(kvm::launch_fold_fused(dv, src, run, fused_waves(st), stream));
+  } else {
+    int rc = fold_launches(st, dv, src, m, m_after, so, sn, in_place, kbar_block, stream);
+    if (rc != KVM_OK) return rc;
+    if (st->trace_assign && st->folds < st->trace_max)
+      HIP_TRY(hipMemcpyAsync(st->trace_assign + st->folds * ntok, dv.pi, ntok * 4,
+                             hipMemcpyDeviceToDevice, stream));
+    if (st->trace_score && st->folds < st->trace_max)
+      HIP_TRY(hipMemcpyAsync(st->trace_score + st->folds * ntok * 2, dv.score, ntok * 8,
+                             hipMemcpyDeviceToDevice, stream));
+  }
   if (assign_out)
     HIP_TRY(hipMemcpyAsync(assign_out, dv.pi, ntok * 4, hipMemcpyDeviceToDevice, stream));
   if (score_out)
     HIP_TRY(hipMemcpyAsync(score_out, dv.score, ntok * 8, hipMemcpyDeviceToDevice, stream));
-  if (st->trace_assign && st->folds < st->trace_max)
-    HIP_TRY(hipMemcpyAsync(st->trace_assign + st->folds * ntok, dv.pi, ntok * 4,
-                           hipMemcpyDeviceToDevice, stream));
-  if (st->trace_score && st->folds < st->trace_max)
-    HIP_TRY(hipMemcpyAsync(st->trace_score + st->folds * ntok * 2, dv.score, ntok * 8,
-                           hipMemcpyDeviceToDevice, stream));
   st->m = m_after;
   st->folds += 1;
   if (in_place) st->inplace += 1;
@@ -384,7 +405,9 @@ hipError_t next_sync_event(kvm_state *st, hipEvent_t *out) {
 struct BwdLayout {
   size_t wsK, wsV, dsK, dsV, drho, khat, vhat, xhat, rden, dkhat, dvhat, dk_acc, dv_acc, delta, P, dS, par64, total;
 };
-BwdLayout bwd_layout(const kvm_config &c, int64_t Mcap, int64_t T) {
+// mfma_path: the attention adjoints run on the matrix cores (bwd_on_mfma); that one flag decides
+// the layout here and the launches in run_backward alike.
+BwdLayout bwd_layout(const kvm_config &c, int64_t Mcap, int64_t T, bool mfma_path) {
   const size_t U = (size_t)c.batch * c.n_kv_heads, d = c.head_dim, C = c.chunk_len;
   const size_t L = C * c.n_bswa_chunks, es = esize(c.io_dtype), M = (size_t)Mcap;
   const size_t G = c.n_q_heads / c.n_kv_heads, Tn = (size_t)T;
@@ -408,14 +431,11 @@ BwdLayout bwd_layout(const kvm_config &c, int64_t Mcap, int64_t T) {
   l.dvhat = take(U * M * d * 4);
   // full-size accumulators of dk, dv on the vector-ALU path; on the matrix-core path a ring of
   // one window's blocks and one more (see kvm::Bwd)
-  const char *env_g = getenv("KVM_BACKWARD_GENERIC");
-  const bool mfma_path = c.io_dtype == KVM_BF16 && c.head_dim == 128 && !(env_g && env_g[0] == '1');
   l.dk_acc = take(U * (mfma_path ? L + C : Tn) * d * 4);
   l.dv_acc = take(U * (mfma_path ? L + C : Tn) * d * 4);
   l.delta = take((size_t)c.batch * Tn * c.n_q_heads * 4);
   // the chunk's probabilities and logit adjoints are written out only by the vector-ALU kernels
-  const char *env = getenv("KVM_BACKWARD_GENERIC");
-  const bool probs = !(c.io_dtype == KVM_BF16 && c.head_dim == 128) || (env && env[0] == '1');
+  const bool probs = !mfma_path;
   l.P = take(probs ? U * G * C * (M + L) * 4 : 0);
   l.dS = take(probs ? U * G * C * (M + L) * 4 : 0);
   l.par64 = take((2 * (size_t)c.n_kv_heads * d + 2 * (size_t)c.n_q_heads) * 8);
@@ -424,6 +444,12 @@ BwdLayout bwd_layout(const kvm_config &c, int64_t Mcap, int64_t T) {
 }
 
 bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+
+// The backward's attention adjoints run on the matrix cores for the shapes those kernels are
+// written and tested for, unless kvm_debug_set asked for the vector-ALU kernels.
+bool bwd_on_mfma(const kvm_state *st) {
+  return kvm::backward_on_mfma(st->dv) && st->dbg[KVM_DEBUG_BACKWARD_PATH] != 1;
+}
 
 // RAII bracket: records a start event now and a stop event when it goes out of scope.
 struct ProfileSpan {
@@ -554,6 +580,7 @@ int kvm_state_init(kvm_state **out, const kvm_config *cfg, void *dev_buf, size_t
                    int64_t max_tokens) {
   if (!out || !config_ok(cfg) || !dev_buf || max_tokens < 0) return KVM_ERR_ARG;
   if (((uintptr_t)dev_buf & 255) != 0) return KVM_ERR_ARG;
+  if (!aligned16(cfg->ln_gamma) || !aligned16(cfg->ln_beta)) return KVM_ERR_ARG;
   std::vector<int64_t> table = table_of(cfg);
   const int64_t Mcap = capacity_rows(*cfg, table, max_tokens);
   if (layout_of(*cfg, Mcap).total > bytes) return KVM_ERR_CAPACITY;
@@ -566,6 +593,7 @@ int kvm_state_init(kvm_state **out, const kvm_config *cfg, void *dev_buf, size_t
   st->bytes = bytes;
   bind(st->dv, st->cfg, dev_buf, Mcap);
   st->mfma = use_mfma(*cfg);
+  st->fused = st->mfma && kvm::fold_fused_fits(st->dv);
   st->group = group_of(*cfg);
   *out = st;
   return KVM_OK;
@@ -583,6 +611,12 @@ int kvm_state_destroy(kvm_state *st) {
       if (fs) (void)hipStreamDestroy(fs);
   }
   delete st;
+  return KVM_OK;
+}
+
+int kvm_debug_set(kvm_state *st, int knob, int value) {
+  if (!st || knob < 0 || knob >= KVM_DEBUG_KNOBS || value < 0) return KVM_ERR_ARG;
+  st->dbg[knob] = value;
   return KVM_OK;
 }
 
@@ -691,12 +725,9 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
     int64_t m_max = 0;
     for (const Chunk &ch : plan) m_max = ch.m > m_max ? ch.m : m_max;
     const double copy_us = (double)dv.U * (double)m_max * (double)d * (double)es * 4.0 / 4.0e6;  // at ~4 TB/s
-    static const int forced = [] {
-      const char *e = getenv("KVM_PREFILL_SERIAL");  // "0" / "1": for comparisons
-      return e ? (e[0] == '1' ? 1 : 0) : -1;
-    }();
+    const int forced = st->dbg[KVM_DEBUG_PREFILL_SCHEDULE];  // 1 serial, 2 pipelined: for comparisons
     // (and a call of a few chunks has nothing to pipeline: the events would cost more than they buy)
-    const bool serial = forced >= 0 ? forced == 1 : (copy_us > 45.0 || plan.size() <= 4);
+    const bool serial = forced ? forced == 1 : (copy_us > 45.0 || plan.size() <= 4);
     if (serial) {
       for (const Chunk &ch : plan) {
         AttnArgs a;
@@ -752,11 +783,9 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
     for (const Chunk &ch : plan) m_max = ch.m > m_max ? ch.m : m_max;
     const double fold_mb = (double)dv.U * ((double)m_max * d * es * 5.0 + (double)C * d * es * 4.0) / 1.0e6;
     if (fold_mb < 96.0 && dv.B % 2 == 0) n_chains = 2;
-    static const int forced = [] {
-      const char *e = getenv("KVM_FOLD_CHAINS");  // 1 or 2: for comparisons
-      return e ? atoi(e) : 0;
-    }();
+    const int forced = st->dbg[KVM_DEBUG_FOLD_CHAINS];  // 1 or 2: for comparisons
     if ((forced == 1 || forced == 2) && dv.B % forced == 0) n_chains = forced;
+    if (use_fused(st)) n_chains = 1;  // one workgroup per unit already: nothing to split
   }
   hipStream_t fstream[kvm_state::kMaxChains];
   Dev cdv[kvm_state::kMaxChains];
@@ -836,6 +865,19 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
           m = steps[i].m_after;
         }
       }
+      if (use_fused(st)) {
+        ProfileSpan span(st, 1, fstream[0], run);
+        kvm::FoldRunArgs fr = fused_run(st, false);
+        fr.n = run;
+        for (int i = 0; i < run; ++i) {
+          const int64_t lo = plan[next_fold + i].s + C - L;
+          const int64_t fold_no = st->folds + i;
+          fr.s[i] = {(int32_t)steps[i].m, (int32_t)steps[i].m_after, steps[i].so, steps[i].sn,
+                     batched ? lo - lo0 : 0, fold_no < st->trace_max ? fold_no : -1};
+        }
+        HIP_TRY(kvm::launch_fold_fused(dv, batched ? advance(in, lo0 - t0, es) : advance(ring, lo0 % L, es), fr,
+                                       fused_waves(st), fstream[0]));
+      } else
       for (int c2 = 0; c2 < n_chains; ++c2) {
         // the timing bracket goes on the first chain only (the chains run side by side)
         ProfileSpan span(c2 == 0 ? st : nullptr, 1, fstream[c2], run);
@@ -1152,7 +1194,7 @@ int kvm_state_fold(kvm_state *st, const void *k_blk, const void *v_blk, const fl
 
 size_t kvm_backward_workspace_bytes(const kvm_state *st, int64_t T) {
   if (!st || T <= 0) return 0;
-  return bwd_layout(st->cfg, st->dv.Mcap, T).total;
+  return bwd_layout(st->cfg, st->dv.Mcap, T, bwd_on_mfma(st)).total;
 }
 
 int kvm_prefill_backward(kvm_state *st, const void *q, const void *k, const void *v, const float *gate,
@@ -1184,13 +1226,15 @@ int kvm_prefill_backward(kvm_state *st, const void *q, const void *k, const void
   }
   if (st->tokens != T || st->folds != folds || st->m != m) return KVM_ERR_STATE;
   if (folds > 0 && (!assign || !score)) return KVM_ERR_ARG;
-  const BwdLayout l = bwd_layout(c, st->dv.Mcap, T);
+  const bool on_mfma = bwd_on_mfma(st);
+  const BwdLayout l = bwd_layout(c, st->dv.Mcap, T, on_mfma);
   if (workspace_bytes < l.total || ((uintptr_t)workspace & 255)) return KVM_ERR_ARG;
   const void *ptrs[] = {q, k, v, out, dout, grads->dq, grads->dk, grads->dv};
   for (const void *p : ptrs)
     if (!aligned16(p)) return KVM_ERR_ARG;
   kvm::Bwd a;
   a.dv = st->dv;
+  a.on_mfma = on_mfma;
   a.T = T;
   a.q = q; a.k = k; a.v = v; a.out = out; a.dout = dout;
   a.gate = gate; a.lse = lse; a.assign = assign; a.score = score;
@@ -1209,7 +1253,7 @@ int kvm_prefill_backward(kvm_state *st, const void *q, const void *k, const void
   a.P = (float *)(w + l.P); a.dS = (float *)(w + l.dS);
   a.par64 = (double *)(w + l.par64);
   kvm::BwdStreams x;
-  if (kvm::backward_on_mfma(st->dv)) {
+  if (on_mfma) {
     for (hipStream_t &fs : st->fold_streams)
       if (!fs) HIP_TRY(hipStreamCreateWithFlags(&fs, hipStreamNonBlocking));
     x.side = st->fold_streams[0];

@@ -87,6 +87,27 @@ hipError_t launch_merge_inplace(const Dev &dv, const Src &src, bool check_app, i
 hipError_t launch_refresh(const Dev &dv, int m, int slot, hipStream_t st);
 hipError_t launch_ring_copy(const Dev &dv, const Src &src, int64_t src_t0, int64_t p0, int64_t p1,
                             hipStream_t st);
+// fold_fused.hip (bf16, d = 128): a run of up to kFoldMaxSteps consecutive folds in one launch,
+// one workgroup per unit.  Step i folds the block whose first token is src's token s[i].tok, from
+// s[i].m to s[i].m_after rows, reading readout slot s[i].so and writing slot s[i].sn (the same slot
+// when in_place; otherwise untouched rows are copied over).  trace >= 0: the fold's assignments
+// and scores also go to trace_assign / trace_score at that fold index (trace_stride = tokens of
+// one fold over all units).
+constexpr int kFoldMaxSteps = 8;
+struct FoldStep {
+  int32_t m, m_after, so, sn;
+  int64_t tok;
+  int64_t trace;
+};
+struct FoldRunArgs {
+  int32_t n, in_place;
+  FoldStep s[kFoldMaxSteps];
+  int32_t *trace_assign;
+  float *trace_score;
+  int64_t trace_stride;
+};
+bool fold_fused_fits(const Dev &dv);
+hipError_t launch_fold_fused(const Dev &dv, const Src &src, const FoldRunArgs &run, int n_waves, hipStream_t st);
 // score_mfma.hip (bf16, d = 128)
 hipError_t launch_score_mfma(const Dev &dv, int slot, int row0, int row1, bool first_pass, hipStream_t st);
 // attn_rows.hip
@@ -111,6 +132,7 @@ hipError_t launch_attn_mfma(const Dev &dv, const AttnArgs &a, hipStream_t st);
 // capacity (Mcap rows per unit).
 struct Bwd {
   Dev dv;  // dimensions, parameters and the final sums (sK, sV, rho) of the state after the forward
+  bool on_mfma;  // attention adjoints on the matrix cores (decides the workspace layout and the launches)
   int64_t T;
   const void *q, *k, *v, *out, *dout;
   const float *gate, *lse;

@@ -447,3 +447,43 @@ def test_f32_strided_operands_generic_path():
     w = synth().shrink(synth().WORKLOADS["tiny_f32"], batch=2, seq=640 + 23)
     ties, st = run_prefill_case(w, plain=False, split=256, widen=_widened)
     assert ties.total == 0
+
+
+# ----------------------------------------------------------------------------- the two fold paths
+@pytest.mark.parametrize("waves", [8, 16])
+@pytest.mark.parametrize("shape", ["fixed", "sqrt", "gqa"])
+def test_fold_paths_agree(shape, waves):
+    """bf16 / d = 128 states fold with one launch per run of folds (one workgroup per unit); the
+    kernel-per-step path they can be switched to (kvm_debug_set) must take the same decisions:
+    assignments, row counts and key sums equal to the bit (both score with the same matrix-core
+    arithmetic and add exact products in fp64), value sums to the bit too (same adds in the same
+    order); radii and the value readout may differ in the last fp32 bit (sums over a row's
+    channels are taken in another order), outputs accordingly."""
+    pkg, sy = kvm(), synth()
+    from paper_2605_09877_amd import binding
+    w = {"fixed": sy.shrink(sy.WORKLOADS["prefill_fixed"], batch=2, n_q_heads=2, n_kv_heads=2, seq=3072 + 77),
+         "sqrt": sy.shrink(sy.WORKLOADS["prefill_sqrt"], batch=1, n_q_heads=2, n_kv_heads=2, seq=6144),
+         "gqa": sy.shrink(sy.WORKLOADS["prefill_gqa_32k"], batch=1, n_q_heads=8, n_kv_heads=2, seq=4096 + 512)}[shape]
+    q, k, v = sy.make_qkv(w, DEV)
+    params = sy.make_params(w, DEV, plain=False)
+    res = []
+    for path in (1, 2):
+        st = pkg.state_for(w, device=DEV, **params)
+        st.debug_set(binding.KVM_DEBUG_FOLD_PATH, path)
+        st.debug_set(binding.KVM_DEBUG_FOLD_WAVES, waves)
+        assign, score = st.trace(w.seq // w.chunk_len + 1)
+        y = st.prefill(q, k, v, params["gate"])
+        torch.cuda.synchronize()
+        res.append((y, assign[:st.folds].clone(), score[:st.folds].clone(), st.export(), st.rows, st.folds))
+    a, b = res
+    assert a[4] == b[4] and a[5] == b[5]
+    assert torch.equal(a[1], b[1]), "assignments differ between the fold paths"
+    # scores: equal where both paths use the matrix cores; a token that moved to a row appended
+    # in the same fold was scored against it on the vector ALU by the kernel-per-step path
+    assert torch.equal(torch.isnan(a[2]), torch.isnan(b[2]))
+    torch.testing.assert_close(torch.nan_to_num(a[2], nan=0.0), torch.nan_to_num(b[2], nan=0.0), rtol=1e-5, atol=1e-4)
+    for key in ("sK", "sV", "n", "w", "khat"):
+        assert torch.equal(a[3][key], b[3][key]), key
+    torch.testing.assert_close(a[3]["rho"], b[3]["rho"], rtol=1e-6, atol=0)
+    torch.testing.assert_close(a[3]["vhat"].float(), b[3]["vhat"].float(), rtol=2 ** -7, atol=1e-6)
+    torch.testing.assert_close(a[0].float(), b[0].float(), rtol=2e-2, atol=2e-2)
