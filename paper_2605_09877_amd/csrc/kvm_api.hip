@@ -343,7 +343,6 @@ int fold_trace(const kvm_state *st, const Dev &dv, int64_t u0, int64_t fold, hip
 // The fused path: one launch per run of folds (bf16, d = 128 states whose tables fit LDS), unless
 // kvm_debug_set asked for the kernel-per-step path.
 bool use_fused(const kvm_state *st) { return st->fused && st->dbg[KVM_DEBUG_FOLD_PATH] != 2; }
-int fused_waves(const kvm_state *st) { return st->dbg[KVM_DEBUG_FOLD_WAVES] == 16 ? 16 : 8; }
 kvm::FoldRunArgs fused_run(const kvm_state *st, bool in_place) {
   kvm::FoldRunArgs run;
   run.n = 0;
@@ -367,8 +366,10 @@ int fold_block(kvm_state *st, const Src &src, int64_t e, int32_t *assign_out, fl
   if (use_fused(st)) {
     kvm::FoldRunArgs run = fused_run(st, in_place);
     run.n = 1;
-    run.s[0] = {(int32_t)m, (int32_t)m_after, so, sn, 0, st->folds < st->trace_max ? st->folds : -1};
-    HIP_TRY(kvm::launch_fold_fused(dv, src, run, fused_waves(st), stream));
+    run.s[0] = {(int32_t)m, (int32_t)m_after, so, sn, 0, st->folds < st->trace_max ? (int32_t)st->folds : -1, 0};
+    HIP_TRY(kvm::launch_memkey(dv, src, 1, stream));
+    // a fold of its own (decode, the fold entry point, the chunk-by-chunk schedule): nothing runs beside it
+    HIP_TRY(kvm::launch_fold_fused(dv, src, run, st->dbg[KVM_DEBUG_FOLD_WAVES] == 8, stream));
   } else {
     int rc = fold_launches(st, dv, src, m, m_after, so, sn, in_place, kbar_block, stream);
     if (rc != KVM_OK) return rc;
@@ -787,6 +788,21 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
     if ((forced == 1 || forced == 2) && dv.B % forced == 0) n_chains = forced;
     if (use_fused(st)) n_chains = 1;  // one workgroup per unit already: nothing to split
   }
+  // The one-launch folds run beside the attention launches.  Where attention is the larger part
+  // of the call they take the narrow workgroup, which shares a compute unit with an attention
+  // workgroup; where the fold chain is the critical path they take the wide one.  Estimates per
+  // chunk from the shape: attention at ~0.7 PFLOP/s, a fold at ~15 us + 30 us per (512 tokens x
+  // 1024 rows).
+  bool narrow_folds = false;
+  {
+    int64_t m_max = 0;
+    for (const Chunk &ch : plan) m_max = ch.m > m_max ? ch.m : m_max;
+    const double attn_us = 4.0 * d * (double)C * (double)(m_max + L) * dv.Hq * dv.B / 0.7e9;
+    const double fold_us = 15.0 + 30.0 * ((double)C / 512.0) * ((double)m_max / 1024.0);
+    narrow_folds = attn_us > fold_us;
+    if (st->dbg[KVM_DEBUG_FOLD_WAVES] == 8) narrow_folds = true;
+    if (st->dbg[KVM_DEBUG_FOLD_WAVES] == 16) narrow_folds = false;
+  }
   hipStream_t fstream[kvm_state::kMaxChains];
   Dev cdv[kvm_state::kMaxChains];
   const int cb = dv.B / n_chains;  // sequences per chain
@@ -873,10 +889,11 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
           const int64_t lo = plan[next_fold + i].s + C - L;
           const int64_t fold_no = st->folds + i;
           fr.s[i] = {(int32_t)steps[i].m, (int32_t)steps[i].m_after, steps[i].so, steps[i].sn,
-                     batched ? lo - lo0 : 0, fold_no < st->trace_max ? fold_no : -1};
+                     batched ? lo - lo0 : 0, fold_no < st->trace_max ? (int32_t)fold_no : -1, i};
         }
-        HIP_TRY(kvm::launch_fold_fused(dv, batched ? advance(in, lo0 - t0, es) : advance(ring, lo0 % L, es), fr,
-                                       fused_waves(st), fstream[0]));
+        const Src fsrc = batched ? advance(in, lo0 - t0, es) : advance(ring, lo0 % L, es);
+        HIP_TRY(kvm::launch_memkey(dv, fsrc, run, fstream[0]));
+        HIP_TRY(kvm::launch_fold_fused(dv, fsrc, fr, narrow_folds, fstream[0]));
       } else
       for (int c2 = 0; c2 < n_chains; ++c2) {
         // the timing bracket goes on the first chain only (the chains run side by side)

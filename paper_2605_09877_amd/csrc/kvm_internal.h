@@ -88,16 +88,18 @@ hipError_t launch_refresh(const Dev &dv, int m, int slot, hipStream_t st);
 hipError_t launch_ring_copy(const Dev &dv, const Src &src, int64_t src_t0, int64_t p0, int64_t p1,
                             hipStream_t st);
 // fold_fused.hip (bf16, d = 128): a run of up to kFoldMaxSteps consecutive folds in one launch,
-// one workgroup per unit.  Step i folds the block whose first token is src's token s[i].tok, from
-// s[i].m to s[i].m_after rows, reading readout slot s[i].so and writing slot s[i].sn (the same slot
-// when in_place; otherwise untouched rows are copied over).  trace >= 0: the fold's assignments
-// and scores also go to trace_assign / trace_score at that fold index (trace_stride = tokens of
-// one fold over all units).
+// one workgroup per unit.  Step i folds the block whose first token is src's token s[i].tok and
+// whose memory keys are in slab s[i].kbar_block of the scratch (launch_memkey), from s[i].m to
+// s[i].m_after rows, reading readout slot s[i].so and writing slot s[i].sn (the same slot when
+// in_place; otherwise untouched rows are copied over).  trace >= 0: the fold's assignments and
+// scores also go to trace_assign / trace_score at that fold index (trace_stride = tokens of one
+// fold over all units).  narrow: the 8-wave workgroup that fits beside an attention workgroup on
+// a compute unit; otherwise 16 waves and the unit to itself.
 constexpr int kFoldMaxSteps = 8;
 struct FoldStep {
   int32_t m, m_after, so, sn;
   int64_t tok;
-  int64_t trace;
+  int32_t trace, kbar_block;
 };
 struct FoldRunArgs {
   int32_t n, in_place;
@@ -107,7 +109,7 @@ struct FoldRunArgs {
   int64_t trace_stride;
 };
 bool fold_fused_fits(const Dev &dv);
-hipError_t launch_fold_fused(const Dev &dv, const Src &src, const FoldRunArgs &run, int n_waves, hipStream_t st);
+hipError_t launch_fold_fused(const Dev &dv, const Src &src, const FoldRunArgs &run, bool narrow, hipStream_t st);
 // score_mfma.hip (bf16, d = 128)
 hipError_t launch_score_mfma(const Dev &dv, int slot, int row0, int row1, bool first_pass, hipStream_t st);
 // attn_rows.hip

@@ -89,19 +89,16 @@ __global__ __launch_bounds__(512, 2) void score_mfma_kernel(Dev dv, int slot, in
     const int t = 2 * sg + tp;
     if (!wave_active || t >= n_tiles) continue;
     const uint16_t *Kt = Ks[sg & 1][tp];
-    // two accumulation chains (channels 0..63 and 64..127), so that consecutive matrix
-    // instructions do not wait for each other
-    f32x16 acc0, acc1;
+    // one accumulation chain over the channels in ascending order (the order the one-launch fold
+    // path uses too, so that both paths produce the same fp32 scores)
+    f32x16 acc0;
     {
       bf16x8 kf[8];
 #pragma unroll
       for (int i = 0; i < 8; ++i) kf[i] = ktile_frag(Kt, koff, rh, i);
       const f32x16 zero = {0.f};
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        acc0 = mfma32(kf[ks], kreg[ks], ks == 0 ? zero : acc0);
-        acc1 = mfma32(kf[ks + 4], kreg[ks + 4], ks == 0 ? zero : acc1);
-      }
+      for (int ks = 0; ks < 8; ++ks) acc0 = mfma32(kf[ks], kreg[ks], ks == 0 ? zero : acc0);
     }
     // rows this lane sees, ascending in v
     const int base = row0 + t * kTileKeys + 32 * rh;
@@ -110,7 +107,7 @@ __global__ __launch_bounds__(512, 2) void score_mfma_kernel(Dev dv, int slot, in
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int i = base + mfma_row(v, g);
-        const float sc = acc0[v] + acc1[v];
+        const float sc = acc0[v];
         if (i < row1) {
           best_all = fmaxf(best_all, sc);
           if (i >= dv.S && sc > best) {
@@ -122,7 +119,7 @@ __global__ __launch_bounds__(512, 2) void score_mfma_kernel(Dev dv, int slot, in
     } else {
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const float sc = acc0[v] + acc1[v];
+        const float sc = acc0[v];
         if (sc > best) {
           best = sc;
           best_i = base + mfma_row(v, g);
