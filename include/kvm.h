@@ -240,7 +240,8 @@ int kvm_state_import(kvm_state *st, const double *sK, const float *sV, const flo
 /* Choices the library normally makes by itself, forced for tests and comparisons (no passage of
  * the paper).  value 0 gives the choice back to the library.  Takes effect from the next call on.
  *   KVM_DEBUG_FOLD_PATH         1: a run of folds is one launch, one workgroup per unit (bf16,
- *                               head_dim 128; the default there), 2: one kernel per fold step
+ *                               head_dim 128, block lengths 64 * 2^k up to 1024), 2: one kernel
+ *                               per fold step (the default)
  *   KVM_DEBUG_FOLD_WAVES        8 or 16: wavefronts of a fold workgroup on the one-launch path
  *   KVM_DEBUG_PREFILL_SCHEDULE  1: chunk by chunk on the caller's stream, folds in place,
  *                               2: folds ahead on the library's stream, attention in groups

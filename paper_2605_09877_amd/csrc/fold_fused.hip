@@ -178,22 +178,46 @@ __device__ __forceinline__ void score_pass(const Dev &dv, const Ctx &cx, int slo
     const int gi = wave / wpg, sub = wave % wpg;
     const bool active = gi < Gp;
     const int j = (g0 + (active ? gi : 0)) * 32 + l32;
-    if (n_stages > 0) issue_stage(0);
+    // The memory keys of this round's token groups, as B operands (lane = 32 g + i holds token i,
+    // channels 16 ks + 8 g .. + 7): the block's rows go through LDS as 64-token tiles in the K
+    // layout (coalesced 1-KiB pieces) instead of sixteen scattered bytes per lane and step.  When
+    // they fit the ring's second half they travel together with the first stage of K-hat.
+    const int kb_tiles = (Gp + 1) / 2;
+    const bool together = kb_tiles <= ST;
+    const int kb_buf0 = together ? ST : 0;
+#pragma unroll
+    for (int i = 0; i < 2 * ST; ++i)
+      if (i < kb_tiles) {
+        const char *from = (const char *)(kbar_blk + (int64_t)(g0 / 2 + i) * kTileKeys * D);
+#pragma unroll
+        for (int n = 0; n < 16 / NW; ++n) {
+          const int piece = wave + NW * n;
+          dma16(from, (uint32_t)(4 * piece + (int)dl.rl) * (D * 2) + kcol,
+                ks_addr + (uint32_t)(kb_buf0 + i) * kTileBytes + (uint32_t)piece * 1024u);
+        }
+      }
+    if (together && n_stages > 0) issue_stage(0);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
     bf16x8 kreg[8];
     {
-      const uint16_t *krow = kbar_blk + (int64_t)j * D;
+      const int gsel = active ? gi : 0;
+      const uint16_t *Kb = Ks + (kb_buf0 + gsel / 2) * kTileElems;
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        Frag8 f;
-        f.q = *reinterpret_cast<const uint4 *>(krow + 16 * ks + 8 * g);
-        kreg[ks] = f.v;
-      }
+      for (int ks = 0; ks < 8; ++ks) kreg[ks] = ktile_frag(Kb, koff, gsel & 1, ks);
+    }
+    if (!together) {
+      __builtin_amdgcn_s_waitcnt(0);
+      __syncthreads();   // every wave has its operands: the ring is free for K-hat
+      if (n_stages > 0) issue_stage(0);
     }
     // The winner is kept as a wave-uniform code (32-row block number * 16 + accumulator element)
     // and turned into a row at the end: selecting a scalar costs no register per candidate.
     float best_all = -INFINITY, best = -INFINITY;
     int best_code = -1;
     for (int sg = 0; sg < n_stages; ++sg) {
+      // (together: stage 0 has landed with the memory keys; this wait is for the operand reads,
+      // after which the ring's second half may be overwritten by stage 1)
       __builtin_amdgcn_s_waitcnt(0);
       __syncthreads();
       if (sg + 1 < n_stages) issue_stage(sg + 1);
@@ -219,6 +243,15 @@ __device__ __forceinline__ void score_pass(const Dev &dv, const Ctx &cx, int slo
                   acc[rh] = mfma32(kf[slot2], kreg[ks], ks == 0 ? zero : acc[rh]);
                   if (ks + 2 < 8) kf[slot2] = ktile_frag(Kt, koff, rh, ks + 2);
                 }
+              // pin that order: four LDS reads up front, then one read behind every matrix
+              // instruction, so that no matrix instruction waits for the read issued just before it
+              __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+              for (int q = 0; q < 12; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+              }
+              __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
             }
 #pragma unroll
             for (int rh = 0; rh < 2; ++rh) {
@@ -350,6 +383,17 @@ __device__ __forceinline__ void select_tokens(const Dev &dv, const Ctx &cx, int 
   __syncthreads();
 }
 
+// 1 / sqrt(x) in fp64 from the hardware estimate and two Newton steps (y <- y (1.5 - 0.5 x y^2)):
+// within a few units of the last place, against some 300 instructions for the correctly rounded
+// division of the correctly rounded root; the result is rounded to bf16 afterwards.
+__device__ __forceinline__ double rsqrt64(double x) {
+  double y = __builtin_amdgcn_rsq(x);
+  const double hx = 0.5 * x;
+  y = y * fma(-hx * y, y, 1.5);
+  y = y * fma(-hx * y, y, 1.5);
+  return y;
+}
+
 // Readout row of sums (sk, sv, rho): LN_s on the key sums in fp64, stored radius on the value sums;
 // 16 lanes hold the row, 8 channels each.  Rounding to bf16 is the hardware's (nearest even).
 __device__ __forceinline__ void write_readout16(const Dev &dv, int slot, int64_t ro, int ch0, const double (&sk)[8],
@@ -359,18 +403,19 @@ __device__ __forceinline__ void write_readout16(const Dev &dv, int slot, int64_t
   double s = 0.0;
 #pragma unroll
   for (int e = 0; e < 8; ++e) s += sk[e];
-  const double mean = group_sum<16>(s) / (double)D;
+  const double mean = group_sum<16>(s) * (1.0 / (double)D);   // D is a power of two: exact
   double qq = 0.0;
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     const double dl = sk[e] - mean;
     qq += dl * dl;
   }
-  const double rden = 1.0 / sqrt(group_sum<16>(qq) / (double)D + (double)dv.ln_eps);
+  const double rden = rsqrt64(group_sum<16>(qq) * (1.0 / (double)D) + (double)dv.ln_eps);
   float nn = 0.f;
 #pragma unroll
   for (int e = 0; e < 8; ++e) nn += sv[e] * sv[e];
-  const float vs = rho / fmaxf(sqrtf(group_sum<16>(nn)), dv.norm_eps);
+  // (hardware root and reciprocal, an ulp of fp32 each: far below the bf16 the result is rounded to)
+  const float vs = rho * __builtin_amdgcn_rcpf(fmaxf(__builtin_amdgcn_sqrtf(group_sum<16>(nn)), dv.norm_eps));
   uint32_t kw[4], vw[4];
 #pragma unroll
   for (int e = 0; e < 8; e += 2) {
@@ -494,75 +539,88 @@ __device__ __forceinline__ int group_min16(int x) {
 }
 
 // Step 5: the touched rows, 16 lanes each.
+struct RowLoad {
+  double2 k2[4];
+  float4 v4[2];
+  uint4 kraw, vraw;
+  float rho, w, gt;
+  int n, mine, len, t_cur, row;
+};
+
 template <int NW>
 __device__ __forceinline__ void merge_rows(const Dev &dv, const Ctx &cx, const RowCtx &rc, int slot_new, int n_rows) {
   constexpr int D = kHeadDim, NG = 4 * NW;
   const int C = dv.C;
   const int *next = cx.s_next(), *pi = cx.s_pi(), *rank = cx.s_rank();
-  for (int ri = rc.gid; ri < n_rows; ri += NG) {
+  auto fetch = [&](RowLoad &L, int t) {
+    L.kraw = *reinterpret_cast<const uint4 *>(rc.kbar + (int64_t)t * D + rc.ch0);
+    L.vraw = *reinterpret_cast<const uint4 *>(rc.vsrc + (int64_t)t * rc.v_t + rc.ch0);
+    L.gt = rc.gsrc ? rc.gsrc[(int64_t)t * rc.g_t] : 1.f;
+  };
+  auto start = [&](RowLoad &L, int ri) {
     const int row = cx.s_rows()[ri];
+    L.row = row;
     const int64_t ro = (int64_t)cx.u * dv.Mcap + row;
     // the sums are asked for first; the list is walked while they travel
     const double2 *pk = reinterpret_cast<const double2 *>(dv.sK + ro * D + rc.ch0);
     const float4 *pv = reinterpret_cast<const float4 *>(dv.sV + ro * D + rc.ch0);
-    double2 k2[4];
-    float4 v4[2];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) k2[q] = pk[q];
-    v4[0] = pv[0];
-    v4[1] = pv[1];
-    const float rho = dv.rho[ro];
-    float w = dv.w[ro];
-    int n = dv.n[ro];
+    for (int q = 0; q < 4; ++q) L.k2[q] = pk[q];
+    L.v4[0] = pv[0];
+    L.v4[1] = pv[1];
+    L.rho = dv.rho[ro];
+    L.w = dv.w[ro];
+    L.n = dv.n[ro];
     // lane i of the group keeps the i-th token of the list (any order); longer lists are scanned
     int mine = kNoRow, len = 0;
     for (int t = cx.s_head()[row]; t >= 0 && len <= kListMax; t = next[t], ++len)
       if (len == rc.c16) mine = t;
-    // the first token (the smallest position) is asked for before the sums are waited for
-    int t_cur = len <= kListMax ? group_min16(mine) : kNoRow;
-    uint4 kraw = {}, vraw = {};
-    float gt = 1.f;
-    auto fetch = [&](int t) {
-      kraw = *reinterpret_cast<const uint4 *>(rc.kbar + (int64_t)t * D + rc.ch0);
-      vraw = *reinterpret_cast<const uint4 *>(rc.vsrc + (int64_t)t * rc.v_t + rc.ch0);
-      gt = rc.gsrc ? rc.gsrc[(int64_t)t * rc.g_t] : 1.f;
-    };
-    if (t_cur != kNoRow) fetch(t_cur);
+    L.mine = mine;
+    L.len = len;
+    // the first token (the smallest position) is asked for together with the sums
+    L.t_cur = len <= kListMax ? group_min16(mine) : kNoRow;
+    if (L.t_cur != kNoRow) fetch(L, L.t_cur);
+  };
+  auto finish = [&](RowLoad &L) {
+    const int64_t ro = (int64_t)cx.u * dv.Mcap + L.row;
     double sk[8];
     float sv[8];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      sk[2 * q] = k2[q].x;
-      sk[2 * q + 1] = k2[q].y;
+      sk[2 * q] = L.k2[q].x;
+      sk[2 * q + 1] = L.k2[q].y;
     }
-    sv[0] = v4[0].x; sv[1] = v4[0].y; sv[2] = v4[0].z; sv[3] = v4[0].w;
-    sv[4] = v4[1].x; sv[5] = v4[1].y; sv[6] = v4[1].z; sv[7] = v4[1].w;
+    sv[0] = L.v4[0].x; sv[1] = L.v4[0].y; sv[2] = L.v4[0].z; sv[3] = L.v4[0].w;
+    sv[4] = L.v4[1].x; sv[5] = L.v4[1].y; sv[6] = L.v4[1].z; sv[7] = L.v4[1].w;
+    float w = L.w;
+    int n = L.n;
     auto add_fetched = [&]() {
       float kf[8], vf[8];
-      unpack16<bf16_t>(kraw, kf);
-      unpack16<bf16_t>(vraw, vf);
+      unpack16<bf16_t>(L.kraw, kf);
+      unpack16<bf16_t>(L.vraw, vf);
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        sk[e] = fma((double)gt, (double)kf[e], sk[e]);
-        sv[e] = fmaf(gt, vf[e], sv[e]);
+        sk[e] = fma((double)L.gt, (double)kf[e], sk[e]);
+        sv[e] = fmaf(L.gt, vf[e], sv[e]);
       }
-      w += gt;
+      w += L.gt;
       n += 1;
     };
-    if (len <= kListMax) {
+    if (L.len <= kListMax) {
       // ascending position: the smallest token not yet added, len times
-      for (int q = 0; q < len; ++q) {
+      int t_cur = L.t_cur;
+      for (int q = 0; q < L.len; ++q) {
         add_fetched();
-        if (q + 1 < len) {
-          t_cur = group_min16(mine > t_cur ? mine : kNoRow);
-          fetch(t_cur);
+        if (q + 1 < L.len) {
+          t_cur = group_min16(L.mine > t_cur ? L.mine : kNoRow);
+          fetch(L, t_cur);
         }
       }
     } else {
       // a long list (many tokens on one row): scan the block's targets in position order instead
       for (int t = 0; t < C; ++t)
-        if (pi[t] == row && rank[t] < 0) {
-          fetch(t);
+        if (pi[t] == L.row && rank[t] < 0) {
+          fetch(L, t);
           add_fetched();
         }
     }
@@ -578,7 +636,12 @@ __device__ __forceinline__ void merge_rows(const Dev &dv, const Ctx &cx, const R
         dv.n[ro] = n;
       }
     }
-    write_readout16(dv, slot_new, ro, rc.ch0, sk, sv, rho, rc.ga, rc.be);
+    write_readout16(dv, slot_new, ro, rc.ch0, sk, sv, L.rho, rc.ga, rc.be);
+  };
+  for (int ri = rc.gid; ri < n_rows; ri += NG) {
+    RowLoad A;
+    start(A, ri);
+    finish(A);
   }
 }
 
@@ -677,7 +740,7 @@ __global__ __launch_bounds__(64 * NW, 4) void fold_fused_kernel(FoldKernelArgs a
         // the new rows first, so that the remaining tokens can be scored against them too
         create_rows<NW>(dv, cx, rc, m, n_app, st.sn);
         __syncthreads();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
         score_pass<NW>(dv, cx, st.sn, m, m_after, false, kbar_blk);
       }
       FOLD_STAMP();
@@ -703,8 +766,31 @@ __global__ __launch_bounds__(64 * NW, 4) void fold_fused_kernel(FoldKernelArgs a
     }
     // the next fold of the run reads what this one wrote (this workgroup's own stores)
     __syncthreads();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
   }
+}
+
+// The readout rows [0, m) of every unit recomputed from the stored sums (after an import), with the
+// arithmetic of the folds above, so that a state that was exported and imported continues to the
+// bit like one that was not.
+__global__ __launch_bounds__(256) void refresh16_kernel(Dev dv, int m, int slot) {
+  constexpr int D = kHeadDim;
+  const int u = blockIdx.y, h = u % dv.Hkv;
+  const int row = blockIdx.x * 16 + (threadIdx.x >> 4), c16 = threadIdx.x & 15, ch0 = 8 * c16;
+  if (row >= m) return;
+  const int64_t ro = (int64_t)u * dv.Mcap + row;
+  const float *gam = dv.gamma ? dv.gamma + h * D : kOnes, *bet = dv.beta ? dv.beta + h * D : kZeros;
+  float ga[8], be[8];
+  double sk[8];
+  float sv[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    ga[e] = gam[ch0 + e];
+    be[e] = bet[ch0 + e];
+    sk[e] = dv.sK[ro * D + ch0 + e];
+    sv[e] = dv.sV[ro * D + ch0 + e];
+  }
+  write_readout16(dv, slot, ro, ch0, sk, sv, dv.rho[ro], ga, be);
 }
 
 constexpr size_t kLdsWide = 160 * 1024, kLdsNarrow = 96 * 1024;
@@ -717,6 +803,12 @@ bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 bool fold_fused_fits(const Dev &dv) {
   if (!(dv.io == 1 && dv.d == kHeadDim && dv.C % 64 == 0 && dv.C <= 1024 && pow2(dv.C / 32))) return false;
   return fold_lds(dv.C, dv.Mcap, 16).total <= kLdsWide && fold_lds(dv.C, dv.Mcap, 8).total <= kLdsNarrow;
+}
+
+hipError_t launch_refresh16(const Dev &dv, int m, int slot, hipStream_t st) {
+  if (m <= 0) return hipSuccess;
+  hipLaunchKernelGGL(refresh16_kernel, dim3((m + 15) / 16, dv.U), dim3(256), 0, st, dv, m, slot);
+  return hipGetLastError();
 }
 
 hipError_t launch_fold_fused(const Dev &dv, const Src &src, const FoldRunArgs &run, bool narrow, hipStream_t st) {

@@ -340,9 +340,11 @@ int fold_trace(const kvm_state *st, const Dev &dv, int64_t u0, int64_t fold, hip
   return KVM_OK;
 }
 
-// The fused path: one launch per run of folds (bf16, d = 128 states whose tables fit LDS), unless
-// kvm_debug_set asked for the kernel-per-step path.
-bool use_fused(const kvm_state *st) { return st->fused && st->dbg[KVM_DEBUG_FOLD_PATH] != 2; }
+// The one-launch fold path (a run of folds in one kernel, one workgroup per unit; bf16, d = 128
+// states whose tables fit LDS) is taken when kvm_debug_set asks for it.  Measured, it does not beat
+// the kernel-per-step path on any of the workloads here: one compute unit per unit of the state is
+// slower than a launch over the whole chip by more than the launch boundaries cost.
+bool use_fused(const kvm_state *st) { return st->fused && st->dbg[KVM_DEBUG_FOLD_PATH] == 1; }
 kvm::FoldRunArgs fused_run(const kvm_state *st, bool in_place) {
   kvm::FoldRunArgs run;
   run.n = 0;
@@ -1400,7 +1402,10 @@ int kvm_state_import(kvm_state *st, const double *sK, const float *sV, const flo
   if (win_k) HIP_TRY(hipMemcpyAsync(dv.winK, win_k, win, hipMemcpyDeviceToDevice, stream));
   if (win_v) HIP_TRY(hipMemcpyAsync(dv.winV, win_v, win, hipMemcpyDeviceToDevice, stream));
   if (win_g) HIP_TRY(hipMemcpyAsync(dv.winG, win_g, U * dv.L * 4, hipMemcpyDeviceToDevice, stream));
-  HIP_TRY(kvm::launch_refresh(dv, (int)m, slot_of(st, folds), stream));
+  if (use_fused(st))
+    HIP_TRY(kvm::launch_refresh16(dv, (int)m, slot_of(st, folds), stream));
+  else
+    HIP_TRY(kvm::launch_refresh(dv, (int)m, slot_of(st, folds), stream));
   st->m = m;
   st->tokens = tokens_seen;
   st->folds = folds;

@@ -109,6 +109,8 @@ struct FoldRunArgs {
   int64_t trace_stride;
 };
 bool fold_fused_fits(const Dev &dv);
+// readout rows [0, m) recomputed from the sums with the one-launch path's arithmetic
+hipError_t launch_refresh16(const Dev &dv, int m, int slot, hipStream_t st);
 hipError_t launch_fold_fused(const Dev &dv, const Src &src, const FoldRunArgs &run, bool narrow, hipStream_t st);
 // score_mfma.hip (bf16, d = 128)
 hipError_t launch_score_mfma(const Dev &dv, int slot, int row0, int row1, bool first_pass, hipStream_t st);

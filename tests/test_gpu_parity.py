@@ -26,11 +26,12 @@ def synth():
 
 
 def run_prefill_case(w, plain, split=None, decode_tail=0, check_lse=True, units=None, tweak=None, case=None,
-                     widen=None):
+                     widen=None, knobs=None):
     """Prefill (optionally in two calls, optionally finishing with decode steps) on the GPU and in
     the oracle; compare sizes, assignments, scores, outputs, lse and the final state.  widen: the
     library is handed q, k, v, gate, out and lse as views of wider buffers (element strides through
-    kvm_strides) instead of dense tensors.  Returns (Ties, state)."""
+    kvm_strides) instead of dense tensors.  knobs: {kvm_debug_set knob: value} applied to the state.
+    Returns (Ties, state)."""
     pkg, sy = kvm(), synth()
     q, k, v = sy.make_qkv(w, DEV)
     params = sy.make_params(w, DEV, plain=plain)
@@ -38,6 +39,8 @@ def run_prefill_case(w, plain, split=None, decode_tail=0, check_lse=True, units=
         tweak(params)
     gate = params["gate"]
     st = pkg.state_for(w, device=DEV, **params)
+    for knob, value in (knobs or {}).items():
+        st.debug_set(knob, value)
     T = w.seq
     Tp = T - decode_tail
     n_trace = T // w.chunk_len + 1
@@ -487,3 +490,35 @@ def test_fold_paths_agree(shape, waves):
     torch.testing.assert_close(a[3]["rho"], b[3]["rho"], rtol=1e-6, atol=0)
     torch.testing.assert_close(a[3]["vhat"].float(), b[3]["vhat"].float(), rtol=2 ** -7, atol=1e-6)
     torch.testing.assert_close(a[0].float(), b[0].float(), rtol=2e-2, atol=2e-2)
+
+
+@pytest.mark.parametrize("waves", [8, 16])
+@pytest.mark.parametrize("case", ["fixed", "sqrt", "gqa", "decode_tail", "table", "three_blocks"])
+def test_one_launch_fold_path_against_the_oracle(case, waves):
+    """The one-launch fold path (kvm_debug_set; not the default), both workgroup shapes, against
+    the oracle to the bars of the other tests: plain merges, append-all, partial appends with the
+    second scoring pass, folds in place during decode steps, a budget table, a three-block window."""
+    from paper_2605_09877_amd import binding
+    sy = synth()
+    knobs = {binding.KVM_DEBUG_FOLD_PATH: 1, binding.KVM_DEBUG_FOLD_WAVES: waves}
+    if case == "fixed":
+        w = sy.shrink(sy.WORKLOADS["prefill_fixed"], batch=2, n_q_heads=2, n_kv_heads=2, seq=2560 + 77)
+        run_prefill_case(w, plain=False, knobs=knobs)
+    elif case == "sqrt":
+        w = sy.shrink(sy.WORKLOADS["prefill_sqrt"], batch=1, n_q_heads=2, n_kv_heads=2, seq=6144)
+        run_prefill_case(w, plain=True, knobs=knobs)
+    elif case == "gqa":
+        w = sy.shrink(sy.WORKLOADS["prefill_gqa_32k"], batch=1, n_q_heads=8, n_kv_heads=2, seq=4096)
+        run_prefill_case(w, plain=False, knobs=knobs)
+    elif case == "decode_tail":
+        w = sy.shrink(sy.WORKLOADS["prefill_fixed"], batch=1, n_q_heads=2, n_kv_heads=2, seq=1024 + 300,
+                      chunk_len=128, budget_fixed=256)
+        run_prefill_case(w, plain=False, split=512, decode_tail=300 - 128 + 45, knobs=knobs)
+    elif case == "table":
+        table = (256, 256, 512, 640, 700, 720, 730, 736, 736)
+        w = sy.shrink(sy.WORKLOADS["prefill_fixed"], batch=1, n_q_heads=2, n_kv_heads=2, budget_kind="table",
+                      budget_table=table, seq=12 * 256 + 19)
+        run_prefill_case(w, plain=False, knobs=knobs)
+    else:
+        w = sy.shrink(sy.WORKLOADS["prefill_fixed"], batch=1, n_q_heads=2, n_kv_heads=2, n_bswa_chunks=3, seq=3072 + 45)
+        run_prefill_case(w, plain=False, knobs=knobs)
