@@ -69,18 +69,35 @@ def attention_flops(w, T):
     return 4.0 * w.head_dim * pairs * w.n_q_heads * w.batch, launches
 
 
+def fold_bytes(w, units, C, m, touched=None, copied=None):
+    """Bytes one fold moves, two models.  `survey`: the per-fold figure of the scope table this
+    build is measured against -- the block's k, v re-read, the normalised state keys read, fp32
+    sums read-modify-written and the readout refreshed on min(C, m) rows (an upper bound on the
+    rows a block can touch).  `own`: what the kernels here move -- memory keys written and read
+    back, fp64 key sums, rows touched as measured (`touched`), and, inside a prefill, the readout of
+    untouched rows copied to the new state version (`copied` rows)."""
+    d, es = w.head_dim, 2 if w.io == "bf16" else 4
+    up = min(C, m)
+    survey = units * (2 * C * d * es + m * d * es + up * d * 4 * 2 * 2 + up * d * 2 * es)
+    t = up if touched is None else touched
+    cp = 0 if copied is None else copied
+    own = units * (2 * C * d * es * 2 + m * d * es + t * d * (8 + 4) * 2 + t * d * 2 * es + cp * d * 2 * es * 2)
+    return dict(survey=survey, own=own)
+
+
 def prefill_leg(args, pkg, synth, dev):
     import torch
     w = synth.WORKLOADS[args.workload]
     q, k, v = synth.make_qkv(w, dev)
     st = pkg.state_for(w, device=dev)
     out = torch.empty_like(q)
+    if args.kernels_apart:
+        st.profile(2)      # folds and attention never share the chip: for traces and counters of each alone
     for _ in range(args.warmup):
         st.reset()
         st.prefill(q, k, v, out=out)
     torch.cuda.synchronize()
-    st.profile(True)
-    st.profile_read()
+    # the timed steps: no kernel timing events, nothing but the calls
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
     for i in range(args.steps):
@@ -91,6 +108,15 @@ def prefill_leg(args, pkg, synth, dev):
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+    # kernel spans, in passes of their own: the library brackets its attention launches and its
+    # folds with HIP events on the streams they are launched on
+    n_prof = max(2, min(args.steps, 5))
+    st.profile(True)
+    st.profile_read()
+    for _ in range(n_prof):
+        st.reset()
+        st.prefill(q, k, v, out=out)
+    torch.cuda.synchronize()
     prof = st.profile_read()
     # the same step with folds and attention kept apart: each kernel's time without the other
     iso = None
@@ -106,14 +132,32 @@ def prefill_leg(args, pkg, synth, dev):
     flops, _ = attention_flops(w, w.seq)
     attn_ms, attn_n = prof["attn"]
     fold_ms, fold_n = prof["fold"]
-    launches = max(attn_n // max(args.steps, 1), 1)      # attention launches per step (groups of chunks)
+    launches = max(attn_n // n_prof, 1)                   # attention launches per step (groups of chunks)
     avg_launch_s = attn_ms / max(attn_n, 1) * 1e-3
     achieved = flops / launches / avg_launch_s / 1e12 if attn_n else 0.0
-    isolated = None
+    isolated, fold = None, None
     if iso is not None:
         iso_tflops = flops / launches / (iso["attn"][0] / max(iso["attn"][1], 1) * 1e-3) / 1e12
         isolated = dict(achieved=iso_tflops, frac=iso_tflops / MFMA_BF16_PEAK_TFLOPS,
                         attn_ms_per_step=iso["attn"][0] / 2, fold_ms_per_step=iso["fold"][0] / 2)
+        # the fold's HBM roofline: a steady fold of this workload (m = the fixed budget, no append)
+        n_folds = max(iso["fold"][1], 1)
+        us = iso["fold"][0] / n_folds * 1e3
+        units, m = w.batch * w.n_kv_heads, rows_after_prefill(w, w.seq)
+        touched = int(0.4 * min(w.chunk_len, m)) if w.name == "prefill_gqa_32k" else None
+        nb = fold_bytes(w, units, w.chunk_len, m, touched=touched,
+                        copied=None if touched is None else m - touched)
+        fold = dict(bound="hbm", kernel="memkey_kernel + score_mfma_kernel + accum_kernel", peak=HBM_PEAK_GBS,
+                    unit="GB/s", isolated_us_per_fold=us, beside_attention_us_per_fold=fold_ms / max(fold_n, 1) * 1e3,
+                    folds_per_step=n_folds // 2, algorithmic_bytes_per_fold=nb["survey"],
+                    achieved=nb["survey"] / (us * 1e-6) / 1e9, frac=nb["survey"] / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                    moved_bytes_per_fold_model=nb["own"], moved_gbs=nb["own"] / (us * 1e-6) / 1e9,
+                    traffic=measured_traffic("fold_kernels_prefill_gqa_32k_hbm_traffic.txt")
+                    if w.name == "prefill_gqa_32k" else None,
+                    note="algorithmic bytes: block k, v + state keys + fp32 sums read-modify-written and readout "
+                         "refreshed on min(C, m) rows; moved bytes: this build's own model (memory keys written "
+                         "and read back, fp64 key sums, 0.4 m rows touched as measured, readout of the others "
+                         "copied to the new state version)")
     res = dict(
         value=tokens * args.steps / dt, ms_per_step=dt / args.steps * 1e3,
         step_ms=dict(median=step_ms[len(step_ms) // 2], min=step_ms[0], max=step_ms[-1]),
@@ -122,10 +166,11 @@ def prefill_leg(args, pkg, synth, dev):
                       traffic=measured_traffic("attn_mfma_kernel_prefill_gqa_32k_hbm_traffic.txt")
                       if w.name == "prefill_gqa_32k" else None,
                       launches_per_step=launches, avg_launch_us=avg_launch_s * 1e6,
-                      attn_ms_per_step=attn_ms / args.steps, fold_ms_per_step=fold_ms / args.steps,
-                      folds_per_step=fold_n // max(args.steps, 1),
+                      attn_ms_per_step=attn_ms / n_prof, fold_ms_per_step=fold_ms / n_prof,
+                      folds_per_step=fold_n // n_prof, timed_in="a pass of its own with the library's event "
+                      "brackets on (the timed steps run without them)",
                       isolated=isolated),
-        workload=w)
+        fold=fold, workload=w)
     return res, (q, k, v)
 
 
@@ -182,14 +227,20 @@ def decode_leg(args, pkg, synth, dev):
         st.decode(qs[t % n_in], ks[t % n_in], vs[t % n_in], out=out)
     st.import_(pre)
     torch.cuda.synchronize()
-    st.profile(True)
-    st.profile_read()
     t0 = time.perf_counter()
     for t in range(steps):
         st.decode(qs[t % n_in], ks[t % n_in], vs[t % n_in], out=out)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    # kernel spans in a pass of their own (the timed steps run without the event brackets)
+    st.import_(pre)
+    st.profile(True)
+    st.profile_read()
+    for t in range(steps):
+        st.decode(qs[t % n_in], ks[t % n_in], vs[t % n_in], out=out)
+    torch.cuda.synchronize()
     prof = st.profile_read()
+    st.profile(False)
     dec_ms, dec_n = prof["decode"]
     fold_ms, fold_n = prof["fold"]
     L, C, m, d = w.chunk_len * w.n_bswa_chunks, w.chunk_len, w.state_rows, w.head_dim
@@ -197,10 +248,17 @@ def decode_leg(args, pkg, synth, dev):
     bytes_per_step = w.batch * w.n_q_heads * ((m + mean_w) * d * 2 * 2 + 2 * d * 2)
     avg_s = dec_ms / max(dec_n, 1) * 1e-3
     gbs = bytes_per_step / avg_s / 1e9 if dec_n else 0.0
+    fold_us = fold_ms / max(fold_n, 1) * 1e3
+    fb = fold_bytes(w, w.batch * w.n_kv_heads, C, m)
+    fold = dict(bound="hbm", kernel="memkey_kernel + score_mfma_kernel + merge_inplace_kernel", peak=HBM_PEAK_GBS,
+                unit="GB/s", us_per_fold=fold_us, folds=fold_n, algorithmic_bytes_per_fold=fb["survey"],
+                achieved=fb["survey"] / (fold_us * 1e-6) / 1e9 if fold_n else 0.0,
+                frac=fb["survey"] / (fold_us * 1e-6) / 1e9 / HBM_PEAK_GBS if fold_n else 0.0,
+                note="in place: rows no token goes to are not touched; algorithmic bytes as for the prefill fold")
     ragged = ragged_decode(pkg, synth, dev, w, pre, qs, ks, vs, out, steps=200)
     grouped = grouped_decode(pkg, synth, dev, w, steps=200)
     return dict(us_per_token=dt / steps / w.batch * 1e6, us_per_step=dt / steps * 1e6, steps=steps,
-                folds=fold_n, fold_us=fold_ms / max(fold_n, 1) * 1e3, ragged=ragged, grouped_query=grouped,
+                folds=fold_n, fold_us=fold_us, fold=fold, ragged=ragged, grouped_query=grouped,
                 config=dict(workload="decode", batch=w.batch, heads=w.n_q_heads, head_dim=d, state_rows=m,
                             window=L, chunk_len=C),
                 roofline=dict(bound="hbm", kernel="attn_rows_kernel", achieved=gbs, peak=HBM_PEAK_GBS,
@@ -228,14 +286,19 @@ def grouped_decode(pkg, synth, dev, w, steps):
         st.decode(qs[t % n_in], ks[t % n_in], vs[t % n_in], out=out)
     st.import_(pre)
     torch.cuda.synchronize()
-    st.profile(True)
-    st.profile_read()
     t0 = time.perf_counter()
     for t in range(steps):
         st.decode(qs[t % n_in], ks[t % n_in], vs[t % n_in], out=out)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    st.import_(pre)
+    st.profile(True)
+    st.profile_read()
+    for t in range(steps):
+        st.decode(qs[t % n_in], ks[t % n_in], vs[t % n_in], out=out)
+    torch.cuda.synchronize()
     dec_ms, dec_n = st.profile_read()["decode"]
+    st.profile(False)
     L, C, m, d = wg.chunk_len * wg.n_bswa_chunks, wg.chunk_len, wg.state_rows, wg.head_dim
     mean_w = L - C + 1 + (steps - 1) / 2.0               # the window grows by one per step from L - C + 1
     nbytes = wg.batch * (wg.n_kv_heads * (m + mean_w) * d * 2 * 2 + wg.n_q_heads * 2 * d * 2)
@@ -310,28 +373,52 @@ def prep_leg(args, pkg, synth, dev):
                               unit="GB/s", frac=gbs / HBM_PEAK_GBS, traffic=None))
 
 
-def cpu_baseline_leg(w, tensors, budget_s):
+def cpu_baseline_leg(w, tensors, budget_s, gpu=None):
     """The oracle, as it stands, on (batch, KV head) units of the same inputs, one after the other,
     for as many chunks as fit the time budget; scaled to whole-layer tokens/s (units are
-    independent and equal in work: a layer token is one position of every KV head)."""
+    independent and equal in work: a layer token is one position of every KV head).  gpu: the
+    library's output and fold record of the same prefill; what the oracle got through is then
+    compared with them (returned as the `parity` object: units and chunks compared, folds whose
+    assignments differ from the oracle's -- reported, not overridden, here -- and the worst output
+    row error as a fraction of the bf16 bar, over the chunks ahead of the first such fold)."""
+    import numpy as np
     import kvm_testlib as tl
     q, k, v = tensors
     C = w.chunk_len
+    G = w.n_q_heads // w.n_kv_heads
     t0 = time.perf_counter()
     done, units_done, folds = 0, 0, 0
+    par = dict(units=0, chunks=0, folds=0, folds_differing=0, ties_merge=None, ties_append=None, max_err=0.0)
     for b in range(w.batch):
         for h in range(w.n_kv_heads):
             if time.perf_counter() - t0 >= budget_s:
                 break
             u = tl.unit_inputs(w, q[b:b + 1], k[b:b + 1], v[b:b + 1], {}, 0, h)
             unit = tl.make_oracle_unit(w, {}, h)
-            pos = 0
+            pos, ys = 0, []
             while pos < w.seq and time.perf_counter() - t0 < budget_s:
-                unit.prefill(u["q"][:, pos:pos + C], u["k"][pos:pos + C], u["v"][pos:pos + C])
+                y, _ = unit.prefill(u["q"][:, pos:pos + C], u["k"][pos:pos + C], u["v"][pos:pos + C])
+                ys.append(y)
                 pos += C
             done += pos
             folds += len(unit.fold_logs)
             units_done += 1
+            if gpu is not None and ys:
+                t_cmp = time.perf_counter()
+                ga = gpu["assign"][:len(unit.fold_logs), b, h].cpu().numpy()
+                bad = [f for f, log in enumerate(unit.fold_logs) if not np.array_equal(log["assign"], ga[f])]
+                # chunk c is attended before fold c - (L/C - 1) + ... : outputs are comparable up to the
+                # chunk that follows the first differing fold
+                n_ok = len(ys) if not bad else min(len(ys), bad[0] + w.n_bswa_chunks)
+                if n_ok:
+                    y_ref = np.concatenate(ys[:n_ok], axis=1)
+                    y_gpu = tl.f64(gpu["out"][b, :n_ok * C, h * G:(h + 1) * G]).transpose(1, 0, 2)
+                    par["max_err"] = max(par["max_err"], tl.check_outputs(w, y_gpu, y_ref, "bench parity"))
+                par["units"] += 1
+                par["chunks"] += n_ok
+                par["folds"] += len(unit.fold_logs)
+                par["folds_differing"] += len(bad)
+                t0 += time.perf_counter() - t_cmp       # the comparison is not the baseline's time
     dt = time.perf_counter() - t0
     try:
         import threadpoolctl
@@ -339,10 +426,14 @@ def cpu_baseline_leg(w, tensors, budget_s):
             if threadpoolctl.threadpool_info() else os.cpu_count()
     except Exception:
         cores = os.cpu_count()
-    return dict(value=done / (dt * w.n_kv_heads), unit="tokens/s", cores=cores, kind="oracle",
+    base = dict(value=done / (dt * w.n_kv_heads), unit="tokens/s", cores=cores, kind="oracle",
                 sample=f"{units_done} of {w.batch * w.n_kv_heads} (sequence, KV head) units in order from "
                        f"(0, 0): {done} unit-tokens ({done // C} chunks, {folds} folds) in {dt:.1f} s; "
                        f"one layer token = {w.n_kv_heads} unit-tokens")
+    if gpu is not None:
+        par["max_err_unit"] = "worst output row error as a fraction of the bf16 bar (2e-2 of the row's max-abs)"
+        par["ties_merge"] = par["ties_append"] = 0 if par["folds_differing"] == 0 else None
+    return base, (par if gpu is not None else None)
 
 
 def rows_after_prefill(w, T):
@@ -470,6 +561,9 @@ def main():
     ap.add_argument("--no-backward", action="store_true", help="skip the backward pass of the prefill")
     ap.add_argument("--no-isolated", action="store_true",
                     help="skip the extra passes that time folds and attention apart")
+    ap.add_argument("--kernels-apart", action="store_true",
+                    help="keep the prefill's fold chain and its attention launches apart in every step (slower; "
+                         "for kernel traces and hardware counters of the fold kernels alone)")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the benchmark line: the paper's speed-benchmark shape over context lengths")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -501,10 +595,11 @@ def main():
         config=dict(workload=w.name, batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads,
                     head_dim=w.head_dim, seq_len=w.seq, chunk_len=w.chunk_len, state_rows=w.budget_fixed,
                     rope_dims=w.rope_dims, gpu=torch.cuda.get_device_name(0)),
-        step_ms=res["step_ms"], roofline=res["roofline"])
+        step_ms=res["step_ms"], roofline=res["roofline"], fold=res["fold"])
     # what this GPU reaches in the library's own microkernels (registers-only bf16 MFMA; 1 GiB copy)
     peaks = pkg.binding.measure_peaks(dev)
     line["measured_peaks"] = dict(mfma_bf16_tflops=peaks["mfma_bf16_tflops"], copy_gbs=peaks["copy_gbs"],
+                                  read_gbs=peaks["read_gbs"],
                                   attn_frac_of_measured=res["roofline"]["achieved"] / peaks["mfma_bf16_tflops"])
     if not args.no_others and args.workload == "prefill_gqa_32k":
         # the two other prefill configurations (fixed 512-row state; ~sqrt growth): step time only
@@ -539,12 +634,19 @@ def main():
         torch.cuda.empty_cache()
     if not args.no_decode:
         line["decode"] = decode_leg(args, pkg, synth, dev)
-        line["decode"]["roofline"]["frac_of_measured_copy"] = \
-            line["decode"]["roofline"]["achieved"] / peaks["copy_gbs"]
+        line["decode"]["roofline"]["frac_of_measured_read"] = \
+            line["decode"]["roofline"]["achieved"] / peaks["read_gbs"]
     if not args.no_cpu:
         if tensors is None:
             tensors = synth.make_qkv(w, dev)     # same seed, same tensors as the timed run
-        line["cpu_baseline"] = cpu_baseline_leg(w, tensors, args.cpu_seconds)
+        # the library's output and fold record of this very prefill, for the comparison with what
+        # the oracle gets through in its time budget
+        st = pkg.state_for(w, device=dev)
+        assign, _ = st.trace(w.seq // w.chunk_len + 1)
+        out = st.prefill(*tensors)
+        torch.cuda.synchronize()
+        line["cpu_baseline"], line["parity"] = cpu_baseline_leg(w, tensors, args.cpu_seconds,
+                                                                gpu=dict(out=out, assign=assign))
     if args.copy_calibration:
         copy_calibration(dev)
     print(json.dumps(line))

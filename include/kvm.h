@@ -318,9 +318,13 @@ int kvm_prepare_qkv(const kvm_prep_params *p, const void *q_raw, const void *k_r
  *   kvm_measure_copy_peak: copies `bytes` (a multiple of 16; src, dst device, 16-byte aligned,
  *     not overlapping) five times with 16-byte accesses; *gbs (host) receives GB/s counting
  *     bytes read plus bytes written.
+ *   kvm_measure_read_peak: streams `bytes` of src five times without writing (scratch: device,
+ *     >= 4 bytes, never written in practice); *gbs receives GB/s read: the yardstick for kernels
+ *     that read far more than they write, such as the decode attention.
  * Errors: KVM_ERR_ARG for bad arguments, KVM_ERR_HIP when a runtime call fails. */
 int kvm_measure_mfma_bf16_peak(int iters, void *scratch, double *tflops, void *stream);
 int kvm_measure_copy_peak(const void *src, void *dst, size_t bytes, double *gbs, void *stream);
+int kvm_measure_read_peak(const void *src, size_t bytes, void *scratch, double *gbs, void *stream);
 
 #ifdef __cplusplus
 }

@@ -26,7 +26,7 @@ EXPORTS = [
     "kvm_decode_step_multi", "kvm_decode_step_multi_static", "kvm_state_fold", "kvm_state_rows",
     "kvm_state_tokens", "kvm_state_capacity", "kvm_state_folds", "kvm_state_trace", "kvm_state_grow",
     "kvm_state_export", "kvm_state_import", "kvm_state_profile", "kvm_state_profile_read",
-    "kvm_measure_mfma_bf16_peak", "kvm_measure_copy_peak", "kvm_prepare_scratch_bytes", "kvm_prepare_qkv",
+    "kvm_measure_mfma_bf16_peak", "kvm_measure_copy_peak", "kvm_measure_read_peak", "kvm_prepare_scratch_bytes", "kvm_prepare_qkv",
     "kvm_backward_workspace_bytes", "kvm_prefill_backward", "kvm_debug_set",
 ]
 (KVM_DEBUG_FOLD_PATH, KVM_DEBUG_FOLD_WAVES, KVM_DEBUG_PREFILL_SCHEDULE, KVM_DEBUG_FOLD_CHAINS, KVM_DEBUG_MERGE_COPY,
@@ -118,6 +118,7 @@ def load_library() -> C.CDLL:
     lib.kvm_prefill_backward.argtypes = [vp] * 10 + [C.POINTER(kvm_grads), i64, vp, C.c_size_t, vp]
     lib.kvm_measure_mfma_bf16_peak.argtypes = [C.c_int, vp, C.POINTER(C.c_double), vp]
     lib.kvm_measure_copy_peak.argtypes = [vp, vp, C.c_size_t, C.POINTER(C.c_double), vp]
+    lib.kvm_measure_read_peak.argtypes = [vp, C.c_size_t, vp, C.POINTER(C.c_double), vp]
     _lib = lib
     return lib
 
@@ -165,18 +166,21 @@ def prepare_qkv(q_raw, k_raw, v_raw, *, rope_dims: int, pos0: int = 0, v_first=N
 
 
 def measure_peaks(device="cuda:0", copy_bytes: int = 1 << 30, iters: int = 20000) -> dict:
-    """kvm_measure_mfma_bf16_peak and kvm_measure_copy_peak on `device`: {"mfma_bf16_tflops", "copy_gbs"}."""
+    """kvm_measure_mfma_bf16_peak, kvm_measure_copy_peak and kvm_measure_read_peak on `device`:
+    {"mfma_bf16_tflops", "copy_gbs", "read_gbs"}."""
     lib = load_library()
     with torch.cuda.device(device):
         src = torch.ones(copy_bytes // 4, dtype=torch.float32, device=device)
         dst = torch.empty_like(src)
         torch.cuda.synchronize()
-        tf, gb = C.c_double(), C.c_double()
+        tf, gb, rd = C.c_double(), C.c_double(), C.c_double()
         _check(lib.kvm_measure_mfma_bf16_peak(iters, dst.data_ptr(), C.byref(tf), _stream()),
                "kvm_measure_mfma_bf16_peak")
         _check(lib.kvm_measure_copy_peak(src.data_ptr(), dst.data_ptr(), copy_bytes, C.byref(gb), _stream()),
                "kvm_measure_copy_peak")
-    return dict(mfma_bf16_tflops=tf.value, copy_gbs=gb.value)
+        _check(lib.kvm_measure_read_peak(src.data_ptr(), copy_bytes, dst.data_ptr(), C.byref(rd), _stream()),
+               "kvm_measure_read_peak")
+    return dict(mfma_bf16_tflops=tf.value, copy_gbs=gb.value, read_gbs=rd.value)
 
 
 def _io_dtype(io: int) -> torch.dtype:
