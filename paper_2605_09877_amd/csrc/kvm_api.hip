@@ -841,8 +841,9 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
       // keys are computed by one launch (blocks taken from the ring go one at a time)
       const int64_t lo0 = plan[next_fold].s + C - L;
       int run = 1;
+      const int run_cap = use_fused(st) && G > kvm::kFoldMaxSteps ? kvm::kFoldMaxSteps : G;
       if (lo0 >= t0)
-        while (run < G && next_fold + run <= last_chunk && next_fold + run < n_chunks &&
+        while (run < run_cap && next_fold + run <= last_chunk && next_fold + run < n_chunks &&
                plan[next_fold + run].folds)
           ++run;
       const bool batched = lo0 >= t0;

@@ -73,3 +73,27 @@ def test_full_size_decode_sampled_units():
         worst = max(worst, tl.check_outputs(w, tl.f64(y_gpu[b, :, h:h + 1]).transpose(1, 0, 2), y_ref,
                                             f"decode unit {(b, h)}"))
     tl.record_parity("full_size_decode[1000 steps]", len(units), all_ties, worst, w.io)
+
+
+def test_paper_speed_benchmark_shape_growth_budget_sampled_units():
+    """The configuration bench.py --sweep times (the paper's "Speed Benchmarks" shape): 8 sequences
+    x 32 heads (no grouping), head_dim 128, 256-token chunks, a budget of 16 * ceil(sqrt(e)) rows
+    (1456 rows after 8192 tokens).  At this size the library runs the prefill chunk by chunk with
+    folds in place against a large, growing state, a schedule the other workloads do not take;
+    sampled units are replayed by the oracle over all 32 chunks and 31 folds."""
+    sy = synth()
+    w = sy.shrink(sy.WORKLOADS["prefill_fixed"], name="paper_shape_sqrt", batch=8, n_q_heads=32, n_kv_heads=32,
+                  head_dim=128, chunk_len=256, rope_dims=32, seq=8192, budget_kind="sqrt", budget_scale=16.0)
+    ties, st = run_prefill_case(w, plain=True, units=sample_units(w), check_lse=True)
+    assert st.rows == 16 * 91 and st.folds == 31          # ceil(sqrt(8192)) = 91
+
+
+def test_full_budget_is_exact_causal_attention_over_memory_keys():
+    """The sweep's comparator: a budget that never fills, so every block is appended whole and a
+    query attends every earlier token (as its memory key once it has left the window)."""
+    sy = synth()
+    w = sy.shrink(sy.WORKLOADS["prefill_fixed"], name="paper_shape_full", batch=2, n_q_heads=4, n_kv_heads=4,
+                  head_dim=128, chunk_len=256, rope_dims=32, seq=4096, budget_kind="fixed", budget_fixed=4096 + 256)
+    ties, st = run_prefill_case(w, plain=True, units=[(0, 0), (1, 3)], check_lse=True)
+    # every token of the blocks folded so far (all but the last window block) has a row of its own
+    assert st.rows == 4096 - 512 + 256 and ties.total == 0
