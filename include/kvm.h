@@ -13,11 +13,18 @@
  *    the caller; the library owns only the small host handle `kvm_state`.  Pointers inside
  *    `kvm_config` named ln_*, tau_* are DEVICE pointers too; `budget_table` is a HOST pointer
  *    that is copied at init.
- *  - Every call enqueues its kernels on the caller's stream (`void *stream` is a hipStream_t,
- *    NULL = the default stream) and returns without synchronising the host.  Calls on one
+ *  - Every call orders its work on the caller's stream (`void *stream` is a hipStream_t passed as
+ *    a plain pointer so that this header needs no HIP header; NULL = the default stream) and
+ *    returns without synchronising the host: work the caller enqueues on that stream afterwards
+ *    sees all of it.  kvm_prefill_chunked and kvm_prefill_backward also use two streams the state
+ *    owns (default priority, non-blocking, created at first use): part of their kernels runs there,
+ *    forked from and joined back to the caller's stream by events inside the call.  Calls on one
  *    state must be issued in order on one stream (or be ordered by the caller).
- *  - Return value: KVM_OK (0) or a negative kvm_status.  Argument and capacity errors are
- *    detected before anything is enqueued, so a failed call leaves the state untouched.
+ *  - Return value: KVM_OK (0) or a negative kvm_status.  Argument, state and capacity errors
+ *    (KVM_ERR_ARG, KVM_ERR_STATE, KVM_ERR_CAPACITY, KVM_ERR_UNSUPPORTED, KVM_ERR_LIMIT) are detected
+ *    before anything is enqueued: such a call leaves the state untouched.  KVM_ERR_HIP means a
+ *    runtime call failed part-way: the streams are still joined back to the caller's, but the
+ *    state's contents are undefined from then on (destroy it, or import a checkpoint).
  *  - q and k arrive already prepared (normalised, partially RoPE-rotated on the first
  *    `rope_dims` channels) as the paper states at the end of "KVM weight preparation"; the
  *    library needs `rope_dims` only to zero the rotary sub-space of memory keys.
@@ -104,7 +111,11 @@ size_t kvm_state_bytes(const kvm_config *cfg, int64_t max_tokens);
 
 /* Bind an empty state (m = 0, no tokens seen) to caller memory `dev_buf` (256-byte aligned,
  * at least kvm_state_bytes(cfg, max_tokens) bytes).  Enqueues nothing.  The buffer must stay
- * alive until kvm_state_destroy; its contents need not be initialised. */
+ * alive until kvm_state_destroy; its contents need not be initialised.  What the buffer holds is
+ * the layer's recurrent state as "Compressed State and BSWA Window" describes it -- the running
+ * gated sums of memory keys and values and the stored radii of m rows, the last L tokens -- plus
+ * the normalised readout rows of "Readout" and scratch; its row capacity follows the budget rule
+ * ("We choose n_append as follows": M* = max(m, min(B(e), m + C))) replayed up to max_tokens. */
 int kvm_state_init(kvm_state **out, const kvm_config *cfg, void *dev_buf, size_t bytes,
                    int64_t max_tokens);
 int kvm_state_destroy(kvm_state *st);
@@ -121,8 +132,10 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
                         const float *gate, void *out, float *lse, int64_t T,
                         const kvm_strides *strides, void *stream);
 
-/* One new token per sequence: append (k, v, g) to the window, attend the query over state and
- * window, and fold when this token completes a chunk with e >= L.
+/* One new token per sequence ("Readout" with a single query; "Chunks and attention regions": the
+ * window is the current block so far plus the n_bswa_chunks - 1 blocks before it): append
+ * (k, v, g) to the window, attend the query over state and window, and fold when this token
+ * completes a chunk with e >= L.
  *   q, out: [B, H_q, d]; k, v: [B, H_kv, d]; gate: [B, H_kv] or NULL. */
 int kvm_decode_step(kvm_state *st, const void *q, const void *k, const void *v,
                     const float *gate, void *out, void *stream);
@@ -167,7 +180,8 @@ int kvm_decode_step_multi_static(kvm_state *const *states, int32_t n_states, con
  *   n_tokens must equal C; e = end of the chunk just attended (argument of the budget);
  *   assign_out: nullable int32 [B, H_kv, n_tokens], the row each token went to (an appended
  *   token gets its new row);  score_out: nullable fp32 [B, H_kv, n_tokens, 2] =
- *   (append score s_j, winning merge score), NaN where not computed.
+ *   (append score s_j of "Append", winning merge score max_i of "Merge"), NaN where not computed
+ *   (the two numbers the backward pass needs to tell a row's creator from the tokens merged into it).
  * Used by the two calls above; exported for callers that keep their own window. */
 int kvm_state_fold(kvm_state *st, const void *k_blk, const void *v_blk, const float *gate_blk,
                    int32_t n_tokens, int64_t e, int32_t *assign_out, float *score_out,
@@ -219,12 +233,20 @@ int kvm_state_folds(const kvm_state *st, int64_t *folds_out);     /* folds done 
 int kvm_state_trace(kvm_state *st, int32_t *assign, float *score, int64_t max_folds);
 
 /* Move the state into a larger buffer sized for `new_max_tokens` (growth scheduler: called
- * after KVM_ERR_CAPACITY).  Copies on `stream`; the old buffer may be freed once the stream has
- * passed this point. */
+ * after KVM_ERR_CAPACITY; with a growing budget -- the power-law and saturating schedules of the
+ * budget paragraph -- the rows a state needs are a function of the tokens it will see).  Copies
+ * on `stream`; the old buffer may be freed once the stream has passed this point.  The capacity is
+ * named by tokens, like kvm_state_bytes, so that caller and library size the buffer by one rule. */
 int kvm_state_grow(kvm_state *st, void *new_buf, size_t new_bytes, int64_t new_max_tokens,
                    void *stream);
 
-/* Copy the state out / in (checkpoint).  Every pointer is nullable (skipped).  Rows are dense:
+/* Copy the state out / in (checkpoint: the recurrent state of "Compressed State and BSWA Window"
+ * is all a sequence carries from one chunk to the next).  Every pointer is nullable (skipped).
+ * kvm_state_import trusts its counters: m rows, tokens_seen and folds (the number of folds done,
+ * which numbers the records of kvm_state_trace) must be those of the exported state, or describe
+ * a state the caller built (any m up to the capacity; tokens_seen then only has to make the next
+ * fold fall where the caller wants it).  Key sums are fp64, as the library holds them.
+ * Rows are dense:
  *   sK fp64 [B, H_kv, m, d], sV fp32 [B, H_kv, m, d], rho fp32 [B, H_kv, m],
  *   w fp32 [B, H_kv, m] (1 + merged gates), n int32 [B, H_kv, m] (tokens in the row),
  *   khat, vhat I/O dtype [B, H_kv, m, d] (normalised readout; export only),

@@ -74,5 +74,45 @@ def build(verbose: bool = True) -> str:
     return LIB
 
 
+def build_host_checked(out_dir: str):
+    """Host side only (`--cuda-host-only`: no kernel is compiled), with AddressSanitizer and UBSan,
+    as a library of its own in `out_dir`: for tests of the host logic on a machine without a GPU.
+    The device images the host objects refer to are replaced by zero-filled placeholders, so this
+    build can check arguments, sizes and plans but can launch nothing.  Returns (library path,
+    path of the sanitizer runtime to preload into the process that loads it)."""
+    os.makedirs(out_dir, exist_ok=True)
+    san = ["-fsanitize=address,undefined", "-fno-omit-frame-pointer"]
+    flags = ["-O1", "-g", "--cuda-host-only", "--offload-arch=gfx950", "-fPIC", "-std=c++17", *san]
+
+    def one(src):
+        obj = os.path.join(out_dir, src.replace(".hip", ".o"))
+        r = subprocess.run([_hipcc(), *flags, "-c", os.path.join(CSRC, src), "-o", obj], capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc (host only) failed for {src}:\n{r.stdout}\n{r.stderr}")
+        return obj
+
+    with ThreadPoolExecutor(max_workers=4) as ex:
+        objs = list(ex.map(one, SOURCES))
+    undefined = subprocess.run(["nm", "-u", *objs], capture_output=True, text=True, check=True).stdout
+    images = sorted({t for t in undefined.split() if t.startswith("__hip_fatbin_")})
+    stub = os.path.join(out_dir, "device_image_placeholders.cpp")
+    with open(stub, "w") as f:
+        for name in images:
+            f.write(f'extern "C" {{ __attribute__((aligned(4096))) char {name}[4096] = {{0}}; }}\n')
+    stub_o = stub.replace(".cpp", ".o")
+    subprocess.run(["g++", "-fPIC", "-c", stub, "-o", stub_o], check=True)
+    lib = os.path.join(out_dir, "libkvm_hostcheck.so")
+    r = subprocess.run([_hipcc(), "-shared", "-fPIC", "--cuda-host-only", *san, "-shared-libsan", *objs, stub_o, "-o", lib],
+                       capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"link (host only) failed:\n{r.stdout}\n{r.stderr}")
+    clang = os.path.join(os.path.dirname(os.path.realpath(_hipcc())), "..", "lib", "llvm", "bin", "clang")
+    if not os.path.exists(clang):
+        clang = "/opt/rocm/llvm/bin/clang"
+    runtime = subprocess.run([clang, "-print-file-name=libclang_rt.asan-x86_64.so"], capture_output=True, text=True,
+                             check=True).stdout.strip()
+    return lib, runtime
+
+
 if __name__ == "__main__":
     build()

@@ -813,6 +813,9 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
     fstream[c2] = st->fold_streams[c2];
     cdv[c2] = n_chains == 1 ? dv : batch_view(dv, c2 * cb, cb, es);
   }
+  // From here on work is forked onto the fold streams.  Whatever happens, the caller's stream
+  // waits for them before the call returns: they may still be reading the caller's k, v and gate.
+  auto forked = [&]() -> int {
   st->sync_used = 0;
   std::vector<hipEvent_t> slot_busy(dv.NS, nullptr);
   hipEvent_t ev;
@@ -974,6 +977,18 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
     if (rc != KVM_OK) return rc;
     rc = wait_for_folds();
     if (rc != KVM_OK) return rc;
+  }
+  return KVM_OK;
+  };
+  const int rc_forked = forked();
+  if (rc_forked != KVM_OK) {
+    // best effort (the runtime has already failed once): join the fold streams back
+    for (int c2 = 0; c2 < n_chains; ++c2) {
+      hipEvent_t e = nullptr;
+      if (next_sync_event(st, &e) == hipSuccess && hipEventRecord(e, fstream[c2]) == hipSuccess)
+        (void)hipStreamWaitEvent(stream, e, 0);
+    }
+    return rc_forked;
   }
   // keep the last L tokens for the calls that follow
   const int64_t p0 = t_end - L > t0 ? t_end - L : t0;
@@ -1282,7 +1297,16 @@ int kvm_prefill_backward(kvm_state *st, const void *q, const void *k, const void
     for (hipEvent_t *e : {&x.fork, &x.dq_done, &x.join_state, &x.join_window[0], &x.join_window[1]})
       HIP_TRY(next_sync_event(st, e));
   }
-  HIP_TRY(kvm::run_backward(a, chunks.data(), (int)chunks.size(), (hipStream_t)stream, x));
+  const hipError_t e_run = kvm::run_backward(a, chunks.data(), (int)chunks.size(), (hipStream_t)stream, x);
+  if (e_run != hipSuccess) {
+    // the side streams may still be reading the caller's tensors: join them back (best effort)
+    for (hipStream_t side : {x.side, x.side2}) {
+      hipEvent_t e = nullptr;
+      if (side && next_sync_event(st, &e) == hipSuccess && hipEventRecord(e, side) == hipSuccess)
+        (void)hipStreamWaitEvent((hipStream_t)stream, e, 0);
+    }
+    return hip_fail(e_run, "kvm::run_backward");
+  }
   return KVM_OK;
 }
 

@@ -106,6 +106,36 @@ def test_argument_and_capacity_errors_before_any_launch():
     st = kb.kvm_strides(*([128] * 18))
     st.q_t = 100                                         # not a multiple of 8 elements
     assert lib.kvm_prefill_chunked(h, p, p, p, None, p, None, 256, C.byref(st), None) == kb.KVM_ERR_ARG
+    # every stride the kernels take on trust is checked up front: a token or head stride shorter
+    # than a row, a negative stride, a k/v token stride whose tile offsets leave 32 bits, and lse
+    # strides that cannot address B * T * H_q distinct floats
+    names = [f for f, _ in kb.kvm_strides._fields_]
+
+    def strides(**kw):
+        dense = dict(q_b=256 * 512, q_t=512, q_h=128, k_b=256 * 256, k_t=256, k_h=128, v_b=256 * 256, v_t=256,
+                     v_h=128, o_b=256 * 512, o_t=512, o_h=128, g_b=512, g_t=2, g_h=1, lse_b=1024, lse_t=4, lse_h=1)
+        dense.update(kw)
+        return kb.kvm_strides(*[dense[n] for n in names])
+
+    for bad in (dict(k_t=64), dict(v_h=64), dict(q_t=-512), dict(o_b=-8), dict(k_t=(1 << 23) + 8),
+                dict(v_t=(1 << 23) + 8)):
+        assert lib.kvm_prefill_chunked(h, p, p, p, None, p, None, 256, C.byref(strides(**bad)), None) \
+            == kb.KVM_ERR_ARG, bad
+    for bad in (dict(lse_h=0), dict(lse_t=-4), dict(lse_b=0)):
+        assert lib.kvm_prefill_chunked(h, p, p, p, None, p, p, 256, C.byref(strides(**bad)), None) \
+            == kb.KVM_ERR_ARG, bad
+    assert lib.kvm_prefill_chunked(h, p, p, p, p, p, None, 256, C.byref(strides(g_t=-2)), None) == kb.KVM_ERR_ARG
+    assert lib.kvm_state_tokens(h, C.byref(v)) == 0 and v.value == 0      # nothing was consumed
+    # debugging knobs: unknown knob refused, known ones accepted and reset by 0
+    assert lib.kvm_debug_set(h, kb.KVM_DEBUG_KNOBS, 1) == kb.KVM_ERR_ARG
+    assert lib.kvm_debug_set(h, -1, 1) == kb.KVM_ERR_ARG
+    assert lib.kvm_debug_set(None, kb.KVM_DEBUG_FOLD_PATH, 1) == kb.KVM_ERR_ARG
+    assert lib.kvm_debug_set(h, kb.KVM_DEBUG_FOLD_CHAINS, 2) == kb.KVM_OK
+    assert lib.kvm_debug_set(h, kb.KVM_DEBUG_FOLD_CHAINS, 0) == kb.KVM_OK
+    # the allocation-free decode refuses what its fixed scratch cannot describe, before any HIP call
+    hs = (C.c_void_p * 1)(h)
+    assert lib.kvm_decode_step_multi_static(hs, 0, p, p, p, None, p, None) == kb.KVM_ERR_ARG
+    assert lib.kvm_decode_step_multi_static(None, 1, p, p, p, None, p, None) == kb.KVM_ERR_ARG
     assert lib.kvm_state_fold(h, p, p, None, 255, 512, None, None, None) == kb.KVM_ERR_ARG
     assert lib.kvm_decode_step(h, p, None, p, None, p, None) == kb.KVM_ERR_ARG
     assert lib.kvm_state_grow(h, FAKE_DEV_PTR, 16, 65536, None) == kb.KVM_ERR_CAPACITY
@@ -146,3 +176,27 @@ def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(kb, "LIB_PATH", str(tmp_path / "libkvm.so"))
     with pytest.raises(FileNotFoundError):
         kb.load_library()
+
+
+def test_host_logic_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """The library's host side (argument checks, growth replay, plans, sizes) is compiled again with
+    AddressSanitizer and UBSan -- host code only, kernels left out -- and this file's other tests
+    run against that build in a child process: a stray write or a signed overflow in the host
+    logic ends the child with a sanitizer report."""
+    import subprocess
+    import sys
+    from paper_2605_09877_amd import build
+    lib, runtime = build.build_host_checked(str(tmp_path))
+    runner = (
+        "import sys, pytest\n"
+        "import paper_2605_09877_amd.binding as kb\n"
+        f"kb.LIB_PATH = {lib!r}\n"
+        "sys.exit(pytest.main(['-x', '-q', '-p', 'no:cacheprovider', '-k', 'not sanitizers and not loudly', "
+        f"{os.path.abspath(__file__)!r}]))\n")
+    env = dict(os.environ, PYTHONPATH=ROOT + os.pathsep + os.path.join(ROOT, "tests"),
+               ASAN_OPTIONS="verify_asan_link_order=0:detect_leaks=0:halt_on_error=1:abort_on_error=1",
+               UBSAN_OPTIONS="halt_on_error=1:print_stacktrace=1")
+    env["LD_PRELOAD"] = (env.get("LD_PRELOAD", "") + " " + runtime).strip()
+    r = subprocess.run([sys.executable, "-c", runner], env=env, capture_output=True, text=True, timeout=600, cwd=ROOT)
+    assert r.returncode == 0, r.stdout[-3000:] + r.stderr[-3000:]
+    assert " passed" in r.stdout and "runtime error" not in r.stderr and "AddressSanitizer" not in r.stderr
