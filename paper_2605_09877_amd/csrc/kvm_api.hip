@@ -341,10 +341,18 @@ int fold_trace(const kvm_state *st, const Dev &dv, int64_t u0, int64_t fold, hip
 }
 
 // The one-launch fold path (a run of folds in one kernel, one workgroup per unit; bf16, d = 128
-// states whose tables fit LDS) is taken when kvm_debug_set asks for it.  Measured, it does not beat
-// the kernel-per-step path on any of the workloads here: one compute unit per unit of the state is
-// slower than a launch over the whole chip by more than the launch boundaries cost.
-bool use_fused(const kvm_state *st) { return st->fused && st->dbg[KVM_DEBUG_FOLD_PATH] == 1; }
+// states whose tables fit LDS) is taken when there are at least as many units as compute units,
+// so that one workgroup per unit fills the chip (measured on 256 units of the paper's benchmark
+// shape: 17 % off the prefill with a growing state, 2 % with 256 rows), or when kvm_debug_set asks
+// for it.  With fewer units one compute unit per unit of the state is slower than launches over
+// the whole chip by more than the launch boundaries cost (64 units: 13-15 ms against 11 ms).
+constexpr int kFusedMinUnits = 256;
+bool use_fused(const kvm_state *st) {
+  if (!st->fused) return false;
+  const int forced = st->dbg[KVM_DEBUG_FOLD_PATH];
+  if (forced == 1 || forced == 2) return forced == 1;
+  return st->dv.U >= kFusedMinUnits;
+}
 kvm::FoldRunArgs fused_run(const kvm_state *st, bool in_place) {
   kvm::FoldRunArgs run;
   run.n = 0;
@@ -370,8 +378,9 @@ int fold_block(kvm_state *st, const Src &src, int64_t e, int32_t *assign_out, fl
     run.n = 1;
     run.s[0] = {(int32_t)m, (int32_t)m_after, so, sn, 0, st->folds < st->trace_max ? (int32_t)st->folds : -1, 0};
     HIP_TRY(kvm::launch_memkey(dv, src, 1, stream));
-    // a fold of its own (decode, the fold entry point, the chunk-by-chunk schedule): nothing runs beside it
-    HIP_TRY(kvm::launch_fold_fused(dv, src, run, st->dbg[KVM_DEBUG_FOLD_WAVES] == 8, stream));
+    // a fold of its own (decode, the fold entry point, the chunk-by-chunk schedule): the narrow
+    // workgroup, two to a compute unit, unless asked otherwise (measured 3 % ahead of the wide one)
+    HIP_TRY(kvm::launch_fold_fused(dv, src, run, st->dbg[KVM_DEBUG_FOLD_WAVES] != 16, stream));
   } else {
     int rc = fold_launches(st, dv, src, m, m_after, so, sn, in_place, kbar_block, stream);
     if (rc != KVM_OK) return rc;
@@ -790,21 +799,9 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
     if ((forced == 1 || forced == 2) && dv.B % forced == 0) n_chains = forced;
     if (use_fused(st)) n_chains = 1;  // one workgroup per unit already: nothing to split
   }
-  // The one-launch folds run beside the attention launches.  Where attention is the larger part
-  // of the call they take the narrow workgroup, which shares a compute unit with an attention
-  // workgroup; where the fold chain is the critical path they take the wide one.  Estimates per
-  // chunk from the shape: attention at ~0.7 PFLOP/s, a fold at ~15 us + 30 us per (512 tokens x
-  // 1024 rows).
-  bool narrow_folds = false;
-  {
-    int64_t m_max = 0;
-    for (const Chunk &ch : plan) m_max = ch.m > m_max ? ch.m : m_max;
-    const double attn_us = 4.0 * d * (double)C * (double)(m_max + L) * dv.Hq * dv.B / 0.7e9;
-    const double fold_us = 15.0 + 30.0 * ((double)C / 512.0) * ((double)m_max / 1024.0);
-    narrow_folds = attn_us > fold_us;
-    if (st->dbg[KVM_DEBUG_FOLD_WAVES] == 8) narrow_folds = true;
-    if (st->dbg[KVM_DEBUG_FOLD_WAVES] == 16) narrow_folds = false;
-  }
+  // The one-launch folds of this schedule take the wide workgroup (16 waves, one per compute
+  // unit) unless asked otherwise: measured 7 % to 11 % ahead of the narrow one beside attention.
+  const bool narrow_folds = st->dbg[KVM_DEBUG_FOLD_WAVES] == 8;
   hipStream_t fstream[kvm_state::kMaxChains];
   Dev cdv[kvm_state::kMaxChains];
   const int cb = dv.B / n_chains;  // sequences per chain
