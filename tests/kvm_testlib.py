@@ -147,7 +147,14 @@ def check_state(w, exp: dict, unit: ko.KVMUnit, b: int, h: int):
     sK = exp["sK"][b, h].cpu().numpy()
     # both sides add exact products g * k-bar to an fp64 sum in position order
     np.testing.assert_array_equal(sK, st.sK)
-    np.testing.assert_allclose(exp["sV"][b, h].cpu().numpy(), st.sV, rtol=2e-5, atol=1e-5)
+    # the value sums are fp32 running sums on the GPU: each of a row's n additions rounds to within
+    # 2^-24 of the partial sum, which is of the size of the row's largest element, so an element
+    # may be off by n * 2^-24 * max|row| in absolute terms (it shows on elements that cancel to
+    # far below the row's scale) on top of the relative bar
+    sV_gpu = exp["sV"][b, h].cpu().numpy().astype(np.float64)
+    row_abs = np.asarray(st.n, np.float64)[:, None] * 2.0 ** -24 * np.abs(st.sV).max(axis=1, keepdims=True)
+    bad = np.abs(sV_gpu - st.sV) > 2e-5 * np.abs(st.sV) + 1e-5 + row_abs
+    assert not bad.any(), f"{int(bad.sum())} of {bad.size} value-sum elements outside the fp32 summation bound"
     np.testing.assert_allclose(exp["rho"][b, h].cpu().numpy(), st.rho, rtol=1e-6)
     np.testing.assert_allclose(exp["w"][b, h].cpu().numpy(), st.w, rtol=1e-5)
     np.testing.assert_array_equal(exp["n"][b, h].cpu().numpy(), st.n)

@@ -26,14 +26,17 @@ def synth():
 
 
 def run_prefill_case(w, plain, split=None, decode_tail=0, check_lse=True, units=None, tweak=None, case=None,
-                     widen=None, knobs=None):
+                     widen=None, knobs=None, mutate=None):
     """Prefill (optionally in two calls, optionally finishing with decode steps) on the GPU and in
     the oracle; compare sizes, assignments, scores, outputs, lse and the final state.  widen: the
     library is handed q, k, v, gate, out and lse as views of wider buffers (element strides through
     kvm_strides) instead of dense tensors.  knobs: {kvm_debug_set knob: value} applied to the state.
+    mutate(q, k, v): edits the generated tensors in place before either side sees them.
     Returns (Ties, state)."""
     pkg, sy = kvm(), synth()
     q, k, v = sy.make_qkv(w, DEV)
+    if mutate is not None:
+        mutate(q, k, v)
     params = sy.make_params(w, DEV, plain=plain)
     if tweak is not None:
         tweak(params)
@@ -220,6 +223,63 @@ def test_short_inputs():
         run_prefill_case(w, plain=False)
     w = synth().shrink(synth().WORKLOADS["prefill_fixed"], batch=1, n_q_heads=1, n_kv_heads=1, seq=37)
     run_prefill_case(w, plain=True)
+
+
+# ----------------------------------------------------------------------------- degenerate inputs
+def _few_distinct_tokens(n_distinct):
+    """Every token of a sequence is one of n_distinct (k, v) pairs, in rotation: memory keys repeat,
+    so scores tie exactly -- between tokens (append selection: the lower position goes first) and,
+    once rows built from the same tokens exist, between rows (merge: the lowest row wins)."""
+    def mutate(q, k, v):
+        T = k.shape[1]
+        idx = torch.arange(T, device=k.device) % n_distinct
+        k.copy_(k[:, :n_distinct][:, idx])
+        v.copy_(v[:, :n_distinct][:, idx])
+    return mutate
+
+
+def _zero_stretch(lo, hi):
+    """Tokens lo .. hi-1 have k = 0 and v = 0: LN_s of a constant vector (variance 0), rows of
+    radius 0, value sums of norm 0."""
+    def mutate(q, k, v):
+        k[:, lo:hi] = 0
+        v[:, lo:hi] = 0
+    return mutate
+
+
+FOLD_PATHS = {"kernel per step": {0: 2}, "one launch": {0: 1}}     # KVM_DEBUG_FOLD_PATH
+
+
+@pytest.mark.parametrize("path", list(FOLD_PATHS))
+def test_bf16_exact_ties_between_tokens_and_between_rows(path):
+    w = synth().shrink(synth().WORKLOADS["prefill_fixed"], batch=1, n_q_heads=2, n_kv_heads=2, seq=2048,
+                       chunk_len=128, budget_kind="sqrt", budget_scale=6.0)
+    ties, st = run_prefill_case(w, plain=False, mutate=_few_distinct_tokens(5), knobs=FOLD_PATHS[path])
+    assert ties.total == 0      # exact ties are decided by the stated order, not counted as near-ties
+
+
+def test_f32_exact_ties_between_tokens_and_between_rows():
+    w = synth().shrink(synth().WORKLOADS["tiny_f32"], seq=768, budget_kind="sqrt", budget_scale=4.0)
+    ties, st = run_prefill_case(w, plain=False, mutate=_few_distinct_tokens(3))
+    assert ties.total == 0
+
+
+@pytest.mark.parametrize("path", list(FOLD_PATHS))
+def test_bf16_zero_keys_and_values(path):
+    """A stretch of all-zero tokens that covers whole blocks (state creation from zeros included in
+    the second case) and is later merged into and attended: no NaN, no Inf, parity as usual."""
+    w = synth().shrink(synth().WORKLOADS["prefill_fixed"], batch=1, n_q_heads=2, n_kv_heads=2, seq=1536,
+                       chunk_len=128, budget_fixed=192)
+    for lo, hi in ((300, 700), (0, 256)):
+        ties, st = run_prefill_case(w, plain=False, mutate=_zero_stretch(lo, hi), knobs=FOLD_PATHS[path])
+        exp = st.export()
+        for name in ("khat", "vhat", "sV", "rho"):
+            assert torch.isfinite(exp[name].float()).all(), name
+
+
+def test_f32_zero_keys_and_values():
+    w = synth().shrink(synth().WORKLOADS["tiny_f32"], seq=640)
+    run_prefill_case(w, plain=False, mutate=_zero_stretch(0, 200))
 
 
 def test_bf16_head_dim_64_generic_kernels():
