@@ -147,7 +147,8 @@ def prefill_leg(args, pkg, synth, dev):
         touched = int(0.4 * min(w.chunk_len, m)) if w.name == "prefill_gqa_32k" else None
         nb = fold_bytes(w, units, w.chunk_len, m, touched=touched,
                         copied=None if touched is None else m - touched)
-        fold = dict(bound="hbm", kernel="memkey_kernel + score_mfma_kernel + accum_kernel", peak=HBM_PEAK_GBS,
+        fold = dict(bound="hbm", kernel="memkey_kernel + fold_fused_kernel" if st.fold_path == 1
+                    else "memkey_kernel + score_mfma_kernel + accum_kernel", peak=HBM_PEAK_GBS,
                     unit="GB/s", isolated_us_per_fold=us, beside_attention_us_per_fold=fold_ms / max(fold_n, 1) * 1e3,
                     folds_per_step=n_folds // 2, algorithmic_bytes_per_fold=nb["survey"],
                     achieved=nb["survey"] / (us * 1e-6) / 1e9, frac=nb["survey"] / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
@@ -250,7 +251,8 @@ def decode_leg(args, pkg, synth, dev):
     gbs = bytes_per_step / avg_s / 1e9 if dec_n else 0.0
     fold_us = fold_ms / max(fold_n, 1) * 1e3
     fb = fold_bytes(w, w.batch * w.n_kv_heads, C, m)
-    fold = dict(bound="hbm", kernel="memkey_kernel + score_mfma_kernel + merge_inplace_kernel", peak=HBM_PEAK_GBS,
+    fold = dict(bound="hbm", kernel="memkey_kernel + fold_fused_kernel" if st.fold_path == 1
+                else "memkey_kernel + score_mfma_kernel + merge_inplace_kernel", peak=HBM_PEAK_GBS,
                 unit="GB/s", us_per_fold=fold_us, folds=fold_n, algorithmic_bytes_per_fold=fb["survey"],
                 achieved=fb["survey"] / (fold_us * 1e-6) / 1e9 if fold_n else 0.0,
                 frac=fb["survey"] / (fold_us * 1e-6) / 1e9 / HBM_PEAK_GBS if fold_n else 0.0,

@@ -226,6 +226,10 @@ int kvm_state_rows(const kvm_state *st, int64_t *m_out);          /* current m, 
 int kvm_state_tokens(const kvm_state *st, int64_t *tokens_seen);
 int kvm_state_capacity(const kvm_state *st, int64_t *rows_out);   /* rows the bound buffer holds */
 int kvm_state_folds(const kvm_state *st, int64_t *folds_out);     /* folds done so far */
+/* Which code path this state's folds take as things stand (its shape, the debug knobs):
+ * 1 = a run of folds in one launch, one workgroup per unit; 2 = one kernel per fold step.
+ * For reports (bench.py names the kernels it timed); both paths compute the same fold. */
+int kvm_state_fold_path(const kvm_state *st, int64_t *path_out);
 
 /* Record every later fold's assignments and scores: fold number f (0 = the creation fold of
  * this state, counted over its whole life) writes assign[f] as int32 [B, H_kv, C] and

@@ -24,7 +24,7 @@ EXPORTS = [
     "kvm_strerror", "kvm_last_hip_error", "kvm_state_rows_for", "kvm_state_bytes", "kvm_state_init",
     "kvm_state_destroy", "kvm_prefill_chunked", "kvm_decode_step", "kvm_decode_multi_workspace_bytes",
     "kvm_decode_step_multi", "kvm_decode_step_multi_static", "kvm_state_fold", "kvm_state_rows",
-    "kvm_state_tokens", "kvm_state_capacity", "kvm_state_folds", "kvm_state_trace", "kvm_state_grow",
+    "kvm_state_tokens", "kvm_state_capacity", "kvm_state_folds", "kvm_state_fold_path", "kvm_state_trace", "kvm_state_grow",
     "kvm_state_export", "kvm_state_import", "kvm_state_profile", "kvm_state_profile_read",
     "kvm_measure_mfma_bf16_peak", "kvm_measure_copy_peak", "kvm_measure_read_peak", "kvm_prepare_scratch_bytes", "kvm_prepare_qkv",
     "kvm_backward_workspace_bytes", "kvm_prefill_backward", "kvm_debug_set",
@@ -102,7 +102,7 @@ def load_library() -> C.CDLL:
     lib.kvm_decode_step_multi.argtypes = [C.POINTER(vp), i32, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
     lib.kvm_decode_step_multi_static.argtypes = [C.POINTER(vp), i32, vp, vp, vp, vp, vp, vp]
     lib.kvm_state_fold.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp, vp]
-    for name in ("kvm_state_rows", "kvm_state_tokens", "kvm_state_capacity", "kvm_state_folds"):
+    for name in ("kvm_state_rows", "kvm_state_tokens", "kvm_state_capacity", "kvm_state_folds", "kvm_state_fold_path"):
         getattr(lib, name).argtypes = [vp, C.POINTER(i64)]
     lib.kvm_state_trace.argtypes = [vp, vp, vp, i64]
     lib.kvm_state_grow.argtypes = [vp, vp, C.c_size_t, i64, vp]
@@ -288,6 +288,11 @@ class KVMState:
     @property
     def folds(self) -> int:
         return self._i64(self.lib.kvm_state_folds)
+
+    @property
+    def fold_path(self) -> int:
+        """1: a run of folds is one launch (one workgroup per unit); 2: one kernel per fold step."""
+        return self._i64(self.lib.kvm_state_fold_path)
 
     def rows_for(self, max_tokens: int) -> int:
         return self.lib.kvm_state_rows_for(C.byref(self.cfg), max_tokens)

@@ -1322,6 +1322,11 @@ int kvm_state_capacity(const kvm_state *st, int64_t *rows_out) {
   *rows_out = st->dv.Mcap;
   return KVM_OK;
 }
+int kvm_state_fold_path(const kvm_state *st, int64_t *path_out) {
+  if (!st || !path_out) return KVM_ERR_ARG;
+  *path_out = use_fused(st) ? 1 : 2;
+  return KVM_OK;
+}
 int kvm_state_folds(const kvm_state *st, int64_t *folds_out) {
   if (!st || !folds_out) return KVM_ERR_ARG;
   *folds_out = st->folds;
