@@ -274,9 +274,11 @@ int kvm_state_import(kvm_state *st, const double *sK, const float *sV, const flo
  *   KVM_DEBUG_FOLD_CHAINS       1 or 2: fold chains side by side (kernel-per-step path)
  *   KVM_DEBUG_MERGE_COPY        1 / 2: token-centred merge with row copies on / off (same path)
  *   KVM_DEBUG_BACKWARD_PATH     1: attention adjoints on the vector ALU on every shape (it also
- *                               sizes kvm_backward_workspace_bytes: set it before asking) */
+ *                               sizes kvm_backward_workspace_bytes: set it before asking)
+ *   KVM_DEBUG_FOLD_SPLIT        1, 2, 4 or 8: workgroups that share a unit's state rows on the
+ *                               one-launch path (ignored where the shape does not allow it) */
 enum { KVM_DEBUG_FOLD_PATH = 0, KVM_DEBUG_FOLD_WAVES = 1, KVM_DEBUG_PREFILL_SCHEDULE = 2, KVM_DEBUG_FOLD_CHAINS = 3,
-       KVM_DEBUG_MERGE_COPY = 4, KVM_DEBUG_BACKWARD_PATH = 5, KVM_DEBUG_KNOBS = 8 };
+       KVM_DEBUG_MERGE_COPY = 4, KVM_DEBUG_BACKWARD_PATH = 5, KVM_DEBUG_FOLD_SPLIT = 6, KVM_DEBUG_KNOBS = 8 };
 int kvm_debug_set(kvm_state *st, int knob, int value);
 
 /* Kernel timing for benchmarks (no passage of the paper: a measurement aid).  While enabled,

@@ -30,7 +30,7 @@ EXPORTS = [
     "kvm_backward_workspace_bytes", "kvm_prefill_backward", "kvm_debug_set",
 ]
 (KVM_DEBUG_FOLD_PATH, KVM_DEBUG_FOLD_WAVES, KVM_DEBUG_PREFILL_SCHEDULE, KVM_DEBUG_FOLD_CHAINS, KVM_DEBUG_MERGE_COPY,
- KVM_DEBUG_BACKWARD_PATH) = range(6)
+ KVM_DEBUG_BACKWARD_PATH, KVM_DEBUG_FOLD_SPLIT) = range(7)
 KVM_DEBUG_KNOBS = 8  # number of knobs the library knows of; kvm_debug_set refuses any index from here on
 
 

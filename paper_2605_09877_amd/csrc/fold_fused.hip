@@ -29,6 +29,19 @@
 //      fp64 on keys, stored radius on values) are written; rows nothing was added to are copied
 //      to the new state version (prefill) or left alone (in place).
 // Integer decisions rest on fp64 LN_s and fp64 key sums, as everywhere in this library.
+//
+// With fewer units than compute units one workgroup per unit leaves most of the chip idle, so a
+// unit can be given `split` workgroups (a power of two) that divide its state rows among them in
+// 64-row tiles, tile t belonging to workgroup t mod split: a workgroup scores the whole block
+// against its own rows, merges the tokens bound for its own rows, creates the new rows that fall
+// to it and copies its own untouched rows.  Everything a workgroup reads of the state it wrote
+// itself, so the only data that crosses workgroups is each token's partial winner: one exchange
+// per scoring pass through a small table in global memory.  An entry is one 64-bit word (score,
+// row, a 16-bit tag of the exchange it belongs to) written and read with relaxed device-scope
+// atomics: no fences, no flags beside the data; a reader spins on the tag, with a clock limit that
+// ends the wait and raises an error word instead of hanging.  The workgroups of a launch must be
+// able to be resident together (the host checks the grid against the chip); kernels that run
+// beside it on other streams only delay a workgroup's start, they never wait for this kernel.
 #include <cstddef>
 
 #include "kvm_device.h"
@@ -72,9 +85,12 @@ struct FoldLds {
   uint32_t masks;    // u64   [C / 64] taken-token masks
   uint32_t counters; // int   [4]
   uint32_t head;     // int   [Mcap] last token pushed on the row's list, or -1
+  uint32_t lall;     // float [C]  this workgroup's own winners of a scoring pass (split > 1)
+  uint32_t lbest;    // float [C]
+  uint32_t lidx;     // int   [C]
   uint32_t total;
 };
-__host__ __device__ inline FoldLds fold_lds(int C, int Mcap, int NW) {
+__host__ __device__ inline FoldLds fold_lds(int C, int Mcap, int NW, int split = 1) {
   FoldLds l;
   uint32_t o = 0;
   auto take = [&](uint32_t bytes) {
@@ -94,6 +110,9 @@ __host__ __device__ inline FoldLds fold_lds(int C, int Mcap, int NW) {
   l.masks = take(8u * ((C + 63) / 64));
   l.counters = take(16);
   l.head = take(4u * Mcap);
+  l.lall = take(split > 1 ? 4u * C : 0u);
+  l.lbest = take(split > 1 ? 4u * C : 0u);
+  l.lidx = take(split > 1 ? 4u * C : 0u);
   l.total = o;
   return l;
 }
@@ -102,6 +121,12 @@ struct Ctx {
   unsigned char *smem;
   FoldLds l;
   int u, tid, lane, wave;
+  int part, split;   // this workgroup's number among the unit's workgroups, and how many they are
+  // the workgroup that owns a state row: 64-row tiles dealt round robin
+  __device__ bool owns(int row) const { return ((row >> 6) & (split - 1)) == part; }
+  __device__ float *s_lall() const { return (float *)(smem + l.lall); }
+  __device__ float *s_lbest() const { return (float *)(smem + l.lbest); }
+  __device__ int *s_lidx() const { return (int *)(smem + l.lidx); }
   __device__ float *s_app() const { return (float *)(smem + l.app); }
   __device__ float *s_best() const { return (float *)(smem + l.best); }
   __device__ int *s_pi() const { return (int *)(smem + l.pi); }
@@ -140,11 +165,16 @@ __device__ __forceinline__ void score_pass(const Dev &dv, const Ctx &cx, int slo
   const int lane = cx.lane, wave = cx.wave, u = cx.u;
   const int g = lane >> 5, l32 = lane & 31;
   const int C = dv.C, TG = C / 32;
-  const int n_tiles = (row1 - row0 + kTileKeys - 1) / kTileKeys;
+  // Tiles are 64-row blocks of the state counted from row 0; this workgroup takes the ones that
+  // fall to it, tile t_first, t_first + split, ...: local tile number lt <-> tile t_first + lt * split.
+  const int t_lo = row0 >> 6, t_hi = (row1 + kTileKeys - 1) >> 6;
+  const int t_first = t_lo + ((cx.part - t_lo) & (cx.split - 1));
+  const int n_tiles = t_first < t_hi ? (t_hi - t_first + cx.split - 1) / cx.split : 0;
   const int n_stages = (n_tiles + ST - 1) / ST;
+  const int row_lo = row0 > dv.S ? row0 : dv.S;   // first row that may win a merge
   uint16_t *Ks = (uint16_t *)(cx.smem + cx.l.tiles);
   const uint32_t ks_addr = lds_addr_of(Ks);
-  const char *khat = (const char *)dv.khat + (slot * dv.slot_elems + ((int64_t)u * dv.Mcap + row0) * D) * 2;
+  const char *khat = (const char *)dv.khat + (slot * dv.slot_elems + (int64_t)u * dv.Mcap * D) * 2;
   uint32_t koff[8];
   ktile_offsets(lane, koff);
   // a tile is sixteen 1-KiB pieces of four rows; wave w fetches pieces w, w + NW, ... of every
@@ -157,7 +187,7 @@ __device__ __forceinline__ void score_pass(const Dev &dv, const Ctx &cx, int slo
     for (int i = 0; i < ST; ++i) {
       const int t = ST * sg + i;
       if (t < n_tiles) {
-        const int base = t * kTileKeys, valid = row1 - row0 - base;
+        const int base = (t_first + t * cx.split) * kTileKeys, valid = row1 - base;
 #pragma unroll
         for (int n = 0; n < 16 / NW; ++n) {
           const int piece = wave + NW * n;
@@ -255,17 +285,17 @@ __device__ __forceinline__ void score_pass(const Dev &dv, const Ctx &cx, int slo
             }
 #pragma unroll
             for (int rh = 0; rh < 2; ++rh) {
-              const int blk = 2 * t + rh, base = row0 + 32 * blk;
-              if (base < row1) {
-                const bool edge = base < dv.S || base + 32 > row1;
+              const int blk = 2 * (t_first + t * cx.split) + rh, base = 32 * blk;
+              if (base < row1 && base + 32 > row0) {
+                const bool edge = base < row_lo || base + 32 > row1;
                 if (edge) {
 #pragma unroll
                   for (int v = 0; v < 16; ++v) {
                     const int i2 = base + mfma_row(v, g);
                     const float sc = acc[rh][v];
-                    if (i2 < row1) {
+                    if (i2 < row1 && i2 >= row0) {
                       best_all = fmaxf(best_all, sc);
-                      if (i2 >= dv.S && sc > best) {
+                      if (i2 >= row_lo && sc > best) {
                         best = sc;
                         best_code = 16 * blk + v;
                       }
@@ -286,7 +316,7 @@ __device__ __forceinline__ void score_pass(const Dev &dv, const Ctx &cx, int slo
         }
       }
     }
-    int best_i = best_code < 0 ? kNoRow : row0 + 32 * (best_code >> 4) + mfma_row(best_code & 15, g);
+    int best_i = best_code < 0 ? kNoRow : 32 * (best_code >> 4) + mfma_row(best_code & 15, g);
     best_all = fmaxf(best_all, best);
     {
       // the other lane half holds the other rows of the same token
@@ -320,7 +350,12 @@ __device__ __forceinline__ void score_pass(const Dev &dv, const Ctx &cx, int slo
       }
     }
     if (active && sub == 0 && g == 0) {
-      if (first) {
+      if (cx.split > 1) {
+        // this workgroup's rows only: the unit's winner is settled by the exchange that follows
+        cx.s_lall()[j] = best_all;
+        cx.s_lbest()[j] = best;
+        cx.s_lidx()[j] = best_i;
+      } else if (first) {
         cx.s_app()[j] = best_all;
         cx.s_best()[j] = best;
         cx.s_pi()[j] = best_i;
@@ -332,6 +367,82 @@ __device__ __forceinline__ void score_pass(const Dev &dv, const Ctx &cx, int slo
     }
     __syncthreads();   // tile buffers and the merge scratch are free again
   }
+}
+
+// ------------------------------------------------------------------------------------------------
+// The exchange after a scoring pass (split > 1): every workgroup of the unit publishes its own
+// winners and reads the others'; all of them end up with the same unit-wide result in LDS, as
+// score_pass leaves it when a unit has one workgroup.
+// Table: [unit][exchange parity][workgroup][2][C] 64-bit words; word 0 of a token = (merge score,
+// row in 16 bits, tag), word 1 = (append score, tag).  A workgroup cannot be two exchanges ahead of
+// a sibling (it needs the sibling's entries of the exchange in between), so two parities suffice.
+// tag: the low 16 bits of the exchange's number, which the host never reuses within a state's life
+// before every entry has been rewritten many times; the table starts zeroed and 0 is never a tag.
+__device__ __forceinline__ unsigned long long xchg_pack(float score, uint32_t low16, uint32_t tag) {
+  return ((unsigned long long)__float_as_uint(score) << 32) | ((unsigned long long)(low16 & 0xffffu) << 16) |
+         (unsigned long long)(tag & 0xffffu);
+}
+// gave_up: a word in LDS, set by the first wait of the workgroup that ran into the limit; from then
+// on its waits return at once (a workgroup loses at most one time limit, whatever went wrong),
+// with an entry that names no row, so that nothing downstream indexes with it.
+__device__ __forceinline__ unsigned long long xchg_wait(const unsigned long long *p, uint32_t tag, int32_t *err,
+                                                        volatile int *gave_up) {
+  unsigned long long v = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if ((uint32_t)(v & 0xffffu) == tag) return v;
+  const unsigned long long t0 = wall_clock64();   // 100 MHz
+  while (*gave_up == 0) {
+    __builtin_amdgcn_s_sleep(4);
+    v = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if ((uint32_t)(v & 0xffffu) == tag) return v;
+    if (wall_clock64() - t0 > 20000000ull) {   // 200 ms: a sibling that never came
+      *gave_up = 1;
+      __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+  }
+  return xchg_pack(-INFINITY, 0xffffu, tag);
+}
+template <int NW>
+__device__ __forceinline__ void exchange_winners(const Dev &dv, const Ctx &cx, unsigned long long *xtab,
+                                                 uint32_t xnum, bool first, int32_t *err) {
+  constexpr int NT = 64 * NW;
+  const int C = dv.C;
+  const uint32_t tag = xnum & 0xffffu;
+  volatile int *gave_up = cx.s_cnt() + 2;
+  unsigned long long *base = xtab + (((size_t)cx.u * 2 + (xnum & 1u)) * cx.split) * 2 * C;
+  for (int j = cx.tid; j < C; j += NT) {
+    float best = cx.s_lbest()[j], best_all = cx.s_lall()[j];
+    int best_i = cx.s_lidx()[j];
+    unsigned long long *mine = base + (size_t)cx.part * 2 * C;
+    __hip_atomic_store(mine + j, xchg_pack(best, best_i == kNoRow ? 0xffffu : (uint32_t)best_i, tag), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+    if (first)
+      __hip_atomic_store(mine + C + j, xchg_pack(best_all, 0, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (int o = 1; o < cx.split; ++o) {
+      const unsigned long long *theirs = base + (size_t)((cx.part + o) & (cx.split - 1)) * 2 * C;
+      const unsigned long long w0 = xchg_wait(theirs + j, tag, err, gave_up);
+      const float ob = __uint_as_float((uint32_t)(w0 >> 32));
+      const uint32_t oi16 = (uint32_t)(w0 >> 16) & 0xffffu;
+      const int oi = oi16 == 0xffffu ? kNoRow : (int)oi16;
+      if (oi != kNoRow && (best_i == kNoRow || beats(ob, oi, best, best_i))) {
+        best = ob;
+        best_i = oi;
+      }
+      if (first) {
+        const unsigned long long w1 = xchg_wait(theirs + C + j, tag, err, gave_up);
+        best_all = fmaxf(best_all, __uint_as_float((uint32_t)(w1 >> 32)));
+      }
+    }
+    if (first) {
+      cx.s_app()[j] = best_all;
+      cx.s_best()[j] = best;
+      cx.s_pi()[j] = best_i;
+      cx.s_rank()[j] = -1;
+    } else if (cx.s_rank()[j] < 0 && best_i != kNoRow && best > cx.s_best()[j]) {
+      cx.s_best()[j] = best;
+      cx.s_pi()[j] = best_i;
+    }
+  }
+  __syncthreads();
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -466,6 +577,7 @@ __device__ __forceinline__ void create_rows(const Dev &dv, const Ctx &cx, const 
                                             int slot_new) {
   constexpr int D = kHeadDim, NG = 4 * NW;
   for (int a = rc.gid; a < n_app; a += NG) {
+    if (!cx.owns(m + a)) continue;
     const int t = cx.s_creator()[a];
     const int64_t ro = (int64_t)cx.u * dv.Mcap + m + a;
     const uint4 kraw = *reinterpret_cast<const uint4 *>(rc.kbar + (int64_t)t * D + rc.ch0);
@@ -512,6 +624,7 @@ __device__ __forceinline__ int build_lists(const Dev &dv, const Ctx &cx) {
     int row = kNoRow;
     if (j < C && cx.s_rank()[j] < 0) {
       row = cx.s_pi()[j];
+      row = row != kNoRow && cx.owns(row) ? row : kNoRow;   // other rows are other workgroups' work
       if (row != kNoRow) {
         const int old = atomicExch(&cx.s_head()[row], j);
         cx.s_next()[j] = old;
@@ -664,7 +777,7 @@ __device__ __forceinline__ void copy_untouched(const Dev &dv, const Ctx &cx, int
 #pragma unroll
     for (int q = 0; q < UN; ++q) {
       const int r = r0 + q * NG;
-      on[q] = r < m && (all || head[r] < 0);
+      on[q] = r < m && (all || head[r] < 0) && cx.owns(r);
       if (on[q]) {
         kk[q] = *reinterpret_cast<const uint4 *>(ko + (int64_t)r * D + 8 * c16);
         vv[q] = *reinterpret_cast<const uint4 *>(vo + (int64_t)r * D + 8 * c16);
@@ -703,13 +816,24 @@ __global__ __launch_bounds__(64 * NW, 4) void fold_fused_kernel(FoldKernelArgs a
   const FoldStep *steps = reinterpret_cast<const FoldStep *>(
       (const char *)__builtin_amdgcn_kernarg_segment_ptr() + offsetof(FoldKernelArgs, run) + offsetof(FoldRunArgs, s));
   const int C = dv.C;
-  Ctx cx{smem, fold_lds(C, dv.Mcap, NW), (int)blockIdx.x, (int)threadIdx.x, (int)(threadIdx.x & 63),
-         __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6))};
+  // Workgroup -> (unit, part).  The workgroups of a unit read the same block of tokens: where the
+  // number of units allows it they get ids 8 apart, which the hardware hands to one accelerator
+  // die, whose L2 then fetches the block once.
+  const int split = args.run.split;
+  const int bid = (int)blockIdx.x;
+  const bool by_die = dv.U % 8 == 0;
+  const int u_ = by_die ? (bid / (8 * split)) * 8 + bid % 8 : bid / split;
+  const int part_ = by_die ? (bid / 8) % split : bid % split;
+  Ctx cx{smem, fold_lds(C, dv.Mcap, NW, split), u_, (int)threadIdx.x, (int)(threadIdx.x & 63),
+         __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)), part_, split};
+  unsigned long long *const xtab = args.run.xtab;
+  int32_t *const xerr = args.run.err;
   const int u = cx.u, tid = cx.tid;
   const float qnan = __uint_as_float(0x7fc00000u);
 #ifdef KVM_FOLD_STAMPS
   if (threadIdx.x == 0) cx.s_cnt()[3] = 0;
 #endif
+  if (threadIdx.x == 0) cx.s_cnt()[2] = 0;   // no wait has given up (read after barriers only)
 
   for (int si = 0; si < run_n; ++si) {
     FOLD_STAMP();
@@ -733,6 +857,7 @@ __global__ __launch_bounds__(64 * NW, 4) void fold_fused_kernel(FoldKernelArgs a
       if (!run_in_place) copy_untouched<NW>(dv, cx, m, st.so, st.sn, true);
     } else {
       score_pass<NW>(dv, cx, st.so, 0, m, true, kbar_blk);
+      if (split > 1) exchange_winners<NW>(dv, cx, xtab, st.xnum, true, xerr);
       FOLD_STAMP();
       const RowCtx rc = row_ctx(dv, cx, src, st.tok, kbar_blk);
       if (n_app > 0) {
@@ -742,6 +867,7 @@ __global__ __launch_bounds__(64 * NW, 4) void fold_fused_kernel(FoldKernelArgs a
         __syncthreads();
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
         score_pass<NW>(dv, cx, st.sn, m, m_after, false, kbar_blk);
+        if (split > 1) exchange_winners<NW>(dv, cx, xtab, st.xnum + 1u, false, xerr);
       }
       FOLD_STAMP();
       const int n_rows = build_lists<NW>(dv, cx);
@@ -752,7 +878,7 @@ __global__ __launch_bounds__(64 * NW, 4) void fold_fused_kernel(FoldKernelArgs a
     }
     FOLD_STAMP();
     // what the fold decided, for the record and for the entry point's optional outputs
-    {
+    if (cx.part == 0) {
       const int64_t base = (int64_t)u * C;
       for (int j = tid; j < C; j += NT) {
         const int p = cx.s_pi()[j];
@@ -800,9 +926,14 @@ bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 
 // The shapes this path takes: bf16, head_dim 128; blocks of 2^k * 32 tokens up to 1024 (the waves
 // that share a token group split a stage's tiles by a power of two); tables that fit LDS.
-bool fold_fused_fits(const Dev &dv) {
+bool fold_fused_fits(const Dev &dv, int split) {
   if (!(dv.io == 1 && dv.d == kHeadDim && dv.C % 64 == 0 && dv.C <= 1024 && pow2(dv.C / 32))) return false;
-  return fold_lds(dv.C, dv.Mcap, 16).total <= kLdsWide && fold_lds(dv.C, dv.Mcap, 8).total <= kLdsNarrow;
+  if (!pow2(split) || split > kFoldMaxSplit || dv.Mcap >= 0xffff) return false;   // rows travel in 16 bits
+  return fold_lds(dv.C, dv.Mcap, 16, split).total <= kLdsWide && fold_lds(dv.C, dv.Mcap, 8, split).total <= kLdsNarrow;
+}
+
+size_t fold_exchange_bytes(const Dev &dv, int split) {
+  return split > 1 ? (size_t)dv.Ufull * 2 * split * 2 * dv.C * sizeof(unsigned long long) : 0;
 }
 
 hipError_t launch_refresh16(const Dev &dv, int m, int slot, hipStream_t st) {
@@ -819,11 +950,23 @@ hipError_t launch_fold_fused(const Dev &dv, const Src &src, const FoldRunArgs &r
                                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsNarrow);
   if (attr16 != hipSuccess) return attr16;
   if (attr8 != hipSuccess) return attr8;
+  const int split = run.split;
+  if (split < 1 || (split > 1 && (!run.xtab || !run.err))) return hipErrorInvalidValue;
+  if (split > 1) {
+    // the unit's workgroups wait for each other: all of the grid must fit the chip at once (one
+    // workgroup of either shape per compute unit at least)
+    int dev = 0, cus = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return e;
+    if ((int64_t)dv.U * split > cus) return hipErrorInvalidValue;
+  }
   FoldKernelArgs args{dv, src, run};
+  const unsigned grid = (unsigned)(dv.U * split);
   if (narrow)
-    hipLaunchKernelGGL(fold_fused_kernel<8>, dim3(dv.U), dim3(512), fold_lds(dv.C, dv.Mcap, 8).total, st, args);
+    hipLaunchKernelGGL(fold_fused_kernel<8>, dim3(grid), dim3(512), fold_lds(dv.C, dv.Mcap, 8, split).total, st, args);
   else
-    hipLaunchKernelGGL(fold_fused_kernel<16>, dim3(dv.U), dim3(1024), fold_lds(dv.C, dv.Mcap, 16).total, st, args);
+    hipLaunchKernelGGL(fold_fused_kernel<16>, dim3(grid), dim3(1024), fold_lds(dv.C, dv.Mcap, 16, split).total, st, args);
   return hipGetLastError();
 }
 

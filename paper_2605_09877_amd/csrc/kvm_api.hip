@@ -30,6 +30,15 @@ struct kvm_state {
   int64_t trace_max = 0;
   bool mfma = false;  // bf16, d = 128, C % 64 == 0: matrix-core kernels
   bool fused = false; // folds run as one launch per run of folds (fold_fused.hip)
+  // a unit's rows shared among several workgroups of that launch: the exchange table (part of the
+  // state buffer), whether it has been zeroed, the next exchange number (never reused: the
+  // table's entries are told apart by it), and the error word the kernel raises when a wait for a
+  // sibling workgroup ran into its time limit (host memory the device can write)
+  unsigned long long *xtab = nullptr;
+  size_t xtab_bytes = 0;
+  bool xtab_clean = false;
+  uint32_t xchg = 2;
+  int32_t *xerr_host = nullptr, *xerr_dev = nullptr;
   // kvm_debug_set knobs (0 = the library's own choice)
   int dbg[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   int group = 1;      // chunks per attention launch in prefill; the readout has 2 * group slots
@@ -138,7 +147,7 @@ int64_t capacity_rows(const kvm_config &c, const std::vector<int64_t> &table, in
 }
 
 struct Layout {
-  size_t sK, sV, rho, w, n, khat, vhat, winK, winV, winG, kbar, score, pi, app, creator, total;
+  size_t sK, sV, rho, w, n, khat, vhat, winK, winV, winG, kbar, score, pi, app, xtab, xtab_bytes, creator, total;
 };
 
 bool use_mfma(const kvm_config &c) {
@@ -147,6 +156,7 @@ bool use_mfma(const kvm_config &c) {
 // Chunks per prefill attention launch.  The matrix-core path launches groups of chunks so that
 // a launch has thousands of workgroups; the generic path launches chunk by chunk.
 int group_of(const kvm_config &c) { return use_mfma(c) ? 8 : 1; }
+constexpr int kClusterBelowUnits = 256;  // compute units of the chip this library is written for
 
 Layout layout_of(const kvm_config &c, int64_t Mcap) {
   const size_t U = (size_t)c.batch * c.n_kv_heads, d = c.head_dim, C = c.chunk_len;
@@ -173,6 +183,11 @@ Layout layout_of(const kvm_config &c, int64_t Mcap) {
   l.score = take(U * C * 8);
   l.pi = take(U * C * 4);
   l.app = take(U * C * 4);
+  // exchange table of the one-launch fold when a unit's rows are shared among workgroups: only
+  // states with fewer units than the chip has compute units ever do that
+  l.xtab_bytes = use_mfma(c) && U < (size_t)kClusterBelowUnits
+                     ? U * 2 * (size_t)kvm::kFoldMaxSplit * 2 * C * sizeof(unsigned long long) : 0;
+  l.xtab = take(l.xtab_bytes);
   l.creator = take(U * C * 4);
   l.total = o;
   return l;
@@ -347,20 +362,79 @@ int fold_trace(const kvm_state *st, const Dev &dv, int64_t u0, int64_t fold, hip
 // for it.  With fewer units one compute unit per unit of the state is slower than launches over
 // the whole chip by more than the launch boundaries cost (64 units: 13-15 ms against 11 ms).
 constexpr int kFusedMinUnits = 256;
-bool use_fused(const kvm_state *st) {
-  if (!st->fused) return false;
-  const int forced = st->dbg[KVM_DEBUG_FOLD_PATH];
-  if (forced == 1 || forced == 2) return forced == 1;
-  return st->dv.U >= kFusedMinUnits;
+// With fewer units a unit's rows can be shared among `split` workgroups of the launch (a power of
+// two, at most kFoldMaxSplit; units x split workgroups must be resident together, one per compute
+// unit): 0 = the kernel-per-step path.
+int fold_split(const kvm_state *st) {
+  if (!st->fused) return 0;
+  const int path = st->dbg[KVM_DEBUG_FOLD_PATH];
+  if (path == 2) return 0;
+  const int U = st->dv.U;
+  int want = st->dbg[KVM_DEBUG_FOLD_SPLIT];
+  if (want == 0) {
+    if (U >= kFusedMinUnits) return 1;
+    if (path != 1) return 0;
+    want = 1;
+  }
+  if (want == 1) return 1;
+  const bool ok = (want == 2 || want == 4 || want == 8) && st->xtab && (int64_t)U * want <= kClusterBelowUnits &&
+                  st->dv.Mcap / 64 >= want && kvm::fold_fused_fits(st->dv, want);
+  return ok ? want : 1;
 }
-kvm::FoldRunArgs fused_run(const kvm_state *st, bool in_place) {
+bool use_fused(const kvm_state *st) { return fold_split(st) > 0; }
+
+__global__ __launch_bounds__(256) void zero_words_kernel(unsigned long long *p, size_t n) {
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0ull;
+}
+
+// Arguments of a one-launch run; with shared rows also what the exchange needs: the table zeroed
+// once (on `stream`, ahead of the first launch that uses it) and the error word.
+int fused_run(kvm_state *st, bool in_place, hipStream_t stream, kvm::FoldRunArgs *out) {
   kvm::FoldRunArgs run;
   run.n = 0;
   run.in_place = in_place ? 1 : 0;
   run.trace_assign = st->trace_assign;
   run.trace_score = st->trace_score;
   run.trace_stride = (int64_t)st->dv.U * st->dv.C;
-  return run;
+  run.split = fold_split(st);
+  run.xtab = nullptr;
+  run.err = nullptr;
+  if (run.split > 1) {
+    if (!st->xerr_host) {
+      HIP_TRY(hipHostMalloc((void **)&st->xerr_host, sizeof(int32_t), hipHostMallocMapped));
+      *st->xerr_host = 0;
+      HIP_TRY(hipHostGetDevicePointer((void **)&st->xerr_dev, st->xerr_host, 0));
+    }
+    if (!st->xtab_clean) {
+      hipLaunchKernelGGL(zero_words_kernel, dim3(256), dim3(256), 0, stream, st->xtab, st->xtab_bytes / 8);
+      HIP_TRY(hipGetLastError());
+      st->xtab_clean = true;
+    }
+    run.xtab = st->xtab;
+    run.err = st->xerr_dev;
+  }
+  *out = run;
+  return KVM_OK;
+}
+// The exchange numbers of one fold (first scoring pass, and the second one when some but not all
+// of the block is appended): consecutive, never 0 in their low 16 bits.
+uint32_t take_exchanges(kvm_state *st, int64_t m, int64_t m_after) {
+  const int64_t n_app = m_after - m;
+  const uint32_t need = n_app == st->dv.C ? 0u : n_app > 0 ? 2u : 1u;
+  if (((st->xchg & 0xffffu) == 0u) || (need == 2u && ((st->xchg + 1u) & 0xffffu) == 0u)) {
+    // skip the number whose tag would be 0, keeping the parity sequence strictly alternating
+    st->xchg += 2u;
+  }
+  const uint32_t first = st->xchg;
+  st->xchg += need;
+  return first;
+}
+int cluster_error(const kvm_state *st) {
+  if (st->xerr_host && *(volatile int32_t *)st->xerr_host != 0) {
+    g_hip_error = "a fold workgroup waited for a sibling workgroup past its time limit; the state is undefined";
+    return KVM_ERR_HIP;
+  }
+  return KVM_OK;
 }
 
 int fold_block(kvm_state *st, const Src &src, int64_t e, int32_t *assign_out, float *score_out,
@@ -374,9 +448,12 @@ int fold_block(kvm_state *st, const Src &src, int64_t e, int32_t *assign_out, fl
   const int so = slot_of(st, st->folds), sn = in_place ? so : slot_of(st, st->folds + 1);
   const size_t ntok = (size_t)dv.U * dv.C;
   if (use_fused(st)) {
-    kvm::FoldRunArgs run = fused_run(st, in_place);
+    kvm::FoldRunArgs run;
+    const int rc_run = fused_run(st, in_place, stream, &run);
+    if (rc_run != KVM_OK) return rc_run;
     run.n = 1;
-    run.s[0] = {(int32_t)m, (int32_t)m_after, so, sn, 0, st->folds < st->trace_max ? (int32_t)st->folds : -1, 0};
+    run.s[0] = {(int32_t)m, (int32_t)m_after, so, sn, 0, st->folds < st->trace_max ? (int32_t)st->folds : -1, 0,
+                take_exchanges(st, m, m_after), 0u};
     HIP_TRY(kvm::launch_memkey(dv, src, 1, stream));
     // a fold of its own (decode, the fold entry point, the chunk-by-chunk schedule): the narrow
     // workgroup, two to a compute unit, unless asked otherwise (measured 3 % ahead of the wide one)
@@ -604,6 +681,12 @@ int kvm_state_init(kvm_state **out, const kvm_config *cfg, void *dev_buf, size_t
   st->buf = dev_buf;
   st->bytes = bytes;
   bind(st->dv, st->cfg, dev_buf, Mcap);
+  {
+    const Layout l = layout_of(st->cfg, Mcap);
+    st->xtab = l.xtab_bytes ? (unsigned long long *)((char *)dev_buf + l.xtab) : nullptr;
+    st->xtab_bytes = l.xtab_bytes;
+    st->xtab_clean = false;
+  }
   st->mfma = use_mfma(*cfg);
   st->fused = st->mfma && kvm::fold_fused_fits(st->dv);
   st->group = group_of(*cfg);
@@ -621,6 +704,7 @@ int kvm_state_destroy(kvm_state *st) {
     for (auto e : st->sync_events) (void)hipEventDestroy(e);
     for (hipStream_t fs : st->fold_streams)
       if (fs) (void)hipStreamDestroy(fs);
+    if (st->xerr_host) (void)hipHostFree(st->xerr_host);
   }
   delete st;
   return KVM_OK;
@@ -662,6 +746,7 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
                         const float *gate, void *out, float *lse, int64_t T,
                         const kvm_strides *sp, void *stream_) {
   if (!st || !q || !k || !v || !out || T <= 0) return KVM_ERR_ARG;
+  if (cluster_error(st) != KVM_OK) return KVM_ERR_HIP;
   hipStream_t stream = (hipStream_t)stream_;
   const kvm_config &c = st->cfg;
   const Dev &dv = st->dv;
@@ -801,7 +886,9 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
   }
   // The one-launch folds of this schedule take the wide workgroup (16 waves, one per compute
   // unit) unless asked otherwise: measured 7 % to 11 % ahead of the narrow one beside attention.
-  const bool narrow_folds = st->dbg[KVM_DEBUG_FOLD_WAVES] == 8;
+  // With a unit's rows shared among workgroups the narrow one is the default: it is the shape that
+  // fits beside an attention workgroup, and sharing is chosen where the folds are to run hidden.
+  const bool narrow_folds = st->dbg[KVM_DEBUG_FOLD_WAVES] == 8 || (st->dbg[KVM_DEBUG_FOLD_WAVES] == 0 && fold_split(st) > 1);
   hipStream_t fstream[kvm_state::kMaxChains];
   Dev cdv[kvm_state::kMaxChains];
   const int cb = dv.B / n_chains;  // sequences per chain
@@ -886,13 +973,16 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
       }
       if (use_fused(st)) {
         ProfileSpan span(st, 1, fstream[0], run);
-        kvm::FoldRunArgs fr = fused_run(st, false);
+        kvm::FoldRunArgs fr;
+        const int rc_run = fused_run(st, false, fstream[0], &fr);
+        if (rc_run != KVM_OK) return rc_run;
         fr.n = run;
         for (int i = 0; i < run; ++i) {
           const int64_t lo = plan[next_fold + i].s + C - L;
           const int64_t fold_no = st->folds + i;
           fr.s[i] = {(int32_t)steps[i].m, (int32_t)steps[i].m_after, steps[i].so, steps[i].sn,
-                     batched ? lo - lo0 : 0, fold_no < st->trace_max ? (int32_t)fold_no : -1, i};
+                     batched ? lo - lo0 : 0, fold_no < st->trace_max ? (int32_t)fold_no : -1, i,
+                     take_exchanges(st, steps[i].m, steps[i].m_after), 0u};
         }
         const Src fsrc = batched ? advance(in, lo0 - t0, es) : advance(ring, lo0 % L, es);
         HIP_TRY(kvm::launch_memkey(dv, fsrc, run, fstream[0]));
@@ -998,6 +1088,7 @@ int kvm_decode_step(kvm_state *st, const void *q, const void *k, const void *v,
                     const float *gate, void *out, void *stream_) {
   if (!st || !q || !k || !v || !out) return KVM_ERR_ARG;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return KVM_ERR_ARG;
+  if (cluster_error(st) != KVM_OK) return KVM_ERR_HIP;
   hipStream_t stream = (hipStream_t)stream_;
   const kvm_config &c = st->cfg;
   const Dev &dv = st->dv;
@@ -1375,6 +1466,13 @@ int kvm_state_grow(kvm_state *st, void *new_buf, size_t new_bytes, int64_t new_m
   st->dv = nd;
   st->buf = new_buf;
   st->bytes = new_bytes;
+  {
+    const Layout l = layout_of(c, Mnew);
+    st->xtab = l.xtab_bytes ? (unsigned long long *)((char *)new_buf + l.xtab) : nullptr;
+    st->xtab_bytes = l.xtab_bytes;
+    st->xtab_clean = false;
+  }
+  st->fused = st->mfma && kvm::fold_fused_fits(st->dv);
   return KVM_OK;
 }
 

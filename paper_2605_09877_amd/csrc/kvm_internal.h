@@ -96,10 +96,12 @@ hipError_t launch_ring_copy(const Dev &dv, const Src &src, int64_t src_t0, int64
 // fold over all units).  narrow: the 8-wave workgroup that fits beside an attention workgroup on
 // a compute unit; otherwise 16 waves and the unit to itself.
 constexpr int kFoldMaxSteps = 8;
+constexpr int kFoldMaxSplit = 8;   // workgroups that may share a unit's rows
 struct FoldStep {
   int32_t m, m_after, so, sn;
   int64_t tok;
   int32_t trace, kbar_block;
+  uint32_t xnum, pad;   // number of the fold's first exchange among the unit's workgroups (split > 1)
 };
 struct FoldRunArgs {
   int32_t n, in_place;
@@ -107,8 +109,12 @@ struct FoldRunArgs {
   int32_t *trace_assign;
   float *trace_score;
   int64_t trace_stride;
+  int32_t split;               // workgroups per unit (a power of two); 1: none of the next two is used
+  unsigned long long *xtab;    // the exchange table, fold_exchange_bytes() of zeroed device memory
+  int32_t *err;                // set to 1 when a wait for a sibling workgroup ran into its time limit
 };
-bool fold_fused_fits(const Dev &dv);
+bool fold_fused_fits(const Dev &dv, int split = 1);
+size_t fold_exchange_bytes(const Dev &dv, int split);
 // readout rows [0, m) recomputed from the sums with the one-launch path's arithmetic
 hipError_t launch_refresh16(const Dev &dv, int m, int slot, hipStream_t st);
 hipError_t launch_fold_fused(const Dev &dv, const Src &src, const FoldRunArgs &run, bool narrow, hipStream_t st);

@@ -513,15 +513,16 @@ def test_f32_strided_operands_generic_path():
 
 
 # ----------------------------------------------------------------------------- the two fold paths
-@pytest.mark.parametrize("waves", [8, 16])
+@pytest.mark.parametrize("waves,split", [(8, 1), (16, 1), (8, 2), (8, 4), (16, 2), (8, 8)])
 @pytest.mark.parametrize("shape", ["fixed", "sqrt", "gqa"])
-def test_fold_paths_agree(shape, waves):
+def test_fold_paths_agree(shape, waves, split):
     """bf16 / d = 128 states fold with one launch per run of folds (one workgroup per unit); the
     kernel-per-step path they can be switched to (kvm_debug_set) must take the same decisions:
     assignments, row counts and key sums equal to the bit (both score with the same matrix-core
     arithmetic and add exact products in fp64), value sums to the bit too (same adds in the same
     order); radii and the value readout may differ in the last fp32 bit (sums over a row's
-    channels are taken in another order), outputs accordingly."""
+    channels are taken in another order), outputs accordingly.  split > 1: a unit's rows are shared
+    among that many workgroups of the launch, which settle every token's winner by an exchange."""
     pkg, sy = kvm(), synth()
     from paper_2605_09877_amd import binding
     w = {"fixed": sy.shrink(sy.WORKLOADS["prefill_fixed"], batch=2, n_q_heads=2, n_kv_heads=2, seq=3072 + 77),
@@ -534,6 +535,7 @@ def test_fold_paths_agree(shape, waves):
         st = pkg.state_for(w, device=DEV, **params)
         st.debug_set(binding.KVM_DEBUG_FOLD_PATH, path)
         st.debug_set(binding.KVM_DEBUG_FOLD_WAVES, waves)
+        st.debug_set(binding.KVM_DEBUG_FOLD_SPLIT, split)
         assign, score = st.trace(w.seq // w.chunk_len + 1)
         y = st.prefill(q, k, v, params["gate"])
         torch.cuda.synchronize()
@@ -552,15 +554,15 @@ def test_fold_paths_agree(shape, waves):
     torch.testing.assert_close(a[0].float(), b[0].float(), rtol=2e-2, atol=2e-2)
 
 
-@pytest.mark.parametrize("waves", [8, 16])
+@pytest.mark.parametrize("waves,split", [(8, 1), (16, 1), (8, 4), (16, 2)])
 @pytest.mark.parametrize("case", ["fixed", "sqrt", "gqa", "decode_tail", "table", "three_blocks"])
-def test_one_launch_fold_path_against_the_oracle(case, waves):
+def test_one_launch_fold_path_against_the_oracle(case, waves, split):
     """The one-launch fold path (kvm_debug_set; not the default), both workgroup shapes, against
     the oracle to the bars of the other tests: plain merges, append-all, partial appends with the
     second scoring pass, folds in place during decode steps, a budget table, a three-block window."""
     from paper_2605_09877_amd import binding
     sy = synth()
-    knobs = {binding.KVM_DEBUG_FOLD_PATH: 1, binding.KVM_DEBUG_FOLD_WAVES: waves}
+    knobs = {binding.KVM_DEBUG_FOLD_PATH: 1, binding.KVM_DEBUG_FOLD_WAVES: waves, binding.KVM_DEBUG_FOLD_SPLIT: split}
     if case == "fixed":
         w = sy.shrink(sy.WORKLOADS["prefill_fixed"], batch=2, n_q_heads=2, n_kv_heads=2, seq=2560 + 77)
         run_prefill_case(w, plain=False, knobs=knobs)
