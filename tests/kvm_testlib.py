@@ -78,8 +78,8 @@ def tie_ceiling(w, n_folds):
     return 0 if w.io == "f32" else (n_folds + 3) // 4
 
 
-# What the parity tests of a session saw, one record per test case: written to
-# gpurun_out/parity_stats.json by tests/conftest.py when the session ends.
+# What the parity tests of a session saw, one record per test case: written to a JSON file
+# (parity_stats.json in the run's output folder) by tests/conftest.py when the session ends.
 PARITY_LOG = []
 
 
