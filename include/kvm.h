@@ -24,7 +24,9 @@
  *    (KVM_ERR_ARG, KVM_ERR_STATE, KVM_ERR_CAPACITY, KVM_ERR_UNSUPPORTED, KVM_ERR_LIMIT) are detected
  *    before anything is enqueued: such a call leaves the state untouched.  KVM_ERR_HIP means a
  *    runtime call failed part-way: the streams are still joined back to the caller's, but the
- *    state's contents are undefined from then on (destroy it, or import a checkpoint).
+ *    state's contents are undefined from then on (destroy it, or import a checkpoint).  The same
+ *    code reports, on the next call on the state, that a fold kernel whose workgroups wait for
+ *    each other (KVM_DEBUG_FOLD_SPLIT) ran into the time limit of such a wait.
  *  - q and k arrive already prepared (normalised, partially RoPE-rotated on the first
  *    `rope_dims` channels) as the paper states at the end of "KVM weight preparation"; the
  *    library needs `rope_dims` only to zero the rotary sub-space of memory keys.

@@ -1302,6 +1302,7 @@ int kvm_state_fold(kvm_state *st, const void *k_blk, const void *v_blk, const fl
   if (!st || !k_blk || !v_blk) return KVM_ERR_ARG;
   if (n_tokens != st->dv.C) return KVM_ERR_ARG;
   if (!aligned16(k_blk) || !aligned16(v_blk)) return KVM_ERR_ARG;
+  if (cluster_error(st) != KVM_OK) return KVM_ERR_HIP;
   const Dev &dv = st->dv;
   Src src;
   src.k = k_blk; src.v = v_blk; src.g = gate_blk;
