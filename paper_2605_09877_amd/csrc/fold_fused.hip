@@ -417,21 +417,33 @@ __device__ __forceinline__ void exchange_winners(const Dev &dv, const Ctx &cx, u
                        __HIP_MEMORY_SCOPE_AGENT);
     if (first)
       __hip_atomic_store(mine + C + j, xchg_pack(best_all, 0, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    for (int o = 1; o < cx.split; ++o) {
-      const unsigned long long *theirs = base + (size_t)((cx.part + o) & (cx.split - 1)) * 2 * C;
-      const unsigned long long w0 = xchg_wait(theirs + j, tag, err, gave_up);
-      const float ob = __uint_as_float((uint32_t)(w0 >> 32));
-      const uint32_t oi16 = (uint32_t)(w0 >> 16) & 0xffffu;
-      const int oi = oi16 == 0xffffu ? kNoRow : (int)oi16;
-      if (oi != kNoRow && (best_i == kNoRow || beats(ob, oi, best, best_i))) {
-        best = ob;
-        best_i = oi;
+    // the siblings' entries: all of them asked for at once (each read goes to memory, one or two
+    // microseconds away), then the stragglers waited for one by one
+    unsigned long long w0[kFoldMaxSplit - 1], w1[kFoldMaxSplit - 1];
+#pragma unroll
+    for (int o = 1; o < kFoldMaxSplit; ++o)
+      if (o < cx.split) {
+        const unsigned long long *theirs = base + (size_t)((cx.part + o) & (cx.split - 1)) * 2 * C;
+        w0[o - 1] = __hip_atomic_load(theirs + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (first) w1[o - 1] = __hip_atomic_load(theirs + C + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
-      if (first) {
-        const unsigned long long w1 = xchg_wait(theirs + C + j, tag, err, gave_up);
-        best_all = fmaxf(best_all, __uint_as_float((uint32_t)(w1 >> 32)));
+#pragma unroll
+    for (int o = 1; o < kFoldMaxSplit; ++o)
+      if (o < cx.split) {
+        const unsigned long long *theirs = base + (size_t)((cx.part + o) & (cx.split - 1)) * 2 * C;
+        if ((uint32_t)(w0[o - 1] & 0xffffu) != tag) w0[o - 1] = xchg_wait(theirs + j, tag, err, gave_up);
+        const float ob = __uint_as_float((uint32_t)(w0[o - 1] >> 32));
+        const uint32_t oi16 = (uint32_t)(w0[o - 1] >> 16) & 0xffffu;
+        const int oi = oi16 == 0xffffu ? kNoRow : (int)oi16;
+        if (oi != kNoRow && (best_i == kNoRow || beats(ob, oi, best, best_i))) {
+          best = ob;
+          best_i = oi;
+        }
+        if (first) {
+          if ((uint32_t)(w1[o - 1] & 0xffffu) != tag) w1[o - 1] = xchg_wait(theirs + C + j, tag, err, gave_up);
+          best_all = fmaxf(best_all, __uint_as_float((uint32_t)(w1[o - 1] >> 32)));
+        }
       }
-    }
     if (first) {
       cx.s_app()[j] = best_all;
       cx.s_best()[j] = best;
