@@ -349,9 +349,15 @@ class KVMState:
         if out is None:
             out = torch.empty_like(q)
         self._chk(out, q.shape, self.dtype, "out")
-        with torch.cuda.device(self.device):
+        # a decode step is a few microseconds of GPU work: entering a device context costs as much,
+        # so it is entered only when another device is current
+        if torch.cuda.current_device() == self.device.index:
             _check(self.lib.kvm_decode_step(self.handle, q.data_ptr(), k.data_ptr(), v.data_ptr(), _ptr(gate),
                                             out.data_ptr(), _stream()), "kvm_decode_step")
+        else:
+            with torch.cuda.device(self.device):
+                _check(self.lib.kvm_decode_step(self.handle, q.data_ptr(), k.data_ptr(), v.data_ptr(), _ptr(gate),
+                                                out.data_ptr(), _stream()), "kvm_decode_step")
         return out
 
     def fold(self, k_blk, v_blk, gate_blk=None, *, e: int):
