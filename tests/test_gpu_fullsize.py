@@ -31,6 +31,18 @@ def test_full_size_prefill_sampled_units(name, rows):
     print(f"{name}: ties counted in sampled units: {ties}")
 
 
+@pytest.mark.parametrize("name,split", [("prefill_gqa_32k", 4), ("prefill_sqrt", 8)])
+def test_full_size_prefill_with_rows_shared_among_workgroups(name, split):
+    """The one-launch fold with a unit's rows shared among `split` workgroups (kvm_debug_set), at
+    full size and beside the attention launches: 256 workgroups that wait for each other's winners
+    at every fold while the chip is busy with other kernels."""
+    from paper_2605_09877_amd import binding
+    w = synth().WORKLOADS[name]
+    ties, st = run_prefill_case(w, plain=True, units=sample_units(w), check_lse=True,
+                                knobs={binding.KVM_DEBUG_FOLD_PATH: 1, binding.KVM_DEBUG_FOLD_SPLIT: split})
+    assert st.fold_path == 1 and st.folds == w.seq // w.chunk_len - 1 and ties.total == 0
+
+
 def test_full_size_decode_sampled_units():
     """Batched decode workload at full size: 64 x 32 heads, 2048 rows + 256-token window, all of
     its 1000 successive steps (seven folds); sampled units replayed by the oracle."""
