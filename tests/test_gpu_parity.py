@@ -282,6 +282,62 @@ def test_f32_zero_keys_and_values():
     run_prefill_case(w, plain=False, mutate=_zero_stretch(0, 200))
 
 
+@pytest.mark.parametrize("path", list(FOLD_PATHS))
+def test_bf16_every_channel_rotary_all_memory_keys_equal(path):
+    """rope_dims = head_dim: zero_r removes every channel, so every memory key is LN_s of the zero
+    vector (= beta) and every similarity is the same number: the fold is decided by the tie rules
+    alone (lowest eligible row; appended tokens by position)."""
+    w = synth().shrink(synth().WORKLOADS["prefill_fixed"], batch=1, n_q_heads=2, n_kv_heads=2, seq=1536 + 20,
+                       chunk_len=128, rope_dims=128, budget_kind="sqrt", budget_scale=6.0)
+    ties, st = run_prefill_case(w, plain=False, knobs=FOLD_PATHS[path])
+    assert ties.total == 0
+
+
+def test_f32_every_channel_rotary_all_memory_keys_equal():
+    w = synth().shrink(synth().WORKLOADS["tiny_f32"], seq=700, rope_dims=64, budget_kind="sqrt", budget_scale=4.0)
+    ties, st = run_prefill_case(w, plain=False)
+    assert ties.total == 0
+
+
+@pytest.mark.parametrize("n_sink", [0, 3])
+@pytest.mark.parametrize("path", list(FOLD_PATHS))
+def test_bf16_sink_counts(path, n_sink):
+    """No sink row at all, and three: the rows below n_sink never receive a token but count for the
+    append score."""
+    w = synth().shrink(synth().WORKLOADS["prefill_fixed"], batch=1, n_q_heads=2, n_kv_heads=2, seq=2048 + 31,
+                       chunk_len=128, budget_fixed=200, n_sink=n_sink)
+    ties, st = run_prefill_case(w, plain=False, knobs=FOLD_PATHS[path])
+    exp = st.export()
+    if n_sink:
+        assert int(exp["n"][:, :, :n_sink].max()) == 1      # a sink row holds its creator only
+
+
+@pytest.mark.parametrize("split", [0, 1, 4])
+def test_bf16_units_not_a_multiple_of_eight(split):
+    """3 sequences x 3 KV heads = 9 units (workgroup -> unit mappings that deal units round robin
+    over the accelerator dies have a ragged last round; the batch cannot be halved either), two
+    query heads per KV head; on the kernel-per-step path and on the one-launch path with one and
+    with four workgroups per unit."""
+    from paper_2605_09877_amd import binding
+    w = synth().shrink(synth().WORKLOADS["prefill_fixed"], batch=3, n_q_heads=6, n_kv_heads=3, seq=2048 + 64 + 9,
+                       chunk_len=128, budget_kind="sqrt", budget_scale=7.0)
+    knobs = {binding.KVM_DEBUG_FOLD_PATH: 2} if split == 0 else \
+        {binding.KVM_DEBUG_FOLD_PATH: 1, binding.KVM_DEBUG_FOLD_SPLIT: split}
+    run_prefill_case(w, plain=False, split=1024, decode_tail=9, knobs=knobs)
+
+
+def test_bf16_budget_of_one_block_and_a_single_fold():
+    """A budget equal to the block length (the state is created full and never grows: every later
+    block merges whole), and a sequence that ends right after its first fold."""
+    w = synth().shrink(synth().WORKLOADS["prefill_fixed"], batch=1, n_q_heads=2, n_kv_heads=2, seq=1280,
+                       chunk_len=128, budget_fixed=128)
+    ties, st = run_prefill_case(w, plain=False)
+    assert st.rows == 128
+    w = synth().shrink(w, seq=256)          # T = L: attention over the window only, then one fold
+    ties, st = run_prefill_case(w, plain=False)
+    assert st.folds == 1 and st.rows == 128
+
+
 def test_bf16_head_dim_64_generic_kernels():
     w = synth().shrink(synth().WORKLOADS["prefill_fixed"], batch=1, n_q_heads=2, n_kv_heads=1, head_dim=64,
                        rope_dims=16, seq=768 + 10, chunk_len=96, budget_fixed=160)
