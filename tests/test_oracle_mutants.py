@@ -62,6 +62,24 @@ FORWARD = [
     ("append score skips the sink rows", "s_max = sim.max(axis=1)", "s_max = sim[:, S:].max(axis=1)"),
     ("softmax without the window's values", "vals = np.concatenate([vhat, v_win], axis=0) if m else v_win",
      "vals = np.concatenate([vhat, 0 * v_win], axis=0) if m else v_win"),
+    ("state logits not divided by sqrt(d)", "ls = tau_state[h] * (q[h] @ khat.T) / math.sqrt(d) if m",
+     "ls = tau_state[h] * (q[h] @ khat.T) if m"),
+    ("log-sum-exp without the maximum", "lse[h] = (mx + np.log(z))[:, 0]", "lse[h] = np.log(z)[:, 0]"),
+    ("a query sees its own successor", "visible = win_pos[None, :] <= q_pos[:, None]",
+     "visible = win_pos[None, :] <= q_pos[:, None] + 1"),
+    ("a query does not see itself", "visible = win_pos[None, :] <= q_pos[:, None]",
+     "visible = win_pos[None, :] < q_pos[:, None]"),
+    ("square-root budget rounds down", "return math.isqrt(e - 1) + 1", "return math.isqrt(e)"),
+    ("LN_s epsilon outside the root", "return (x - mu) / np.sqrt(var + eps) * gamma + beta",
+     "return (x - mu) / (np.sqrt(var) + eps) * gamma + beta"),
+    ("LN_s bias dropped", "return (x - mu) / np.sqrt(var + eps) * gamma + beta",
+     "return (x - mu) / np.sqrt(var + eps) * gamma"),
+    ("value readout divides by the squared norm", "nrm = np.sqrt((state.sV * state.sV).sum(axis=-1, keepdims=True))",
+     "nrm = (state.sV * state.sV).sum(axis=-1, keepdims=True)"),
+    ("bf16 rounding truncates", "u = (u + np.uint64(0x7FFF) + lsb) & np.uint64(0xFFFF0000)",
+     "u = u & np.uint64(0xFFFF0000)"),
+    ("bf16 ties round away from zero", "u = (u + np.uint64(0x7FFF) + lsb) & np.uint64(0xFFFF0000)",
+     "u = (u + np.uint64(0x8000)) & np.uint64(0xFFFF0000)"),
 ]
 
 BACKWARD = [
