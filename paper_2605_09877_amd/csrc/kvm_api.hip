@@ -873,14 +873,13 @@ int kvm_prefill_chunked(kvm_state *st, const void *q, const void *k, const void 
   // chain is bound by their latencies, not by bytes, and the batch is split into two halves
   // whose chains run side by side on streams of their own (units are independent).  Two, not
   // more: with four chains the step was measured 40 % to 100 % slower, with four, eight and
-  // sixteen hardware queues alike.  Measured ahead by 4 % at 20-30 MB per fold and still by 1-2 %
-  // at 117 MB (64 units of 1024 rows, 512-token blocks), the largest shape tried.
+  // sixteen hardware queues alike.
   int n_chains = 1;
   {
     int64_t m_max = 0;
     for (const Chunk &ch : plan) m_max = ch.m > m_max ? ch.m : m_max;
     const double fold_mb = (double)dv.U * ((double)m_max * d * es * 5.0 + (double)C * d * es * 4.0) / 1.0e6;
-    if (fold_mb < 128.0 && dv.B % 2 == 0) n_chains = 2;
+    if (fold_mb < 96.0 && dv.B % 2 == 0) n_chains = 2;
     const int forced = st->dbg[KVM_DEBUG_FOLD_CHAINS];  // 1 or 2: for comparisons
     if ((forced == 1 || forced == 2) && dv.B % forced == 0) n_chains = forced;
     if (use_fused(st)) n_chains = 1;  // one workgroup per unit already: nothing to split
